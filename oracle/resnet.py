@@ -1,0 +1,202 @@
+"""Oracle: one local SGD iteration of one sub-ResNet, float64 -- TEST INFRASTRUCTURE ONLY.
+
+Algorithm 1's inner loop (W_s <- W_s - eta * dL/dW_s) on the network a worker keeps:
+the stem, the residual blocks in its block list (ascending global index), and the head.
+A block that is absent contributes nothing: the residual stream passes through unchanged
+(Appendix B, forward recursion with mask M = 0; with M = 1 everywhere the sub-ResNet is the
+global ResNet).
+
+Network (post-activation blocks, the benchmark configurations' layer list):
+  stem   conv (3x3 s1 p1 | 7x7 s2 p3) -> BN -> ReLU [-> maxpool 3x3 s2 p1]
+  basic  conv3x3(stride) -> BN -> ReLU -> conv3x3 -> BN ; + shortcut ; ReLU
+  bottle conv1x1 -> BN -> ReLU -> conv3x3(stride) -> BN -> ReLU -> conv1x1(x4) -> BN ; + shortcut ; ReLU
+  shortcut: identity, or conv1x1(stride) -> BN in the first block of a stage when shape changes
+  head   global mean pool -> FC + bias -> softmax cross-entropy, mean over the batch
+Update (momentum per the paper's experimental section; form is the usual one):
+  g <- g + wd*w ; v <- mu*v + g ; w <- w - lr*v   (every trainable parameter alike)
+Parameters are dicts keyed -1 (stem), b (block), B (head) of logical-layout arrays.
+Pins: tests/test_oracle_step.py (finite differences of the loss w.r.t. every parameter,
+a float64 autograd library as third opinion, SGD closed form, all-blocks == full model).
+"""
+import numpy as np
+
+from . import layers as L
+
+
+def block_table(model):
+    exp = 4 if model["block_kind"] == 1 else 1
+    tab, c_in = [], model["widths"][0]
+    for si, (w, nb) in enumerate(zip(model["widths"], model["blocks"])):
+        for bi in range(nb):
+            stride = 2 if (bi == 0 and si > 0) else 1
+            c_out = w * exp
+            tab.append(dict(c_in=c_in, width=w, c_out=c_out, stride=stride,
+                            has_ds=(bi == 0 and (stride != 1 or c_in != c_out))))
+            c_in = c_out
+    return tab
+
+
+TRAINABLE_SUFFIXES = ("_w", "_g", "_b")
+
+
+def is_trainable(name):
+    return name.endswith(TRAINABLE_SUFFIXES)
+
+
+def param_count(model, block, trainable_only=True):
+    """Number of parameters of the stem (-1), a block, or the head (B) -- closed form from the
+    layer shapes (no conv bias; BN gamma+beta; FC weight+bias)."""
+    tab = block_table(model)
+    B = len(tab)
+    bn = (lambda c: 2 * c) if trainable_only else (lambda c: 4 * c)
+    if block == -1:
+        rs = 3 if model["stem_kind"] == 0 else 7
+        w0 = model["widths"][0]
+        return w0 * model["in_c"] * rs * rs + bn(w0)
+    if block == B:
+        return model["num_classes"] * tab[-1]["c_out"] + model["num_classes"]
+    t = tab[block]
+    if model["block_kind"] == 0:
+        n = t["width"] * t["c_in"] * 9 + bn(t["width"]) + t["c_out"] * t["width"] * 9 + bn(t["c_out"])
+    else:
+        n = (t["width"] * t["c_in"] + bn(t["width"]) + t["width"] * t["width"] * 9 + bn(t["width"])
+             + t["c_out"] * t["width"] + bn(t["c_out"]))
+    if t["has_ds"]:
+        n += t["c_out"] * t["c_in"] + bn(t["c_out"])
+    return n
+
+
+class _Tape:
+    """Forward caches, so the backward is the exact adjoint of the forward just computed."""
+
+    def __init__(self):
+        self.stats = {}      # (block, bn name) -> (mean, biased var, m)
+
+
+def _conv_bn(x, p, conv, bn, stride, pad, eps, relu, tape, key):
+    y = L.conv2d_fwd(x, p[conv + "_w"], stride, pad)
+    z, cache = L.bn_fwd(y, p[bn + "_g"].astype(np.float64), p[bn + "_b"].astype(np.float64), eps)
+    m = y.shape[0] * y.shape[2] * y.shape[3]
+    tape.stats[(key, bn)] = (cache[2], cache[3], m)
+    a = np.maximum(z, 0.0) if relu else z
+    return a, dict(x=x, cache=cache, z=z, conv=conv, bn=bn, stride=stride, pad=pad, relu=relu)
+
+
+def _conv_bn_bwd(da, ctx, p, grads):
+    """da: gradient w.r.t. the (post-ReLU if relu) output.  ReLU'(0) = 0."""
+    dz = da * (ctx["z"] > 0) if ctx["relu"] else da
+    dy, dg, db = L.bn_bwd(dz, ctx["cache"], p[ctx["bn"] + "_g"].astype(np.float64))
+    grads[ctx["bn"] + "_g"] = dg
+    grads[ctx["bn"] + "_b"] = db
+    w = p[ctx["conv"] + "_w"]
+    grads[ctx["conv"] + "_w"] = L.conv2d_wgrad(dy, ctx["x"], w.shape, ctx["stride"], ctx["pad"])
+    return dy, w
+
+
+def forward_backward(model, blocks, params, x, labels, need_input_grad=False, backward=True):
+    """Loss and gradients of the sub-ResNet made of `blocks` (ascending global indices).
+
+    Returns loss, grads (same keys as params, trainable tensors only), tape (batch statistics),
+    and the input gradient if asked.  backward=False stops after the loss (grads = None).
+    """
+    tab = block_table(model)
+    B = len(tab)
+    eps = model["bn_eps"]
+    tape = _Tape()
+    x = np.asarray(x, np.float64)
+    # ---- forward
+    st = params[-1]
+    if model["stem_kind"] == 0:
+        a, stem_ctx = _conv_bn(x, st, "conv", "bn", 1, 1, eps, True, tape, -1)
+        pool_cache = None
+    else:
+        a, stem_ctx = _conv_bn(x, st, "conv", "bn", 2, 3, eps, True, tape, -1)
+        a, pool_cache = L.maxpool_fwd(a, 3, 2, 1)
+    ctxs = []
+    for b in blocks:
+        t, p = tab[b], params[b]
+        inp = a
+        if model["block_kind"] == 0:
+            h, c1 = _conv_bn(inp, p, "conv1", "bn1", t["stride"], 1, eps, True, tape, b)
+            h, c2 = _conv_bn(h, p, "conv2", "bn2", 1, 1, eps, False, tape, b)
+            chain = [c1, c2]
+        else:
+            h, c1 = _conv_bn(inp, p, "conv1", "bn1", 1, 0, eps, True, tape, b)
+            h, c2 = _conv_bn(h, p, "conv2", "bn2", t["stride"], 1, eps, True, tape, b)
+            h, c3 = _conv_bn(h, p, "conv3", "bn3", 1, 0, eps, False, tape, b)
+            chain = [c1, c2, c3]
+        if t["has_ds"]:
+            sc, cd = _conv_bn(inp, p, "ds", "dsbn", t["stride"], 0, eps, False, tape, b)
+        else:
+            sc, cd = inp, None
+        pre = h + sc
+        a = np.maximum(pre, 0.0)
+        ctxs.append((b, chain, cd, pre))
+    feat_shape = a.shape
+    pooled = L.avgpool_fwd(a)
+    hd = params[B]
+    z = L.fc_fwd(pooled, hd["fc_w"].astype(np.float64), hd["fc_b"].astype(np.float64))
+    loss, dz = L.softmax_ce(z, np.asarray(labels))
+    if not backward:
+        return loss, None, tape, None
+    # ---- backward
+    grads = {}
+    dpooled, dw, db = L.fc_bwd(dz, pooled, hd["fc_w"].astype(np.float64))
+    grads[B] = {"fc_w": dw, "fc_b": db}
+    g = L.avgpool_bwd(dpooled, feat_shape)
+    for b, chain, cd, pre in reversed(ctxs):
+        t, p = tab[b], params[b]
+        gb = {}
+        gpre = g * (pre > 0)
+        d = gpre
+        for ctx in reversed(chain):
+            dy, w = _conv_bn_bwd(d, ctx, p, gb)
+            d = L.conv2d_dgrad(dy, w, ctx["x"].shape, ctx["stride"], ctx["pad"])
+        if cd is not None:
+            dy, w = _conv_bn_bwd(gpre, cd, p, gb)
+            d = d + L.conv2d_dgrad(dy, w, cd["x"].shape, cd["stride"], cd["pad"])
+        else:
+            d = d + gpre
+        g = d
+        grads[b] = gb
+    gs = {}
+    if pool_cache is not None:
+        g = L.maxpool_bwd(g, pool_cache)
+    dy, w = _conv_bn_bwd(g, stem_ctx, st, gs)
+    grads[-1] = gs
+    dx = None
+    if need_input_grad:
+        dx = L.conv2d_dgrad(dy, w, stem_ctx["x"].shape, stem_ctx["stride"], stem_ctx["pad"])
+    return loss, grads, tape, dx
+
+
+def sgd_update(params, momentum_buf, grads, lr, mu, wd):
+    """g <- g + wd*w ; v <- mu*v + g ; w <- w - lr*v on every trainable tensor (float64)."""
+    new_p, new_v = {}, {}
+    for b, gb in grads.items():
+        new_p[b] = {k: np.asarray(v, np.float64).copy() for k, v in params[b].items()}
+        new_v[b] = {k: np.asarray(v, np.float64).copy() for k, v in momentum_buf[b].items()}
+        for name, g in gb.items():
+            w = np.asarray(params[b][name], np.float64)
+            gg = g + wd * w
+            v = mu * np.asarray(momentum_buf[b][name], np.float64) + gg
+            new_v[b][name] = v
+            new_p[b][name] = w - lr * v
+    return new_p, new_v
+
+
+def local_step(model, blocks, params, momentum_buf, x, labels, lr, mu, wd):
+    """One local SGD iteration of the sub-ResNet holding `blocks`.
+
+    params / momentum_buf need entries for -1, every b in blocks, and B.
+    Returns loss, grads, new_params (incl. updated BN running statistics), new_momentum.
+    """
+    loss, grads, tape, _ = forward_backward(model, blocks, params, x, labels)
+    new_p, new_v = sgd_update(params, momentum_buf, grads, lr, mu, wd)
+    mom = model["bn_momentum"]
+    for (b, bn), (mean, var, m) in tape.stats.items():
+        rm, rv = L.bn_running_update(np.asarray(params[b][bn + "_rm"], np.float64),
+                                     np.asarray(params[b][bn + "_rv"], np.float64),
+                                     mean, var, m, mom)
+        new_p[b][bn + "_rm"], new_p[b][bn + "_rv"] = rm, rv
+    return loss, grads, new_p, new_v

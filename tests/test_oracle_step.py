@@ -1,0 +1,200 @@
+"""Pins for oracle/resnet.py: finite differences of the loss, an independent float64 autograd
+network as third opinion, SGD closed form, sub-ResNet semantics (Appendix B: mask = 1 is the
+full network, mask = 0 passes the residual stream through)."""
+import copy
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import resnet as OR
+from resist_inputs import get_config, make_batch, make_params, zeros_like_params
+
+
+def _tiny_models():
+    basic = get_config("cfg1")["model"]
+    strided = dict(basic, widths=[8, 16], blocks=[2, 2], in_h=8, in_w=8, num_classes=5)
+    bottle = dict(basic, block_kind=1, stem_kind=1, widths=[4, 8], blocks=[2, 2], in_h=20, in_w=20,
+                  num_classes=7)
+    return {"basic": basic, "strided": strided, "bottleneck": bottle}
+
+
+def _torch_loss(model, blocks, params, x, labels):
+    """The same network written with a float64 autograd library (library special case)."""
+    tab = OR.block_table(model)
+    B = len(tab)
+    tp = {b: {k: torch.tensor(np.asarray(v, np.float64), requires_grad=OR.is_trainable(k))
+              for k, v in p.items()} for b, p in params.items()}
+    eps = model["bn_eps"]
+
+    def cbn(a, p, conv, bn, stride, pad, relu):
+        y = F.conv2d(a, p[conv + "_w"], stride=stride, padding=pad)
+        y = F.batch_norm(y, None, None, p[bn + "_g"], p[bn + "_b"], True, 0.1, eps)
+        return F.relu(y) if relu else y
+
+    a = torch.tensor(np.asarray(x, np.float64))
+    if model["stem_kind"] == 0:
+        a = cbn(a, tp[-1], "conv", "bn", 1, 1, True)
+    else:
+        a = F.max_pool2d(cbn(a, tp[-1], "conv", "bn", 2, 3, True), 3, 2, 1)
+    for b in blocks:
+        t, p = tab[b], tp[b]
+        if model["block_kind"] == 0:
+            h = cbn(a, p, "conv1", "bn1", t["stride"], 1, True)
+            h = cbn(h, p, "conv2", "bn2", 1, 1, False)
+        else:
+            h = cbn(a, p, "conv1", "bn1", 1, 0, True)
+            h = cbn(h, p, "conv2", "bn2", t["stride"], 1, True)
+            h = cbn(h, p, "conv3", "bn3", 1, 0, False)
+        sc = cbn(a, p, "ds", "dsbn", t["stride"], 0, False) if t["has_ds"] else a
+        a = F.relu(h + sc)
+    z = F.linear(a.mean(dim=(2, 3)), tp[B]["fc_w"], tp[B]["fc_b"])
+    loss = F.cross_entropy(z, torch.tensor(np.asarray(labels), dtype=torch.long))
+    return loss, tp
+
+
+@pytest.mark.parametrize("name", ["basic", "strided", "bottleneck"])
+@pytest.mark.parametrize("drop", [False, True])
+def test_gradients_match_autograd_library(name, drop):
+    model = _tiny_models()[name]
+    B = sum(model["blocks"])
+    blocks = list(range(B))
+    if drop:                                   # a sub-ResNet: drop one non-first block
+        blocks.remove(1)
+    params = make_params(model, 3, perturb_bn=True)
+    x, y = make_batch(model, 4, 5)
+    loss, grads, _, _ = OR.forward_backward(model, blocks, params, x, y)
+    tl, tp = _torch_loss(model, blocks, params, x, y)
+    tl.backward()
+    assert math.isclose(loss, float(tl.detach()), rel_tol=1e-12)
+    for b in [-1] + blocks + [B]:
+        for k, g in grads[b].items():
+            np.testing.assert_allclose(g, tp[b][k].grad.numpy(), rtol=1e-8, atol=1e-11,
+                                       err_msg=f"block {b} {k}")
+    assert set(grads.keys()) == set([-1, B] + blocks)
+
+
+def test_finite_differences_every_parameter_cfg1():
+    """Central differences of the float64 loss w.r.t. all 9 978 parameters of the tiny config."""
+    cfg = get_config("cfg1")
+    model = cfg["model"]
+    params = {b: {k: v.astype(np.float64) for k, v in p.items()}
+              for b, p in make_params(model, 0, perturb_bn=True).items()}
+    x, y = make_batch(model, cfg["batch"], 0)
+    blocks = [0, 1]
+    loss, grads, _, _ = OR.forward_backward(model, blocks, params, x, y)
+    assert sum(g.size for gb in grads.values() for g in gb.values()) == 9978
+    h = 1e-5
+    worst = 0.0
+    for b, gb in grads.items():
+        for k, g in gb.items():
+            w = params[b][k]
+            flat = w.reshape(-1)
+            fd = np.empty(flat.size)
+            for i in range(flat.size):
+                old = flat[i]
+                flat[i] = old + h
+                lp = OR.forward_backward(model, blocks, params, x, y, backward=False)[0]
+                flat[i] = old - h
+                lm = OR.forward_backward(model, blocks, params, x, y, backward=False)[0]
+                flat[i] = old
+                fd[i] = (lp - lm) / (2 * h)
+            tol = 1e-7 + 1e-5 * np.abs(g.reshape(-1))
+            # a ReLU kink inside [w-h, w+h] breaks the difference quotient, not the gradient:
+            # such elements are re-measured with a 100x smaller step
+            for i in np.nonzero(np.abs(fd - g.reshape(-1)) > tol)[0]:
+                old = flat[i]
+                flat[i] = old + h / 100
+                lp = OR.forward_backward(model, blocks, params, x, y, backward=False)[0]
+                flat[i] = old - h / 100
+                lm = OR.forward_backward(model, blocks, params, x, y, backward=False)[0]
+                flat[i] = old
+                fd[i] = (lp - lm) / (2 * h / 100)
+            err = np.abs(fd - g.reshape(-1))
+            worst = max(worst, float((err / tol).max()))
+            assert (err <= tol).all(), f"block {b} {k}: max err {err.max():.3e}"
+    assert worst < 1.0
+
+
+@pytest.mark.parametrize("name", ["strided", "bottleneck"])
+def test_finite_differences_sampled(name):
+    model = _tiny_models()[name]
+    B = sum(model["blocks"])
+    blocks = [0, 2, 3]                        # block 1 dropped: a genuine sub-ResNet
+    params = {b: {k: v.astype(np.float64) for k, v in p.items()}
+              for b, p in make_params(model, 11, perturb_bn=True).items()}
+    x, y = make_batch(model, 3, 12)
+    loss, grads, _, dx = OR.forward_backward(model, blocks, params, x, y, need_input_grad=True)
+    rng = np.random.default_rng(0)
+    h = 1e-5
+    for b, gb in grads.items():
+        for k, g in gb.items():
+            flat = params[b][k].reshape(-1)
+            for i in rng.choice(flat.size, size=min(6, flat.size), replace=False):
+                old = flat[i]
+                flat[i] = old + h
+                lp = OR.forward_backward(model, blocks, params, x, y, backward=False)[0]
+                flat[i] = old - h
+                lm = OR.forward_backward(model, blocks, params, x, y, backward=False)[0]
+                flat[i] = old
+                fd = (lp - lm) / (2 * h)
+                assert abs(fd - g.reshape(-1)[i]) <= 1e-7 + 1e-5 * abs(fd), f"block {b} {k}[{i}]"
+    # input gradient (exercises the stem's data gradient and the max-pool routing)
+    xd = x.astype(np.float64)
+    for idx in [(0, 0, 3, 3), (2, 2, 7, 1), (1, 1, 0, 0)]:
+        e = np.zeros_like(xd)
+        e[idx] = h
+        fd = (OR.forward_backward(model, blocks, params, xd + e, y, backward=False)[0]
+              - OR.forward_backward(model, blocks, params, xd - e, y, backward=False)[0]) / (2 * h)
+        assert abs(fd - dx[idx]) <= 1e-7 + 1e-5 * abs(fd)
+
+
+def test_absent_block_is_identity_and_untouched():
+    """A block outside the list neither affects the loss nor receives a gradient/update."""
+    model = _tiny_models()["strided"]
+    params = make_params(model, 1)
+    x, y = make_batch(model, 4, 2)
+    mom = zeros_like_params(params)
+    loss_a, grads, new_p, _ = OR.local_step(model, [0, 2, 3], params, mom, x, y, 0.1, 0.9, 0.0)
+    params2 = copy.deepcopy(params)
+    params2[1]["conv1_w"] += 1.0
+    loss_b = OR.local_step(model, [0, 2, 3], params2, mom, x, y, 0.1, 0.9, 0.0)[0]
+    assert loss_a == loss_b
+    assert 1 not in grads and 1 not in new_p
+
+
+def test_sgd_closed_form_two_steps():
+    cfg = get_config("cfg1")
+    model = cfg["model"]
+    p0 = make_params(model, 0)
+    x, y = make_batch(model, 4, 0)
+    lr, mu, wd = 0.1, 0.9, 5e-4
+    v0 = zeros_like_params(p0)
+    _, g1, p1, v1 = OR.local_step(model, [0, 1], p0, v0, x, y, lr, mu, wd)
+    for b, gb in g1.items():
+        for k, g in gb.items():
+            w0 = p0[b][k].astype(np.float64)
+            np.testing.assert_allclose(p1[b][k], w0 - lr * (g + wd * w0), rtol=1e-14, atol=1e-16)
+            np.testing.assert_allclose(v1[b][k], g + wd * w0, rtol=1e-14, atol=1e-16)
+    _, g2, p2, v2 = OR.local_step(model, [0, 1], p1, v1, x, y, lr, mu, wd)
+    for b, gb in g2.items():
+        for k, g in gb.items():
+            v = mu * v1[b][k] + g + wd * p1[b][k]
+            np.testing.assert_allclose(v2[b][k], v, rtol=1e-14, atol=1e-16)
+            np.testing.assert_allclose(p2[b][k], p1[b][k] - lr * v, rtol=1e-14, atol=1e-16)
+    # running statistics move toward the batch statistics and are not touched by SGD
+    assert not np.allclose(p1[-1]["bn_rm"], p0[-1]["bn_rm"])
+    assert "bn_rm" not in g1[-1]
+
+
+def test_param_count_matches_tensors():
+    for name in ["cfg1", "cfg2", "cfg4"]:
+        model = get_config(name)["model"]
+        params = make_params(model, 0)
+        for b, p in params.items():
+            n_train = sum(v.size for k, v in p.items() if OR.is_trainable(k))
+            n_all = sum(v.size for v in p.values())
+            assert OR.param_count(model, b) == n_train
+            assert OR.param_count(model, b, trainable_only=False) == n_all

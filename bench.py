@@ -1,0 +1,146 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: images/s of one local SGD step of a sub-ResNet.
+
+A "step" is one resist_local_step (forward + backward + SGD update of every block the sub-ResNet
+keeps) on one synthetic batch already resident in HBM.  Default workload: the CIFAR-shaped
+sub-ResNet 0 of S=4 (batch 128, fp32), the configuration the metric is quoted on.
+Prints ONE JSON line with the throughput, the roofline of the dominant kernel (durations from HIP
+events recorded on the stream the kernels run on) and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # dense MFMA peaks of MI355X
+PEAK_HBM_GBS = 8000.0
+
+
+def _measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` from committed rocprofv3 --pmc runs, if recorded."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(kernel)
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", help="cfg1 | cfg2 | cfg3 | cfg5 (fp32 workloads)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-batch", type=int, default=32)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the S sub-ResNets are stepped sequentially on it "
+              "and no collective exists to scale over. Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2107_00961_amd as R
+    from paper_2107_00961_amd.harness import SubResNet, to_device_batch
+    from resist_inputs import get_config, make_batch, make_params
+
+    cfg = get_config(args.workload)
+    model, batch = cfg["model"], cfg["batch"]
+    subs, _ = R.partition(model, cfg["S"], cfg["min_depth"], cfg["part_seed"], 0)
+    blocks = subs[0]
+    params = make_params(model, 0)
+    sub = SubResNet(model, blocks, params, batch, keep_grads=False)
+    x, y = make_batch(model, batch, cfg["data_seed"])
+    xd, yd = to_device_batch(x, y)
+    lr, mu, wd = cfg["lr"] * 0.01, cfg["momentum"], cfg["weight_decay"]   # small lr: many steps on one batch stay finite
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        sub.step(xd, yd, lr, mu, wd, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        sub.step(xd, yd, lr, mu, wd, stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    loss = float(sub.loss.cpu()[0])
+
+    # per-kernel durations: the same steps again with event timing switched on
+    R.profile_enable(True)
+    psteps = max(1, min(args.steps, 10))
+    t1 = time.perf_counter()
+    for _ in range(psteps):
+        sub.step(xd, yd, lr, mu, wd, stream)
+    torch.cuda.synchronize()
+    ms_profiled = (time.perf_counter() - t1) / psteps * 1e3
+    stats = R.profile_read()
+    R.profile_enable(False)
+    stats.sort(key=lambda s: -s["ms"])
+    kernels = [dict(name=s["name"], launches_per_step=s["launches"] / psteps,
+                    ms_per_step=round(s["ms"] / psteps, 4),
+                    avg_us=round(s["ms"] / s["launches"] * 1e3, 2),
+                    tflops=round(s["flops"] / (s["ms"] * 1e-3) / 1e12, 2) if s["flops"] else None,
+                    gbs=round(s["bytes"] / (s["ms"] * 1e-3) / 1e9, 1) if s["bytes"] else None)
+               for s in stats]
+    dom = stats[0]
+    dtype = "bf16" if model.get("compute_dtype", 0) == 1 else "f32"
+    if dom["flops"] > 0:
+        ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+        roof = dict(bound="mfma", kernel=dom["name"], achieved=round(ach, 2), peak=PEAK_TFLOPS[dtype],
+                    unit="TFLOP/s", frac=round(ach / PEAK_TFLOPS[dtype], 4),
+                    avg_launch_us=round(dom["ms"] / dom["launches"] * 1e3, 2),
+                    traffic=_measured_traffic(dom["name"]))
+    else:
+        ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
+        roof = dict(bound="hbm", kernel=dom["name"], achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                    frac=round(ach / PEAK_HBM_GBS, 4), avg_launch_us=round(dom["ms"] / dom["launches"] * 1e3, 2),
+                    traffic=_measured_traffic(dom["name"]))
+    conv_flops = sum(s["flops"] for s in stats)
+    conv_ms = sum(s["ms"] for s in stats if s["flops"])
+    roof["all_conv_tflops"] = round(conv_flops / (conv_ms * 1e-3) / 1e12, 2) if conv_ms else None
+    roof["all_conv_frac"] = round(roof["all_conv_tflops"] / PEAK_TFLOPS[dtype], 4) if conv_ms else None
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import layers as OL
+        from oracle import resnet as OR
+        from resist_inputs import zeros_like_params
+        nb = min(args.cpu_sample_batch, batch)
+        xs, ys = make_batch(model, nb, cfg["data_seed"])
+        OL._conv_lib()                         # build/load outside the timed region
+        t2 = time.perf_counter()
+        OR.local_step(model, blocks, params, zeros_like_params(params), xs, ys, cfg["lr"], mu, wd)
+        tc = time.perf_counter() - t2
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cpu = dict(value=round(nb / tc, 3), unit="images/s", cores=cores, kind="oracle",
+                   sample=f"one full step of the same sub-ResNet on a batch of {nb} (of {batch}) images, {tc:.1f} s")
+
+    out = {
+        "metric": "images/sec per sub-ResNet local SGD step",
+        "value": round(batch / (ms_per_step * 1e-3), 1),
+        "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": f"{args.workload}: CIFAR-shaped sub-ResNet 0 of S={cfg['S']}" if args.workload != "cfg1"
+                   else "cfg1: tiny 2-block network",
+                   "batch": batch, "blocks": blocks, "block_kind": "basic" if model["block_kind"] == 0 else "bottleneck",
+                   "widths": model["widths"], "blocks_per_stage": model["blocks"], "classes": model["num_classes"]},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "ms_per_step_with_event_timing": round(ms_profiled, 4),
+        "final_loss": loss,
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,179 @@
+/*
+ * resist.h -- C ABI of the MI355X (gfx950) library for the data-parallel hot path of ResIST:
+ * the random layer-wise split of a global ResNet into S sub-ResNets, one local SGD iteration
+ * of one sub-ResNet, and the reassembly that averages blocks shared between sub-ResNets
+ * (the paper's Algorithm 1: subResNets(), the inner update W_s <- W_s - eta dL/dW_s, aggregate()).
+ *
+ * Conventions common to every call
+ *   - Return value: 0 (RESIST_OK) or a negative resist_status; resist_last_error() then holds a
+ *     message.  No exception or abort crosses this boundary; arguments are validated before any
+ *     kernel is launched.
+ *   - "device" pointers are HIP device memory owned by the caller (16-byte aligned); the library
+ *     allocates no device memory, keeps no state between calls, enqueues its kernels on the
+ *     caller's stream and returns without synchronising.  "host" pointers are ordinary memory.
+ *   - Same inputs give bit-identical outputs from run to run (no floating-point atomics).
+ *   - Blocks of the global network are numbered 0..B-1 in network order; -1 names the stem and
+ *     B the head (global pooling + fully connected layer).  Stem and head belong to every
+ *     sub-ResNet (Sec. 2.2: initial and final layers are shared; Appendix B: the last layer is
+ *     never dropped).
+ *
+ * Parameter buffers.  Every block (and the stem, and the head) owns ONE contiguous fp32 buffer:
+ *     [ trainable tensors ... | BN running statistics ... ]
+ *   trainable part, in order: conv1 W, bn1 gamma, bn1 beta, conv2 W, bn2 gamma, bn2 beta,
+ *   [conv3 W, bn3 gamma, bn3 beta,] [downsample W, its gamma, its beta]; stem: conv W, gamma,
+ *   beta; head: fc W [classes][C], fc bias.  Then running mean, running var of each BN in the
+ *   same order.  Each tensor starts at a multiple of 4 floats (zero padding after it if needed).
+ *   Convolution weights are stored [K][R][S][C] (output channel, filter row, filter column, input
+ *   channel; C fastest), i.e. element (k,c,r,s) of the logical [K,C,R,S] filter sits at
+ *   ((k*R + r)*S + s)*C + c.  resist_block_layout() reports every tensor's offset and shape.
+ *   Momentum and gradient buffers mirror the trainable part (the first n_trainable floats).
+ *   Activations inside the library are NHWC; the input batch is passed as logical [N,C,H,W].
+ */
+#ifndef RESIST_H
+#define RESIST_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RESIST_MAX_STAGES 4
+
+typedef enum {
+  RESIST_OK = 0,
+  RESIST_EINVAL = -1,     /* bad argument value (NULL, negative size, S < 1, unknown kind ...)   */
+  RESIST_ESHAPE = -2,     /* model description / block list inconsistent with what kernels need   */
+  RESIST_EWORKSPACE = -3, /* workspace or output capacity too small                               */
+  RESIST_EHIP = -4,       /* a HIP runtime call or kernel launch reported an error                */
+  RESIST_EUNSUPPORTED = -5
+} resist_status;
+
+/* The GLOBAL ResNet (Sec. 2.1: sections of blocks of equal channel width).  Plain data. */
+typedef struct {
+  int32_t block_kind;    /* 0 basic: conv3x3-BN-ReLU-conv3x3-BN, +shortcut, ReLU
+                            1 bottleneck: conv1x1-BN-ReLU-conv3x3-BN-ReLU-conv1x1(x4)-BN, +, ReLU */
+  int32_t stem_kind;     /* 0: conv3x3 stride 1 pad 1, BN, ReLU
+                            1: conv7x7 stride 2 pad 3, BN, ReLU, maxpool 3x3 stride 2 pad 1       */
+  int32_t in_c, in_h, in_w;
+  int32_t num_stages;                 /* 1..RESIST_MAX_STAGES                                    */
+  int32_t width[RESIST_MAX_STAGES];   /* channel width per stage (multiple of 16)                */
+  int32_t blocks[RESIST_MAX_STAGES];  /* residual blocks per stage (>= 1)                        */
+  int32_t num_classes;
+  int32_t compute_dtype; /* 0: fp32 MFMA.  1: bf16 MFMA operands, fp32 accumulate, fp32 masters  */
+  float bn_eps;
+  float bn_momentum;
+} resist_model_desc;
+/* The first block of stage i > 0 has stride 2 (on its 3x3 convolution); a first block whose input
+ * and output shapes differ gets a conv1x1(stride)-BN shortcut; all other shortcuts are identity. */
+
+typedef struct {
+  int32_t kind;     /* 0 conv weight, 1 BN gamma, 2 BN beta, 3 BN running mean, 4 BN running var,
+                       5 FC weight, 6 FC bias                                                    */
+  int32_t layer;    /* 0 conv1 (or the stem conv / the FC), 1 conv2, 2 conv3, 3 downsample        */
+  int64_t offset;   /* in floats from the start of the block buffer                              */
+  int64_t count;    /* number of floats (without padding)                                        */
+  int32_t dims[4];  /* conv: K,R,S,C;  vector: C,0,0,0;  FC weight: classes,C,0,0                */
+} resist_tensor_info;
+
+/* Number of residual blocks B of the global network.  host. */
+int resist_num_blocks(const resist_model_desc *desc, int32_t *num_blocks);
+
+/*
+ * Random layer-wise split (Sec. 2.2; Sec. 2.6 "Subnetwork Depth"): the indices of the partitionable
+ * blocks are permuted at random and dealt round-robin so that every sub-ResNet receives the same
+ * number D = max(ceil(P/S), min(min_depth, P)) of them; sub s takes permuted positions
+ * s, s+S, s+2S, ... (mod P), skipping forward over blocks it already holds, so blocks are shared
+ * when S does not divide P or the depth floor asks for it.  Non-partitionable blocks go to every
+ * sub-ResNet.  Random source: splitmix64 with state seed ^ (round * 0x9E3779B97F4A7C15),
+ * Fisher-Yates from the top index down with j = next() mod (i+1).  Pure function; host only.
+ *   partitionable  host [B] flags, or NULL = every block except the first of each stage
+ *   sub_offsets    host [S+1] out: sub s owns sub_blocks[sub_offsets[s] .. sub_offsets[s+1])
+ *   sub_blocks     host [cap] out: global block indices, ascending within a sub-ResNet
+ *   owner_count    host [B] out: number of sub-ResNets holding each block (>= 1)
+ * RESIST_EWORKSPACE if cap is too small (nothing is written past cap).
+ */
+int resist_partition(const resist_model_desc *desc, const uint8_t *partitionable, int32_t S,
+                     int32_t min_depth, uint64_t seed, uint64_t round, int32_t *sub_offsets,
+                     int32_t *sub_blocks, int32_t cap, int32_t *owner_count);
+
+/* Size in floats of the parameter buffer of `block` (-1 stem, 0..B-1, B head): total, and the
+ * trainable prefix that momentum / gradient buffers mirror.  host. */
+int resist_block_param_count(const resist_model_desc *desc, int32_t block, int64_t *n_total,
+                             int64_t *n_trainable);
+
+/* Tensors inside the parameter buffer of `block`, in buffer order.  host.  Writes at most cap
+ * entries and always the true number to *n_tensors. */
+int resist_block_layout(const resist_model_desc *desc, int32_t block, resist_tensor_info *out,
+                        int32_t cap, int32_t *n_tensors);
+
+/* Bytes of device workspace resist_local_step needs for this sub-ResNet and batch size.  host. */
+int resist_workspace_bytes(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks,
+                           int32_t batch, int64_t *bytes);
+
+/*
+ * One local SGD iteration of one sub-ResNet on one batch (Algorithm 1, inner loop): forward,
+ * backward (data and weight gradients), and the update  g += wd*w; v = mu*v + g; w -= lr*v  of
+ * every trainable parameter the sub-ResNet holds.  Blocks not in `blocks` are not computed: the
+ * residual stream passes through (Appendix B, mask = 0).  BN uses batch statistics (biased
+ * variance) and updates the running statistics (unbiased variance, bn_momentum).
+ *   blocks          host [nblocks] ascending global block indices; must contain the first block
+ *                   of every stage
+ *   block_params    host array [nblocks+2] of device fp32 buffers: stem, blocks..., head; updated
+ *                   in place
+ *   block_momentum  host array [nblocks+2] of device fp32 buffers (n_trainable floats each);
+ *                   updated in place
+ *   block_grads     NULL, or host array [nblocks+2] of device fp32 buffers (n_trainable floats
+ *                   each) that receive dL/dW (before weight decay)
+ *   x               device [batch,in_c,in_h,in_w] fp32;  labels: device [batch] int32 in
+ *                   [0,num_classes)
+ *   workspace       device, at least resist_workspace_bytes(); contents undefined afterwards
+ *   loss_out        device, 1 float: mean cross-entropy of the batch (before the update)
+ *   hip_stream      hipStream_t (NULL = default stream)
+ */
+int resist_local_step(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks,
+                      void *const *block_params, void *const *block_momentum,
+                      void *const *block_grads, const float *x, const int32_t *labels,
+                      int32_t batch, float lr, float momentum, float weight_decay, void *workspace,
+                      int64_t workspace_bytes, float *loss_out, void *hip_stream);
+
+/*
+ * Reassembly (Sec. 2.3; Appendix B: W = sum_v W_v M_v / sum_v M_v, last layer a = sum_v a_v / S):
+ * every float of every block buffer of the global model (running statistics included) becomes the
+ * mean over the sub-ResNets that hold the block -- fp32 sum in ascending sub-ResNet order, then one
+ * division; a block held by one sub-ResNet is copied bit for bit; a block held by none is left
+ * untouched.  Stem and head are averaged over all S.
+ *   sub_offsets, sub_blocks   host, as written by resist_partition
+ *   sub_block_params          host [S] arrays; sub_block_params[s] is a host array
+ *                             [n_s + 2] of device buffers: stem, the blocks of s in order, head
+ *   global_block_params       host array [B+2] of device buffers: stem, blocks 0..B-1, head
+ */
+int resist_aggregate(const resist_model_desc *desc, int32_t S, const int32_t *sub_offsets,
+                     const int32_t *sub_blocks, void *const *const *sub_block_params,
+                     void *const *global_block_params, void *hip_stream);
+
+/*
+ * Optional per-kernel timing, for benchmarks (not a step of the paper's method).  While enabled,
+ * every kernel launch is bracketed by two HIP events on the stream it is launched on.
+ * resist_profile_enable(on) clears the statistics and switches timing on or off (off by default);
+ * resist_profile_read waits for the recorded events and returns, per kernel, the number of launches,
+ * the summed duration, and the summed algorithmic FLOPs and bytes of those launches.  Writes at
+ * most cap entries and always the true number to *n.  host; not thread-safe against running steps.
+ */
+typedef struct {
+  char name[64];
+  int64_t launches;
+  double ms;      /* summed launch durations (event to event)  */
+  double flops;   /* summed algorithmic floating-point operations (2 per multiply-add) */
+  double bytes;   /* summed algorithmic bytes read + written   */
+} resist_kernel_stat;
+int resist_profile_enable(int on);
+int resist_profile_read(resist_kernel_stat *out, int32_t cap, int32_t *n);
+
+/* Message for the last non-zero status returned on this thread (static storage). */
+const char *resist_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RESIST_H */

@@ -1,0 +1,16 @@
+"""MI355X (gfx950) library for the data-parallel hot path of ResIST: thin Python binding.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in include/resist.h;
+this package only marshals arguments (ctypes) and packs logical tensors into the library's
+buffer layout.  There is no CPU fallback: importing works without a GPU (host-only calls such
+as `partition` run anywhere), device calls need the built library and a gfx950 device.
+"""
+from .binding import (ResistError, aggregate, block_layout, block_param_count, conv2d_dgrad,
+                      conv2d_forward, conv2d_wgrad, lib, local_step, model_desc, num_blocks,
+                      pack_block, partition, profile_enable, profile_read, unpack_block,
+                      workspace_bytes)
+
+__all__ = ["ResistError", "aggregate", "block_layout", "block_param_count", "conv2d_dgrad",
+           "conv2d_forward", "conv2d_wgrad", "lib", "local_step", "model_desc", "num_blocks",
+           "pack_block", "partition", "profile_enable", "profile_read", "unpack_block",
+           "workspace_bytes"]

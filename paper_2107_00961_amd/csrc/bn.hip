@@ -1,0 +1,324 @@
+// Training-mode batch normalisation on NHWC activations viewed as a matrix [M = N*H*W][C], fused
+// with ReLU and the residual add of a block (forward), and with the ReLU mask (backward).
+//   forward   mean_c, var_c (biased) over the M rows; a = [relu](gamma*(y-mean)*invstd + beta [+ res])
+//   backward  gm = g*[mask>0]; dbeta = sum gm; dgamma = sum gm*xhat;
+//             dy = gamma*invstd*(gm - dbeta/M - xhat*dgamma/M)
+// These kernels are bound by HBM bandwidth.  Per-channel sums are accumulated in float64 (the
+// vector fp64 rate is far above what the memory stream needs), in a fixed order, so results are
+// bit-stable from run to run and free of the cancellation a float32 sum-of-squares would suffer.
+#include "internal.h"
+
+namespace resist {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxParts = 512;  // row-slices per channel tile
+
+struct ColMap {
+  int tpr;       // threads per row (each owns 4 consecutive channels)
+  int rpp;       // rows per pass of one workgroup
+  int ctiles;    // channel tiles of tpr*4 channels
+};
+inline ColMap col_map(int C) {
+  ColMap m;
+  const int c4 = C / 4;
+  m.tpr = c4 >= kThreads ? kThreads : c4;   // C is a multiple of 16, so c4 >= 4
+  // tpr must divide 256: round down to a power of two that divides c4
+  int t = 1;
+  while (t * 2 <= m.tpr && (c4 % (t * 2)) == 0 && t * 2 <= kThreads) t *= 2;
+  m.tpr = t;
+  m.rpp = kThreads / m.tpr;
+  m.ctiles = c4 / m.tpr;
+  return m;
+}
+inline int num_parts(int64_t M, const ColMap &m) {
+  // aim at ~2048 workgroups in total, at least 8 passes of rows each
+  int64_t want = 2048 / m.ctiles;
+  if (want < 1) want = 1;
+  int64_t maxp = (M + (int64_t)m.rpp * 8 - 1) / ((int64_t)m.rpp * 8);
+  int64_t p = want < maxp ? want : maxp;
+  if (p < 1) p = 1;
+  if (p > kMaxParts) p = kMaxParts;
+  return (int)p;
+}
+
+// ---- forward statistics --------------------------------------------------------------------------
+// grid (parts, ctiles); scratch layout [2][parts][C] doubles: sum, sum of squares
+__global__ __launch_bounds__(kThreads) void bn_stats_partial_kernel(const float *__restrict__ y, long long M, int C,
+                                                                    int tpr, int rpp, double *__restrict__ scratch) {
+  __shared__ double red[2][kThreads][4];
+  const int tid = threadIdx.x;
+  const int tc = tid % tpr, tr = tid / tpr;
+  const int c = (blockIdx.y * tpr + tc) * 4;
+  const int parts = gridDim.x;
+  const long long rows_per_part = (M + parts - 1) / parts;
+  const long long r0 = blockIdx.x * rows_per_part;
+  long long r1 = r0 + rows_per_part;
+  if (r1 > M) r1 = M;
+  double s[4] = {0, 0, 0, 0}, q[4] = {0, 0, 0, 0};
+  for (long long r = r0 + tr; r < r1; r += rpp) {
+    const f32x4 v = *reinterpret_cast<const f32x4 *>(y + r * C + c);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const double d = (double)v[e];
+      s[e] += d;
+      q[e] = fma(d, d, q[e]);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { red[0][tid][e] = s[e]; red[1][tid][e] = q[e]; }
+  __syncthreads();
+  if (tr == 0) {
+    for (int j = 1; j < rpp; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { s[e] += red[0][j * tpr + tc][e]; q[e] += red[1][j * tpr + tc][e]; }
+    double *ps = scratch + (size_t)blockIdx.x * C + c;
+    double *pq = scratch + (size_t)(parts + blockIdx.x) * C + c;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { ps[e] = s[e]; pq[e] = q[e]; }
+  }
+}
+
+// one thread per channel; parts <= 512 values each, summed in index order
+__global__ __launch_bounds__(kThreads) void bn_stats_final_kernel(const double *__restrict__ scratch, int parts, int C,
+                                                                  long long M, float eps, float momentum,
+                                                                  float *__restrict__ mean, float *__restrict__ invstd,
+                                                                  float *__restrict__ rmean, float *__restrict__ rvar) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  double s = 0, q = 0;
+  for (int p = 0; p < parts; ++p) {
+    s += scratch[(size_t)p * C + c];
+    q += scratch[(size_t)(parts + p) * C + c];
+  }
+  const double m = s / (double)M;
+  double var = q / (double)M - m * m;
+  if (var < 0) var = 0;
+  mean[c] = (float)m;
+  invstd[c] = (float)(1.0 / sqrt(var + (double)eps));
+  if (rmean) {
+    const double unb = M > 1 ? var * ((double)M / (double)(M - 1)) : var;
+    rmean[c] = (float)((1.0 - momentum) * (double)rmean[c] + (double)momentum * m);
+    rvar[c] = (float)((1.0 - momentum) * (double)rvar[c] + (double)momentum * unb);
+  }
+}
+
+// ---- forward apply -------------------------------------------------------------------------------
+struct ApplyArgs {
+  const float *y; const float *gamma; const float *beta; const float *mean; const float *invstd;
+  const float *res;                                       // raw residual or second pre-BN tensor
+  const float *rgamma; const float *rbeta; const float *rmean; const float *rinvstd;  // BN of res
+  float *a;
+  long long M; int C; int tpr, rpp; int relu;
+};
+
+__global__ __launch_bounds__(kThreads) void bn_apply_kernel(ApplyArgs p) {
+  const int tid = threadIdx.x;
+  const int tc = tid % p.tpr, tr = tid / p.tpr;
+  const int c = (blockIdx.y * p.tpr + tc) * 4;
+  float sc[4], sh[4], rsc[4], rsh[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    sc[e] = p.gamma[c + e] * p.invstd[c + e];
+    sh[e] = p.beta[c + e] - p.mean[c + e] * sc[e];
+    if (p.rgamma) {
+      rsc[e] = p.rgamma[c + e] * p.rinvstd[c + e];
+      rsh[e] = p.rbeta[c + e] - p.rmean[c + e] * rsc[e];
+    } else {
+      rsc[e] = 1.f; rsh[e] = 0.f;
+    }
+  }
+  const long long stride = (long long)gridDim.x * p.rpp;
+  for (long long r = (long long)blockIdx.x * p.rpp + tr; r < p.M; r += stride) {
+    const size_t off = (size_t)r * p.C + c;
+    const f32x4 v = *reinterpret_cast<const f32x4 *>(p.y + off);
+    f32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = fmaf(v[e], sc[e], sh[e]);
+    if (p.res) {
+      const f32x4 rv = *reinterpret_cast<const f32x4 *>(p.res + off);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] += fmaf(rv[e], rsc[e], rsh[e]);
+    }
+    if (p.relu) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = o[e] > 0.f ? o[e] : 0.f;
+    }
+    *reinterpret_cast<f32x4 *>(p.a + off) = o;
+  }
+}
+
+// ---- backward ------------------------------------------------------------------------------------
+// pass 1: per-channel sums of gm and gm*xhat; scratch [2][parts][C]
+__global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const float *__restrict__ g, const float *__restrict__ mask,
+                                                                  const float *__restrict__ y, long long M, int C, int tpr,
+                                                                  int rpp, const float *__restrict__ mean,
+                                                                  const float *__restrict__ invstd,
+                                                                  double *__restrict__ scratch) {
+  __shared__ double red[2][kThreads][4];
+  const int tid = threadIdx.x;
+  const int tc = tid % tpr, tr = tid / tpr;
+  const int c = (blockIdx.y * tpr + tc) * 4;
+  const int parts = gridDim.x;
+  const long long rows_per_part = (M + parts - 1) / parts;
+  const long long r0 = blockIdx.x * rows_per_part;
+  long long r1 = r0 + rows_per_part;
+  if (r1 > M) r1 = M;
+  float mu[4], is[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { mu[e] = mean[c + e]; is[e] = invstd[c + e]; }
+  double sb[4] = {0, 0, 0, 0}, sg[4] = {0, 0, 0, 0};
+  for (long long r = r0 + tr; r < r1; r += rpp) {
+    const size_t off = (size_t)r * C + c;
+    f32x4 gv = *reinterpret_cast<const f32x4 *>(g + off);
+    const f32x4 yv = *reinterpret_cast<const f32x4 *>(y + off);
+    if (mask) {
+      const f32x4 mv = *reinterpret_cast<const f32x4 *>(mask + off);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) gv[e] = mv[e] > 0.f ? gv[e] : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float xh = (yv[e] - mu[e]) * is[e];
+      sb[e] += (double)gv[e];
+      sg[e] = fma((double)gv[e], (double)xh, sg[e]);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { red[0][tid][e] = sb[e]; red[1][tid][e] = sg[e]; }
+  __syncthreads();
+  if (tr == 0) {
+    for (int j = 1; j < rpp; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { sb[e] += red[0][j * tpr + tc][e]; sg[e] += red[1][j * tpr + tc][e]; }
+    double *pb = scratch + (size_t)blockIdx.x * C + c;
+    double *pg = scratch + (size_t)(parts + blockIdx.x) * C + c;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { pb[e] = sb[e]; pg[e] = sg[e]; }
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const double *__restrict__ scratch, int parts, int C,
+                                                                float *__restrict__ dgamma, float *__restrict__ dbeta) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  double b = 0, g = 0;
+  for (int p = 0; p < parts; ++p) {
+    b += scratch[(size_t)p * C + c];
+    g += scratch[(size_t)(parts + p) * C + c];
+  }
+  dbeta[c] = (float)b;
+  dgamma[c] = (float)g;
+}
+
+struct BwdApplyArgs {
+  const float *g; const float *mask; const float *y;
+  const float *gamma; const float *mean; const float *invstd; const float *dgamma; const float *dbeta;
+  float *dy; float *gm_out;
+  long long M; int C; int tpr, rpp;
+};
+
+__global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BwdApplyArgs p) {
+  const int tid = threadIdx.x;
+  const int tc = tid % p.tpr, tr = tid / p.tpr;
+  const int c = (blockIdx.y * p.tpr + tc) * 4;
+  const float invM = 1.0f / (float)p.M;
+  float mu[4], is[4], k0[4], k1[4], k2[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    mu[e] = p.mean[c + e]; is[e] = p.invstd[c + e];
+    k0[e] = p.gamma[c + e] * is[e];          // scale
+    k1[e] = p.dbeta[c + e] * invM;           // mean of gm
+    k2[e] = p.dgamma[c + e] * invM;          // mean of gm*xhat
+  }
+  const long long stride = (long long)gridDim.x * p.rpp;
+  for (long long r = (long long)blockIdx.x * p.rpp + tr; r < p.M; r += stride) {
+    const size_t off = (size_t)r * p.C + c;
+    f32x4 gv = *reinterpret_cast<const f32x4 *>(p.g + off);
+    const f32x4 yv = *reinterpret_cast<const f32x4 *>(p.y + off);
+    if (p.mask) {
+      const f32x4 mv = *reinterpret_cast<const f32x4 *>(p.mask + off);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) gv[e] = mv[e] > 0.f ? gv[e] : 0.f;
+    }
+    f32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float xh = (yv[e] - mu[e]) * is[e];
+      o[e] = k0[e] * (gv[e] - k1[e] - xh * k2[e]);
+    }
+    *reinterpret_cast<f32x4 *>(p.dy + off) = o;
+    if (p.gm_out) *reinterpret_cast<f32x4 *>(p.gm_out + off) = gv;
+  }
+}
+
+int check_bn(int64_t M, int C) {
+  if (M < 1 || C < 16 || (C % 16)) return set_error(RESIST_ESHAPE, "BN on [%lld][%d]: C must be a positive multiple of 16", (long long)M, C);
+  return RESIST_OK;
+}
+
+unsigned apply_grid_x(int64_t M, const ColMap &m) {
+  int64_t want = 4096 / m.ctiles;
+  if (want < 1) want = 1;
+  const int64_t maxb = (M + m.rpp - 1) / m.rpp;
+  return (unsigned)(want < maxb ? want : maxb);
+}
+
+}  // namespace
+
+int64_t bn_scratch_doubles(int C) { return (int64_t)2 * kMaxParts * C; }
+
+int bn_stats_f32(const float *y, int64_t M, int C, const BnBufs &b, float eps, float momentum,
+                 double *scratch, hipStream_t st) {
+  RESIST_TRY(check_bn(M, C));
+  const ColMap m = col_map(C);
+  const int parts = num_parts(M, m);
+  prof::Scope ps("bn_stats", 0, 4.0 * M * C, st);
+  hipLaunchKernelGGL(bn_stats_partial_kernel, dim3(parts, m.ctiles), dim3(kThreads), 0, st, y, (long long)M, C, m.tpr, m.rpp, scratch);
+  RESIST_CHECK_LAUNCH("bn_stats_partial");
+  hipLaunchKernelGGL(bn_stats_final_kernel, dim3((C + kThreads - 1) / kThreads), dim3(kThreads), 0, st, scratch, parts, C,
+                     (long long)M, eps, momentum, b.mean, b.invstd, b.rmean, b.rvar);
+  RESIST_CHECK_LAUNCH("bn_stats_final");
+  return RESIST_OK;
+}
+
+int bn_apply_f32(const float *y, int64_t M, int C, const BnBufs &b, const float *res, const BnBufs *res_bn,
+                 bool relu, float *a, hipStream_t st) {
+  RESIST_TRY(check_bn(M, C));
+  const ColMap m = col_map(C);
+  ApplyArgs p{};
+  p.y = y; p.gamma = b.gamma; p.beta = b.beta; p.mean = b.mean; p.invstd = b.invstd;
+  p.res = res;
+  if (res_bn) { p.rgamma = res_bn->gamma; p.rbeta = res_bn->beta; p.rmean = res_bn->mean; p.rinvstd = res_bn->invstd; }
+  p.a = a; p.M = M; p.C = C; p.tpr = m.tpr; p.rpp = m.rpp; p.relu = relu ? 1 : 0;
+  prof::Scope ps("bn_apply", 0, 4.0 * M * C * (res ? 3 : 2), st);
+  hipLaunchKernelGGL(bn_apply_kernel, dim3(apply_grid_x(M, m), m.ctiles), dim3(kThreads), 0, st, p);
+  RESIST_CHECK_LAUNCH("bn_apply");
+  return RESIST_OK;
+}
+
+int bn_backward_f32(const float *g, const float *mask, const float *y, int64_t M, int C, const BnBufs &b,
+                    float *dy, float *gm_out, double *scratch, hipStream_t st) {
+  RESIST_TRY(check_bn(M, C));
+  const ColMap m = col_map(C);
+  const int parts = num_parts(M, m);
+  prof::Scope ps("bn_backward", 0, 4.0 * M * C * ((mask ? 3 : 2) + (mask ? 4 : 3) + (gm_out ? 1 : 0)), st);
+  hipLaunchKernelGGL(bn_bwd_partial_kernel, dim3(parts, m.ctiles), dim3(kThreads), 0, st, g, mask, y, (long long)M, C, m.tpr,
+                     m.rpp, b.mean, b.invstd, scratch);
+  RESIST_CHECK_LAUNCH("bn_bwd_partial");
+  hipLaunchKernelGGL(bn_bwd_final_kernel, dim3((C + kThreads - 1) / kThreads), dim3(kThreads), 0, st, scratch, parts, C,
+                     b.dgamma, b.dbeta);
+  RESIST_CHECK_LAUNCH("bn_bwd_final");
+  BwdApplyArgs p{};
+  p.g = g; p.mask = mask; p.y = y; p.gamma = b.gamma; p.mean = b.mean; p.invstd = b.invstd;
+  p.dgamma = b.dgamma; p.dbeta = b.dbeta; p.dy = dy; p.gm_out = gm_out;
+  p.M = M; p.C = C; p.tpr = m.tpr; p.rpp = m.rpp;
+  hipLaunchKernelGGL(bn_bwd_apply_kernel, dim3(apply_grid_x(M, m), m.ctiles), dim3(kThreads), 0, st, p);
+  RESIST_CHECK_LAUNCH("bn_bwd_apply");
+  return RESIST_OK;
+}
+
+}  // namespace resist

@@ -1,0 +1,508 @@
+// fp32 implicit-GEMM convolutions on the CDNA4 matrix cores (v_mfma_f32_32x32x2_f32).
+//
+// The convolutions of a residual block (the paper's local update, Algorithm 1 inner loop, is an
+// ordinary SGD step of the blocks a worker keeps) are computed as GEMMs whose A operand is
+// gathered on the fly from the NHWC activation tensor:
+//   forward  Y[m=(n,p,q)][k]  = sum_{r,s,c} X[n, p*st+r-pad, q*st+s-pad, c] * W[k][r][s][c]
+//   dgrad    dX[m=(n,h,w)][c] = sum_{r,s,k} dY[n, (h+pad-r)/st, (w+pad-s)/st, k] * WT[c][r][s][k]
+//            (terms with a non-integer or out-of-range source pixel vanish; for stride 2 the output
+//             pixels are processed one parity class at a time so that no such term is ever issued)
+//   wgrad    dW[k][r][s][c]   = sum_{m=(n,p,q)} dY[m][k] * X[n, p*st+r-pad, q*st+s-pad, c]
+// Tiles are staged through LDS (double buffered, one barrier per K-chunk); every wave owns a
+// grid of 32x32 accumulator tiles held in registers.
+#include "internal.h"
+
+namespace resist {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kBK = 32;        // K-chunk (floats) staged per step
+constexpr int kLDK = kBK + 4;  // LDS row pitch for K-contiguous tiles (conflict-free b128 reads)
+
+struct IgemmArgs {
+  const float *in;      // [N][IH][IW][IC]
+  const float *wt;      // [OC][R][S][IC]
+  float *out;           // [N][OH][OW][OC]
+  const float *addend;  // optional, indexed like out
+  int N, IH, IW, IC;
+  int OH, OW, OC;
+  int R, S, stride, pad;
+  int cls;              // 1, or 2 when output pixels are split into 2x2 parity classes
+  int OHc, OWc;         // OH/cls, OW/cls
+  int Mrows;            // N*OHc*OWc: GEMM rows per class
+  int tiles_m, tiles_n;
+};
+
+// A-gather modes
+constexpr int kFwd = 0;  // source pixel = out*stride + tap - pad
+constexpr int kBwd = 1;  // source pixel = (out + pad - tap) / stride
+
+template <int BM, int BN, int WGM, int WGN, int MODE>
+__global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
+  constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 MFMA tiles per wave
+  constexpr int PA = BM / 32, PB = BN / 32;      // load passes (32 rows per pass)
+  static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1, "4 waves");
+  __shared__ float As[2][BM][kLDK];
+  __shared__ float Bs[2][BN][kLDK];
+  __shared__ int row_off[BM];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  // tile coordinates: N-tiles fastest so that tiles sharing the same input rows run together
+  int bid = blockIdx.x;
+  const int tn = bid % a.tiles_n;
+  bid /= a.tiles_n;
+  const int tm = bid % a.tiles_m;
+  const int cidx = bid / a.tiles_m;  // parity class
+  const int ph = cidx / a.cls, pw = cidx % a.cls;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  // which filter taps contribute to this class (all of them unless MODE==kBwd with stride 2)
+  unsigned tapmask = 0;
+  int ntaps = 0;
+  for (int r = 0; r < a.R; ++r)
+    for (int s = 0; s < a.S; ++s) {
+      bool ok = true;
+      if (MODE == kBwd) ok = ((ph + a.pad - r) % a.stride == 0) && ((pw + a.pad - s) % a.stride == 0);
+      if (ok) { tapmask |= 1u << (r * a.S + s); ++ntaps; }
+    }
+
+  // per-thread source rows for the A gather
+  const int lrow = tid >> 3, kvec = (tid & 7) * 4;
+  int nbase[PA], hb[PA], wb[PA];
+#pragma unroll
+  for (int i = 0; i < PA; ++i) {
+    const int m = m0 + i * 32 + lrow;
+    if (m < a.Mrows) {
+      const int n = m / (a.OHc * a.OWc);
+      const int rem = m - n * (a.OHc * a.OWc);
+      const int oh = (rem / a.OWc) * a.cls + ph, ow = (rem % a.OWc) * a.cls + pw;
+      nbase[i] = n * a.IH * a.IW;
+      hb[i] = MODE == kFwd ? oh * a.stride - a.pad : oh + a.pad;
+      wb[i] = MODE == kFwd ? ow * a.stride - a.pad : ow + a.pad;
+    } else {
+      nbase[i] = 0;
+      hb[i] = MODE == kFwd ? -(1 << 28) : -(1 << 28);
+      wb[i] = hb[i];
+    }
+  }
+  for (int r = tid; r < BM; r += kThreads) {
+    const int m = m0 + r;
+    int off = -1;
+    if (m < a.Mrows) {
+      const int n = m / (a.OHc * a.OWc);
+      const int rem = m - n * (a.OHc * a.OWc);
+      const int oh = (rem / a.OWc) * a.cls + ph, ow = (rem % a.OWc) * a.cls + pw;
+      off = (n * a.OH + oh) * a.OW + ow;
+    }
+    row_off[r] = off;
+  }
+
+  const int cchunks = (a.IC + kBK - 1) / kBK;
+  const int nchunks = ntaps * cchunks;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  f32x4 ra[PA], rb[PB];
+  int tap = -1, c0 = a.IC;  // iteration state; advance() moves to the first valid (tap, c0)
+  auto advance = [&]() {
+    c0 += kBK;
+    if (c0 >= a.IC) {
+      c0 = 0;
+      do { ++tap; } while (tap < 32 && !((tapmask >> tap) & 1u));
+    }
+  };
+  auto load_global = [&]() {
+    const int r = tap / a.S, s = tap - r * a.S;
+    const bool kok = (c0 + kvec) < a.IC;
+#pragma unroll
+    for (int i = 0; i < PA; ++i) {
+      int ih, iw;
+      bool ok;
+      if (MODE == kFwd) {
+        ih = hb[i] + r; iw = wb[i] + s;
+        ok = ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
+      } else {
+        const int th = hb[i] - r, tw = wb[i] - s;
+        ih = th / a.stride; iw = tw / a.stride;   // exact by construction of the tap mask
+        ok = th >= 0 && tw >= 0 && ih < a.IH && iw < a.IW;
+      }
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (ok && kok)
+        v = *reinterpret_cast<const f32x4 *>(a.in + (size_t)(nbase[i] + ih * a.IW + iw) * a.IC + c0 + kvec);
+      ra[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+      const int oc = n0 + i * 32 + lrow;
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (oc < a.OC && kok)
+        v = *reinterpret_cast<const f32x4 *>(a.wt + ((size_t)(oc * a.R + r) * a.S + s) * a.IC + c0 + kvec);
+      rb[i] = v;
+    }
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < PA; ++i) *reinterpret_cast<f32x4 *>(&As[buf][i * 32 + lrow][kvec]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < PB; ++i) *reinterpret_cast<f32x4 *>(&Bs[buf][i * 32 + lrow][kvec]) = rb[i];
+  };
+
+  if (nchunks > 0) {
+    advance();
+    load_global();
+    store_lds(0);
+  }
+  __syncthreads();
+
+  const int lr = lane & 31, lk = (lane >> 5) * 4;
+  for (int it = 0; it < nchunks; ++it) {
+    const int buf = it & 1;
+    if (it + 1 < nchunks) {
+      advance();
+      load_global();
+    }
+#pragma unroll
+    for (int ks = 0; ks < kBK / 8; ++ks) {
+      f32x4 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        fa[i] = *reinterpret_cast<const f32x4 *>(&As[buf][wm * WTM + i * 32 + lr][ks * 8 + lk]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        fb[j] = *reinterpret_cast<const f32x4 *>(&Bs[buf][wn * WTN + j * 32 + lr][ks * 8 + lk]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][e], fb[j][e], acc[i][j], 0, 0, 0);
+    }
+    if (it + 1 < nchunks) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue: lane holds column (lane%32), rows 8*(e/4) + 4*(lane/32) + e%4 of each 32x32 tile
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + wn * WTN + j * 32 + lr;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = wm * WTM + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        const int ro = row_off[row];
+        if (ro >= 0 && col < a.OC) {
+          const size_t off = (size_t)ro * a.OC + col;
+          float v = acc[i][j][e];
+          if (a.addend) v += a.addend[off];
+          a.out[off] = v;
+        }
+      }
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN, int MODE>
+int launch_igemm(IgemmArgs a, hipStream_t st) {
+  a.tiles_m = (a.Mrows + BM - 1) / BM;
+  a.tiles_n = (a.OC + BN - 1) / BN;
+  const long long grid = (long long)a.tiles_m * a.tiles_n * a.cls * a.cls;
+  if (grid <= 0 || grid > 0x7fffffffLL) return set_error(RESIST_ESHAPE, "igemm grid %lld", grid);
+  {
+    static const std::string label = std::string(MODE == kFwd ? "igemm_f32_fwd_" : "igemm_f32_bwd_") + std::to_string(BM) + "x" + std::to_string(BN);
+    // algorithmic work of the convolution this launch computes (forward or data gradient)
+    const double flops = 2.0 * a.N * (MODE == kFwd ? (double)a.OH * a.OW : (double)a.IH * a.IW) * a.OC * a.IC * a.R * a.S;
+    const double bytes = 4.0 * ((double)a.N * a.IH * a.IW * a.IC + (double)a.N * a.OH * a.OW * a.OC * (a.addend ? 2 : 1) + (double)a.OC * a.R * a.S * a.IC);
+    prof::Scope ps(label.c_str(), flops, bytes, st);
+    hipLaunchKernelGGL((igemm_f32_kernel<BM, BN, WGM, WGN, MODE>), dim3((unsigned)grid), dim3(kThreads), 0, st, a);
+  }
+  RESIST_CHECK_LAUNCH("igemm_f32");
+  return RESIST_OK;
+}
+
+template <int MODE>
+int dispatch_igemm(const IgemmArgs &a, hipStream_t st) {
+  // pick the largest tile that still yields enough workgroups to cover the 256 compute units
+  const long long classes = (long long)a.cls * a.cls;
+  auto tiles = [&](int bm, int bn) {
+    return (long long)((a.Mrows + bm - 1) / bm) * ((a.OC + bn - 1) / bn) * classes;
+  };
+  if (a.OC > 64 && tiles(128, 128) >= 512) return launch_igemm<128, 128, 2, 2, MODE>(a, st);
+  if (tiles(128, 64) >= 512) return launch_igemm<128, 64, 2, 2, MODE>(a, st);
+  return launch_igemm<64, 64, 2, 2, MODE>(a, st);
+}
+
+int check_geom(const ConvGeom &g) {
+  if (g.N < 1 || g.H < 1 || g.W < 1 || g.C < 4 || g.K < 4 || (g.C & 3) || (g.K & 3))
+    return set_error(RESIST_ESHAPE, "conv shape N%d H%d W%d C%d K%d (C, K must be multiples of 4)", g.N, g.H, g.W, g.C, g.K);
+  if (g.R != g.S || (g.R != 1 && g.R != 3 && g.R != 5 && g.R != 7) || g.R * g.S > 32)
+    return set_error(RESIST_ESHAPE, "filter %dx%d unsupported", g.R, g.S);
+  if (g.stride < 1 || g.stride > 2 || g.pad < 0 || g.pad >= g.R)
+    return set_error(RESIST_ESHAPE, "stride %d pad %d unsupported", g.stride, g.pad);
+  if (g.P < 1 || g.Q < 1) return set_error(RESIST_ESHAPE, "empty convolution output");
+  const long long lim = 0x7fffffffLL;
+  if ((long long)g.N * g.H * g.W * g.C > lim || (long long)g.N * g.P * g.Q * g.K > lim ||
+      (long long)g.K * g.R * g.S * g.C > lim)
+    return set_error(RESIST_ESHAPE, "tensor exceeds 2^31 elements");
+  return RESIST_OK;
+}
+
+}  // namespace
+
+int conv_fwd_f32(const ConvGeom &g, const float *x, const float *w, float *y, hipStream_t st) {
+  RESIST_TRY(check_geom(g));
+  IgemmArgs a{};
+  a.in = x; a.wt = w; a.out = y; a.addend = nullptr;
+  a.N = g.N; a.IH = g.H; a.IW = g.W; a.IC = g.C;
+  a.OH = g.P; a.OW = g.Q; a.OC = g.K;
+  a.R = g.R; a.S = g.S; a.stride = g.stride; a.pad = g.pad;
+  a.cls = 1; a.OHc = g.P; a.OWc = g.Q;
+  a.Mrows = g.N * g.P * g.Q;
+  return dispatch_igemm<kFwd>(a, st);
+}
+
+int conv_dgrad_f32(const ConvGeom &g, const float *dy, const float *wT, float *dx, const float *addend,
+                   hipStream_t st) {
+  RESIST_TRY(check_geom(g));
+  if (g.stride == 2 && ((g.H & 1) || (g.W & 1)))
+    return set_error(RESIST_ESHAPE, "stride-2 dgrad needs even input size, got %dx%d", g.H, g.W);
+  IgemmArgs a{};
+  a.in = dy; a.wt = wT; a.out = dx; a.addend = addend;
+  a.N = g.N; a.IH = g.P; a.IW = g.Q; a.IC = g.K;
+  a.OH = g.H; a.OW = g.W; a.OC = g.C;
+  a.R = g.R; a.S = g.S; a.stride = g.stride; a.pad = g.pad;
+  a.cls = g.stride; a.OHc = g.H / g.stride; a.OWc = g.W / g.stride;
+  a.Mrows = g.N * a.OHc * a.OWc;
+  return dispatch_igemm<kBwd>(a, st);
+}
+
+// ---- filter transpose  wT[c][r][s][k] = w[k][r][s][c] -------------------------------------------
+namespace {
+__global__ __launch_bounds__(256) void transpose_filter_kernel(const float *__restrict__ w, float *__restrict__ wT,
+                                                               int K, int RS, int C) {
+  // 32x32 tiles of the [K][C] matrix at a fixed tap, through LDS so both sides stay coalesced
+  __shared__ float tile[32][33];
+  const int tap = blockIdx.z;
+  const int k0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  for (int i = ty; i < 32; i += 8) {
+    const int k = k0 + i, c = c0 + tx;
+    tile[i][tx] = (k < K && c < C) ? w[((size_t)k * RS + tap) * C + c] : 0.f;
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    const int c = c0 + i, k = k0 + tx;
+    if (k < K && c < C) wT[((size_t)c * RS + tap) * K + k] = tile[tx][i];
+  }
+}
+}  // namespace
+
+int transpose_filter_f32(const ConvGeom &g, const float *w, float *wT, hipStream_t st) {
+  dim3 grid((g.C + 31) / 32, (g.K + 31) / 32, g.R * g.S);
+  prof::Scope ps("transpose_filter", 0, 8.0 * g.K * g.R * g.S * g.C, st);
+  hipLaunchKernelGGL(transpose_filter_kernel, grid, dim3(256), 0, st, w, wT, g.K, g.R * g.S, g.C);
+  RESIST_CHECK_LAUNCH("transpose_filter");
+  return RESIST_OK;
+}
+
+// ---- wgrad --------------------------------------------------------------------------------------
+namespace {
+
+struct WgradArgs {
+  const float *dy;  // [M][K]
+  const float *x;   // [N][H][W][C]
+  float *out;       // [splits][K][R][S][C]
+  int N, H, W, C, K, R, S, stride, pad, P, Q;
+  int M;            // N*P*Q
+  int rows_per_split;
+  int tiles_k, tiles_c;
+};
+
+template <int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(kThreads) void wgrad_f32_kernel(WgradArgs a) {
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int LDA = BM + 32, LDB = BN + 32;   // rows kk and kk+1 land on different bank halves
+  constexpr int TPRA = BM / 4, TPRB = BN / 4;   // threads per 32-row-chunk row
+  constexpr int RPA = kThreads / TPRA, RPB = kThreads / TPRB;  // rows per pass
+  constexpr int PA = kBK / RPA, PB = kBK / RPB;
+  __shared__ float As[2][kBK][LDA];
+  __shared__ float Bs[2][kBK][LDB];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int tk = blockIdx.x / a.tiles_c, tc = blockIdx.x % a.tiles_c;
+  const int tap = blockIdx.y, split = blockIdx.z;
+  const int r = tap / a.S, s = tap - r * a.S;
+  const int k0 = tk * BM, c0 = tc * BN;
+  const int mbeg = split * a.rows_per_split;
+  const int mend = min(a.M, mbeg + a.rows_per_split);
+  const int nchunks = (mend - mbeg + kBK - 1) / kBK;
+
+  const int arow = tid / TPRA, acol = (tid % TPRA) * 4;
+  const int brow = tid / TPRB, bcol = (tid % TPRB) * 4;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  f32x4 ra[PA], rb[PB];
+  auto load_global = [&](int mc) {
+#pragma unroll
+    for (int i = 0; i < PA; ++i) {
+      const int m = mc + i * RPA + arow;
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (m < mend && k0 + acol < a.K) v = *reinterpret_cast<const f32x4 *>(a.dy + (size_t)m * a.K + k0 + acol);
+      ra[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+      const int m = mc + i * RPB + brow;
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (m < mend && c0 + bcol < a.C) {
+        const int n = m / (a.P * a.Q);
+        const int rem = m - n * (a.P * a.Q);
+        const int p = rem / a.Q, q = rem - p * a.Q;
+        const int ih = p * a.stride + r - a.pad, iw = q * a.stride + s - a.pad;
+        if (ih >= 0 && ih < a.H && iw >= 0 && iw < a.W)
+          v = *reinterpret_cast<const f32x4 *>(a.x + ((size_t)(n * a.H + ih) * a.W + iw) * a.C + c0 + bcol);
+      }
+      rb[i] = v;
+    }
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < PA; ++i) *reinterpret_cast<f32x4 *>(&As[buf][i * RPA + arow][acol]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < PB; ++i) *reinterpret_cast<f32x4 *>(&Bs[buf][i * RPB + brow][bcol]) = rb[i];
+  };
+
+  if (nchunks > 0) {
+    load_global(mbeg);
+    store_lds(0);
+  }
+  __syncthreads();
+  const int lr = lane & 31, lh = lane >> 5;
+  for (int it = 0; it < nchunks; ++it) {
+    const int buf = it & 1;
+    if (it + 1 < nchunks) load_global(mbeg + (it + 1) * kBK);
+#pragma unroll
+    for (int kk = 0; kk < kBK; kk += 2) {
+      float fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = As[buf][kk + lh][wm * WTM + i * 32 + lr];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = Bs[buf][kk + lh][wn * WTN + j * 32 + lr];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    if (it + 1 < nchunks) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  float *out = a.out + (size_t)split * a.K * a.R * a.S * a.C;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int c = c0 + wn * WTN + j * 32 + lr;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int k = k0 + wm * WTM + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+        if (k < a.K && c < a.C) out[((size_t)k * a.R * a.S + tap) * a.C + c] = acc[i][j][e];
+      }
+    }
+}
+
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part, float *__restrict__ out,
+                                                            long long n4, int splits) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n4) return;
+  const f32x4 *p = reinterpret_cast<const f32x4 *>(part);
+  f32x4 acc = p[i];
+  for (int z = 1; z < splits; ++z) acc += p[i + (long long)z * n4];
+  reinterpret_cast<f32x4 *>(out)[i] = acc;
+}
+
+struct WgradPlan { int bm, bn, splits, rows_per_split; };
+
+WgradPlan plan_wgrad(const ConvGeom &g) {
+  WgradPlan p;
+  p.bm = (g.K >= 128 && g.C >= 128 && (long long)g.K * g.C * g.R * g.S >= 128LL * 128 * 9 * 16) ? 128 : 64;
+  p.bn = p.bm;
+  const long long tiles = (long long)((g.K + p.bm - 1) / p.bm) * ((g.C + p.bn - 1) / p.bn) * g.R * g.S;
+  const long long M = (long long)g.N * g.P * g.Q;
+  long long splits = (768 + tiles - 1) / tiles;
+  const long long max_splits = (M + 255) / 256;  // at least 256 reduction rows per split
+  if (splits > max_splits) splits = max_splits;
+  if (splits < 1) splits = 1;
+  if (splits > 256) splits = 256;
+  long long rps = (M + splits - 1) / splits;
+  rps = (rps + kBK - 1) / kBK * kBK;
+  p.rows_per_split = (int)rps;
+  p.splits = (int)((M + rps - 1) / rps);
+  return p;
+}
+
+}  // namespace
+
+int64_t wgrad_scratch_floats(const ConvGeom &g) {
+  const WgradPlan p = plan_wgrad(g);
+  return p.splits > 1 ? (int64_t)p.splits * g.K * g.R * g.S * g.C : 0;
+}
+
+int conv_wgrad_f32(const ConvGeom &g, const float *dy, const float *x, float *dw, float *partial,
+                   hipStream_t st) {
+  RESIST_TRY(check_geom(g));
+  const WgradPlan p = plan_wgrad(g);
+  if (p.splits > 1 && !partial) return set_error(RESIST_EWORKSPACE, "wgrad needs split scratch");
+  WgradArgs a{};
+  a.dy = dy; a.x = x; a.out = p.splits > 1 ? partial : dw;
+  a.N = g.N; a.H = g.H; a.W = g.W; a.C = g.C; a.K = g.K; a.R = g.R; a.S = g.S;
+  a.stride = g.stride; a.pad = g.pad; a.P = g.P; a.Q = g.Q;
+  a.M = g.N * g.P * g.Q;
+  a.rows_per_split = p.rows_per_split;
+  a.tiles_k = (g.K + p.bm - 1) / p.bm;
+  a.tiles_c = (g.C + p.bn - 1) / p.bn;
+  dim3 grid(a.tiles_k * a.tiles_c, g.R * g.S, p.splits);
+  {
+    const double flops = 2.0 * a.M * g.K * g.C * g.R * g.S;
+    const double bytes = 4.0 * ((double)a.M * g.K + (double)g.N * g.H * g.W * g.C + (double)g.K * g.R * g.S * g.C);
+    prof::Scope ps(p.bm == 128 ? "wgrad_f32_128x128" : "wgrad_f32_64x64", flops, bytes, st);
+    if (p.bm == 128)
+      hipLaunchKernelGGL((wgrad_f32_kernel<128, 128, 2, 2>), grid, dim3(kThreads), 0, st, a);
+    else
+      hipLaunchKernelGGL((wgrad_f32_kernel<64, 64, 2, 2>), grid, dim3(kThreads), 0, st, a);
+  }
+  RESIST_CHECK_LAUNCH("wgrad_f32");
+  if (p.splits > 1) {
+    const long long n4 = (long long)g.K * g.R * g.S * g.C / 4;
+    prof::Scope ps("splitk_reduce", 0, 16.0 * n4 * (p.splits + 1), st);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, partial, dw, n4, p.splits);
+    RESIST_CHECK_LAUNCH("splitk_reduce");
+  }
+  return RESIST_OK;
+}
+
+}  // namespace resist

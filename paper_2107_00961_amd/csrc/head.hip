@@ -1,0 +1,235 @@
+// Pooling, the fully connected head and the loss of the sub-ResNet's training step (fp32, NHWC).
+// These are small or bandwidth-bound kernels; every reduction runs in a fixed order.
+#include "internal.h"
+
+namespace resist {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+// ---- max pool 3x3 stride 2 pad 1 -----------------------------------------------------------------
+// argmax stores the window tap (r*3+s) of the first maximum in row-major window order.
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                          uint8_t *__restrict__ arg, int N, int H, int W, int C, int P, int Q) {
+  const long long total = (long long)N * P * Q * (C / 4);
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % (C / 4)) * 4;
+  long long pix = i / (C / 4);
+  const int q = (int)(pix % Q); pix /= Q;
+  const int p = (int)(pix % P);
+  const int n = (int)(pix / P);
+  f32x4 best = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  int bi[4] = {0, 0, 0, 0};
+  bool any = false;
+  for (int r = 0; r < 3; ++r) {
+    const int ih = p * 2 + r - 1;
+    if (ih < 0 || ih >= H) continue;
+    for (int s = 0; s < 3; ++s) {
+      const int iw = q * 2 + s - 1;
+      if (iw < 0 || iw >= W) continue;
+      const f32x4 v = *reinterpret_cast<const f32x4 *>(x + ((size_t)(n * H + ih) * W + iw) * C + c);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (!any || v[e] > best[e]) { best[e] = v[e]; bi[e] = r * 3 + s; }
+      any = true;
+    }
+  }
+  const size_t off = ((size_t)(n * P + p) * Q + q) * C + c;
+  *reinterpret_cast<f32x4 *>(y + off) = best;
+  *reinterpret_cast<uchar4 *>(arg + off) = make_uchar4((uint8_t)bi[0], (uint8_t)bi[1], (uint8_t)bi[2], (uint8_t)bi[3]);
+}
+
+// gather form: every input pixel looks at the (at most 2x2) windows that cover it
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(const float *__restrict__ dy, const uint8_t *__restrict__ arg,
+                                                          float *__restrict__ dx, int N, int H, int W, int C, int P, int Q) {
+  const long long total = (long long)N * H * W * (C / 4);
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % (C / 4)) * 4;
+  long long pix = i / (C / 4);
+  const int w = (int)(pix % W); pix /= W;
+  const int h = (int)(pix % H);
+  const int n = (int)(pix / H);
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  // windows p with 2p-1 <= h <= 2p+1
+  for (int p = (h >> 1); p <= ((h + 1) >> 1); ++p) {
+    if (p < 0 || p >= P) continue;
+    const int r = h - (2 * p - 1);
+    for (int q = (w >> 1); q <= ((w + 1) >> 1); ++q) {
+      if (q < 0 || q >= Q) continue;
+      const int s = w - (2 * q - 1);
+      const size_t off = ((size_t)(n * P + p) * Q + q) * C + c;
+      const uchar4 a = *reinterpret_cast<const uchar4 *>(arg + off);
+      const f32x4 g = *reinterpret_cast<const f32x4 *>(dy + off);
+      const int tap = r * 3 + s;
+      if (a.x == tap) acc[0] += g[0];
+      if (a.y == tap) acc[1] += g[1];
+      if (a.z == tap) acc[2] += g[2];
+      if (a.w == tap) acc[3] += g[3];
+    }
+  }
+  *reinterpret_cast<f32x4 *>(dx + ((size_t)(n * H + h) * W + w) * C + c) = acc;
+}
+
+// ---- global mean pool ------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void avgpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int N, int HW, int C) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N * (C / 4)) return;
+  const int c = (i % (C / 4)) * 4, n = i / (C / 4);
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int p = 0; p < HW; ++p) acc += *reinterpret_cast<const f32x4 *>(x + ((size_t)n * HW + p) * C + c);
+  const float inv = 1.0f / (float)HW;
+  *reinterpret_cast<f32x4 *>(y + (size_t)n * C + c) = acc * inv;
+}
+
+__global__ __launch_bounds__(256) void avgpool_bwd_kernel(const float *__restrict__ dy, float *__restrict__ dx, int N, int HW, int C) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (long long)N * HW * (C / 4)) return;
+  const int c = (int)(i % (C / 4)) * 4;
+  const int n = (int)(i / ((long long)HW * (C / 4)));
+  const float inv = 1.0f / (float)HW;
+  const f32x4 g = *reinterpret_cast<const f32x4 *>(dy + (size_t)n * C + c);
+  reinterpret_cast<f32x4 *>(dx)[i] = g * inv;
+}
+
+// ---- fully connected -------------------------------------------------------------------------------
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  return v;
+}
+
+// one wave per output z[n][j]
+__global__ __launch_bounds__(64) void fc_fwd_kernel(const float *__restrict__ x, const float *__restrict__ w,
+                                                    const float *__restrict__ b, float *__restrict__ z, int N, int C, int J) {
+  const int j = blockIdx.x, n = blockIdx.y, lane = threadIdx.x;
+  float acc = 0.f;
+  for (int c = lane * 4; c < C; c += 256) {
+    const f32x4 xv = *reinterpret_cast<const f32x4 *>(x + (size_t)n * C + c);
+    const f32x4 wv = *reinterpret_cast<const f32x4 *>(w + (size_t)j * C + c);
+    acc += xv[0] * wv[0] + xv[1] * wv[1] + xv[2] * wv[2] + xv[3] * wv[3];
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) z[(size_t)n * J + j] = acc + b[j];
+}
+
+__global__ __launch_bounds__(256) void fc_bwd_dx_kernel(const float *__restrict__ dz, const float *__restrict__ w,
+                                                        float *__restrict__ dx, int N, int C, int J) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N * C) return;
+  const int c = i % C, n = i / C;
+  float acc = 0.f;
+  for (int j = 0; j < J; ++j) acc = fmaf(dz[(size_t)n * J + j], w[(size_t)j * C + c], acc);
+  dx[i] = acc;
+}
+
+__global__ __launch_bounds__(256) void fc_bwd_dw_kernel(const float *__restrict__ dz, const float *__restrict__ x,
+                                                        float *__restrict__ dw, int N, int C, int J) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= J * C) return;
+  const int c = i % C, j = i / C;
+  float acc = 0.f;
+  for (int n = 0; n < N; ++n) acc = fmaf(dz[(size_t)n * J + j], x[(size_t)n * C + c], acc);
+  dw[i] = acc;
+}
+
+// db over the padded length (multiple of 4): entries past J are written as zero
+__global__ __launch_bounds__(256) void fc_bwd_db_kernel(const float *__restrict__ dz, float *__restrict__ db, int N, int J, int Jpad) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= Jpad) return;
+  float acc = 0.f;
+  if (j < J)
+    for (int n = 0; n < N; ++n) acc += dz[(size_t)n * J + j];
+  db[j] = acc;
+}
+
+// ---- softmax cross-entropy ---------------------------------------------------------------------------
+// one wave per sample: row_loss[n] = logsumexp(z_n) - z_n[label]; dz = (softmax - onehot)/N
+__global__ __launch_bounds__(64) void softmax_ce_kernel(const float *__restrict__ z, const int32_t *__restrict__ labels,
+                                                        float *__restrict__ row_loss, float *__restrict__ dz, int N, int J) {
+  const int n = blockIdx.x, lane = threadIdx.x;
+  const float *zr = z + (size_t)n * J;
+  float mx = -INFINITY;
+  for (int j = lane; j < J; j += 64) mx = fmaxf(mx, zr[j]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  float se = 0.f;
+  for (int j = lane; j < J; j += 64) se += expf(zr[j] - mx);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
+  const int lab = labels[n];
+  const float invN = 1.0f / (float)N;
+  const float inv = 1.0f / se;
+  for (int j = lane; j < J; j += 64) {
+    const float p = expf(zr[j] - mx) * inv;
+    dz[(size_t)n * J + j] = (p - (j == lab ? 1.f : 0.f)) * invN;
+  }
+  // a label outside [0,J) is a caller error: it must not turn into an out-of-bounds read
+  if (lane == 0) row_loss[n] = (lab >= 0 && lab < J) ? (logf(se) + mx) - zr[lab] : NAN;
+}
+
+__global__ void mean_loss_kernel(const float *__restrict__ row_loss, float *__restrict__ loss, int N) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    double acc = 0;
+    for (int n = 0; n < N; ++n) acc += (double)row_loss[n];
+    *loss = (float)(acc / (double)N);
+  }
+}
+
+unsigned blocks_for(long long n, int t = 256) { return (unsigned)((n + t - 1) / t); }
+
+}  // namespace
+
+int maxpool_fwd_f32(const float *x, float *y, uint8_t *argmax, int N, int H, int W, int C, int P, int Q, hipStream_t st) {
+  prof::Scope ps("maxpool_fwd", 0, 0, st);
+  hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(blocks_for((long long)N * P * Q * (C / 4))), dim3(256), 0, st, x, y, argmax, N, H, W, C, P, Q);
+  RESIST_CHECK_LAUNCH("maxpool_fwd");
+  return RESIST_OK;
+}
+int maxpool_bwd_f32(const float *dy, const uint8_t *argmax, float *dx, int N, int H, int W, int C, int P, int Q, hipStream_t st) {
+  prof::Scope ps("maxpool_bwd", 0, 0, st);
+  hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(blocks_for((long long)N * H * W * (C / 4))), dim3(256), 0, st, dy, argmax, dx, N, H, W, C, P, Q);
+  RESIST_CHECK_LAUNCH("maxpool_bwd");
+  return RESIST_OK;
+}
+int avgpool_fwd_f32(const float *x, float *y, int N, int HW, int C, hipStream_t st) {
+  prof::Scope ps("avgpool_fwd", 0, 0, st);
+  hipLaunchKernelGGL(avgpool_fwd_kernel, dim3(blocks_for((long long)N * (C / 4))), dim3(256), 0, st, x, y, N, HW, C);
+  RESIST_CHECK_LAUNCH("avgpool_fwd");
+  return RESIST_OK;
+}
+int avgpool_bwd_f32(const float *dy, float *dx, int N, int HW, int C, hipStream_t st) {
+  prof::Scope ps("avgpool_bwd", 0, 0, st);
+  hipLaunchKernelGGL(avgpool_bwd_kernel, dim3(blocks_for((long long)N * HW * (C / 4))), dim3(256), 0, st, dy, dx, N, HW, C);
+  RESIST_CHECK_LAUNCH("avgpool_bwd");
+  return RESIST_OK;
+}
+int fc_fwd_f32(const float *x, const float *w, const float *b, float *z, int N, int C, int J, hipStream_t st) {
+  prof::Scope ps("fc_fwd", 0, 0, st);
+  hipLaunchKernelGGL(fc_fwd_kernel, dim3(J, N), dim3(64), 0, st, x, w, b, z, N, C, J);
+  RESIST_CHECK_LAUNCH("fc_fwd");
+  return RESIST_OK;
+}
+int fc_bwd_f32(const float *dz, const float *x, const float *w, float *dx, float *dw, float *db, int N, int C, int J, hipStream_t st) {
+  prof::Scope ps("fc_bwd", 0, 0, st);
+  hipLaunchKernelGGL(fc_bwd_dx_kernel, dim3(blocks_for((long long)N * C)), dim3(256), 0, st, dz, w, dx, N, C, J);
+  RESIST_CHECK_LAUNCH("fc_bwd_dx");
+  hipLaunchKernelGGL(fc_bwd_dw_kernel, dim3(blocks_for((long long)J * C)), dim3(256), 0, st, dz, x, dw, N, C, J);
+  RESIST_CHECK_LAUNCH("fc_bwd_dw");
+  const int Jpad = (J + 3) & ~3;
+  hipLaunchKernelGGL(fc_bwd_db_kernel, dim3(blocks_for(Jpad)), dim3(256), 0, st, dz, db, N, J, Jpad);
+  RESIST_CHECK_LAUNCH("fc_bwd_db");
+  return RESIST_OK;
+}
+int softmax_ce_f32(const float *z, const int32_t *labels, float *loss, float *dz, float *row_loss, int N, int J, hipStream_t st) {
+  prof::Scope ps("softmax_ce", 0, 0, st);
+  hipLaunchKernelGGL(softmax_ce_kernel, dim3(N), dim3(64), 0, st, z, labels, row_loss, dz, N, J);
+  RESIST_CHECK_LAUNCH("softmax_ce");
+  hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(64), 0, st, row_loss, loss, N);
+  RESIST_CHECK_LAUNCH("mean_loss");
+  return RESIST_OK;
+}
+
+}  // namespace resist

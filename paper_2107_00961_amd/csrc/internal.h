@@ -1,0 +1,156 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "resist.h"
+#include "resist_ops.h"
+
+namespace resist {
+
+int set_error(int code, const char *fmt, ...);
+#define RESIST_CHECK_HIP(expr)                                                          \
+  do {                                                                                  \
+    hipError_t e__ = (expr);                                                            \
+    if (e__ != hipSuccess)                                                              \
+      return ::resist::set_error(RESIST_EHIP, "%s: %s", #expr, hipGetErrorString(e__)); \
+  } while (0)
+#define RESIST_CHECK_LAUNCH(name)                                                        \
+  do {                                                                                   \
+    hipError_t e__ = hipGetLastError();                                                  \
+    if (e__ != hipSuccess)                                                               \
+      return ::resist::set_error(RESIST_EHIP, "launch %s: %s", name, hipGetErrorString(e__)); \
+  } while (0)
+#define RESIST_TRY(expr)      \
+  do {                        \
+    int rc__ = (expr);        \
+    if (rc__ != 0) return rc__; \
+  } while (0)
+
+// ---- optional per-kernel event timing (prof.cpp) ----------------------------------------------
+namespace prof {
+bool enabled();
+struct Scope {   // brackets the launches made during its lifetime with two events on `st`
+  Scope(const char *label, double flops, double bytes, hipStream_t st);
+  ~Scope();
+  hipStream_t st_;
+  int idx_;
+};
+}  // namespace prof
+
+// ---- static description of the global network -------------------------------------------------
+struct BlockShape {
+  int stage, index;         // position
+  int c_in, width, c_out;   // channels
+  int stride;               // 1 or 2 (on the 3x3 convolution)
+  bool has_ds;              // conv1x1(stride)+BN shortcut
+  int h_in, w_in, h_out, w_out;
+};
+
+struct TensorSlot {  // one tensor inside a block buffer
+  int kind, layer;
+  int64_t offset, count;
+  int dims[4];
+};
+
+struct BlockLayout {
+  std::vector<TensorSlot> slots;
+  int64_t n_total = 0, n_trainable = 0;
+  // find offset of (kind, layer); -1 if absent
+  int64_t off(int kind, int layer) const {
+    for (const auto &s : slots)
+      if (s.kind == kind && s.layer == layer) return s.offset;
+    return -1;
+  }
+};
+
+struct Net {
+  resist_model_desc d;
+  std::vector<BlockShape> blocks;   // B entries
+  std::vector<int> stage_first;     // first block index of each stage
+  int stem_rs, stem_stride, stem_pad;
+  int stem_h, stem_w;               // stem conv output spatial size
+  int body_h, body_w;               // after optional max-pool
+  int head_c;                       // channels entering the head
+  int expansion;
+};
+
+int build_net(const resist_model_desc *desc, Net *net);          // validates
+int block_layout(const Net &net, int block, BlockLayout *out);   // block in [-1, B]
+
+enum { T_CONVW = 0, T_GAMMA = 1, T_BETA = 2, T_RMEAN = 3, T_RVAR = 4, T_FCW = 5, T_FCB = 6 };
+
+// ---- kernels (launchers return a resist_status) -----------------------------------------------
+struct ConvGeom {
+  int N, H, W, C;   // input activation (NHWC)
+  int K, R, S;      // filter
+  int stride, pad;
+  int P, Q;         // output spatial
+};
+inline ConvGeom make_geom(int N, int H, int W, int C, int K, int R, int stride, int pad) {
+  ConvGeom g{N, H, W, C, K, R, R, stride, pad, 0, 0};
+  g.P = (H + 2 * pad - R) / stride + 1;
+  g.Q = (W + 2 * pad - R) / stride + 1;
+  return g;
+}
+
+// fp32 implicit-GEMM convolution family (conv_f32.hip)
+int conv_fwd_f32(const ConvGeom &g, const float *x, const float *w, float *y, hipStream_t st);
+// dx = dgrad(dy, wT) [+ addend]; wT is the [C][R][S][K] transpose made by transpose_filter_f32
+int conv_dgrad_f32(const ConvGeom &g, const float *dy, const float *wT, float *dx,
+                   const float *addend, hipStream_t st);
+int transpose_filter_f32(const ConvGeom &g, const float *w, float *wT, hipStream_t st);
+// dw = wgrad(dy, x); partial: split-K scratch of wgrad_scratch_floats(g) floats
+int64_t wgrad_scratch_floats(const ConvGeom &g);
+int conv_wgrad_f32(const ConvGeom &g, const float *dy, const float *x, float *dw, float *partial,
+                   hipStream_t st);
+
+// stem helpers (stem.hip): NCHW fp32 image -> im2col rows [N*P*Q][kpad], column (r*S+s)*C+c
+int stem_im2col_f32(const float *x_nchw, float *col, int N, int C, int H, int W, int R, int stride,
+                    int pad, int P, int Q, int kpad, hipStream_t st);
+int pad_rows_f32(const float *src, float *dst, int rows, int n, int npad, hipStream_t st);    // [rows][n] -> [rows][npad]
+int unpad_rows_f32(const float *src, float *dst, int rows, int n, int npad, hipStream_t st);  // [rows][npad] -> [rows][n]
+
+// BatchNorm on [M][C] fp32 (bn.hip)
+struct BnBufs {
+  const float *gamma, *beta;
+  float *rmean, *rvar;       // running statistics (updated by stats)
+  float *mean, *invstd;      // [C] saved batch statistics
+  float *dgamma, *dbeta;     // [C] gradient outputs
+};
+int64_t bn_scratch_doubles(int C);   // partial-sum scratch for one BN call
+int bn_stats_f32(const float *y, int64_t M, int C, const BnBufs &b, float eps, float momentum,
+                 double *scratch, hipStream_t st);
+// a = [relu]( gamma*xhat(y)+beta [+ res] )            res: raw tensor, or BN(res_y) if res_bn given
+int bn_apply_f32(const float *y, int64_t M, int C, const BnBufs &b, const float *res,
+                 const BnBufs *res_bn, bool relu, float *a, hipStream_t st);
+// gm = g * [mask>0] (mask may be NULL: no masking); dbeta = sum gm; dgamma = sum gm*xhat(y);
+// dy = gamma*invstd*(gm - dbeta/M - xhat*dgamma/M); optionally stores gm to gm_out.
+int bn_backward_f32(const float *g, const float *mask, const float *y, int64_t M, int C,
+                    const BnBufs &b, float *dy, float *gm_out, double *scratch, hipStream_t st);
+
+// pooling / head / loss (head.hip)
+int maxpool_fwd_f32(const float *x, float *y, uint8_t *argmax, int N, int H, int W, int C, int P,
+                    int Q, hipStream_t st);
+int maxpool_bwd_f32(const float *dy, const uint8_t *argmax, float *dx, int N, int H, int W, int C,
+                    int P, int Q, hipStream_t st);
+int avgpool_fwd_f32(const float *x, float *y, int N, int HW, int C, hipStream_t st);
+int avgpool_bwd_f32(const float *dy, float *dx, int N, int HW, int C, hipStream_t st);
+int fc_fwd_f32(const float *x, const float *w, const float *b, float *z, int N, int C, int J,
+               hipStream_t st);
+int fc_bwd_f32(const float *dz, const float *x, const float *w, float *dx, float *dw, float *db,
+               int N, int C, int J, hipStream_t st);
+int softmax_ce_f32(const float *z, const int32_t *labels, float *loss, float *dz, float *row_loss,
+                   int N, int J, hipStream_t st);
+
+// update / reassembly (update.hip)
+struct SgdSeg { float *w; float *v; const float *g; int64_t n; };
+int sgd_momentum_f32(const std::vector<SgdSeg> &segs, float lr, float mu, float wd, hipStream_t st);
+struct AggSeg { float *dst; const float *src[16]; int count; int64_t n; };
+int aggregate_f32(const std::vector<AggSeg> &segs, hipStream_t st);
+int fill_zero_f32(float *p, int64_t n, hipStream_t st);
+
+}  // namespace resist

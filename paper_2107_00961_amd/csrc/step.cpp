@@ -1,0 +1,413 @@
+// resist_local_step: one SGD iteration of one sub-ResNet (the paper's Algorithm 1, inner loop),
+// resist_workspace_bytes, and resist_aggregate (Sec. 2.3).  Host-side orchestration only: this file
+// lays out the workspace, walks the kept blocks forward and backward, and enqueues the kernels.
+// A block that is not in the list is simply not launched -- the residual stream passes through
+// (Appendix B, forward recursion with mask 0).
+#include <algorithm>
+
+#include "internal.h"
+
+namespace resist {
+namespace {
+
+struct Arena {
+  char *base;
+  int64_t off = 0;
+  explicit Arena(void *b) : base((char *)b) {}
+  template <typename T>
+  T *take(int64_t count) {
+    off = (off + 255) & ~(int64_t)255;
+    T *p = (T *)(base + off);   // with base == NULL this is only an offset; never dereferenced
+    off += count * (int64_t)sizeof(T);
+    return p;
+  }
+};
+
+struct ConvLayer {
+  ConvGeom g;
+  int64_t w_off, gamma_off, beta_off, rmean_off, rvar_off;  // offsets inside the block buffer
+  const float *in = nullptr;
+  float *y = nullptr;        // pre-BN output
+  float *a = nullptr;        // post-BN(+ReLU) output; NULL for the layer that ends a block
+  float *mean = nullptr, *invstd = nullptr;
+  int64_t M() const { return (int64_t)g.N * g.P * g.Q; }
+};
+
+struct BlockPlan {
+  int slot;                 // index into block_params (1 + position in `blocks`)
+  std::vector<ConvLayer> convs;
+  bool has_ds = false;
+  ConvLayer ds;
+  const float *in = nullptr;
+  float *out = nullptr;
+  int64_t out_elems = 0;
+};
+
+struct StepPlan {
+  Net net;
+  int batch = 0;
+  std::vector<BlockLayout> layouts;   // per slot: stem, blocks..., head
+  // stem
+  int kpad = 0;
+  ConvLayer stem;                     // geometry of the 1x1 GEMM over im2col rows
+  float *col = nullptr, *wpad = nullptr, *dwpad = nullptr;
+  float *stem_pool = nullptr;
+  uint8_t *stem_argmax = nullptr;
+  std::vector<BlockPlan> blocks;
+  // head
+  float *pooled = nullptr, *z = nullptr, *dz = nullptr, *row_loss = nullptr, *dpooled = nullptr;
+  const float *feat = nullptr;
+  int feat_hw = 0;
+  // shared scratch
+  float *gbuf[2] = {nullptr, nullptr}, *gm = nullptr, *dy0 = nullptr, *dy1 = nullptr, *da = nullptr;
+  float *wT = nullptr, *splitk = nullptr;
+  double *bn_scratch = nullptr;
+  std::vector<float *> own_grads;     // per slot, when the caller passes no gradient buffers
+  int64_t bytes = 0;
+};
+
+ConvLayer make_conv(const BlockLayout &L, int layer, int N, int H, int W, int C, int K, int R, int stride, int pad) {
+  ConvLayer c;
+  c.g = make_geom(N, H, W, C, K, R, stride, pad);
+  c.w_off = L.off(T_CONVW, layer);
+  c.gamma_off = L.off(T_GAMMA, layer);
+  c.beta_off = L.off(T_BETA, layer);
+  c.rmean_off = L.off(T_RMEAN, layer);
+  c.rvar_off = L.off(T_RVAR, layer);
+  return c;
+}
+
+int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks, int32_t batch, void *ws,
+               StepPlan *P) {
+  RESIST_TRY(build_net(desc, &P->net));
+  const Net &net = P->net;
+  const int B = (int)net.blocks.size();
+  if (desc->compute_dtype != 0) return set_error(RESIST_EUNSUPPORTED, "compute_dtype %d is not available in this build", desc->compute_dtype);
+  if (batch < 1) return set_error(RESIST_EINVAL, "batch=%d", batch);
+  if (nblocks < 0 || (nblocks > 0 && !blocks)) return set_error(RESIST_EINVAL, "blocks/nblocks");
+  for (int i = 0; i < nblocks; ++i) {
+    if (blocks[i] < 0 || blocks[i] >= B) return set_error(RESIST_EINVAL, "blocks[%d]=%d outside [0,%d)", i, blocks[i], B);
+    if (i > 0 && blocks[i] <= blocks[i - 1]) return set_error(RESIST_EINVAL, "blocks must be strictly ascending");
+  }
+  for (int f : net.stage_first)
+    if (!std::binary_search(blocks, blocks + nblocks, f))
+      return set_error(RESIST_ESHAPE, "first block %d of a stage is missing: the residual stream would change shape", f);
+  P->batch = batch;
+  const int N = batch;
+  Arena A(ws);
+
+  P->layouts.resize(nblocks + 2);
+  RESIST_TRY(block_layout(net, -1, &P->layouts[0]));
+  for (int i = 0; i < nblocks; ++i) RESIST_TRY(block_layout(net, blocks[i], &P->layouts[i + 1]));
+  RESIST_TRY(block_layout(net, B, &P->layouts[nblocks + 1]));
+
+  int64_t max_act = 0, max_filter = 0, max_splitk = 0;
+  int max_c = 16;
+  auto track = [&](const ConvLayer &c, bool needs_dgrad) {
+    max_act = std::max<int64_t>(max_act, c.M() * c.g.K);
+    max_act = std::max<int64_t>(max_act, (int64_t)c.g.N * c.g.H * c.g.W * c.g.C);
+    if (needs_dgrad) max_filter = std::max<int64_t>(max_filter, (int64_t)c.g.K * c.g.R * c.g.S * c.g.C);
+    max_splitk = std::max<int64_t>(max_splitk, wgrad_scratch_floats(c.g));
+    max_c = std::max(max_c, c.g.K);
+  };
+
+  // ---- stem: im2col rows, then a 1x1 GEMM with kpad input channels
+  {
+    const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
+    P->kpad = (taps + 31) / 32 * 32;
+    const int K0 = net.d.width[0];
+    ConvLayer &s = P->stem;
+    s = make_conv(P->layouts[0], 0, N, net.stem_h, net.stem_w, P->kpad, K0, 1, 1, 0);
+    P->col = A.take<float>(s.M() * P->kpad);
+    P->wpad = A.take<float>((int64_t)K0 * P->kpad);
+    P->dwpad = A.take<float>((int64_t)K0 * P->kpad);
+    s.in = P->col;
+    s.y = A.take<float>(s.M() * K0);
+    s.a = A.take<float>(s.M() * K0);
+    s.mean = A.take<float>(K0);
+    s.invstd = A.take<float>(K0);
+    max_act = std::max<int64_t>(max_act, s.M() * K0);
+    max_splitk = std::max<int64_t>(max_splitk, wgrad_scratch_floats(s.g));
+    max_c = std::max(max_c, K0);
+    if (net.d.stem_kind == 1) {
+      const int64_t n = (int64_t)N * net.body_h * net.body_w * K0;
+      P->stem_pool = A.take<float>(n);
+      P->stem_argmax = A.take<uint8_t>(n);
+    }
+  }
+  const float *cur = net.d.stem_kind == 1 ? P->stem_pool : P->stem.a;
+
+  // ---- residual blocks the sub-ResNet keeps
+  P->blocks.resize(nblocks);
+  for (int i = 0; i < nblocks; ++i) {
+    const BlockShape &bs = net.blocks[blocks[i]];
+    const BlockLayout &L = P->layouts[i + 1];
+    BlockPlan &bp = P->blocks[i];
+    bp.slot = i + 1;
+    bp.in = cur;
+    if (net.d.block_kind == 0) {
+      bp.convs.push_back(make_conv(L, 0, N, bs.h_in, bs.w_in, bs.c_in, bs.width, 3, bs.stride, 1));
+      bp.convs.push_back(make_conv(L, 1, N, bs.h_out, bs.w_out, bs.width, bs.c_out, 3, 1, 1));
+    } else {
+      bp.convs.push_back(make_conv(L, 0, N, bs.h_in, bs.w_in, bs.c_in, bs.width, 1, 1, 0));
+      bp.convs.push_back(make_conv(L, 1, N, bs.h_in, bs.w_in, bs.width, bs.width, 3, bs.stride, 1));
+      bp.convs.push_back(make_conv(L, 2, N, bs.h_out, bs.w_out, bs.width, bs.c_out, 1, 1, 0));
+    }
+    const float *x = bp.in;
+    for (size_t j = 0; j < bp.convs.size(); ++j) {
+      ConvLayer &c = bp.convs[j];
+      c.in = x;
+      c.y = A.take<float>(c.M() * c.g.K);
+      c.mean = A.take<float>(c.g.K);
+      c.invstd = A.take<float>(c.g.K);
+      if (j + 1 < bp.convs.size()) {
+        c.a = A.take<float>(c.M() * c.g.K);
+        x = c.a;
+      }
+      track(c, true);
+    }
+    bp.has_ds = bs.has_ds;
+    if (bs.has_ds) {
+      ConvLayer &d = bp.ds;
+      d = make_conv(L, 3, N, bs.h_in, bs.w_in, bs.c_in, bs.c_out, 1, bs.stride, 0);
+      d.in = bp.in;
+      d.y = A.take<float>(d.M() * d.g.K);
+      d.mean = A.take<float>(d.g.K);
+      d.invstd = A.take<float>(d.g.K);
+      track(d, true);
+    }
+    bp.out_elems = (int64_t)N * bs.h_out * bs.w_out * bs.c_out;
+    bp.out = A.take<float>(bp.out_elems);
+    cur = bp.out;
+  }
+
+  // ---- head
+  {
+    const BlockShape &last = net.blocks[blocks[nblocks - 1]];
+    P->feat = cur;
+    P->feat_hw = last.h_out * last.w_out;
+    const int J = net.d.num_classes;
+    P->pooled = A.take<float>((int64_t)N * net.head_c);
+    P->dpooled = A.take<float>((int64_t)N * net.head_c);
+    P->z = A.take<float>((int64_t)N * J);
+    P->dz = A.take<float>((int64_t)N * J);
+    P->row_loss = A.take<float>(N);
+  }
+
+  // ---- backward scratch shared by all layers (kernels are stream-ordered)
+  P->gbuf[0] = A.take<float>(max_act);
+  P->gbuf[1] = A.take<float>(max_act);
+  P->gm = A.take<float>(max_act);
+  P->dy0 = A.take<float>(max_act);
+  P->dy1 = A.take<float>(max_act);
+  P->da = A.take<float>(max_act);
+  P->wT = A.take<float>(max_filter);
+  P->splitk = A.take<float>(max_splitk);
+  P->bn_scratch = A.take<double>(bn_scratch_doubles(max_c));
+  P->own_grads.resize(nblocks + 2);
+  for (int i = 0; i < nblocks + 2; ++i) P->own_grads[i] = A.take<float>(P->layouts[i].n_trainable);
+  P->bytes = (A.off + 255) & ~(int64_t)255;
+  return RESIST_OK;
+}
+
+BnBufs bn_bufs(const ConvLayer &c, float *params, float *grads) {
+  BnBufs b;
+  b.gamma = params + c.gamma_off;
+  b.beta = params + c.beta_off;
+  b.rmean = params + c.rmean_off;
+  b.rvar = params + c.rvar_off;
+  b.mean = c.mean;
+  b.invstd = c.invstd;
+  b.dgamma = grads + c.gamma_off;
+  b.dbeta = grads + c.beta_off;
+  return b;
+}
+
+}  // namespace
+}  // namespace resist
+
+using namespace resist;
+
+extern "C" int resist_workspace_bytes(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks,
+                                      int32_t batch, int64_t *bytes) {
+  if (!bytes) return set_error(RESIST_EINVAL, "bytes is NULL");
+  StepPlan P;
+  RESIST_TRY(build_plan(desc, blocks, nblocks, batch, nullptr, &P));
+  *bytes = P.bytes;
+  return RESIST_OK;
+}
+
+extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks,
+                                 void *const *block_params, void *const *block_momentum, void *const *block_grads,
+                                 const float *x, const int32_t *labels, int32_t batch, float lr, float momentum,
+                                 float weight_decay, void *workspace, int64_t workspace_bytes, float *loss_out,
+                                 void *hip_stream) {
+  if (!block_params || !block_momentum || !x || !labels || !workspace || !loss_out)
+    return set_error(RESIST_EINVAL, "NULL argument");
+  if (((uintptr_t)workspace & 15) || ((uintptr_t)x & 15)) return set_error(RESIST_EINVAL, "workspace and x must be 16-byte aligned");
+  StepPlan P;
+  RESIST_TRY(build_plan(desc, blocks, nblocks, batch, workspace, &P));
+  if (workspace_bytes < P.bytes) return set_error(RESIST_EWORKSPACE, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes, (long long)P.bytes);
+  const int nslots = nblocks + 2;
+  for (int i = 0; i < nslots; ++i) {
+    if (!block_params[i] || !block_momentum[i] || (block_grads && !block_grads[i]))
+      return set_error(RESIST_EINVAL, "buffer %d is NULL", i);
+    if (((uintptr_t)block_params[i] & 15) || ((uintptr_t)block_momentum[i] & 15) || (block_grads && ((uintptr_t)block_grads[i] & 15)))
+      return set_error(RESIST_EINVAL, "buffer %d is not 16-byte aligned", i);
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  const Net &net = P.net;
+  const int N = batch;
+  const float eps = net.d.bn_eps, bnm = net.d.bn_momentum;
+  auto params = [&](int slot) { return (float *)block_params[slot]; };
+  auto grads = [&](int slot) { return block_grads ? (float *)block_grads[slot] : P.own_grads[slot]; };
+
+  // ================= forward =================
+  {
+    ConvLayer &s = P.stem;
+    const int K0 = net.d.width[0];
+    const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
+    RESIST_TRY(stem_im2col_f32(x, P.col, N, net.d.in_c, net.d.in_h, net.d.in_w, net.stem_rs, net.stem_stride, net.stem_pad,
+                               net.stem_h, net.stem_w, P.kpad, st));
+    RESIST_TRY(pad_rows_f32(params(0) + s.w_off, P.wpad, K0, taps, P.kpad, st));
+    RESIST_TRY(conv_fwd_f32(s.g, P.col, P.wpad, s.y, st));
+    BnBufs b = bn_bufs(s, params(0), grads(0));
+    RESIST_TRY(bn_stats_f32(s.y, s.M(), K0, b, eps, bnm, P.bn_scratch, st));
+    RESIST_TRY(bn_apply_f32(s.y, s.M(), K0, b, nullptr, nullptr, true, s.a, st));
+    if (net.d.stem_kind == 1)
+      RESIST_TRY(maxpool_fwd_f32(s.a, P.stem_pool, P.stem_argmax, N, net.stem_h, net.stem_w, K0, net.body_h, net.body_w, st));
+  }
+  for (BlockPlan &bp : P.blocks) {
+    float *pp = params(bp.slot), *gg = grads(bp.slot);
+    for (size_t j = 0; j < bp.convs.size(); ++j) {
+      ConvLayer &c = bp.convs[j];
+      RESIST_TRY(conv_fwd_f32(c.g, c.in, pp + c.w_off, c.y, st));
+      BnBufs b = bn_bufs(c, pp, gg);
+      RESIST_TRY(bn_stats_f32(c.y, c.M(), c.g.K, b, eps, bnm, P.bn_scratch, st));
+      if (c.a) RESIST_TRY(bn_apply_f32(c.y, c.M(), c.g.K, b, nullptr, nullptr, true, c.a, st));
+    }
+    ConvLayer &last = bp.convs.back();
+    BnBufs bl = bn_bufs(last, pp, gg);
+    if (bp.has_ds) {
+      ConvLayer &d = bp.ds;
+      RESIST_TRY(conv_fwd_f32(d.g, d.in, pp + d.w_off, d.y, st));
+      BnBufs bd = bn_bufs(d, pp, gg);
+      RESIST_TRY(bn_stats_f32(d.y, d.M(), d.g.K, bd, eps, bnm, P.bn_scratch, st));
+      RESIST_TRY(bn_apply_f32(last.y, last.M(), last.g.K, bl, d.y, &bd, true, bp.out, st));
+    } else {
+      RESIST_TRY(bn_apply_f32(last.y, last.M(), last.g.K, bl, bp.in, nullptr, true, bp.out, st));
+    }
+  }
+  const int J = net.d.num_classes, CH = net.head_c;
+  const int hs = nslots - 1;
+  const BlockLayout &HL = P.layouts[hs];
+  float *fcw = params(hs) + HL.off(T_FCW, 0), *fcb = params(hs) + HL.off(T_FCB, 0);
+  RESIST_TRY(avgpool_fwd_f32(P.feat, P.pooled, N, P.feat_hw, CH, st));
+  RESIST_TRY(fc_fwd_f32(P.pooled, fcw, fcb, P.z, N, CH, J, st));
+  RESIST_TRY(softmax_ce_f32(P.z, labels, loss_out, P.dz, P.row_loss, N, J, st));
+
+  // ================= backward =================
+  RESIST_TRY(fc_bwd_f32(P.dz, P.pooled, fcw, P.dpooled, grads(hs) + HL.off(T_FCW, 0), grads(hs) + HL.off(T_FCB, 0), N, CH, J, st));
+  int gi = 0;
+  float *G = P.gbuf[gi];
+  RESIST_TRY(avgpool_bwd_f32(P.dpooled, G, N, P.feat_hw, CH, st));
+  for (int bi = (int)P.blocks.size() - 1; bi >= 0; --bi) {
+    BlockPlan &bp = P.blocks[bi];
+    float *pp = params(bp.slot), *gg = grads(bp.slot);
+    float *Gn = P.gbuf[gi ^ 1];
+    const int nc = (int)bp.convs.size();
+    ConvLayer &last = bp.convs[nc - 1];
+    BnBufs bl = bn_bufs(last, pp, gg);
+    // through the final ReLU and the last BN of the residual branch
+    RESIST_TRY(bn_backward_f32(G, bp.out, last.y, last.M(), last.g.K, bl, P.dy0, bp.has_ds ? nullptr : P.gm, P.bn_scratch, st));
+    if (bp.has_ds) {
+      // shortcut branch: BN and 1x1 convolution; its data gradient initialises Gn
+      ConvLayer &d = bp.ds;
+      BnBufs bd = bn_bufs(d, pp, gg);
+      RESIST_TRY(bn_backward_f32(G, bp.out, d.y, d.M(), d.g.K, bd, P.gm, nullptr, P.bn_scratch, st));
+      RESIST_TRY(conv_wgrad_f32(d.g, P.gm, d.in, gg + d.w_off, P.splitk, st));
+      RESIST_TRY(transpose_filter_f32(d.g, pp + d.w_off, P.wT, st));
+      RESIST_TRY(conv_dgrad_f32(d.g, P.gm, P.wT, Gn, nullptr, st));
+    }
+    float *dy = P.dy0, *dy_other = P.dy1;
+    for (int j = nc - 1; j >= 0; --j) {
+      ConvLayer &c = bp.convs[j];
+      RESIST_TRY(conv_wgrad_f32(c.g, dy, c.in, gg + c.w_off, P.splitk, st));
+      RESIST_TRY(transpose_filter_f32(c.g, pp + c.w_off, P.wT, st));
+      if (j > 0) {
+        ConvLayer &prev = bp.convs[j - 1];
+        RESIST_TRY(conv_dgrad_f32(c.g, dy, P.wT, P.da, nullptr, st));
+        BnBufs bp_ = bn_bufs(prev, pp, gg);
+        RESIST_TRY(bn_backward_f32(P.da, prev.a, prev.y, prev.M(), prev.g.K, bp_, dy_other, nullptr, P.bn_scratch, st));
+        std::swap(dy, dy_other);
+      } else {
+        // gradient w.r.t. the block input = branch + shortcut
+        RESIST_TRY(conv_dgrad_f32(c.g, dy, P.wT, Gn, bp.has_ds ? Gn : P.gm, st));
+      }
+    }
+    gi ^= 1;
+    G = Gn;
+  }
+  {
+    ConvLayer &s = P.stem;
+    const int K0 = net.d.width[0];
+    const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
+    const float *Gs = G;
+    if (net.d.stem_kind == 1) {
+      RESIST_TRY(maxpool_bwd_f32(G, P.stem_argmax, P.da, N, net.stem_h, net.stem_w, K0, net.body_h, net.body_w, st));
+      Gs = P.da;
+    }
+    BnBufs b = bn_bufs(s, params(0), grads(0));
+    RESIST_TRY(bn_backward_f32(Gs, s.a, s.y, s.M(), K0, b, P.dy0, nullptr, P.bn_scratch, st));
+    RESIST_TRY(conv_wgrad_f32(s.g, P.dy0, P.col, P.dwpad, P.splitk, st));
+    RESIST_TRY(unpad_rows_f32(P.dwpad, grads(0) + s.w_off, K0, taps, P.kpad, st));
+  }
+
+  // ================= update =================
+  std::vector<SgdSeg> segs;
+  for (int i = 0; i < nslots; ++i)
+    segs.push_back(SgdSeg{params(i), (float *)block_momentum[i], grads(i), P.layouts[i].n_trainable});
+  RESIST_TRY(sgd_momentum_f32(segs, lr, momentum, weight_decay, st));
+  return RESIST_OK;
+}
+
+extern "C" int resist_aggregate(const resist_model_desc *desc, int32_t S, const int32_t *sub_offsets,
+                                const int32_t *sub_blocks, void *const *const *sub_block_params,
+                                void *const *global_block_params, void *hip_stream) {
+  Net net;
+  RESIST_TRY(build_net(desc, &net));
+  const int B = (int)net.blocks.size();
+  if (S < 1 || !sub_offsets || !sub_blocks || !sub_block_params || !global_block_params)
+    return set_error(RESIST_EINVAL, "NULL argument or S < 1");
+  if (S > 16) return set_error(RESIST_EUNSUPPORTED, "S=%d: at most 16 sub-ResNets supported", S);
+  std::vector<AggSeg> segs(B + 2);
+  for (int key = -1; key <= B; ++key) {
+    BlockLayout L;
+    RESIST_TRY(block_layout(net, key, &L));
+    AggSeg &g = segs[key + 1];
+    g.dst = (float *)global_block_params[key + 1];
+    g.count = 0;
+    g.n = L.n_total;
+    if (!g.dst) return set_error(RESIST_EINVAL, "global buffer %d is NULL", key + 1);
+  }
+  for (int s = 0; s < S; ++s) {
+    const int n_s = sub_offsets[s + 1] - sub_offsets[s];
+    if (n_s < 0) return set_error(RESIST_EINVAL, "sub_offsets not ascending");
+    if (!sub_block_params[s]) return set_error(RESIST_EINVAL, "sub_block_params[%d] is NULL", s);
+    auto add = [&](int key, const void *p) -> int {
+      if (!p) return set_error(RESIST_EINVAL, "sub-ResNet %d: buffer for block %d is NULL", s, key);
+      AggSeg &g = segs[key + 1];
+      g.src[g.count++] = (const float *)p;
+      return RESIST_OK;
+    };
+    RESIST_TRY(add(-1, sub_block_params[s][0]));
+    for (int i = 0; i < n_s; ++i) {
+      const int b = sub_blocks[sub_offsets[s] + i];
+      if (b < 0 || b >= B) return set_error(RESIST_EINVAL, "sub-ResNet %d holds block %d outside [0,%d)", s, b, B);
+      if (i > 0 && b <= sub_blocks[sub_offsets[s] + i - 1]) return set_error(RESIST_EINVAL, "sub-ResNet %d: blocks not ascending", s);
+      RESIST_TRY(add(b, sub_block_params[s][1 + i]));
+    }
+    RESIST_TRY(add(B, sub_block_params[s][1 + n_s]));
+  }
+  return aggregate_f32(segs, (hipStream_t)hip_stream);
+}

@@ -1,0 +1,61 @@
+"""Device-side containers for a sub-ResNet and the global model (allocation + marshalling only).
+
+PyTorch provides device memory and streams; all arithmetic happens inside libresist.so.
+"""
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+class DeviceModel:
+    """Block buffers of a set of blocks on the GPU: [stem, blocks..., head] as float32 tensors."""
+
+    def __init__(self, model, blocks, logical_params, device="cuda"):
+        self.model = model
+        self.blocks = list(blocks)
+        self.nb = B.num_blocks(model)
+        self.keys = [-1] + self.blocks + [self.nb]
+        self.device = device
+        self.params = [torch.from_numpy(B.pack_block(model, k, logical_params[k])).to(device)
+                       for k in self.keys]
+
+    def download(self):
+        """-> {key: {name: logical array}} of the current parameter buffers."""
+        return {k: B.unpack_block(self.model, k, p.cpu().numpy()) for k, p in zip(self.keys, self.params)}
+
+
+class SubResNet(DeviceModel):
+    """One worker's sub-ResNet: parameters, momentum, gradient buffers and workspace."""
+
+    def __init__(self, model, blocks, logical_params, batch, device="cuda", keep_grads=True):
+        super().__init__(model, blocks, logical_params, device)
+        self.batch = batch
+        sizes = [B.block_param_count(model, k)[1] for k in self.keys]
+        self.momentum = [torch.zeros(n, dtype=torch.float32, device=device) for n in sizes]
+        self.grads = ([torch.zeros(n, dtype=torch.float32, device=device) for n in sizes]
+                      if keep_grads else None)
+        self.workspace = torch.empty(B.workspace_bytes(model, self.blocks, batch), dtype=torch.uint8,
+                                     device=device)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=device)
+
+    def step(self, x, labels, lr, mu, wd, stream=None):
+        """x: device float32 [N,C,H,W]; labels: device int32 [N].  Asynchronous."""
+        assert x.shape[0] == self.batch and x.dtype == torch.float32 and labels.dtype == torch.int32
+        B.local_step(self.model, self.blocks, self.params, self.momentum, self.grads, x, labels,
+                     lr, mu, wd, self.workspace, self.loss, stream)
+
+    def download_grads(self):
+        return {k: B.unpack_block(self.model, k, g.cpu().numpy()) for k, g in zip(self.keys, self.grads)}
+
+    def download_momentum(self):
+        return {k: B.unpack_block(self.model, k, v.cpu().numpy()) for k, v in zip(self.keys, self.momentum)}
+
+    def reset_momentum(self):
+        for v in self.momentum:
+            v.zero_()
+
+
+def to_device_batch(x, labels, device="cuda"):
+    return (torch.from_numpy(np.ascontiguousarray(x, np.float32)).to(device),
+            torch.from_numpy(np.ascontiguousarray(labels, np.int32)).to(device))

@@ -1,0 +1,84 @@
+"""GPU parity: the convolution kernels, through the C ABI, against the oracle's direct
+convolution on the same seeded tensors (several tiles, ragged tails, both strides)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2107_00961_amd as R
+from oracle import layers as L
+from tests.gpu_util import assert_close
+
+pytestmark = pytest.mark.gpu
+
+#         N   H   W   C    K   R st pad
+CASES = [(2, 16, 16, 16, 16, 3, 1, 1),      # tiny config's block shape
+         (3, 12, 12, 64, 128, 3, 2, 1),     # stride 2, ragged M = 108
+         (4, 16, 16, 64, 64, 3, 1, 1),      # several M tiles
+         (2, 8, 8, 64, 256, 1, 1, 0),       # 1x1
+         (2, 8, 8, 64, 128, 1, 2, 0),       # 1x1 stride 2 (downsample shortcut)
+         (3, 10, 10, 32, 64, 1, 1, 0),      # stem-as-GEMM shape
+         (2, 6, 6, 48, 80, 3, 1, 1),        # channel counts that are not multiples of the K-chunk
+         (32, 32, 32, 64, 256, 3, 1, 1),    # large enough for the 128x128 tile
+         (2, 8, 8, 512, 512, 3, 1, 1),      # 128x128 weight-gradient tile
+         (5, 14, 14, 32, 32, 3, 2, 1)]      # stride 2 with odd output size 7
+
+
+def _tensors(case, seed=0):
+    N, H, W, C, K, RS, st, pad = case
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((N, C, H, W), dtype=np.float32)
+    w = (rng.standard_normal((K, C, RS, RS), dtype=np.float32) / np.sqrt(C * RS * RS)).astype(np.float32)
+    P, Q = (H + 2 * pad - RS) // st + 1, (W + 2 * pad - RS) // st + 1
+    dy = rng.standard_normal((N, K, P, Q), dtype=np.float32)
+    return x, w, dy
+
+
+def _nhwc(a):
+    return torch.from_numpy(np.ascontiguousarray(a.transpose(0, 2, 3, 1))).cuda()
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_conv_forward(case):
+    print("case", case, flush=True)
+    x, w, _ = _tensors(case)
+    st, pad = case[6], case[7]
+    y = R.conv2d_forward(_nhwc(x), _nhwc(w), st, pad)
+    torch.cuda.synchronize()
+    want = L.conv2d_fwd(x, w, st, pad)
+    assert_close(y.cpu().numpy().transpose(0, 3, 1, 2), want, f"conv fwd {case}")
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_conv_dgrad(case):
+    print("case", case, flush=True)
+    x, w, dy = _tensors(case, 1)
+    N, H, W, C, K, RS, st, pad = case
+    dx = R.conv2d_dgrad(_nhwc(dy), _nhwc(w), (N, H, W, C), st, pad)
+    torch.cuda.synchronize()
+    want = L.conv2d_dgrad(dy, w, x.shape, st, pad)
+    assert_close(dx.cpu().numpy().transpose(0, 3, 1, 2), want, f"conv dgrad {case}")
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_conv_wgrad(case):
+    print("case", case, flush=True)
+    x, w, dy = _tensors(case, 2)
+    N, H, W, C, K, RS, st, pad = case
+    # keep the sums O(1) so the absolute floor of the bound means what it means for real gradients:
+    # an fp32 sum of L products of O(1) terms carries an absolute error ~ sqrt(L) * 2^-24 * sqrt(L)
+    dy = (dy / np.sqrt(dy.shape[0] * dy.shape[2] * dy.shape[3])).astype(np.float32)
+    dw = R.conv2d_wgrad(_nhwc(dy), _nhwc(x), (K, RS, RS, C), st, pad)
+    torch.cuda.synchronize()
+    want = L.conv2d_wgrad(dy, x, w.shape, st, pad)
+    assert_close(dw.cpu().numpy().transpose(0, 3, 1, 2), want, f"conv wgrad {case}")
+
+
+def test_conv_rejects_bad_shapes():
+    x = torch.zeros((1, 4, 4, 6), device="cuda")
+    w = torch.zeros((8, 3, 3, 6), device="cuda")
+    with pytest.raises(R.ResistError):
+        R.conv2d_forward(x, w, 1, 1)          # C not a multiple of 4
+    x = torch.zeros((1, 5, 5, 8), device="cuda")
+    w = torch.zeros((8, 3, 3, 8), device="cuda")
+    with pytest.raises(R.ResistError):
+        R.conv2d_dgrad(torch.zeros((1, 3, 3, 8), device="cuda"), w, (1, 5, 5, 8), 2, 1)   # odd size, stride 2

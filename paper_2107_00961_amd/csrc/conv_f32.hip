@@ -10,6 +10,8 @@
 //   wgrad    dW[k][r][s][c]   = sum_{m=(n,p,q)} dY[m][k] * X[n, p*st+r-pad, q*st+s-pad, c]
 // Tiles are staged through LDS (double buffered, one barrier per K-chunk); every wave owns a
 // grid of 32x32 accumulator tiles held in registers.
+#include <type_traits>
+
 #include "internal.h"
 
 namespace resist {
@@ -20,8 +22,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kBK = 32;        // K-chunk (floats) staged per step
-constexpr int kLDK = kBK + 4;  // LDS row pitch for K-contiguous tiles (conflict-free b128 reads)
+constexpr int kStages = 2;     // LDS double buffering in the implicit-GEMM kernels
 
 struct IgemmArgs {
   const float *in;      // [N][IH][IW][IC]
@@ -41,14 +42,37 @@ struct IgemmArgs {
 constexpr int kFwd = 0;  // source pixel = out*stride + tap - pad
 constexpr int kBwd = 1;  // source pixel = (out + pad - tap) / stride
 
-template <int BM, int BN, int WGM, int WGN, int MODE>
+// Raw buffer descriptor over a tensor: loads whose byte offset is >= `bytes` return zero without
+// touching memory, which is how padding pixels, ragged tile rows and channel tails are filled.
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+constexpr unsigned kOOB = 0x80000000u;   // every tensor is smaller than 2 GiB (checked on the host)
+
+__device__ inline f32x4 buffer_load_f32x4(__amdgpu_buffer_rsrc_t r, unsigned voff) {
+  return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 0));
+}
+
+// BK: K-chunk (floats) staged per step; LDS rows are padded by 4 floats (conflict-free b128 reads).
+//
+// The K loop runs over (filter tap, channel chunk).  Its body is one straight-line block: the
+// source pixel of every tile row is (hc + dh, wc + dw) with per-row (hc, wc) fixed for the whole
+// kernel and per-tap scalars (dh, dw) kept in scalar registers, loads are hardware-bounds-checked
+// buffer loads (an invalid element is requested at an out-of-range offset and comes back as zero),
+// and the tap counters are advanced with selects.  With no branch in the loop the scheduler is free
+// to place the address arithmetic, the LDS traffic and the global loads in the shadow of the MFMAs.
+template <int BM, int BN, int BK, int WGM, int WGN, int MODE>
 __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
+  constexpr int LDK = BK + 4;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
   constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 MFMA tiles per wave
-  constexpr int PA = BM / 32, PB = BN / 32;      // load passes (32 rows per pass)
-  static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1, "4 waves");
-  __shared__ float As[2][BM][kLDK];
-  __shared__ float Bs[2][BN][kLDK];
+  constexpr int KV = BK / 4;                     // lanes per tile row (one float4 each)
+  constexpr int RPP = kThreads / KV;             // tile rows per load pass
+  constexpr int PA = BM / RPP, PB = BN / RPP;    // load passes
+  constexpr int NK = BK / 8;                     // k-steps (8 deep: 4 MFMAs per tile) per chunk
+  static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1 && PA >= 1 && PB >= 1, "tile shape");
+  __shared__ float As[kStages][BM][LDK];
+  __shared__ float Bs[kStages][BN][LDK];
   __shared__ int row_off[BM];
 
   const int tid = threadIdx.x;
@@ -60,38 +84,40 @@ __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
   const int tn = bid % a.tiles_n;
   bid /= a.tiles_n;
   const int tm = bid % a.tiles_m;
-  const int cidx = bid / a.tiles_m;  // parity class
+  const int cidx = bid / a.tiles_m;  // parity class (stride-2 data gradient only)
   const int ph = cidx / a.cls, pw = cidx % a.cls;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  // which filter taps contribute to this class (all of them unless MODE==kBwd with stride 2)
-  unsigned tapmask = 0;
-  int ntaps = 0;
-  for (int r = 0; r < a.R; ++r)
-    for (int s = 0; s < a.S; ++s) {
-      bool ok = true;
-      if (MODE == kBwd) ok = ((ph + a.pad - r) % a.stride == 0) && ((pw + a.pad - s) % a.stride == 0);
-      if (ok) { tapmask |= 1u << (r * a.S + s); ++ntaps; }
-    }
+  // filter taps that contribute: r = r0, r0+rstep, ... < R (all taps unless MODE==kBwd, stride 2)
+  int r0 = 0, s0 = 0, tstep = 1;
+  if (MODE == kBwd && a.stride == 2) { r0 = (ph + a.pad) & 1; s0 = (pw + a.pad) & 1; tstep = 2; }
+  const int nr = r0 < a.R ? (a.R - r0 + tstep - 1) / tstep : 0;
+  const int ns = s0 < a.S ? (a.S - s0 + tstep - 1) / tstep : 0;
+  const int cchunks = (a.IC + BK - 1) / BK;
+  const int nchunks = nr * ns * cchunks;
 
-  // per-thread source rows for the A gather
-  const int lrow = tid >> 3, kvec = (tid & 7) * 4;
-  int nbase[PA], hb[PA], wb[PA];
+  // per-thread tile rows: centre pixel (hc, wc) and byte offset of its first channel of interest
+  const int lrow = tid / KV, kvec = (tid % KV) * 4;
+  int hc[PA], wc[PA], aoff[PA], boff[PB];
 #pragma unroll
   for (int i = 0; i < PA; ++i) {
-    const int m = m0 + i * 32 + lrow;
+    const int m = m0 + i * RPP + lrow;
     if (m < a.Mrows) {
       const int n = m / (a.OHc * a.OWc);
       const int rem = m - n * (a.OHc * a.OWc);
-      const int oh = (rem / a.OWc) * a.cls + ph, ow = (rem % a.OWc) * a.cls + pw;
-      nbase[i] = n * a.IH * a.IW;
-      hb[i] = MODE == kFwd ? oh * a.stride - a.pad : oh + a.pad;
-      wb[i] = MODE == kFwd ? ow * a.stride - a.pad : ow + a.pad;
+      const int ohc = rem / a.OWc, owc = rem - ohc * a.OWc;
+      if (MODE == kFwd) { hc[i] = ohc * a.stride - a.pad; wc[i] = owc * a.stride - a.pad; }
+      else if (a.stride == 1) { hc[i] = ohc + a.pad; wc[i] = owc + a.pad; }
+      else { hc[i] = ohc; wc[i] = owc; }
+      aoff[i] = (((n * a.IH + hc[i]) * a.IW + wc[i]) * a.IC + kvec) * 4;
     } else {
-      nbase[i] = 0;
-      hb[i] = MODE == kFwd ? -(1 << 28) : -(1 << 28);
-      wb[i] = hb[i];
+      hc[i] = -(1 << 24); wc[i] = -(1 << 24); aoff[i] = 0;   // never in range
     }
+  }
+#pragma unroll
+  for (int i = 0; i < PB; ++i) {
+    const int oc = n0 + i * RPP + lrow;
+    boff[i] = oc < a.OC ? (oc * a.R * a.S * a.IC + kvec) * 4 : (int)kOOB;
   }
   for (int r = tid; r < BM; r += kThreads) {
     const int m = m0 + r;
@@ -105,8 +131,8 @@ __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
     row_off[r] = off;
   }
 
-  const int cchunks = (a.IC + kBK - 1) / kBK;
-  const int nchunks = ntaps * cchunks;
+  const __amdgpu_buffer_rsrc_t rin = make_rsrc(a.in, (unsigned)a.N * a.IH * a.IW * a.IC * 4u);
+  const __amdgpu_buffer_rsrc_t rwt = make_rsrc(a.wt, (unsigned)a.OC * a.R * a.S * a.IC * 4u);
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -116,83 +142,81 @@ __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+  // loop state of the chunk that will be requested next (uniform across the workgroup)
+  int tr = r0, ts = s0, tc = 0, issued = 0;
   f32x4 ra[PA], rb[PB];
-  int tap = -1, c0 = a.IC;  // iteration state; advance() moves to the first valid (tap, c0)
-  auto advance = [&]() {
-    c0 += kBK;
-    if (c0 >= a.IC) {
-      c0 = 0;
-      do { ++tap; } while (tap < 32 && !((tapmask >> tap) & 1u));
-    }
-  };
   auto load_global = [&]() {
-    const int r = tap / a.S, s = tap - r * a.S;
-    const bool kok = (c0 + kvec) < a.IC;
+    // tap scalars: source pixel displacement and the byte deltas of activation and filter
+    int dh, dw;
+    if (MODE == kFwd) { dh = tr; dw = ts; }
+    else if (a.stride == 1) { dh = -tr; dw = -ts; }
+    else { dh = (ph + a.pad - tr) >> 1; dw = (pw + a.pad - ts) >> 1; }   // even by construction
+    const bool live = issued < nchunks;
+    const int c0 = tc * BK;
+    const int adelta = ((dh * a.IW + dw) * a.IC + c0) * 4;
+    const int bdelta = ((tr * a.S + ts) * a.IC + c0) * 4;
+    const bool kok = live && (c0 + kvec) < a.IC;
 #pragma unroll
     for (int i = 0; i < PA; ++i) {
-      int ih, iw;
-      bool ok;
-      if (MODE == kFwd) {
-        ih = hb[i] + r; iw = wb[i] + s;
-        ok = ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
-      } else {
-        const int th = hb[i] - r, tw = wb[i] - s;
-        ih = th / a.stride; iw = tw / a.stride;   // exact by construction of the tap mask
-        ok = th >= 0 && tw >= 0 && ih < a.IH && iw < a.IW;
-      }
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (ok && kok)
-        v = *reinterpret_cast<const f32x4 *>(a.in + (size_t)(nbase[i] + ih * a.IW + iw) * a.IC + c0 + kvec);
-      ra[i] = v;
+      const bool ok = kok && (unsigned)(hc[i] + dh) < (unsigned)a.IH && (unsigned)(wc[i] + dw) < (unsigned)a.IW;
+      ra[i] = buffer_load_f32x4(rin, ok ? (unsigned)(aoff[i] + adelta) : kOOB);
     }
 #pragma unroll
-    for (int i = 0; i < PB; ++i) {
-      const int oc = n0 + i * 32 + lrow;
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (oc < a.OC && kok)
-        v = *reinterpret_cast<const f32x4 *>(a.wt + ((size_t)(oc * a.R + r) * a.S + s) * a.IC + c0 + kvec);
-      rb[i] = v;
-    }
+    for (int i = 0; i < PB; ++i) rb[i] = buffer_load_f32x4(rwt, kok ? (unsigned)(boff[i] + bdelta) : kOOB);
+    // advance (tap, channel chunk) without branches
+    ++issued;
+    const bool cwrap = (tc + 1 == cchunks);
+    tc = cwrap ? 0 : tc + 1;
+    const bool swrap = cwrap && (ts + tstep >= a.S);
+    ts = cwrap ? (swrap ? s0 : ts + tstep) : ts;
+    tr = swrap ? tr + tstep : tr;
   };
-  auto store_lds = [&](int buf) {
+  auto store_lds = [&](int stage) {
 #pragma unroll
-    for (int i = 0; i < PA; ++i) *reinterpret_cast<f32x4 *>(&As[buf][i * 32 + lrow][kvec]) = ra[i];
+    for (int i = 0; i < PA; ++i) *reinterpret_cast<f32x4 *>(&As[stage][i * RPP + lrow][kvec]) = ra[i];
 #pragma unroll
-    for (int i = 0; i < PB; ++i) *reinterpret_cast<f32x4 *>(&Bs[buf][i * 32 + lrow][kvec]) = rb[i];
+    for (int i = 0; i < PB; ++i) *reinterpret_cast<f32x4 *>(&Bs[stage][i * RPP + lrow][kvec]) = rb[i];
   };
 
-  if (nchunks > 0) {
-    advance();
-    load_global();
-    store_lds(0);
-  }
+  // prologue: chunk 0 into LDS stage 0, chunk 1 on its way in registers
+  load_global();
+  store_lds(0);
+  load_global();
   __syncthreads();
 
+  // Chunk `it` is multiplied out of stage it&1.  Half way through, the registers holding chunk it+1
+  // (requested one chunk of MFMA time earlier) go to the other stage and chunk it+2 is requested;
+  // fragments of k-step ks+1 are fetched from LDS before the MFMAs of k-step ks.
   const int lr = lane & 31, lk = (lane >> 5) * 4;
   for (int it = 0; it < nchunks; ++it) {
-    const int buf = it & 1;
-    if (it + 1 < nchunks) {
-      advance();
-      load_global();
-    }
+    const int stage = it & 1;
+    f32x4 fa[2][TM], fb[2][TN];
 #pragma unroll
-    for (int ks = 0; ks < kBK / 8; ++ks) {
-      f32x4 fa[TM], fb[TN];
+    for (int i = 0; i < TM; ++i) fa[0][i] = *reinterpret_cast<const f32x4 *>(&As[stage][wm * WTM + i * 32 + lr][lk]);
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        fa[i] = *reinterpret_cast<const f32x4 *>(&As[buf][wm * WTM + i * 32 + lr][ks * 8 + lk]);
+    for (int j = 0; j < TN; ++j) fb[0][j] = *reinterpret_cast<const f32x4 *>(&Bs[stage][wn * WTN + j * 32 + lr][lk]);
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        fb[j] = *reinterpret_cast<const f32x4 *>(&Bs[buf][wn * WTN + j * 32 + lr][ks * 8 + lk]);
+    for (int ks = 0; ks < NK; ++ks) {
+      if (ks + 1 < NK) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+          fa[(ks + 1) & 1][i] = *reinterpret_cast<const f32x4 *>(&As[stage][wm * WTM + i * 32 + lr][(ks + 1) * 8 + lk]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          fb[(ks + 1) & 1][j] = *reinterpret_cast<const f32x4 *>(&Bs[stage][wn * WTN + j * 32 + lr][(ks + 1) * 8 + lk]);
+      }
+      if (ks == NK / 2) {
+        store_lds(stage ^ 1);   // past the last chunk this writes zeros nobody reads
+        load_global();
+      }
 #pragma unroll
       for (int e = 0; e < 4; ++e)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][e], fb[j][e], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[ks & 1][i][e], fb[ks & 1][j][e], acc[i][j], 0, 0, 0);
     }
-    if (it + 1 < nchunks) store_lds(buf ^ 1);
     __syncthreads();
   }
 
@@ -216,19 +240,19 @@ __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE>
+template <int BM, int BN, int BK, int WGM, int WGN, int MODE>
 int launch_igemm(IgemmArgs a, hipStream_t st) {
   a.tiles_m = (a.Mrows + BM - 1) / BM;
   a.tiles_n = (a.OC + BN - 1) / BN;
   const long long grid = (long long)a.tiles_m * a.tiles_n * a.cls * a.cls;
   if (grid <= 0 || grid > 0x7fffffffLL) return set_error(RESIST_ESHAPE, "igemm grid %lld", grid);
   {
-    static const std::string label = std::string(MODE == kFwd ? "igemm_f32_fwd_" : "igemm_f32_bwd_") + std::to_string(BM) + "x" + std::to_string(BN);
+    static const std::string label = std::string(MODE == kFwd ? "igemm_f32_fwd_" : "igemm_f32_bwd_") + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK);
     // algorithmic work of the convolution this launch computes (forward or data gradient)
     const double flops = 2.0 * a.N * (MODE == kFwd ? (double)a.OH * a.OW : (double)a.IH * a.IW) * a.OC * a.IC * a.R * a.S;
     const double bytes = 4.0 * ((double)a.N * a.IH * a.IW * a.IC + (double)a.N * a.OH * a.OW * a.OC * (a.addend ? 2 : 1) + (double)a.OC * a.R * a.S * a.IC);
     prof::Scope ps(label.c_str(), flops, bytes, st);
-    hipLaunchKernelGGL((igemm_f32_kernel<BM, BN, WGM, WGN, MODE>), dim3((unsigned)grid), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((igemm_f32_kernel<BM, BN, BK, WGM, WGN, MODE>), dim3((unsigned)grid), dim3(kThreads), 0, st, a);
   }
   RESIST_CHECK_LAUNCH("igemm_f32");
   return RESIST_OK;
@@ -241,9 +265,10 @@ int dispatch_igemm(const IgemmArgs &a, hipStream_t st) {
   auto tiles = [&](int bm, int bn) {
     return (long long)((a.Mrows + bm - 1) / bm) * ((a.OC + bn - 1) / bn) * classes;
   };
-  if (a.OC > 64 && tiles(128, 128) >= 512) return launch_igemm<128, 128, 2, 2, MODE>(a, st);
-  if (tiles(128, 64) >= 512) return launch_igemm<128, 64, 2, 2, MODE>(a, st);
-  return launch_igemm<64, 64, 2, 2, MODE>(a, st);
+  if (a.OC > 64 && tiles(128, 128) >= 512) return launch_igemm<128, 128, 32, 2, 2, MODE>(a, st);
+  if (tiles(128, 64) >= 512) return launch_igemm<128, 64, 32, 2, 2, MODE>(a, st);
+  if (a.IC % 64 == 0) return launch_igemm<64, 64, 64, 2, 2, MODE>(a, st);
+  return launch_igemm<64, 64, 32, 2, 2, MODE>(a, st);
 }
 
 int check_geom(const ConvGeom &g) {
@@ -254,10 +279,10 @@ int check_geom(const ConvGeom &g) {
   if (g.stride < 1 || g.stride > 2 || g.pad < 0 || g.pad >= g.R)
     return set_error(RESIST_ESHAPE, "stride %d pad %d unsupported", g.stride, g.pad);
   if (g.P < 1 || g.Q < 1) return set_error(RESIST_ESHAPE, "empty convolution output");
-  const long long lim = 0x7fffffffLL;
+  const long long lim = 0x1fffffffLL;   // 2 GiB of fp32: byte offsets stay below the out-of-range marker
   if ((long long)g.N * g.H * g.W * g.C > lim || (long long)g.N * g.P * g.Q * g.K > lim ||
       (long long)g.K * g.R * g.S * g.C > lim)
-    return set_error(RESIST_ESHAPE, "tensor exceeds 2^31 elements");
+    return set_error(RESIST_ESHAPE, "tensor exceeds 2^29 elements");
   return RESIST_OK;
 }
 
@@ -322,6 +347,8 @@ int transpose_filter_f32(const ConvGeom &g, const float *w, float *wT, hipStream
 // ---- wgrad --------------------------------------------------------------------------------------
 namespace {
 
+constexpr int kWBK = 32;  // reduction rows staged per step
+
 struct WgradArgs {
   const float *dy;  // [M][K]
   const float *x;   // [N][H][W][C]
@@ -339,9 +366,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_f32_kernel(WgradArgs a) {
   constexpr int LDA = BM + 32, LDB = BN + 32;   // rows kk and kk+1 land on different bank halves
   constexpr int TPRA = BM / 4, TPRB = BN / 4;   // threads per 32-row-chunk row
   constexpr int RPA = kThreads / TPRA, RPB = kThreads / TPRB;  // rows per pass
-  constexpr int PA = kBK / RPA, PB = kBK / RPB;
-  __shared__ float As[2][kBK][LDA];
-  __shared__ float Bs[2][kBK][LDB];
+  constexpr int PA = kWBK / RPA, PB = kWBK / RPB;
+  __shared__ float As[2][kWBK][LDA];
+  __shared__ float Bs[2][kWBK][LDB];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
@@ -351,7 +378,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_f32_kernel(WgradArgs a) {
   const int k0 = tk * BM, c0 = tc * BN;
   const int mbeg = split * a.rows_per_split;
   const int mend = min(a.M, mbeg + a.rows_per_split);
-  const int nchunks = (mend - mbeg + kBK - 1) / kBK;
+  const int nchunks = (mend - mbeg + kWBK - 1) / kWBK;
 
   const int arow = tid / TPRA, acol = (tid % TPRA) * 4;
   const int brow = tid / TPRB, bcol = (tid % TPRB) * 4;
@@ -403,9 +430,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_f32_kernel(WgradArgs a) {
   const int lr = lane & 31, lh = lane >> 5;
   for (int it = 0; it < nchunks; ++it) {
     const int buf = it & 1;
-    if (it + 1 < nchunks) load_global(mbeg + (it + 1) * kBK);
+    if (it + 1 < nchunks) load_global(mbeg + (it + 1) * kWBK);
 #pragma unroll
-    for (int kk = 0; kk < kBK; kk += 2) {
+    for (int kk = 0; kk < kWBK; kk += 2) {
       float fa[TM], fb[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i) fa[i] = As[buf][kk + lh][wm * WTM + i * 32 + lr];
@@ -459,7 +486,7 @@ WgradPlan plan_wgrad(const ConvGeom &g) {
   if (splits < 1) splits = 1;
   if (splits > 256) splits = 256;
   long long rps = (M + splits - 1) / splits;
-  rps = (rps + kBK - 1) / kBK * kBK;
+  rps = (rps + kWBK - 1) / kWBK * kWBK;
   p.rows_per_split = (int)rps;
   p.splits = (int)((M + rps - 1) / rps);
   return p;

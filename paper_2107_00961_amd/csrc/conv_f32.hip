@@ -349,6 +349,18 @@ namespace {
 
 constexpr int kWBK = 32;  // reduction rows staged per step
 
+// division by a runtime constant: q = (n * mul) >> sh, exact for 0 <= n < 2^31
+struct FastDiv { unsigned mul; int sh; };
+inline FastDiv make_fastdiv(unsigned d) {
+  int L = 0;
+  while ((1ull << L) < d) ++L;
+  FastDiv f;
+  f.sh = 31 + L;
+  f.mul = (unsigned)((1ull << f.sh) / d + 1);
+  return f;
+}
+__device__ inline int fdiv(int n, FastDiv f) { return (int)(((unsigned long long)(unsigned)n * f.mul) >> f.sh); }
+
 struct WgradArgs {
   const float *dy;  // [M][K]
   const float *x;   // [N][H][W][C]
@@ -357,8 +369,14 @@ struct WgradArgs {
   int M;            // N*P*Q
   int rows_per_split;
   int tiles_k, tiles_c;
+  FastDiv div_pq, div_q;
 };
 
+// Weight gradient: rows of the GEMM are output channels, columns are input channels of one filter
+// tap (blockIdx.y), the reduction runs over output pixels m (split over blockIdx.z).  Both operand
+// tiles arrive "reduction-major" ([m][channel]) straight from the NHWC tensors.  Same pipeline as
+// the forward kernel: straight-line loop body, bounds-checked buffer loads, LDS refill in the
+// middle of the MFMAs, fragments fetched one k-step ahead.
 template <int BM, int BN, int WGM, int WGN>
 __global__ __launch_bounds__(kThreads) void wgrad_f32_kernel(WgradArgs a) {
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -367,6 +385,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_f32_kernel(WgradArgs a) {
   constexpr int TPRA = BM / 4, TPRB = BN / 4;   // threads per 32-row-chunk row
   constexpr int RPA = kThreads / TPRA, RPB = kThreads / TPRB;  // rows per pass
   constexpr int PA = kWBK / RPA, PB = kWBK / RPB;
+  constexpr int NK = kWBK / 2;
   __shared__ float As[2][kWBK][LDA];
   __shared__ float Bs[2][kWBK][LDB];
 
@@ -382,6 +401,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_f32_kernel(WgradArgs a) {
 
   const int arow = tid / TPRA, acol = (tid % TPRA) * 4;
   const int brow = tid / TPRB, bcol = (tid % TPRB) * 4;
+  const unsigned acolb = (k0 + acol) < a.K ? (unsigned)(k0 + acol) * 4u : kOOB;
+  const unsigned bcolb = (c0 + bcol) < a.C ? (unsigned)(c0 + bcol) * 4u : kOOB;
+  const __amdgpu_buffer_rsrc_t rdy = make_rsrc(a.dy, (unsigned)a.M * a.K * 4u);
+  const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (unsigned)a.N * a.H * a.W * a.C * 4u);
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -392,59 +415,62 @@ __global__ __launch_bounds__(kThreads) void wgrad_f32_kernel(WgradArgs a) {
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   f32x4 ra[PA], rb[PB];
-  auto load_global = [&](int mc) {
+  int mc = mbeg;   // first reduction row of the chunk requested next
+  auto load_global = [&]() {
 #pragma unroll
     for (int i = 0; i < PA; ++i) {
       const int m = mc + i * RPA + arow;
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (m < mend && k0 + acol < a.K) v = *reinterpret_cast<const f32x4 *>(a.dy + (size_t)m * a.K + k0 + acol);
-      ra[i] = v;
+      ra[i] = buffer_load_f32x4(rdy, m < mend ? (unsigned)m * (unsigned)a.K * 4u + acolb : kOOB);
     }
 #pragma unroll
     for (int i = 0; i < PB; ++i) {
       const int m = mc + i * RPB + brow;
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (m < mend && c0 + bcol < a.C) {
-        const int n = m / (a.P * a.Q);
-        const int rem = m - n * (a.P * a.Q);
-        const int p = rem / a.Q, q = rem - p * a.Q;
-        const int ih = p * a.stride + r - a.pad, iw = q * a.stride + s - a.pad;
-        if (ih >= 0 && ih < a.H && iw >= 0 && iw < a.W)
-          v = *reinterpret_cast<const f32x4 *>(a.x + ((size_t)(n * a.H + ih) * a.W + iw) * a.C + c0 + bcol);
-      }
-      rb[i] = v;
+      const int n = fdiv(m, a.div_pq);
+      const int rem = m - n * (a.P * a.Q);
+      const int p = fdiv(rem, a.div_q), q = rem - p * a.Q;
+      const int ih = p * a.stride + r - a.pad, iw = q * a.stride + s - a.pad;
+      const bool ok = m < mend && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+      rb[i] = buffer_load_f32x4(rx, ok ? (unsigned)((n * a.H + ih) * a.W + iw) * (unsigned)a.C * 4u + bcolb : kOOB);
     }
+    mc += kWBK;
   };
-  auto store_lds = [&](int buf) {
+  auto store_lds = [&](int stage) {
 #pragma unroll
-    for (int i = 0; i < PA; ++i) *reinterpret_cast<f32x4 *>(&As[buf][i * RPA + arow][acol]) = ra[i];
+    for (int i = 0; i < PA; ++i) *reinterpret_cast<f32x4 *>(&As[stage][i * RPA + arow][acol]) = ra[i];
 #pragma unroll
-    for (int i = 0; i < PB; ++i) *reinterpret_cast<f32x4 *>(&Bs[buf][i * RPB + brow][bcol]) = rb[i];
+    for (int i = 0; i < PB; ++i) *reinterpret_cast<f32x4 *>(&Bs[stage][i * RPB + brow][bcol]) = rb[i];
   };
 
-  if (nchunks > 0) {
-    load_global(mbeg);
-    store_lds(0);
-  }
+  load_global();
+  store_lds(0);
+  load_global();
   __syncthreads();
   const int lr = lane & 31, lh = lane >> 5;
   for (int it = 0; it < nchunks; ++it) {
-    const int buf = it & 1;
-    if (it + 1 < nchunks) load_global(mbeg + (it + 1) * kWBK);
+    const int stage = it & 1;
+    float fa[2][TM], fb[2][TN];
 #pragma unroll
-    for (int kk = 0; kk < kWBK; kk += 2) {
-      float fa[TM], fb[TN];
+    for (int i = 0; i < TM; ++i) fa[0][i] = As[stage][lh][wm * WTM + i * 32 + lr];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = As[buf][kk + lh][wm * WTM + i * 32 + lr];
+    for (int j = 0; j < TN; ++j) fb[0][j] = Bs[stage][lh][wn * WTN + j * 32 + lr];
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = Bs[buf][kk + lh][wn * WTN + j * 32 + lr];
+    for (int ks = 0; ks < NK; ++ks) {
+      if (ks + 1 < NK) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[(ks + 1) & 1][i] = As[stage][(ks + 1) * 2 + lh][wm * WTM + i * 32 + lr];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[(ks + 1) & 1][j] = Bs[stage][(ks + 1) * 2 + lh][wn * WTN + j * 32 + lr];
+      }
+      if (ks == NK / 2) {
+        store_lds(stage ^ 1);   // rows past mend were loaded as zeros
+        load_global();
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
     }
-    if (it + 1 < nchunks) store_lds(buf ^ 1);
     __syncthreads();
   }
 
@@ -512,6 +538,8 @@ int conv_wgrad_f32(const ConvGeom &g, const float *dy, const float *x, float *dw
   a.rows_per_split = p.rows_per_split;
   a.tiles_k = (g.K + p.bm - 1) / p.bm;
   a.tiles_c = (g.C + p.bn - 1) / p.bn;
+  a.div_pq = make_fastdiv((unsigned)(g.P * g.Q));
+  a.div_q = make_fastdiv((unsigned)g.Q);
   dim3 grid(a.tiles_k * a.tiles_c, g.R * g.S, p.splits);
   {
     const double flops = 2.0 * a.M * g.K * g.C * g.R * g.S;

@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--workload", default="cfg2", help="cfg1 | cfg2 | cfg3 | cfg5 (fp32 workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=32)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device copy (reference point for HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the S sub-ResNets are stepped sequentially on it "
@@ -60,6 +62,12 @@ def main():
     lr, mu, wd = cfg["lr"] * 0.01, cfg["momentum"], cfg["weight_decay"]   # small lr: many steps on one batch stay finite
     stream = torch.cuda.current_stream()
 
+    if args.calibrate_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         sub.step(xd, yd, lr, mu, wd, stream)
     torch.cuda.synchronize()

@@ -42,6 +42,15 @@ struct IgemmArgs {
 constexpr int kFwd = 0;  // source pixel = out*stride + tap - pad
 constexpr int kBwd = 1;  // source pixel = (out + pad - tap) / stride
 
+// Workgroups are handed to the 8 XCDs round-robin by their linear id, and each XCD has its own L2.
+// This maps the hardware id to a logical tile index such that every XCD works on one contiguous
+// range of logical tiles, so tiles that share operand rows meet in the same L2.
+__device__ inline int xcd_contiguous(int hw_id, int total) {
+  const int xcd = hw_id & 7, slot = hw_id >> 3;
+  const int base = total >> 3, rem = total & 7;
+  return xcd * base + (xcd < rem ? xcd : rem) + slot;
+}
+
 // Raw buffer descriptor over a tensor: loads whose byte offset is >= `bytes` return zero without
 // touching memory, which is how padding pixels, ragged tile rows and channel tails are filled.
 __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, unsigned bytes) {
@@ -80,11 +89,14 @@ __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
   const int wm = wave / WGN, wn = wave % WGN;
 
   // tile coordinates: N-tiles fastest so that tiles sharing the same input rows run together
-  int bid = blockIdx.x;
+  // Logical tile order: N-tiles fastest, so tiles sharing input rows are neighbours; each XCD gets a
+  // contiguous range of them.  The stride-2 data gradient (4 parity classes of unequal work, class
+  // slowest) keeps the hardware round-robin order, which measured faster for its short K loops.
+  int bid = a.cls == 1 ? xcd_contiguous(blockIdx.x, gridDim.x) : (int)blockIdx.x;
   const int tn = bid % a.tiles_n;
   bid /= a.tiles_n;
   const int tm = bid % a.tiles_m;
-  const int cidx = bid / a.tiles_m;  // parity class (stride-2 data gradient only)
+  const int cidx = bid / a.tiles_m;  // parity class
   const int ph = cidx / a.cls, pw = cidx % a.cls;
   const int m0 = tm * BM, n0 = tn * BN;
 
@@ -391,8 +403,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_f32_kernel(WgradArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  const int tk = blockIdx.x / a.tiles_c, tc = blockIdx.x % a.tiles_c;
-  const int tap = blockIdx.y, split = blockIdx.z;
+  // order: tile fastest, then filter tap, then reduction split
+  int bid = blockIdx.x;
+  const int tile = bid % (a.tiles_k * a.tiles_c);
+  bid /= a.tiles_k * a.tiles_c;
+  const int tap = bid % (a.R * a.S), split = bid / (a.R * a.S);
+  const int tk = tile / a.tiles_c, tc = tile % a.tiles_c;
   const int r = tap / a.S, s = tap - r * a.S;
   const int k0 = tk * BM, c0 = tc * BN;
   const int mbeg = split * a.rows_per_split;
@@ -540,7 +556,7 @@ int conv_wgrad_f32(const ConvGeom &g, const float *dy, const float *x, float *dw
   a.tiles_c = (g.C + p.bn - 1) / p.bn;
   a.div_pq = make_fastdiv((unsigned)(g.P * g.Q));
   a.div_q = make_fastdiv((unsigned)g.Q);
-  dim3 grid(a.tiles_k * a.tiles_c, g.R * g.S, p.splits);
+  dim3 grid((unsigned)(a.tiles_k * a.tiles_c * g.R * g.S * p.splits));
   {
     const double flops = 2.0 * a.M * g.K * g.C * g.R * g.S;
     const double bytes = 4.0 * ((double)a.M * g.K + (double)g.N * g.H * g.W * g.C + (double)g.K * g.R * g.S * g.C);

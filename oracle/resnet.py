@@ -15,12 +15,20 @@ Network (post-activation blocks, the benchmark configurations' layer list):
 Update (momentum per the paper's experimental section; form is the usual one):
   g <- g + wd*w ; v <- mu*v + g ; w <- w - lr*v   (every trainable parameter alike)
 Parameters are dicts keyed -1 (stem), b (block), B (head) of logical-layout arrays.
+Optional bfloat16 storage (the ImageNet-shaped configuration: "bf16 activations/weights with fp32
+accumulation and fp32 master weights"): with emulate_bf16=True every tensor that configuration keeps
+in bfloat16 is rounded where it is stored -- the input image and the filters as convolution operands,
+every convolution output, every BN(+ReLU, +shortcut) output, every activation gradient (after the
+mean-pool, max-pool, BN and convolution data-gradient steps; the shortcut's gradient is stored before
+it is added to the branch's).  Statistics, weight gradients, the head, the loss and the update are
+not rounded.  With emulate_bf16=False (default) nothing is rounded.
 Pins: tests/test_oracle_step.py (finite differences of the loss w.r.t. every parameter,
 a float64 autograd library as third opinion, SGD closed form, all-blocks == full model).
 """
 import numpy as np
 
 from . import layers as L
+from . import quant as Q
 
 
 def block_table(model):
@@ -73,27 +81,33 @@ class _Tape:
         self.stats = {}      # (block, bn name) -> (mean, biased var, m)
 
 
-def _conv_bn(x, p, conv, bn, stride, pad, eps, relu, tape, key):
-    y = L.conv2d_fwd(x, p[conv + "_w"], stride, pad)
+def _conv_bn(x, p, conv, bn, stride, pad, eps, relu, tape, key, q):
+    """q: storage rounding of activations and convolution operands (identity unless bf16 is emulated).
+    The BN output is returned unrounded when it ends a block (relu=False): the caller adds the
+    shortcut first and rounds the sum."""
+    wq = q(p[conv + "_w"])
+    y = q(L.conv2d_fwd(x, wq, stride, pad))
     z, cache = L.bn_fwd(y, p[bn + "_g"].astype(np.float64), p[bn + "_b"].astype(np.float64), eps)
     m = y.shape[0] * y.shape[2] * y.shape[3]
     tape.stats[(key, bn)] = (cache[2], cache[3], m)
-    a = np.maximum(z, 0.0) if relu else z
-    return a, dict(x=x, cache=cache, z=z, conv=conv, bn=bn, stride=stride, pad=pad, relu=relu)
+    a = q(np.maximum(z, 0.0)) if relu else z
+    return a, dict(x=x, cache=cache, z=z, conv=conv, bn=bn, stride=stride, pad=pad, relu=relu, wq=wq)
 
 
-def _conv_bn_bwd(da, ctx, p, grads):
+def _conv_bn_bwd(da, ctx, p, grads, q):
     """da: gradient w.r.t. the (post-ReLU if relu) output.  ReLU'(0) = 0."""
     dz = da * (ctx["z"] > 0) if ctx["relu"] else da
     dy, dg, db = L.bn_bwd(dz, ctx["cache"], p[ctx["bn"] + "_g"].astype(np.float64))
+    dy = q(dy)
     grads[ctx["bn"] + "_g"] = dg
     grads[ctx["bn"] + "_b"] = db
-    w = p[ctx["conv"] + "_w"]
+    w = ctx["wq"]
     grads[ctx["conv"] + "_w"] = L.conv2d_wgrad(dy, ctx["x"], w.shape, ctx["stride"], ctx["pad"])
     return dy, w
 
 
-def forward_backward(model, blocks, params, x, labels, need_input_grad=False, backward=True):
+def forward_backward(model, blocks, params, x, labels, need_input_grad=False, backward=True,
+                     emulate_bf16=False):
     """Loss and gradients of the sub-ResNet made of `blocks` (ascending global indices).
 
     Returns loss, grads (same keys as params, trainable tensors only), tape (batch statistics),
@@ -103,34 +117,35 @@ def forward_backward(model, blocks, params, x, labels, need_input_grad=False, ba
     B = len(tab)
     eps = model["bn_eps"]
     tape = _Tape()
-    x = np.asarray(x, np.float64)
+    q = Q.round_bf16 if emulate_bf16 else Q.identity
+    x = q(np.asarray(x, np.float64))
     # ---- forward
     st = params[-1]
     if model["stem_kind"] == 0:
-        a, stem_ctx = _conv_bn(x, st, "conv", "bn", 1, 1, eps, True, tape, -1)
+        a, stem_ctx = _conv_bn(x, st, "conv", "bn", 1, 1, eps, True, tape, -1, q)
         pool_cache = None
     else:
-        a, stem_ctx = _conv_bn(x, st, "conv", "bn", 2, 3, eps, True, tape, -1)
+        a, stem_ctx = _conv_bn(x, st, "conv", "bn", 2, 3, eps, True, tape, -1, q)
         a, pool_cache = L.maxpool_fwd(a, 3, 2, 1)
     ctxs = []
     for b in blocks:
         t, p = tab[b], params[b]
         inp = a
         if model["block_kind"] == 0:
-            h, c1 = _conv_bn(inp, p, "conv1", "bn1", t["stride"], 1, eps, True, tape, b)
-            h, c2 = _conv_bn(h, p, "conv2", "bn2", 1, 1, eps, False, tape, b)
+            h, c1 = _conv_bn(inp, p, "conv1", "bn1", t["stride"], 1, eps, True, tape, b, q)
+            h, c2 = _conv_bn(h, p, "conv2", "bn2", 1, 1, eps, False, tape, b, q)
             chain = [c1, c2]
         else:
-            h, c1 = _conv_bn(inp, p, "conv1", "bn1", 1, 0, eps, True, tape, b)
-            h, c2 = _conv_bn(h, p, "conv2", "bn2", t["stride"], 1, eps, True, tape, b)
-            h, c3 = _conv_bn(h, p, "conv3", "bn3", 1, 0, eps, False, tape, b)
+            h, c1 = _conv_bn(inp, p, "conv1", "bn1", 1, 0, eps, True, tape, b, q)
+            h, c2 = _conv_bn(h, p, "conv2", "bn2", t["stride"], 1, eps, True, tape, b, q)
+            h, c3 = _conv_bn(h, p, "conv3", "bn3", 1, 0, eps, False, tape, b, q)
             chain = [c1, c2, c3]
         if t["has_ds"]:
-            sc, cd = _conv_bn(inp, p, "ds", "dsbn", t["stride"], 0, eps, False, tape, b)
+            sc, cd = _conv_bn(inp, p, "ds", "dsbn", t["stride"], 0, eps, False, tape, b, q)
         else:
             sc, cd = inp, None
         pre = h + sc
-        a = np.maximum(pre, 0.0)
+        a = q(np.maximum(pre, 0.0))
         ctxs.append((b, chain, cd, pre))
     feat_shape = a.shape
     pooled = L.avgpool_fwd(a)
@@ -143,26 +158,28 @@ def forward_backward(model, blocks, params, x, labels, need_input_grad=False, ba
     grads = {}
     dpooled, dw, db = L.fc_bwd(dz, pooled, hd["fc_w"].astype(np.float64))
     grads[B] = {"fc_w": dw, "fc_b": db}
-    g = L.avgpool_bwd(dpooled, feat_shape)
+    g = q(L.avgpool_bwd(dpooled, feat_shape))
     for b, chain, cd, pre in reversed(ctxs):
         t, p = tab[b], params[b]
         gb = {}
         gpre = g * (pre > 0)
         d = gpre
         for ctx in reversed(chain):
-            dy, w = _conv_bn_bwd(d, ctx, p, gb)
+            dy, w = _conv_bn_bwd(d, ctx, p, gb, q)
             d = L.conv2d_dgrad(dy, w, ctx["x"].shape, ctx["stride"], ctx["pad"])
+            if ctx is not chain[0]:
+                d = q(d)
         if cd is not None:
-            dy, w = _conv_bn_bwd(gpre, cd, p, gb)
-            d = d + L.conv2d_dgrad(dy, w, cd["x"].shape, cd["stride"], cd["pad"])
+            dy, w = _conv_bn_bwd(gpre, cd, p, gb, q)
+            d = d + q(L.conv2d_dgrad(dy, w, cd["x"].shape, cd["stride"], cd["pad"]))
         else:
             d = d + gpre
-        g = d
+        g = q(d)
         grads[b] = gb
     gs = {}
     if pool_cache is not None:
-        g = L.maxpool_bwd(g, pool_cache)
-    dy, w = _conv_bn_bwd(g, stem_ctx, st, gs)
+        g = q(L.maxpool_bwd(g, pool_cache))
+    dy, w = _conv_bn_bwd(g, stem_ctx, st, gs, q)
     grads[-1] = gs
     dx = None
     if need_input_grad:
@@ -185,13 +202,13 @@ def sgd_update(params, momentum_buf, grads, lr, mu, wd):
     return new_p, new_v
 
 
-def local_step(model, blocks, params, momentum_buf, x, labels, lr, mu, wd):
+def local_step(model, blocks, params, momentum_buf, x, labels, lr, mu, wd, emulate_bf16=False):
     """One local SGD iteration of the sub-ResNet holding `blocks`.
 
     params / momentum_buf need entries for -1, every b in blocks, and B.
     Returns loss, grads, new_params (incl. updated BN running statistics), new_momentum.
     """
-    loss, grads, tape, _ = forward_backward(model, blocks, params, x, labels)
+    loss, grads, tape, _ = forward_backward(model, blocks, params, x, labels, emulate_bf16=emulate_bf16)
     new_p, new_v = sgd_update(params, momentum_buf, grads, lr, mu, wd)
     mom = model["bn_momentum"]
     for (b, bn), (mean, var, m) in tape.stats.items():

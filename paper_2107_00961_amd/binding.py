@@ -242,6 +242,16 @@ def _conv_shape(N, H, W, Cc, K, R, stride, pad, dtype=0):
     return _ConvShape(N, H, W, Cc, K, R, R, stride, pad, dtype)
 
 
+def _dtype_code(t):
+    """torch dtype of an activation tensor -> the library's dtype code (0 fp32, 1 bf16)."""
+    import torch
+    if t.dtype == torch.float32:
+        return 0
+    if t.dtype == torch.bfloat16:
+        return 1
+    raise ResistError(f"unsupported tensor dtype {t.dtype}")
+
+
 def _conv_ws(shape):
     import torch
     n = C.c_int64()
@@ -250,13 +260,13 @@ def _conv_ws(shape):
 
 
 def conv2d_forward(x, w, stride, pad, stream=None):
-    """x [N,H,W,C], w [K,R,S,C] device tensors -> y [N,P,Q,K]."""
+    """x [N,H,W,C], w [K,R,S,C] device tensors (both float32 or both bfloat16) -> y [N,P,Q,K]."""
     import torch
     N, H, W, Cc = x.shape
     K, R = w.shape[0], w.shape[1]
     P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
     y = torch.empty((N, P, Q, K), dtype=x.dtype, device=x.device)
-    sh = _conv_shape(N, H, W, Cc, K, R, stride, pad)
+    sh = _conv_shape(N, H, W, Cc, K, R, stride, pad, _dtype_code(x))
     ws = _conv_ws(sh)
     _check(lib().resist_conv2d_forward(C.byref(sh), x.data_ptr(), w.data_ptr(), y.data_ptr(),
                                        ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
@@ -268,7 +278,7 @@ def conv2d_dgrad(dy, w, x_shape, stride, pad, stream=None):
     N, H, W, Cc = x_shape
     K, R = w.shape[0], w.shape[1]
     dx = torch.empty((N, H, W, Cc), dtype=dy.dtype, device=dy.device)
-    sh = _conv_shape(N, H, W, Cc, K, R, stride, pad)
+    sh = _conv_shape(N, H, W, Cc, K, R, stride, pad, _dtype_code(dy))
     ws = _conv_ws(sh)
     _check(lib().resist_conv2d_dgrad(C.byref(sh), dy.data_ptr(), w.data_ptr(), dx.data_ptr(),
                                      ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
@@ -280,7 +290,7 @@ def conv2d_wgrad(dy, x, w_shape, stride, pad, stream=None):
     N, H, W, Cc = x.shape
     K, R = w_shape[0], w_shape[1]
     dw = torch.empty((K, R, R, Cc), dtype=torch.float32, device=x.device)
-    sh = _conv_shape(N, H, W, Cc, K, R, stride, pad)
+    sh = _conv_shape(N, H, W, Cc, K, R, stride, pad, _dtype_code(x))
     ws = _conv_ws(sh)
     _check(lib().resist_conv2d_wgrad(C.byref(sh), dy.data_ptr(), x.data_ptr(), dw.data_ptr(),
                                      ws.data_ptr(), ws.numel(), _stream_ptr(stream)))

@@ -6,11 +6,12 @@
 // These kernels are bound by HBM bandwidth.  Per-channel sums are accumulated in float64 (the
 // vector fp64 rate is far above what the memory stream needs), in a fixed order, so results are
 // bit-stable from run to run and free of the cancellation a float32 sum-of-squares would suffer.
+// Activations are stored as fp32 or bf16; a thread owns V = 4 (fp32) or 8 (bf16) consecutive channels
+// (one 16-byte access) and all arithmetic is fp32 / fp64.
+#include "elem.h"
 #include "internal.h"
 
 namespace resist {
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -18,20 +19,19 @@ constexpr int kThreads = 256;
 constexpr int kMaxParts = 512;  // row-slices per channel tile
 
 struct ColMap {
-  int tpr;       // threads per row (each owns 4 consecutive channels)
+  int tpr;       // threads per row (each owns V consecutive channels)
   int rpp;       // rows per pass of one workgroup
-  int ctiles;    // channel tiles of tpr*4 channels
+  int ctiles;    // channel tiles of tpr*V channels
 };
-inline ColMap col_map(int C) {
+inline ColMap col_map(int C, int V) {
   ColMap m;
-  const int c4 = C / 4;
-  m.tpr = c4 >= kThreads ? kThreads : c4;   // C is a multiple of 16, so c4 >= 4
-  // tpr must divide 256: round down to a power of two that divides c4
+  const int cv = C / V;   // C is a multiple of 16, so cv >= 2
+  // tpr must divide 256: the largest power of two that divides cv
   int t = 1;
-  while (t * 2 <= m.tpr && (c4 % (t * 2)) == 0 && t * 2 <= kThreads) t *= 2;
+  while (t * 2 <= cv && (cv % (t * 2)) == 0 && t * 2 <= kThreads) t *= 2;
   m.tpr = t;
   m.rpp = kThreads / m.tpr;
-  m.ctiles = c4 / m.tpr;
+  m.ctiles = cv / m.tpr;
   return m;
 }
 inline int num_parts(int64_t M, const ColMap &m) {
@@ -47,38 +47,43 @@ inline int num_parts(int64_t M, const ColMap &m) {
 
 // ---- forward statistics --------------------------------------------------------------------------
 // grid (parts, ctiles); scratch layout [2][parts][C] doubles: sum, sum of squares
-__global__ __launch_bounds__(kThreads) void bn_stats_partial_kernel(const float *__restrict__ y, long long M, int C,
+template <typename T>
+__global__ __launch_bounds__(kThreads) void bn_stats_partial_kernel(const T *__restrict__ y, long long M, int C,
                                                                     int tpr, int rpp, double *__restrict__ scratch) {
-  __shared__ double red[2][kThreads][4];
+  constexpr int V = Vec<T>::N;
+  __shared__ double red[2][kThreads][V];
   const int tid = threadIdx.x;
   const int tc = tid % tpr, tr = tid / tpr;
-  const int c = (blockIdx.y * tpr + tc) * 4;
+  const int c = (blockIdx.y * tpr + tc) * V;
   const int parts = gridDim.x;
   const long long rows_per_part = (M + parts - 1) / parts;
   const long long r0 = blockIdx.x * rows_per_part;
   long long r1 = r0 + rows_per_part;
   if (r1 > M) r1 = M;
-  double s[4] = {0, 0, 0, 0}, q[4] = {0, 0, 0, 0};
-  for (long long r = r0 + tr; r < r1; r += rpp) {
-    const f32x4 v = *reinterpret_cast<const f32x4 *>(y + r * C + c);
+  double s[V], q[V];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
+  for (int e = 0; e < V; ++e) { s[e] = 0; q[e] = 0; }
+  for (long long r = r0 + tr; r < r1; r += rpp) {
+    float v[V];
+    Vec<T>::load(y + r * C + c, v);
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
       const double d = (double)v[e];
       s[e] += d;
       q[e] = fma(d, d, q[e]);
     }
   }
 #pragma unroll
-  for (int e = 0; e < 4; ++e) { red[0][tid][e] = s[e]; red[1][tid][e] = q[e]; }
+  for (int e = 0; e < V; ++e) { red[0][tid][e] = s[e]; red[1][tid][e] = q[e]; }
   __syncthreads();
   if (tr == 0) {
     for (int j = 1; j < rpp; ++j)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) { s[e] += red[0][j * tpr + tc][e]; q[e] += red[1][j * tpr + tc][e]; }
+      for (int e = 0; e < V; ++e) { s[e] += red[0][j * tpr + tc][e]; q[e] += red[1][j * tpr + tc][e]; }
     double *ps = scratch + (size_t)blockIdx.x * C + c;
     double *pq = scratch + (size_t)(parts + blockIdx.x) * C + c;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { ps[e] = s[e]; pq[e] = q[e]; }
+    for (int e = 0; e < V; ++e) { ps[e] = s[e]; pq[e] = q[e]; }
   }
 }
 
@@ -125,20 +130,24 @@ __global__ __launch_bounds__(kThreads) void bn_stats_final_kernel(const double *
 
 // ---- forward apply -------------------------------------------------------------------------------
 struct ApplyArgs {
-  const float *y; const float *gamma; const float *beta; const float *mean; const float *invstd;
-  const float *res;                                       // raw residual or second pre-BN tensor
+  const void *y; const float *gamma; const float *beta; const float *mean; const float *invstd;
+  const void *res;                                        // raw residual or second pre-BN tensor
   const float *rgamma; const float *rbeta; const float *rmean; const float *rinvstd;  // BN of res
-  float *a;
+  void *a;
   long long M; int C; int tpr, rpp; int relu;
 };
 
+template <typename T>
 __global__ __launch_bounds__(kThreads) void bn_apply_kernel(ApplyArgs p) {
+  constexpr int V = Vec<T>::N;
   const int tid = threadIdx.x;
   const int tc = tid % p.tpr, tr = tid / p.tpr;
-  const int c = (blockIdx.y * p.tpr + tc) * 4;
-  float sc[4], sh[4], rsc[4], rsh[4];
+  const int c = (blockIdx.y * p.tpr + tc) * V;
+  const T *y = static_cast<const T *>(p.y), *res = static_cast<const T *>(p.res);
+  T *a = static_cast<T *>(p.a);
+  float sc[V], sh[V], rsc[V], rsh[V];
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
+  for (int e = 0; e < V; ++e) {
     sc[e] = p.gamma[c + e] * p.invstd[c + e];
     sh[e] = p.beta[c + e] - p.mean[c + e] * sc[e];
     if (p.rgamma) {
@@ -151,70 +160,75 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(ApplyArgs p) {
   const long long stride = (long long)gridDim.x * p.rpp;
   for (long long r = (long long)blockIdx.x * p.rpp + tr; r < p.M; r += stride) {
     const size_t off = (size_t)r * p.C + c;
-    const f32x4 v = *reinterpret_cast<const f32x4 *>(p.y + off);
-    f32x4 o;
+    float v[V], o[V];
+    Vec<T>::load(y + off, v);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) o[e] = fmaf(v[e], sc[e], sh[e]);
-    if (p.res) {
-      const f32x4 rv = *reinterpret_cast<const f32x4 *>(p.res + off);
+    for (int e = 0; e < V; ++e) o[e] = fmaf(v[e], sc[e], sh[e]);
+    if (res) {
+      float rv[V];
+      Vec<T>::load(res + off, rv);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] += fmaf(rv[e], rsc[e], rsh[e]);
+      for (int e = 0; e < V; ++e) o[e] += fmaf(rv[e], rsc[e], rsh[e]);
     }
     if (p.relu) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] = o[e] > 0.f ? o[e] : 0.f;
+      for (int e = 0; e < V; ++e) o[e] = o[e] > 0.f ? o[e] : 0.f;
     }
-    *reinterpret_cast<f32x4 *>(p.a + off) = o;
+    Vec<T>::store(a + off, o);
   }
 }
 
 // ---- backward ------------------------------------------------------------------------------------
 // pass 1: per-channel sums of gm and gm*xhat; scratch [2][parts][C]
-__global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const float *__restrict__ g, const float *__restrict__ mask,
-                                                                  const float *__restrict__ y, long long M, int C, int tpr,
+template <typename T>
+__global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const T *__restrict__ g, const T *__restrict__ mask,
+                                                                  const T *__restrict__ y, long long M, int C, int tpr,
                                                                   int rpp, const float *__restrict__ mean,
                                                                   const float *__restrict__ invstd,
                                                                   double *__restrict__ scratch) {
-  __shared__ double red[2][kThreads][4];
+  constexpr int V = Vec<T>::N;
+  __shared__ double red[2][kThreads][V];
   const int tid = threadIdx.x;
   const int tc = tid % tpr, tr = tid / tpr;
-  const int c = (blockIdx.y * tpr + tc) * 4;
+  const int c = (blockIdx.y * tpr + tc) * V;
   const int parts = gridDim.x;
   const long long rows_per_part = (M + parts - 1) / parts;
   const long long r0 = blockIdx.x * rows_per_part;
   long long r1 = r0 + rows_per_part;
   if (r1 > M) r1 = M;
-  float mu[4], is[4];
+  float mu[V], is[V];
+  double sb[V], sg[V];
 #pragma unroll
-  for (int e = 0; e < 4; ++e) { mu[e] = mean[c + e]; is[e] = invstd[c + e]; }
-  double sb[4] = {0, 0, 0, 0}, sg[4] = {0, 0, 0, 0};
+  for (int e = 0; e < V; ++e) { mu[e] = mean[c + e]; is[e] = invstd[c + e]; sb[e] = 0; sg[e] = 0; }
   for (long long r = r0 + tr; r < r1; r += rpp) {
     const size_t off = (size_t)r * C + c;
-    f32x4 gv = *reinterpret_cast<const f32x4 *>(g + off);
-    const f32x4 yv = *reinterpret_cast<const f32x4 *>(y + off);
+    float gv[V], yv[V];
+    Vec<T>::load(g + off, gv);
+    Vec<T>::load(y + off, yv);
     if (mask) {
-      const f32x4 mv = *reinterpret_cast<const f32x4 *>(mask + off);
+      float mv[V];
+      Vec<T>::load(mask + off, mv);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) gv[e] = mv[e] > 0.f ? gv[e] : 0.f;
+      for (int e = 0; e < V; ++e) gv[e] = mv[e] > 0.f ? gv[e] : 0.f;
     }
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
+    for (int e = 0; e < V; ++e) {
       const float xh = (yv[e] - mu[e]) * is[e];
       sb[e] += (double)gv[e];
       sg[e] = fma((double)gv[e], (double)xh, sg[e]);
     }
   }
 #pragma unroll
-  for (int e = 0; e < 4; ++e) { red[0][tid][e] = sb[e]; red[1][tid][e] = sg[e]; }
+  for (int e = 0; e < V; ++e) { red[0][tid][e] = sb[e]; red[1][tid][e] = sg[e]; }
   __syncthreads();
   if (tr == 0) {
     for (int j = 1; j < rpp; ++j)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) { sb[e] += red[0][j * tpr + tc][e]; sg[e] += red[1][j * tpr + tc][e]; }
+      for (int e = 0; e < V; ++e) { sb[e] += red[0][j * tpr + tc][e]; sg[e] += red[1][j * tpr + tc][e]; }
     double *pb = scratch + (size_t)blockIdx.x * C + c;
     double *pg = scratch + (size_t)(parts + blockIdx.x) * C + c;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { pb[e] = sb[e]; pg[e] = sg[e]; }
+    for (int e = 0; e < V; ++e) { pb[e] = sb[e]; pg[e] = sg[e]; }
   }
 }
 
@@ -230,20 +244,24 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const double *__
 }
 
 struct BwdApplyArgs {
-  const float *g; const float *mask; const float *y;
+  const void *g; const void *mask; const void *y;
   const float *gamma; const float *mean; const float *invstd; const float *dgamma; const float *dbeta;
-  float *dy; float *gm_out;
+  void *dy; void *gm_out;
   long long M; int C; int tpr, rpp;
 };
 
+template <typename T>
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BwdApplyArgs p) {
+  constexpr int V = Vec<T>::N;
   const int tid = threadIdx.x;
   const int tc = tid % p.tpr, tr = tid / p.tpr;
-  const int c = (blockIdx.y * p.tpr + tc) * 4;
+  const int c = (blockIdx.y * p.tpr + tc) * V;
+  const T *g = static_cast<const T *>(p.g), *mask = static_cast<const T *>(p.mask), *y = static_cast<const T *>(p.y);
+  T *dy = static_cast<T *>(p.dy), *gm_out = static_cast<T *>(p.gm_out);
   const float invM = 1.0f / (float)p.M;
-  float mu[4], is[4], k0[4], k1[4], k2[4];
+  float mu[V], is[V], k0[V], k1[V], k2[V];
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
+  for (int e = 0; e < V; ++e) {
     mu[e] = p.mean[c + e]; is[e] = p.invstd[c + e];
     k0[e] = p.gamma[c + e] * is[e];          // scale
     k1[e] = p.dbeta[c + e] * invM;           // mean of gm
@@ -252,25 +270,27 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BwdApplyArgs p) 
   const long long stride = (long long)gridDim.x * p.rpp;
   for (long long r = (long long)blockIdx.x * p.rpp + tr; r < p.M; r += stride) {
     const size_t off = (size_t)r * p.C + c;
-    f32x4 gv = *reinterpret_cast<const f32x4 *>(p.g + off);
-    const f32x4 yv = *reinterpret_cast<const f32x4 *>(p.y + off);
-    if (p.mask) {
-      const f32x4 mv = *reinterpret_cast<const f32x4 *>(p.mask + off);
+    float gv[V], yv[V], o[V];
+    Vec<T>::load(g + off, gv);
+    Vec<T>::load(y + off, yv);
+    if (mask) {
+      float mv[V];
+      Vec<T>::load(mask + off, mv);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) gv[e] = mv[e] > 0.f ? gv[e] : 0.f;
+      for (int e = 0; e < V; ++e) gv[e] = mv[e] > 0.f ? gv[e] : 0.f;
     }
-    f32x4 o;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
+    for (int e = 0; e < V; ++e) {
       const float xh = (yv[e] - mu[e]) * is[e];
       o[e] = k0[e] * (gv[e] - k1[e] - xh * k2[e]);
     }
-    *reinterpret_cast<f32x4 *>(p.dy + off) = o;
-    if (p.gm_out) *reinterpret_cast<f32x4 *>(p.gm_out + off) = gv;
+    Vec<T>::store(dy + off, o);
+    if (gm_out) Vec<T>::store(gm_out + off, gv);   // exact: gm is g or zero
   }
 }
 
-int check_bn(int64_t M, int C) {
+int check_bn(int dt, int64_t M, int C) {
+  if (dt != DT_F32 && dt != DT_BF16) return set_error(RESIST_EINVAL, "dtype %d", dt);
   if (M < 1 || C < 16 || (C % 16)) return set_error(RESIST_ESHAPE, "BN on [%lld][%d]: C must be a positive multiple of 16", (long long)M, C);
   return RESIST_OK;
 }
@@ -282,17 +302,22 @@ unsigned apply_grid_x(int64_t M, const ColMap &m) {
   return (unsigned)(want < maxb ? want : maxb);
 }
 
+inline int vec_of(int dt) { return dt == DT_BF16 ? 8 : 4; }
+
 }  // namespace
 
 int64_t bn_scratch_doubles(int C) { return (int64_t)2 * kMaxParts * C; }
 
-int bn_stats_f32(const float *y, int64_t M, int C, const BnBufs &b, float eps, float momentum,
-                 double *scratch, hipStream_t st) {
-  RESIST_TRY(check_bn(M, C));
-  const ColMap m = col_map(C);
+int bn_stats(int dt, const void *y, int64_t M, int C, const BnBufs &b, float eps, float momentum, double *scratch,
+             hipStream_t st) {
+  RESIST_TRY(check_bn(dt, M, C));
+  const ColMap m = col_map(C, vec_of(dt));
   const int parts = num_parts(M, m);
-  prof::Scope ps("bn_stats", 0, 4.0 * M * C, st);
-  hipLaunchKernelGGL(bn_stats_partial_kernel, dim3(parts, m.ctiles), dim3(kThreads), 0, st, y, (long long)M, C, m.tpr, m.rpp, scratch);
+  prof::Scope ps("bn_stats", 0, (double)esize(dt) * M * C, st);
+  if (dt == DT_BF16)
+    hipLaunchKernelGGL(bn_stats_partial_kernel<__bf16>, dim3(parts, m.ctiles), dim3(kThreads), 0, st, (const __bf16 *)y, (long long)M, C, m.tpr, m.rpp, scratch);
+  else
+    hipLaunchKernelGGL(bn_stats_partial_kernel<float>, dim3(parts, m.ctiles), dim3(kThreads), 0, st, (const float *)y, (long long)M, C, m.tpr, m.rpp, scratch);
   RESIST_CHECK_LAUNCH("bn_stats_partial");
   hipLaunchKernelGGL(bn_stats_final_kernel, dim3(C / 16), dim3(kThreads), 0, st, scratch, parts, C,
                      (long long)M, eps, momentum, b.mean, b.invstd, b.rmean, b.rvar);
@@ -300,29 +325,34 @@ int bn_stats_f32(const float *y, int64_t M, int C, const BnBufs &b, float eps, f
   return RESIST_OK;
 }
 
-int bn_apply_f32(const float *y, int64_t M, int C, const BnBufs &b, const float *res, const BnBufs *res_bn,
-                 bool relu, float *a, hipStream_t st) {
-  RESIST_TRY(check_bn(M, C));
-  const ColMap m = col_map(C);
+int bn_apply(int dt, const void *y, int64_t M, int C, const BnBufs &b, const void *res, const BnBufs *res_bn, bool relu,
+             void *a, hipStream_t st) {
+  RESIST_TRY(check_bn(dt, M, C));
+  const ColMap m = col_map(C, vec_of(dt));
   ApplyArgs p{};
   p.y = y; p.gamma = b.gamma; p.beta = b.beta; p.mean = b.mean; p.invstd = b.invstd;
   p.res = res;
   if (res_bn) { p.rgamma = res_bn->gamma; p.rbeta = res_bn->beta; p.rmean = res_bn->mean; p.rinvstd = res_bn->invstd; }
   p.a = a; p.M = M; p.C = C; p.tpr = m.tpr; p.rpp = m.rpp; p.relu = relu ? 1 : 0;
-  prof::Scope ps("bn_apply", 0, 4.0 * M * C * (res ? 3 : 2), st);
-  hipLaunchKernelGGL(bn_apply_kernel, dim3(apply_grid_x(M, m), m.ctiles), dim3(kThreads), 0, st, p);
+  prof::Scope ps("bn_apply", 0, (double)esize(dt) * M * C * (res ? 3 : 2), st);
+  if (dt == DT_BF16) hipLaunchKernelGGL(bn_apply_kernel<__bf16>, dim3(apply_grid_x(M, m), m.ctiles), dim3(kThreads), 0, st, p);
+  else hipLaunchKernelGGL(bn_apply_kernel<float>, dim3(apply_grid_x(M, m), m.ctiles), dim3(kThreads), 0, st, p);
   RESIST_CHECK_LAUNCH("bn_apply");
   return RESIST_OK;
 }
 
-int bn_backward_f32(const float *g, const float *mask, const float *y, int64_t M, int C, const BnBufs &b,
-                    float *dy, float *gm_out, double *scratch, hipStream_t st) {
-  RESIST_TRY(check_bn(M, C));
-  const ColMap m = col_map(C);
+int bn_backward(int dt, const void *g, const void *mask, const void *y, int64_t M, int C, const BnBufs &b, void *dy,
+                void *gm_out, double *scratch, hipStream_t st) {
+  RESIST_TRY(check_bn(dt, M, C));
+  const ColMap m = col_map(C, vec_of(dt));
   const int parts = num_parts(M, m);
-  prof::Scope ps("bn_backward", 0, 4.0 * M * C * ((mask ? 3 : 2) + (mask ? 4 : 3) + (gm_out ? 1 : 0)), st);
-  hipLaunchKernelGGL(bn_bwd_partial_kernel, dim3(parts, m.ctiles), dim3(kThreads), 0, st, g, mask, y, (long long)M, C, m.tpr,
-                     m.rpp, b.mean, b.invstd, scratch);
+  prof::Scope ps("bn_backward", 0, (double)esize(dt) * M * C * ((mask ? 3 : 2) + (mask ? 4 : 3) + (gm_out ? 1 : 0)), st);
+  if (dt == DT_BF16)
+    hipLaunchKernelGGL(bn_bwd_partial_kernel<__bf16>, dim3(parts, m.ctiles), dim3(kThreads), 0, st, (const __bf16 *)g,
+                       (const __bf16 *)mask, (const __bf16 *)y, (long long)M, C, m.tpr, m.rpp, b.mean, b.invstd, scratch);
+  else
+    hipLaunchKernelGGL(bn_bwd_partial_kernel<float>, dim3(parts, m.ctiles), dim3(kThreads), 0, st, (const float *)g,
+                       (const float *)mask, (const float *)y, (long long)M, C, m.tpr, m.rpp, b.mean, b.invstd, scratch);
   RESIST_CHECK_LAUNCH("bn_bwd_partial");
   hipLaunchKernelGGL(bn_bwd_final_kernel, dim3(C / 16), dim3(kThreads), 0, st, scratch, parts, C,
                      b.dgamma, b.dbeta);
@@ -331,7 +361,8 @@ int bn_backward_f32(const float *g, const float *mask, const float *y, int64_t M
   p.g = g; p.mask = mask; p.y = y; p.gamma = b.gamma; p.mean = b.mean; p.invstd = b.invstd;
   p.dgamma = b.dgamma; p.dbeta = b.dbeta; p.dy = dy; p.gm_out = gm_out;
   p.M = M; p.C = C; p.tpr = m.tpr; p.rpp = m.rpp;
-  hipLaunchKernelGGL(bn_bwd_apply_kernel, dim3(apply_grid_x(M, m), m.ctiles), dim3(kThreads), 0, st, p);
+  if (dt == DT_BF16) hipLaunchKernelGGL(bn_bwd_apply_kernel<__bf16>, dim3(apply_grid_x(M, m), m.ctiles), dim3(kThreads), 0, st, p);
+  else hipLaunchKernelGGL(bn_bwd_apply_kernel<float>, dim3(apply_grid_x(M, m), m.ctiles), dim3(kThreads), 0, st, p);
   RESIST_CHECK_LAUNCH("bn_bwd_apply");
   return RESIST_OK;
 }

@@ -1,4 +1,5 @@
-// fp32 implicit-GEMM convolutions on the CDNA4 matrix cores (v_mfma_f32_32x32x2_f32).
+// Implicit-GEMM convolutions on the CDNA4 matrix cores: fp32 (v_mfma_f32_32x32x2_f32) and
+// bf16 operands with fp32 accumulation (v_mfma_f32_32x32x16_bf16).
 //
 // The convolutions of a residual block (the paper's local update, Algorithm 1 inner loop, is an
 // ordinary SGD step of the blocks a worker keeps) are computed as GEMMs whose A operand is
@@ -18,17 +19,39 @@ namespace resist {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 namespace {
 
 constexpr int kThreads = 256;
 constexpr int kStages = 2;     // LDS double buffering in the implicit-GEMM kernels
 
+// Element traits: a 16-byte vector holds VEC elements; one pair of 16-byte fragments (A, B) feeds
+// the matrix core with 2*VEC values of the GEMM-K axis (lane group l/32 owns VEC consecutive ones).
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int VEC = 4;
+  __device__ static inline void mma(f32x16 &acc, const f32x4 &a, const f32x4 &b) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], b[e], acc, 0, 0, 0);
+  }
+  __device__ static inline float from_f32(float v) { return v; }
+  __device__ static inline float to_f32(float v) { return v; }
+};
+template <> struct Elem<__bf16> {
+  static constexpr int VEC = 8;
+  __device__ static inline void mma(f32x16 &acc, const f32x4 &a, const f32x4 &b) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+  }
+  __device__ static inline __bf16 from_f32(float v) { return (__bf16)v; }   // round to nearest even
+  __device__ static inline float to_f32(__bf16 v) { return (float)v; }
+};
+
 struct IgemmArgs {
-  const float *in;      // [N][IH][IW][IC]
-  const float *wt;      // [OC][R][S][IC]
-  float *out;           // [N][OH][OW][OC]
-  const float *addend;  // optional, indexed like out
+  const void *in;      // [N][IH][IW][IC]
+  const void *wt;      // [OC][R][S][IC]
+  void *out;           // [N][OH][OW][OC]
+  const void *addend;  // optional, indexed like out
   int N, IH, IW, IC;
   int OH, OW, OC;
   int R, S, stride, pad;
@@ -58,11 +81,11 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, unsigned bytes
 }
 constexpr unsigned kOOB = 0x80000000u;   // every tensor is smaller than 2 GiB (checked on the host)
 
-__device__ inline f32x4 buffer_load_f32x4(__amdgpu_buffer_rsrc_t r, unsigned voff) {
+__device__ inline f32x4 buffer_load_16B(__amdgpu_buffer_rsrc_t r, unsigned voff) {
   return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 0));
 }
 
-// BK: K-chunk (floats) staged per step; LDS rows are padded by 4 floats (conflict-free b128 reads).
+// BK: K-chunk (elements) staged per step; LDS rows are padded by 16 bytes (conflict-free b128 reads).
 //
 // The K loop runs over (filter tap, channel chunk).  Its body is one straight-line block: the
 // source pixel of every tile row is (hc + dh, wc + dw) with per-row (hc, wc) fixed for the whole
@@ -70,25 +93,27 @@ __device__ inline f32x4 buffer_load_f32x4(__amdgpu_buffer_rsrc_t r, unsigned vof
 // buffer loads (an invalid element is requested at an out-of-range offset and comes back as zero),
 // and the tap counters are advanced with selects.  With no branch in the loop the scheduler is free
 // to place the address arithmetic, the LDS traffic and the global loads in the shadow of the MFMAs.
-template <int BM, int BN, int BK, int WGM, int WGN, int MODE>
-__global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
-  constexpr int LDK = BK + 4;
+template <typename T, int BM, int BN, int BK, int WGM, int WGN, int MODE>
+__global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
+  using E = Elem<T>;
+  constexpr int VEC = E::VEC;
+  constexpr int ES = (int)sizeof(T);
+  constexpr int LDK = BK + VEC;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
   constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 MFMA tiles per wave
-  constexpr int KV = BK / 4;                     // lanes per tile row (one float4 each)
+  constexpr int KV = BK / VEC;                   // lanes per tile row (16 bytes each)
   constexpr int RPP = kThreads / KV;             // tile rows per load pass
   constexpr int PA = BM / RPP, PB = BN / RPP;    // load passes
-  constexpr int NK = BK / 8;                     // k-steps (8 deep: 4 MFMAs per tile) per chunk
-  static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1 && PA >= 1 && PB >= 1, "tile shape");
-  __shared__ float As[kStages][BM][LDK];
-  __shared__ float Bs[kStages][BN][LDK];
+  constexpr int NK = BK / (2 * VEC);             // k-steps per chunk
+  static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1 && PA >= 1 && PB >= 1 && NK >= 2, "tile shape");
+  __shared__ T As[kStages][BM][LDK];
+  __shared__ T Bs[kStages][BN][LDK];
   __shared__ int row_off[BM];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
-  // tile coordinates: N-tiles fastest so that tiles sharing the same input rows run together
   // Logical tile order: N-tiles fastest, so tiles sharing input rows are neighbours; each XCD gets a
   // contiguous range of them.  The stride-2 data gradient (4 parity classes of unequal work, class
   // slowest) keeps the hardware round-robin order, which measured faster for its short K loops.
@@ -100,7 +125,7 @@ __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
   const int ph = cidx / a.cls, pw = cidx % a.cls;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  // filter taps that contribute: r = r0, r0+rstep, ... < R (all taps unless MODE==kBwd, stride 2)
+  // filter taps that contribute: r = r0, r0+tstep, ... < R (all taps unless MODE==kBwd, stride 2)
   int r0 = 0, s0 = 0, tstep = 1;
   if (MODE == kBwd && a.stride == 2) { r0 = (ph + a.pad) & 1; s0 = (pw + a.pad) & 1; tstep = 2; }
   const int nr = r0 < a.R ? (a.R - r0 + tstep - 1) / tstep : 0;
@@ -109,7 +134,7 @@ __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
   const int nchunks = nr * ns * cchunks;
 
   // per-thread tile rows: centre pixel (hc, wc) and byte offset of its first channel of interest
-  const int lrow = tid / KV, kvec = (tid % KV) * 4;
+  const int lrow = tid / KV, kvec = (tid % KV) * VEC;
   int hc[PA], wc[PA], aoff[PA], boff[PB];
 #pragma unroll
   for (int i = 0; i < PA; ++i) {
@@ -121,7 +146,7 @@ __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
       if (MODE == kFwd) { hc[i] = ohc * a.stride - a.pad; wc[i] = owc * a.stride - a.pad; }
       else if (a.stride == 1) { hc[i] = ohc + a.pad; wc[i] = owc + a.pad; }
       else { hc[i] = ohc; wc[i] = owc; }
-      aoff[i] = (((n * a.IH + hc[i]) * a.IW + wc[i]) * a.IC + kvec) * 4;
+      aoff[i] = (((n * a.IH + hc[i]) * a.IW + wc[i]) * a.IC + kvec) * ES;
     } else {
       hc[i] = -(1 << 24); wc[i] = -(1 << 24); aoff[i] = 0;   // never in range
     }
@@ -129,7 +154,7 @@ __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
 #pragma unroll
   for (int i = 0; i < PB; ++i) {
     const int oc = n0 + i * RPP + lrow;
-    boff[i] = oc < a.OC ? (oc * a.R * a.S * a.IC + kvec) * 4 : (int)kOOB;
+    boff[i] = oc < a.OC ? (oc * a.R * a.S * a.IC + kvec) * ES : (int)kOOB;
   }
   for (int r = tid; r < BM; r += kThreads) {
     const int m = m0 + r;
@@ -143,8 +168,8 @@ __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
     row_off[r] = off;
   }
 
-  const __amdgpu_buffer_rsrc_t rin = make_rsrc(a.in, (unsigned)a.N * a.IH * a.IW * a.IC * 4u);
-  const __amdgpu_buffer_rsrc_t rwt = make_rsrc(a.wt, (unsigned)a.OC * a.R * a.S * a.IC * 4u);
+  const __amdgpu_buffer_rsrc_t rin = make_rsrc(a.in, (unsigned)a.N * a.IH * a.IW * a.IC * ES);
+  const __amdgpu_buffer_rsrc_t rwt = make_rsrc(a.wt, (unsigned)a.OC * a.R * a.S * a.IC * ES);
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -165,16 +190,16 @@ __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
     else { dh = (ph + a.pad - tr) >> 1; dw = (pw + a.pad - ts) >> 1; }   // even by construction
     const bool live = issued < nchunks;
     const int c0 = tc * BK;
-    const int adelta = ((dh * a.IW + dw) * a.IC + c0) * 4;
-    const int bdelta = ((tr * a.S + ts) * a.IC + c0) * 4;
+    const int adelta = ((dh * a.IW + dw) * a.IC + c0) * ES;
+    const int bdelta = ((tr * a.S + ts) * a.IC + c0) * ES;
     const bool kok = live && (c0 + kvec) < a.IC;
 #pragma unroll
     for (int i = 0; i < PA; ++i) {
       const bool ok = kok && (unsigned)(hc[i] + dh) < (unsigned)a.IH && (unsigned)(wc[i] + dw) < (unsigned)a.IW;
-      ra[i] = buffer_load_f32x4(rin, ok ? (unsigned)(aoff[i] + adelta) : kOOB);
+      ra[i] = buffer_load_16B(rin, ok ? (unsigned)(aoff[i] + adelta) : kOOB);
     }
 #pragma unroll
-    for (int i = 0; i < PB; ++i) rb[i] = buffer_load_f32x4(rwt, kok ? (unsigned)(boff[i] + bdelta) : kOOB);
+    for (int i = 0; i < PB; ++i) rb[i] = buffer_load_16B(rwt, kok ? (unsigned)(boff[i] + bdelta) : kOOB);
     // advance (tap, channel chunk) without branches
     ++issued;
     const bool cwrap = (tc + 1 == cchunks);
@@ -199,7 +224,7 @@ __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
   // Chunk `it` is multiplied out of stage it&1.  Half way through, the registers holding chunk it+1
   // (requested one chunk of MFMA time earlier) go to the other stage and chunk it+2 is requested;
   // fragments of k-step ks+1 are fetched from LDS before the MFMAs of k-step ks.
-  const int lr = lane & 31, lk = (lane >> 5) * 4;
+  const int lr = lane & 31, lk = (lane >> 5) * VEC;
   for (int it = 0; it < nchunks; ++it) {
     const int stage = it & 1;
     f32x4 fa[2][TM], fb[2][TN];
@@ -212,27 +237,26 @@ __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
       if (ks + 1 < NK) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
-          fa[(ks + 1) & 1][i] = *reinterpret_cast<const f32x4 *>(&As[stage][wm * WTM + i * 32 + lr][(ks + 1) * 8 + lk]);
+          fa[(ks + 1) & 1][i] = *reinterpret_cast<const f32x4 *>(&As[stage][wm * WTM + i * 32 + lr][(ks + 1) * 2 * VEC + lk]);
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          fb[(ks + 1) & 1][j] = *reinterpret_cast<const f32x4 *>(&Bs[stage][wn * WTN + j * 32 + lr][(ks + 1) * 8 + lk]);
+          fb[(ks + 1) & 1][j] = *reinterpret_cast<const f32x4 *>(&Bs[stage][wn * WTN + j * 32 + lr][(ks + 1) * 2 * VEC + lk]);
       }
       if (ks == NK / 2) {
         store_lds(stage ^ 1);   // past the last chunk this writes zeros nobody reads
         load_global();
       }
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[ks & 1][i][e], fb[ks & 1][j][e], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j) E::mma(acc[i][j], fa[ks & 1][i], fb[ks & 1][j]);
     }
     __syncthreads();
   }
 
   // epilogue: lane holds column (lane%32), rows 8*(e/4) + 4*(lane/32) + e%4 of each 32x32 tile
+  T *out = static_cast<T *>(a.out);
+  const T *addend = static_cast<const T *>(a.addend);
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -245,63 +269,68 @@ __global__ __launch_bounds__(kThreads) void igemm_f32_kernel(IgemmArgs a) {
         if (ro >= 0 && col < a.OC) {
           const size_t off = (size_t)ro * a.OC + col;
           float v = acc[i][j][e];
-          if (a.addend) v += a.addend[off];
-          a.out[off] = v;
+          if (addend) v += E::to_f32(addend[off]);
+          out[off] = E::from_f32(v);
         }
       }
     }
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int MODE>
+template <typename T, int BM, int BN, int BK, int WGM, int WGN, int MODE>
 int launch_igemm(IgemmArgs a, hipStream_t st) {
   a.tiles_m = (a.Mrows + BM - 1) / BM;
   a.tiles_n = (a.OC + BN - 1) / BN;
   const long long grid = (long long)a.tiles_m * a.tiles_n * a.cls * a.cls;
   if (grid <= 0 || grid > 0x7fffffffLL) return set_error(RESIST_ESHAPE, "igemm grid %lld", grid);
   {
-    static const std::string label = std::string(MODE == kFwd ? "igemm_f32_fwd_" : "igemm_f32_bwd_") + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK);
+    static const std::string label = std::string("igemm_") + (sizeof(T) == 4 ? "f32_" : "bf16_") + (MODE == kFwd ? "fwd_" : "bwd_") +
+                                     std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK);
     // algorithmic work of the convolution this launch computes (forward or data gradient)
     const double flops = 2.0 * a.N * (MODE == kFwd ? (double)a.OH * a.OW : (double)a.IH * a.IW) * a.OC * a.IC * a.R * a.S;
-    const double bytes = 4.0 * ((double)a.N * a.IH * a.IW * a.IC + (double)a.N * a.OH * a.OW * a.OC * (a.addend ? 2 : 1) + (double)a.OC * a.R * a.S * a.IC);
+    const double bytes = sizeof(T) * ((double)a.N * a.IH * a.IW * a.IC + (double)a.N * a.OH * a.OW * a.OC * (a.addend ? 2 : 1) +
+                                      (double)a.OC * a.R * a.S * a.IC);
     prof::Scope ps(label.c_str(), flops, bytes, st);
-    hipLaunchKernelGGL((igemm_f32_kernel<BM, BN, BK, WGM, WGN, MODE>), dim3((unsigned)grid), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((igemm_kernel<T, BM, BN, BK, WGM, WGN, MODE>), dim3((unsigned)grid), dim3(kThreads), 0, st, a);
   }
-  RESIST_CHECK_LAUNCH("igemm_f32");
+  RESIST_CHECK_LAUNCH("igemm");
   return RESIST_OK;
 }
 
-template <int MODE>
+template <typename T, int MODE>
 int dispatch_igemm(const IgemmArgs &a, hipStream_t st) {
   // pick the largest tile that still yields enough workgroups to cover the 256 compute units
+  constexpr int V = Elem<T>::VEC;   // K-chunks of 8*V and 16*V elements: 128 and 256 bytes per tile row
   const long long classes = (long long)a.cls * a.cls;
   auto tiles = [&](int bm, int bn) {
     return (long long)((a.Mrows + bm - 1) / bm) * ((a.OC + bn - 1) / bn) * classes;
   };
-  if (a.OC > 64 && tiles(128, 128) >= 512) return launch_igemm<128, 128, 32, 2, 2, MODE>(a, st);
-  if (tiles(128, 64) >= 512) return launch_igemm<128, 64, 32, 2, 2, MODE>(a, st);
-  if (a.IC % 64 == 0) return launch_igemm<64, 64, 64, 2, 2, MODE>(a, st);
-  return launch_igemm<64, 64, 32, 2, 2, MODE>(a, st);
+  if (a.OC > 64 && tiles(128, 128) >= 512) return launch_igemm<T, 128, 128, 8 * V, 2, 2, MODE>(a, st);
+  if (tiles(128, 64) >= 512) return launch_igemm<T, 128, 64, 8 * V, 2, 2, MODE>(a, st);
+  if (a.IC % (16 * V) == 0) return launch_igemm<T, 64, 64, 16 * V, 2, 2, MODE>(a, st);
+  return launch_igemm<T, 64, 64, 8 * V, 2, 2, MODE>(a, st);
 }
 
-int check_geom(const ConvGeom &g) {
-  if (g.N < 1 || g.H < 1 || g.W < 1 || g.C < 4 || g.K < 4 || (g.C & 3) || (g.K & 3))
-    return set_error(RESIST_ESHAPE, "conv shape N%d H%d W%d C%d K%d (C, K must be multiples of 4)", g.N, g.H, g.W, g.C, g.K);
-  if (g.R != g.S || (g.R != 1 && g.R != 3 && g.R != 5 && g.R != 7) || g.R * g.S > 32)
+int check_geom(const ConvGeom &g, int dt) {
+  const int v = dt == DT_BF16 ? 8 : 4;
+  if (dt != DT_F32 && dt != DT_BF16) return set_error(RESIST_EINVAL, "dtype %d", dt);
+  if (g.N < 1 || g.H < 1 || g.W < 1 || g.C < v || g.K < v || (g.C % v) || (g.K % v))
+    return set_error(RESIST_ESHAPE, "conv shape N%d H%d W%d C%d K%d (C, K must be multiples of %d)", g.N, g.H, g.W, g.C, g.K, v);
+  if (g.R != g.S || (g.R != 1 && g.R != 3 && g.R != 5) || g.R * g.S > 32)
     return set_error(RESIST_ESHAPE, "filter %dx%d unsupported", g.R, g.S);
   if (g.stride < 1 || g.stride > 2 || g.pad < 0 || g.pad >= g.R)
     return set_error(RESIST_ESHAPE, "stride %d pad %d unsupported", g.stride, g.pad);
   if (g.P < 1 || g.Q < 1) return set_error(RESIST_ESHAPE, "empty convolution output");
-  const long long lim = 0x1fffffffLL;   // 2 GiB of fp32: byte offsets stay below the out-of-range marker
+  const long long lim = 0x7fffffffLL / (dt == DT_BF16 ? 2 : 4);   // byte offsets stay below the out-of-range marker
   if ((long long)g.N * g.H * g.W * g.C > lim || (long long)g.N * g.P * g.Q * g.K > lim ||
       (long long)g.K * g.R * g.S * g.C > lim)
-    return set_error(RESIST_ESHAPE, "tensor exceeds 2^29 elements");
+    return set_error(RESIST_ESHAPE, "tensor exceeds 2 GiB");
   return RESIST_OK;
 }
 
 }  // namespace
 
-int conv_fwd_f32(const ConvGeom &g, const float *x, const float *w, float *y, hipStream_t st) {
-  RESIST_TRY(check_geom(g));
+int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, hipStream_t st) {
+  RESIST_TRY(check_geom(g, dt));
   IgemmArgs a{};
   a.in = x; a.wt = w; a.out = y; a.addend = nullptr;
   a.N = g.N; a.IH = g.H; a.IW = g.W; a.IC = g.C;
@@ -309,12 +338,11 @@ int conv_fwd_f32(const ConvGeom &g, const float *x, const float *w, float *y, hi
   a.R = g.R; a.S = g.S; a.stride = g.stride; a.pad = g.pad;
   a.cls = 1; a.OHc = g.P; a.OWc = g.Q;
   a.Mrows = g.N * g.P * g.Q;
-  return dispatch_igemm<kFwd>(a, st);
+  return dt == DT_BF16 ? dispatch_igemm<__bf16, kFwd>(a, st) : dispatch_igemm<float, kFwd>(a, st);
 }
 
-int conv_dgrad_f32(const ConvGeom &g, const float *dy, const float *wT, float *dx, const float *addend,
-                   hipStream_t st) {
-  RESIST_TRY(check_geom(g));
+int conv_dgrad(const ConvGeom &g, int dt, const void *dy, const void *wT, void *dx, const void *addend, hipStream_t st) {
+  RESIST_TRY(check_geom(g, dt));
   if (g.stride == 2 && ((g.H & 1) || (g.W & 1)))
     return set_error(RESIST_ESHAPE, "stride-2 dgrad needs even input size, got %dx%d", g.H, g.W);
   IgemmArgs a{};
@@ -324,13 +352,14 @@ int conv_dgrad_f32(const ConvGeom &g, const float *dy, const float *wT, float *d
   a.R = g.R; a.S = g.S; a.stride = g.stride; a.pad = g.pad;
   a.cls = g.stride; a.OHc = g.H / g.stride; a.OWc = g.W / g.stride;
   a.Mrows = g.N * a.OHc * a.OWc;
-  return dispatch_igemm<kBwd>(a, st);
+  return dt == DT_BF16 ? dispatch_igemm<__bf16, kBwd>(a, st) : dispatch_igemm<float, kBwd>(a, st);
 }
 
-// ---- filter transpose  wT[c][r][s][k] = w[k][r][s][c] -------------------------------------------
+// ---- filter preparation: wT[c][r][s][k] = w[k][r][s][c] (and a low-precision copy of w) ------------
 namespace {
-__global__ __launch_bounds__(256) void transpose_filter_kernel(const float *__restrict__ w, float *__restrict__ wT,
-                                                               int K, int RS, int C) {
+template <typename S, typename T>
+__global__ __launch_bounds__(256) void prepare_filter_kernel(const S *__restrict__ w, T *__restrict__ wlp, T *__restrict__ wT,
+                                                             int K, int RS, int C) {
   // 32x32 tiles of the [K][C] matrix at a fixed tap, through LDS so both sides stay coalesced
   __shared__ float tile[32][33];
   const int tap = blockIdx.z;
@@ -338,21 +367,33 @@ __global__ __launch_bounds__(256) void transpose_filter_kernel(const float *__re
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
   for (int i = ty; i < 32; i += 8) {
     const int k = k0 + i, c = c0 + tx;
-    tile[i][tx] = (k < K && c < C) ? w[((size_t)k * RS + tap) * C + c] : 0.f;
+    float v = 0.f;
+    if (k < K && c < C) {
+      v = Elem<S>::to_f32(w[((size_t)k * RS + tap) * C + c]);
+      if (wlp) wlp[((size_t)k * RS + tap) * C + c] = Elem<T>::from_f32(v);
+    }
+    tile[i][tx] = v;
   }
   __syncthreads();
-  for (int i = ty; i < 32; i += 8) {
-    const int c = c0 + i, k = k0 + tx;
-    if (k < K && c < C) wT[((size_t)c * RS + tap) * K + k] = tile[tx][i];
-  }
+  if (wT)
+    for (int i = ty; i < 32; i += 8) {
+      const int c = c0 + i, k = k0 + tx;
+      if (k < K && c < C) wT[((size_t)c * RS + tap) * K + k] = Elem<T>::from_f32(tile[tx][i]);
+    }
 }
 }  // namespace
 
-int transpose_filter_f32(const ConvGeom &g, const float *w, float *wT, hipStream_t st) {
+int prepare_filter(const ConvGeom &g, int src_dt, int dt, const void *w, void *w_lp, void *wT, hipStream_t st) {
+  if (src_dt == DT_BF16 && dt != DT_BF16) return set_error(RESIST_EINVAL, "prepare_filter: bf16 source needs a bf16 target");
   dim3 grid((g.C + 31) / 32, (g.K + 31) / 32, g.R * g.S);
-  prof::Scope ps("transpose_filter", 0, 8.0 * g.K * g.R * g.S * g.C, st);
-  hipLaunchKernelGGL(transpose_filter_kernel, grid, dim3(256), 0, st, w, wT, g.K, g.R * g.S, g.C);
-  RESIST_CHECK_LAUNCH("transpose_filter");
+  prof::Scope ps("prepare_filter", 0, ((double)esize(src_dt) + (w_lp ? esize(dt) : 0) + (wT ? esize(dt) : 0)) * g.K * g.R * g.S * g.C, st);
+  if (src_dt == DT_BF16)
+    hipLaunchKernelGGL((prepare_filter_kernel<__bf16, __bf16>), grid, dim3(256), 0, st, (const __bf16 *)w, (__bf16 *)w_lp, (__bf16 *)wT, g.K, g.R * g.S, g.C);
+  else if (dt == DT_BF16)
+    hipLaunchKernelGGL((prepare_filter_kernel<float, __bf16>), grid, dim3(256), 0, st, (const float *)w, (__bf16 *)w_lp, (__bf16 *)wT, g.K, g.R * g.S, g.C);
+  else
+    hipLaunchKernelGGL((prepare_filter_kernel<float, float>), grid, dim3(256), 0, st, (const float *)w, (float *)w_lp, (float *)wT, g.K, g.R * g.S, g.C);
+  RESIST_CHECK_LAUNCH("prepare_filter");
   return RESIST_OK;
 }
 
@@ -374,8 +415,8 @@ inline FastDiv make_fastdiv(unsigned d) {
 __device__ inline int fdiv(int n, FastDiv f) { return (int)(((unsigned long long)(unsigned)n * f.mul) >> f.sh); }
 
 struct WgradArgs {
-  const float *dy;  // [M][K]
-  const float *x;   // [N][H][W][C]
+  const void *dy;   // [M][K]
+  const void *x;    // [N][H][W][C]
   float *out;       // [splits][K][R][S][C]
   int N, H, W, C, K, R, S, stride, pad, P, Q;
   int M;            // N*P*Q
@@ -384,19 +425,41 @@ struct WgradArgs {
   FastDiv div_pq, div_q;
 };
 
+// 16 bytes of T -> fp32 values written to LDS
+template <typename T> struct ToLds;
+template <> struct ToLds<float> {
+  __device__ static inline void store(float *dst, const f32x4 &v) { *reinterpret_cast<f32x4 *>(dst) = v; }
+};
+template <> struct ToLds<__bf16> {
+  __device__ static inline void store(float *dst, const f32x4 &v) {
+    // a bf16 is the upper half of the fp32 with the same value
+    const unsigned *u = reinterpret_cast<const unsigned *>(&v);
+    f32x4 lo, hi;
+    lo[0] = __builtin_bit_cast(float, u[0] << 16); lo[1] = __builtin_bit_cast(float, u[0] & 0xffff0000u);
+    lo[2] = __builtin_bit_cast(float, u[1] << 16); lo[3] = __builtin_bit_cast(float, u[1] & 0xffff0000u);
+    hi[0] = __builtin_bit_cast(float, u[2] << 16); hi[1] = __builtin_bit_cast(float, u[2] & 0xffff0000u);
+    hi[2] = __builtin_bit_cast(float, u[3] << 16); hi[3] = __builtin_bit_cast(float, u[3] & 0xffff0000u);
+    *reinterpret_cast<f32x4 *>(dst) = lo;
+    *reinterpret_cast<f32x4 *>(dst + 4) = hi;
+  }
+};
+
 // Weight gradient: rows of the GEMM are output channels, columns are input channels of one filter
-// tap (blockIdx.y), the reduction runs over output pixels m (split over blockIdx.z).  Both operand
-// tiles arrive "reduction-major" ([m][channel]) straight from the NHWC tensors.  Same pipeline as
-// the forward kernel: straight-line loop body, bounds-checked buffer loads, LDS refill in the
-// middle of the MFMAs, fragments fetched one k-step ahead.
-template <int BM, int BN, int WGM, int WGN>
-__global__ __launch_bounds__(kThreads) void wgrad_f32_kernel(WgradArgs a) {
+// tap, the reduction runs over output pixels m (split across workgroups).  Both operand tiles arrive
+// "reduction-major" ([m][channel]) straight from the NHWC tensors.  Same pipeline as the forward
+// kernel: straight-line loop body, bounds-checked buffer loads, LDS refill in the middle of the
+// MFMAs, fragments fetched one k-step ahead.  bf16 inputs are widened to fp32 on their way into
+// LDS (exact), so the products and the accumulation are those of the fp32 matrix instruction.
+template <typename T, int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
+  constexpr int VEC = Elem<T>::VEC;
+  constexpr int ES = (int)sizeof(T);
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
-  constexpr int LDA = BM + 32, LDB = BN + 32;   // rows kk and kk+1 land on different bank halves
-  constexpr int TPRA = BM / 4, TPRB = BN / 4;   // threads per 32-row-chunk row
+  constexpr int LDA = BM + 32, LDB = BN + 32;     // rows kk and kk+1 land on different bank halves
+  constexpr int TPRA = BM / VEC, TPRB = BN / VEC; // threads per 32-row-chunk row
   constexpr int RPA = kThreads / TPRA, RPB = kThreads / TPRB;  // rows per pass
-  constexpr int PA = kWBK / RPA, PB = kWBK / RPB;
+  constexpr int PA = (kWBK + RPA - 1) / RPA, PB = (kWBK + RPB - 1) / RPB;
   constexpr int NK = kWBK / 2;
   __shared__ float As[2][kWBK][LDA];
   __shared__ float Bs[2][kWBK][LDB];
@@ -415,12 +478,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_f32_kernel(WgradArgs a) {
   const int mend = min(a.M, mbeg + a.rows_per_split);
   const int nchunks = (mend - mbeg + kWBK - 1) / kWBK;
 
-  const int arow = tid / TPRA, acol = (tid % TPRA) * 4;
-  const int brow = tid / TPRB, bcol = (tid % TPRB) * 4;
-  const unsigned acolb = (k0 + acol) < a.K ? (unsigned)(k0 + acol) * 4u : kOOB;
-  const unsigned bcolb = (c0 + bcol) < a.C ? (unsigned)(c0 + bcol) * 4u : kOOB;
-  const __amdgpu_buffer_rsrc_t rdy = make_rsrc(a.dy, (unsigned)a.M * a.K * 4u);
-  const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (unsigned)a.N * a.H * a.W * a.C * 4u);
+  const int arow = tid / TPRA, acol = (tid % TPRA) * VEC;
+  const int brow = tid / TPRB, bcol = (tid % TPRB) * VEC;
+  const unsigned acolb = (k0 + acol) < a.K ? (unsigned)(k0 + acol) * ES : kOOB;
+  const unsigned bcolb = (c0 + bcol) < a.C ? (unsigned)(c0 + bcol) * ES : kOOB;
+  const __amdgpu_buffer_rsrc_t rdy = make_rsrc(a.dy, (unsigned)a.M * a.K * ES);
+  const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (unsigned)a.N * a.H * a.W * a.C * ES);
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -435,26 +498,30 @@ __global__ __launch_bounds__(kThreads) void wgrad_f32_kernel(WgradArgs a) {
   auto load_global = [&]() {
 #pragma unroll
     for (int i = 0; i < PA; ++i) {
-      const int m = mc + i * RPA + arow;
-      ra[i] = buffer_load_f32x4(rdy, m < mend ? (unsigned)m * (unsigned)a.K * 4u + acolb : kOOB);
+      const int row = i * RPA + arow;
+      const int m = mc + row;
+      ra[i] = buffer_load_16B(rdy, (m < mend && row < kWBK) ? (unsigned)m * (unsigned)a.K * ES + acolb : kOOB);
     }
 #pragma unroll
     for (int i = 0; i < PB; ++i) {
-      const int m = mc + i * RPB + brow;
+      const int row = i * RPB + brow;
+      const int m = mc + row;
       const int n = fdiv(m, a.div_pq);
       const int rem = m - n * (a.P * a.Q);
       const int p = fdiv(rem, a.div_q), q = rem - p * a.Q;
       const int ih = p * a.stride + r - a.pad, iw = q * a.stride + s - a.pad;
-      const bool ok = m < mend && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
-      rb[i] = buffer_load_f32x4(rx, ok ? (unsigned)((n * a.H + ih) * a.W + iw) * (unsigned)a.C * 4u + bcolb : kOOB);
+      const bool ok = m < mend && row < kWBK && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+      rb[i] = buffer_load_16B(rx, ok ? (unsigned)((n * a.H + ih) * a.W + iw) * (unsigned)a.C * ES + bcolb : kOOB);
     }
     mc += kWBK;
   };
   auto store_lds = [&](int stage) {
 #pragma unroll
-    for (int i = 0; i < PA; ++i) *reinterpret_cast<f32x4 *>(&As[stage][i * RPA + arow][acol]) = ra[i];
+    for (int i = 0; i < PA; ++i)
+      if (i * RPA + arow < kWBK) ToLds<T>::store(&As[stage][i * RPA + arow][acol], ra[i]);
 #pragma unroll
-    for (int i = 0; i < PB; ++i) *reinterpret_cast<f32x4 *>(&Bs[stage][i * RPB + brow][bcol]) = rb[i];
+    for (int i = 0; i < PB; ++i)
+      if (i * RPB + brow < kWBK) ToLds<T>::store(&Bs[stage][i * RPB + brow][bcol], rb[i]);
   };
 
   load_global();
@@ -541,9 +608,8 @@ int64_t wgrad_scratch_floats(const ConvGeom &g) {
   return p.splits > 1 ? (int64_t)p.splits * g.K * g.R * g.S * g.C : 0;
 }
 
-int conv_wgrad_f32(const ConvGeom &g, const float *dy, const float *x, float *dw, float *partial,
-                   hipStream_t st) {
-  RESIST_TRY(check_geom(g));
+int conv_wgrad(const ConvGeom &g, int dt, const void *dy, const void *x, float *dw, float *partial, hipStream_t st) {
+  RESIST_TRY(check_geom(g, dt));
   const WgradPlan p = plan_wgrad(g);
   if (p.splits > 1 && !partial) return set_error(RESIST_EWORKSPACE, "wgrad needs split scratch");
   WgradArgs a{};
@@ -559,14 +625,19 @@ int conv_wgrad_f32(const ConvGeom &g, const float *dy, const float *x, float *dw
   dim3 grid((unsigned)(a.tiles_k * a.tiles_c * g.R * g.S * p.splits));
   {
     const double flops = 2.0 * a.M * g.K * g.C * g.R * g.S;
-    const double bytes = 4.0 * ((double)a.M * g.K + (double)g.N * g.H * g.W * g.C + (double)g.K * g.R * g.S * g.C);
-    prof::Scope ps(p.bm == 128 ? "wgrad_f32_128x128" : "wgrad_f32_64x64", flops, bytes, st);
-    if (p.bm == 128)
-      hipLaunchKernelGGL((wgrad_f32_kernel<128, 128, 2, 2>), grid, dim3(kThreads), 0, st, a);
-    else
-      hipLaunchKernelGGL((wgrad_f32_kernel<64, 64, 2, 2>), grid, dim3(kThreads), 0, st, a);
+    const double bytes = esize(dt) * ((double)a.M * g.K + (double)g.N * g.H * g.W * g.C) + 4.0 * g.K * g.R * g.S * g.C;
+    const char *label = dt == DT_BF16 ? (p.bm == 128 ? "wgrad_bf16in_128x128" : "wgrad_bf16in_64x64")
+                                      : (p.bm == 128 ? "wgrad_f32_128x128" : "wgrad_f32_64x64");
+    prof::Scope ps(label, flops, bytes, st);
+    if (dt == DT_BF16) {
+      if (p.bm == 128) hipLaunchKernelGGL((wgrad_kernel<__bf16, 128, 128, 2, 2>), grid, dim3(kThreads), 0, st, a);
+      else hipLaunchKernelGGL((wgrad_kernel<__bf16, 64, 64, 2, 2>), grid, dim3(kThreads), 0, st, a);
+    } else {
+      if (p.bm == 128) hipLaunchKernelGGL((wgrad_kernel<float, 128, 128, 2, 2>), grid, dim3(kThreads), 0, st, a);
+      else hipLaunchKernelGGL((wgrad_kernel<float, 64, 64, 2, 2>), grid, dim3(kThreads), 0, st, a);
+    }
   }
-  RESIST_CHECK_LAUNCH("wgrad_f32");
+  RESIST_CHECK_LAUNCH("wgrad");
   if (p.splits > 1) {
     const long long n4 = (long long)g.K * g.R * g.S * g.C / 4;
     prof::Scope ps("splitk_reduce", 0, 16.0 * n4 * (p.splits + 1), st);

@@ -1,27 +1,33 @@
-// Pooling, the fully connected head and the loss of the sub-ResNet's training step (fp32, NHWC).
-// These are small or bandwidth-bound kernels; every reduction runs in a fixed order.
+// Pooling, the fully connected head and the loss of the sub-ResNet's training step (NHWC).
+// Pooling reads and writes activations in their storage type (fp32 or bf16); pooled features,
+// logits, loss and everything behind them are fp32.  These are small or bandwidth-bound kernels;
+// every reduction runs in a fixed order.
+#include "elem.h"
 #include "internal.h"
 
 namespace resist {
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
 // ---- max pool 3x3 stride 2 pad 1 -----------------------------------------------------------------
 // argmax stores the window tap (r*3+s) of the first maximum in row-major window order.
-__global__ __launch_bounds__(256) void maxpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y,
+// A thread owns V = 4 (fp32) or 8 (bf16) consecutive channels of one pixel.
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y,
                                                           uint8_t *__restrict__ arg, int N, int H, int W, int C, int P, int Q) {
-  const long long total = (long long)N * P * Q * (C / 4);
+  constexpr int V = Vec<T>::N;
+  const long long total = (long long)N * P * Q * (C / V);
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
-  const int c = (int)(i % (C / 4)) * 4;
-  long long pix = i / (C / 4);
+  const int c = (int)(i % (C / V)) * V;
+  long long pix = i / (C / V);
   const int q = (int)(pix % Q); pix /= Q;
   const int p = (int)(pix % P);
   const int n = (int)(pix / P);
-  f32x4 best = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-  int bi[4] = {0, 0, 0, 0};
+  float best[V];
+  int bi[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) { best[e] = -INFINITY; bi[e] = 0; }
   bool any = false;
   for (int r = 0; r < 3; ++r) {
     const int ih = p * 2 + r - 1;
@@ -29,30 +35,37 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const float *__restric
     for (int s = 0; s < 3; ++s) {
       const int iw = q * 2 + s - 1;
       if (iw < 0 || iw >= W) continue;
-      const f32x4 v = *reinterpret_cast<const f32x4 *>(x + ((size_t)(n * H + ih) * W + iw) * C + c);
+      float v[V];
+      Vec<T>::load(x + ((size_t)(n * H + ih) * W + iw) * C + c, v);
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
+      for (int e = 0; e < V; ++e)
         if (!any || v[e] > best[e]) { best[e] = v[e]; bi[e] = r * 3 + s; }
       any = true;
     }
   }
   const size_t off = ((size_t)(n * P + p) * Q + q) * C + c;
-  *reinterpret_cast<f32x4 *>(y + off) = best;
-  *reinterpret_cast<uchar4 *>(arg + off) = make_uchar4((uint8_t)bi[0], (uint8_t)bi[1], (uint8_t)bi[2], (uint8_t)bi[3]);
+  Vec<T>::store(y + off, best);
+#pragma unroll
+  for (int e = 0; e < V; e += 4)
+    *reinterpret_cast<uchar4 *>(arg + off + e) = make_uchar4((uint8_t)bi[e], (uint8_t)bi[e + 1], (uint8_t)bi[e + 2], (uint8_t)bi[e + 3]);
 }
 
 // gather form: every input pixel looks at the (at most 2x2) windows that cover it
-__global__ __launch_bounds__(256) void maxpool_bwd_kernel(const float *__restrict__ dy, const uint8_t *__restrict__ arg,
-                                                          float *__restrict__ dx, int N, int H, int W, int C, int P, int Q) {
-  const long long total = (long long)N * H * W * (C / 4);
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(const T *__restrict__ dy, const uint8_t *__restrict__ arg,
+                                                          T *__restrict__ dx, int N, int H, int W, int C, int P, int Q) {
+  constexpr int V = Vec<T>::N;
+  const long long total = (long long)N * H * W * (C / V);
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
-  const int c = (int)(i % (C / 4)) * 4;
-  long long pix = i / (C / 4);
+  const int c = (int)(i % (C / V)) * V;
+  long long pix = i / (C / V);
   const int w = (int)(pix % W); pix /= W;
   const int h = (int)(pix % H);
   const int n = (int)(pix / H);
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  float acc[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) acc[e] = 0.f;
   // windows p with 2p-1 <= h <= 2p+1
   for (int p = (h >> 1); p <= ((h + 1) >> 1); ++p) {
     if (p < 0 || p >= P) continue;
@@ -61,37 +74,50 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(const float *__restric
       if (q < 0 || q >= Q) continue;
       const int s = w - (2 * q - 1);
       const size_t off = ((size_t)(n * P + p) * Q + q) * C + c;
-      const uchar4 a = *reinterpret_cast<const uchar4 *>(arg + off);
-      const f32x4 g = *reinterpret_cast<const f32x4 *>(dy + off);
+      float g[V];
+      Vec<T>::load(dy + off, g);
       const int tap = r * 3 + s;
-      if (a.x == tap) acc[0] += g[0];
-      if (a.y == tap) acc[1] += g[1];
-      if (a.z == tap) acc[2] += g[2];
-      if (a.w == tap) acc[3] += g[3];
+#pragma unroll
+      for (int e = 0; e < V; ++e)
+        if (arg[off + e] == tap) acc[e] += g[e];
     }
   }
-  *reinterpret_cast<f32x4 *>(dx + ((size_t)(n * H + h) * W + w) * C + c) = acc;
+  Vec<T>::store(dx + ((size_t)(n * H + h) * W + w) * C + c, acc);
 }
 
 // ---- global mean pool ------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void avgpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int N, int HW, int C) {
+template <typename T>
+__global__ __launch_bounds__(256) void avgpool_fwd_kernel(const T *__restrict__ x, float *__restrict__ y, int N, int HW, int C) {
+  constexpr int V = Vec<T>::N;
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= N * (C / 4)) return;
-  const int c = (i % (C / 4)) * 4, n = i / (C / 4);
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (int p = 0; p < HW; ++p) acc += *reinterpret_cast<const f32x4 *>(x + ((size_t)n * HW + p) * C + c);
+  if (i >= N * (C / V)) return;
+  const int c = (i % (C / V)) * V, n = i / (C / V);
+  float acc[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) acc[e] = 0.f;
+  for (int p = 0; p < HW; ++p) {
+    float v[V];
+    Vec<T>::load(x + ((size_t)n * HW + p) * C + c, v);
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] += v[e];
+  }
   const float inv = 1.0f / (float)HW;
-  *reinterpret_cast<f32x4 *>(y + (size_t)n * C + c) = acc * inv;
+#pragma unroll
+  for (int e = 0; e < V; ++e) y[(size_t)n * C + c + e] = acc[e] * inv;
 }
 
-__global__ __launch_bounds__(256) void avgpool_bwd_kernel(const float *__restrict__ dy, float *__restrict__ dx, int N, int HW, int C) {
+template <typename T>
+__global__ __launch_bounds__(256) void avgpool_bwd_kernel(const float *__restrict__ dy, T *__restrict__ dx, int N, int HW, int C) {
+  constexpr int V = Vec<T>::N;
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (long long)N * HW * (C / 4)) return;
-  const int c = (int)(i % (C / 4)) * 4;
-  const int n = (int)(i / ((long long)HW * (C / 4)));
+  if (i >= (long long)N * HW * (C / V)) return;
+  const int c = (int)(i % (C / V)) * V;
+  const int n = (int)(i / ((long long)HW * (C / V)));
   const float inv = 1.0f / (float)HW;
-  const f32x4 g = *reinterpret_cast<const f32x4 *>(dy + (size_t)n * C + c);
-  reinterpret_cast<f32x4 *>(dx)[i] = g * inv;
+  float g[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) g[e] = dy[(size_t)n * C + c + e] * inv;
+  Vec<T>::store(dx + i * V, g);
 }
 
 // ---- fully connected -------------------------------------------------------------------------------
@@ -182,27 +208,43 @@ unsigned blocks_for(long long n, int t = 256) { return (unsigned)((n + t - 1) / 
 
 }  // namespace
 
-int maxpool_fwd_f32(const float *x, float *y, uint8_t *argmax, int N, int H, int W, int C, int P, int Q, hipStream_t st) {
-  prof::Scope ps("maxpool_fwd", 0, 0, st);
-  hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(blocks_for((long long)N * P * Q * (C / 4))), dim3(256), 0, st, x, y, argmax, N, H, W, C, P, Q);
+int maxpool_fwd(int dt, const void *x, void *y, uint8_t *argmax, int N, int H, int W, int C, int P, int Q, hipStream_t st) {
+  const int V = dt == DT_BF16 ? 8 : 4;
+  if (C % V) return set_error(RESIST_ESHAPE, "max-pool: C=%d must be a multiple of %d", C, V);
+  prof::Scope ps("maxpool_fwd", 0, (double)esize(dt) * N * C * ((double)H * W + (double)P * Q) + (double)N * P * Q * C, st);
+  const dim3 grid(blocks_for((long long)N * P * Q * (C / V)));
+  if (dt == DT_BF16) hipLaunchKernelGGL(maxpool_fwd_kernel<__bf16>, grid, dim3(256), 0, st, (const __bf16 *)x, (__bf16 *)y, argmax, N, H, W, C, P, Q);
+  else hipLaunchKernelGGL(maxpool_fwd_kernel<float>, grid, dim3(256), 0, st, (const float *)x, (float *)y, argmax, N, H, W, C, P, Q);
   RESIST_CHECK_LAUNCH("maxpool_fwd");
   return RESIST_OK;
 }
-int maxpool_bwd_f32(const float *dy, const uint8_t *argmax, float *dx, int N, int H, int W, int C, int P, int Q, hipStream_t st) {
-  prof::Scope ps("maxpool_bwd", 0, 0, st);
-  hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(blocks_for((long long)N * H * W * (C / 4))), dim3(256), 0, st, dy, argmax, dx, N, H, W, C, P, Q);
+int maxpool_bwd(int dt, const void *dy, const uint8_t *argmax, void *dx, int N, int H, int W, int C, int P, int Q, hipStream_t st) {
+  const int V = dt == DT_BF16 ? 8 : 4;
+  if (C % V) return set_error(RESIST_ESHAPE, "max-pool: C=%d must be a multiple of %d", C, V);
+  prof::Scope ps("maxpool_bwd", 0, (double)esize(dt) * N * C * ((double)H * W + (double)P * Q) + (double)N * P * Q * C, st);
+  const dim3 grid(blocks_for((long long)N * H * W * (C / V)));
+  if (dt == DT_BF16) hipLaunchKernelGGL(maxpool_bwd_kernel<__bf16>, grid, dim3(256), 0, st, (const __bf16 *)dy, argmax, (__bf16 *)dx, N, H, W, C, P, Q);
+  else hipLaunchKernelGGL(maxpool_bwd_kernel<float>, grid, dim3(256), 0, st, (const float *)dy, argmax, (float *)dx, N, H, W, C, P, Q);
   RESIST_CHECK_LAUNCH("maxpool_bwd");
   return RESIST_OK;
 }
-int avgpool_fwd_f32(const float *x, float *y, int N, int HW, int C, hipStream_t st) {
+int avgpool_fwd(int dt, const void *x, float *y, int N, int HW, int C, hipStream_t st) {
+  const int V = dt == DT_BF16 ? 8 : 4;
+  if (C % V) return set_error(RESIST_ESHAPE, "mean pool: C=%d must be a multiple of %d", C, V);
   prof::Scope ps("avgpool_fwd", 0, 0, st);
-  hipLaunchKernelGGL(avgpool_fwd_kernel, dim3(blocks_for((long long)N * (C / 4))), dim3(256), 0, st, x, y, N, HW, C);
+  const dim3 grid(blocks_for((long long)N * (C / V)));
+  if (dt == DT_BF16) hipLaunchKernelGGL(avgpool_fwd_kernel<__bf16>, grid, dim3(256), 0, st, (const __bf16 *)x, y, N, HW, C);
+  else hipLaunchKernelGGL(avgpool_fwd_kernel<float>, grid, dim3(256), 0, st, (const float *)x, y, N, HW, C);
   RESIST_CHECK_LAUNCH("avgpool_fwd");
   return RESIST_OK;
 }
-int avgpool_bwd_f32(const float *dy, float *dx, int N, int HW, int C, hipStream_t st) {
+int avgpool_bwd(int dt, const float *dy, void *dx, int N, int HW, int C, hipStream_t st) {
+  const int V = dt == DT_BF16 ? 8 : 4;
+  if (C % V) return set_error(RESIST_ESHAPE, "mean pool: C=%d must be a multiple of %d", C, V);
   prof::Scope ps("avgpool_bwd", 0, 0, st);
-  hipLaunchKernelGGL(avgpool_bwd_kernel, dim3(blocks_for((long long)N * HW * (C / 4))), dim3(256), 0, st, dy, dx, N, HW, C);
+  const dim3 grid(blocks_for((long long)N * HW * (C / V)));
+  if (dt == DT_BF16) hipLaunchKernelGGL(avgpool_bwd_kernel<__bf16>, grid, dim3(256), 0, st, dy, (__bf16 *)dx, N, HW, C);
+  else hipLaunchKernelGGL(avgpool_bwd_kernel<float>, grid, dim3(256), 0, st, dy, (float *)dx, N, HW, C);
   RESIST_CHECK_LAUNCH("avgpool_bwd");
   return RESIST_OK;
 }

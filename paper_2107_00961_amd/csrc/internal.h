@@ -97,24 +97,29 @@ inline ConvGeom make_geom(int N, int H, int W, int C, int K, int R, int stride, 
   return g;
 }
 
-// fp32 implicit-GEMM convolution family (conv_f32.hip)
-int conv_fwd_f32(const ConvGeom &g, const float *x, const float *w, float *y, hipStream_t st);
-// dx = dgrad(dy, wT) [+ addend]; wT is the [C][R][S][K] transpose made by transpose_filter_f32
-int conv_dgrad_f32(const ConvGeom &g, const float *dy, const float *wT, float *dx,
-                   const float *addend, hipStream_t st);
-int transpose_filter_f32(const ConvGeom &g, const float *w, float *wT, hipStream_t st);
-// dw = wgrad(dy, x); partial: split-K scratch of wgrad_scratch_floats(g) floats
+// Element types of activations / filters inside the library
+enum { DT_F32 = 0, DT_BF16 = 1 };
+inline int esize(int dt) { return dt == DT_BF16 ? 2 : 4; }
+
+// implicit-GEMM convolution family (conv.hip); dt selects fp32 or bf16 tensors (fp32 accumulation)
+int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, hipStream_t st);
+// dx = dgrad(dy, wT) [+ addend]; wT is the [C][R][S][K] transpose made by prepare_filter
+int conv_dgrad(const ConvGeom &g, int dt, const void *dy, const void *wT, void *dx, const void *addend,
+               hipStream_t st);
+// from a filter stored in src_dt: optional copy in dt (w_lp) and optional transpose in dt (wT)
+int prepare_filter(const ConvGeom &g, int src_dt, int dt, const void *w, void *w_lp, void *wT, hipStream_t st);
+// dw (fp32) = wgrad(dy, x); partial: split-reduction scratch of wgrad_scratch_floats(g) floats
 int64_t wgrad_scratch_floats(const ConvGeom &g);
-int conv_wgrad_f32(const ConvGeom &g, const float *dy, const float *x, float *dw, float *partial,
-                   hipStream_t st);
+int conv_wgrad(const ConvGeom &g, int dt, const void *dy, const void *x, float *dw, float *partial,
+               hipStream_t st);
 
-// stem helpers (stem.hip): NCHW fp32 image -> im2col rows [N*P*Q][kpad], column (r*S+s)*C+c
-int stem_im2col_f32(const float *x_nchw, float *col, int N, int C, int H, int W, int R, int stride,
-                    int pad, int P, int Q, int kpad, hipStream_t st);
-int pad_rows_f32(const float *src, float *dst, int rows, int n, int npad, hipStream_t st);    // [rows][n] -> [rows][npad]
-int unpad_rows_f32(const float *src, float *dst, int rows, int n, int npad, hipStream_t st);  // [rows][npad] -> [rows][n]
+// stem helpers (stem.hip): NCHW fp32 image -> im2col rows [N*P*Q][kpad] in dt, column (r*S+s)*C+c
+int stem_im2col(int dt, const float *x_nchw, void *col, int N, int C, int H, int W, int R, int stride,
+                int pad, int P, int Q, int kpad, hipStream_t st);
+int pad_rows(int dt, const float *src, void *dst, int rows, int n, int npad, hipStream_t st);   // fp32 [rows][n] -> dt [rows][npad]
+int unpad_rows_f32(const float *src, float *dst, int rows, int n, int npad, hipStream_t st);    // [rows][npad] -> [rows][n]
 
-// BatchNorm on [M][C] fp32 (bn.hip)
+// BatchNorm on [M][C] activations in dt, fp32 arithmetic (bn.hip)
 struct BnBufs {
   const float *gamma, *beta;
   float *rmean, *rvar;       // running statistics (updated by stats)
@@ -122,23 +127,23 @@ struct BnBufs {
   float *dgamma, *dbeta;     // [C] gradient outputs
 };
 int64_t bn_scratch_doubles(int C);   // partial-sum scratch for one BN call
-int bn_stats_f32(const float *y, int64_t M, int C, const BnBufs &b, float eps, float momentum,
-                 double *scratch, hipStream_t st);
+int bn_stats(int dt, const void *y, int64_t M, int C, const BnBufs &b, float eps, float momentum,
+             double *scratch, hipStream_t st);
 // a = [relu]( gamma*xhat(y)+beta [+ res] )            res: raw tensor, or BN(res_y) if res_bn given
-int bn_apply_f32(const float *y, int64_t M, int C, const BnBufs &b, const float *res,
-                 const BnBufs *res_bn, bool relu, float *a, hipStream_t st);
+int bn_apply(int dt, const void *y, int64_t M, int C, const BnBufs &b, const void *res,
+             const BnBufs *res_bn, bool relu, void *a, hipStream_t st);
 // gm = g * [mask>0] (mask may be NULL: no masking); dbeta = sum gm; dgamma = sum gm*xhat(y);
 // dy = gamma*invstd*(gm - dbeta/M - xhat*dgamma/M); optionally stores gm to gm_out.
-int bn_backward_f32(const float *g, const float *mask, const float *y, int64_t M, int C,
-                    const BnBufs &b, float *dy, float *gm_out, double *scratch, hipStream_t st);
+int bn_backward(int dt, const void *g, const void *mask, const void *y, int64_t M, int C,
+                const BnBufs &b, void *dy, void *gm_out, double *scratch, hipStream_t st);
 
-// pooling / head / loss (head.hip)
-int maxpool_fwd_f32(const float *x, float *y, uint8_t *argmax, int N, int H, int W, int C, int P,
-                    int Q, hipStream_t st);
-int maxpool_bwd_f32(const float *dy, const uint8_t *argmax, float *dx, int N, int H, int W, int C,
-                    int P, int Q, hipStream_t st);
-int avgpool_fwd_f32(const float *x, float *y, int N, int HW, int C, hipStream_t st);
-int avgpool_bwd_f32(const float *dy, float *dx, int N, int HW, int C, hipStream_t st);
+// pooling / head / loss (head.hip); pooled features, logits and the loss stay fp32
+int maxpool_fwd(int dt, const void *x, void *y, uint8_t *argmax, int N, int H, int W, int C, int P,
+                int Q, hipStream_t st);
+int maxpool_bwd(int dt, const void *dy, const uint8_t *argmax, void *dx, int N, int H, int W, int C,
+                int P, int Q, hipStream_t st);
+int avgpool_fwd(int dt, const void *x, float *y, int N, int HW, int C, hipStream_t st);
+int avgpool_bwd(int dt, const float *dy, void *dx, int N, int HW, int C, hipStream_t st);
 int fc_fwd_f32(const float *x, const float *w, const float *b, float *z, int N, int C, int J,
                hipStream_t st);
 int fc_bwd_f32(const float *dz, const float *x, const float *w, float *dx, float *dw, float *db,

@@ -2,12 +2,15 @@
 // expanded into im2col rows [N*P*Q][kpad] with column (r*S + s)*C + c and zero columns up to kpad
 // (a multiple of the GEMM K-chunk), so that the stem runs as a 1x1 convolution on the same MFMA
 // kernels as every other layer, in both the forward pass and the weight gradient.
+// The rows are written in the storage type of the activations (fp32, or bf16 rounded to nearest even).
+#include "elem.h"
 #include "internal.h"
 
 namespace resist {
 namespace {
 
-__global__ __launch_bounds__(256) void stem_im2col_kernel(const float *__restrict__ x, float *__restrict__ col, int N, int C,
+template <typename T>
+__global__ __launch_bounds__(256) void stem_im2col_kernel(const float *__restrict__ x, T *__restrict__ col, int N, int C,
                                                           int H, int W, int R, int stride, int pad, int P, int Q, int kpad) {
   const long long total = (long long)N * P * Q * kpad;
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -24,41 +27,47 @@ __global__ __launch_bounds__(256) void stem_im2col_kernel(const float *__restric
     const int ih = p * stride + r - pad, iw = q * stride + s - pad;
     if (ih >= 0 && ih < H && iw >= 0 && iw < W) v = x[((size_t)(n * C + c) * H + ih) * W + iw];
   }
-  col[i] = v;
+  Vec<T>::put(col + i, v);
 }
 
-__global__ __launch_bounds__(256) void repitch_rows_kernel(const float *__restrict__ src, float *__restrict__ dst, int rows,
+template <typename T>
+__global__ __launch_bounds__(256) void repitch_rows_kernel(const float *__restrict__ src, T *__restrict__ dst, int rows,
                                                            int n, int src_pitch, int dst_pitch) {
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (long long)rows * dst_pitch) return;
   const int j = (int)(i % dst_pitch);
   const long long r = i / dst_pitch;
-  dst[i] = j < n ? src[r * src_pitch + j] : 0.f;
+  Vec<T>::put(dst + i, j < n ? src[r * src_pitch + j] : 0.f);
 }
 
 }  // namespace
 
-int stem_im2col_f32(const float *x, float *col, int N, int C, int H, int W, int R, int stride, int pad, int P, int Q,
-                    int kpad, hipStream_t st) {
+int stem_im2col(int dt, const float *x, void *col, int N, int C, int H, int W, int R, int stride, int pad, int P, int Q,
+                int kpad, hipStream_t st) {
   const long long total = (long long)N * P * Q * kpad;
   if (total > 0x7fffffffLL * 256) return set_error(RESIST_ESHAPE, "im2col too large");
-  prof::Scope ps("stem_im2col", 0, 4.0 * total, st);
-  hipLaunchKernelGGL(stem_im2col_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, x, col, N, C, H, W, R, stride,
-                     pad, P, Q, kpad);
+  prof::Scope ps("stem_im2col", 0, 4.0 * N * C * H * W + (double)esize(dt) * total, st);
+  const dim3 grid((unsigned)((total + 255) / 256));
+  if (dt == DT_BF16)
+    hipLaunchKernelGGL(stem_im2col_kernel<__bf16>, grid, dim3(256), 0, st, x, (__bf16 *)col, N, C, H, W, R, stride, pad, P, Q, kpad);
+  else
+    hipLaunchKernelGGL(stem_im2col_kernel<float>, grid, dim3(256), 0, st, x, (float *)col, N, C, H, W, R, stride, pad, P, Q, kpad);
   RESIST_CHECK_LAUNCH("stem_im2col");
   return RESIST_OK;
 }
 
-int pad_rows_f32(const float *src, float *dst, int rows, int n, int npad, hipStream_t st) {
+int pad_rows(int dt, const float *src, void *dst, int rows, int n, int npad, hipStream_t st) {
   const long long total = (long long)rows * npad;
-  hipLaunchKernelGGL(repitch_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, src, dst, rows, n, n, npad);
+  const dim3 grid((unsigned)((total + 255) / 256));
+  if (dt == DT_BF16) hipLaunchKernelGGL(repitch_rows_kernel<__bf16>, grid, dim3(256), 0, st, src, (__bf16 *)dst, rows, n, n, npad);
+  else hipLaunchKernelGGL(repitch_rows_kernel<float>, grid, dim3(256), 0, st, src, (float *)dst, rows, n, n, npad);
   RESIST_CHECK_LAUNCH("pad_rows");
   return RESIST_OK;
 }
 
 int unpad_rows_f32(const float *src, float *dst, int rows, int n, int npad, hipStream_t st) {
   const long long total = (long long)rows * n;
-  hipLaunchKernelGGL(repitch_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, src, dst, rows, n, npad, n);
+  hipLaunchKernelGGL(repitch_rows_kernel<float>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, src, dst, rows, n, npad, n);
   RESIST_CHECK_LAUNCH("unpad_rows");
   return RESIST_OK;
 }

@@ -21,14 +21,16 @@ struct Arena {
     off += count * (int64_t)sizeof(T);
     return p;
   }
+  // `count` activation elements of `es` bytes each
+  void *take_act(int64_t count, int es) { return take<char>(count * es); }
 };
 
 struct ConvLayer {
   ConvGeom g;
   int64_t w_off, gamma_off, beta_off, rmean_off, rvar_off;  // offsets inside the block buffer
-  const float *in = nullptr;
-  float *y = nullptr;        // pre-BN output
-  float *a = nullptr;        // post-BN(+ReLU) output; NULL for the layer that ends a block
+  const void *in = nullptr;  // activations are stored in the model's compute type (fp32 or bf16)
+  void *y = nullptr;         // pre-BN output
+  void *a = nullptr;         // post-BN(+ReLU) output; NULL for the layer that ends a block
   float *mean = nullptr, *invstd = nullptr;
   int64_t M() const { return (int64_t)g.N * g.P * g.Q; }
 };
@@ -38,8 +40,8 @@ struct BlockPlan {
   std::vector<ConvLayer> convs;
   bool has_ds = false;
   ConvLayer ds;
-  const float *in = nullptr;
-  float *out = nullptr;
+  const void *in = nullptr;
+  void *out = nullptr;
   int64_t out_elems = 0;
 };
 
@@ -50,17 +52,19 @@ struct StepPlan {
   // stem
   int kpad = 0;
   ConvLayer stem;                     // geometry of the 1x1 GEMM over im2col rows
-  float *col = nullptr, *wpad = nullptr, *dwpad = nullptr;
-  float *stem_pool = nullptr;
+  void *col = nullptr, *wpad = nullptr;   // im2col rows and the padded filter, in the compute type
+  float *dwpad = nullptr;
+  void *stem_pool = nullptr;
   uint8_t *stem_argmax = nullptr;
   std::vector<BlockPlan> blocks;
   // head
   float *pooled = nullptr, *z = nullptr, *dz = nullptr, *row_loss = nullptr, *dpooled = nullptr;
-  const float *feat = nullptr;
+  const void *feat = nullptr;
   int feat_hw = 0;
   // shared scratch
-  float *gbuf[2] = {nullptr, nullptr}, *gm = nullptr, *dy0 = nullptr, *dy1 = nullptr, *da = nullptr;
-  float *wT = nullptr, *splitk = nullptr;
+  void *gbuf[2] = {nullptr, nullptr}, *gm = nullptr, *dy0 = nullptr, *dy1 = nullptr, *da = nullptr;
+  void *wT = nullptr, *wlp = nullptr;     // transposed filter; low-precision copy of a filter (bf16 mode)
+  float *splitk = nullptr;
   double *bn_scratch = nullptr;
   std::vector<float *> own_grads;     // per slot, when the caller passes no gradient buffers
   int64_t bytes = 0;
@@ -82,7 +86,6 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
   RESIST_TRY(build_net(desc, &P->net));
   const Net &net = P->net;
   const int B = (int)net.blocks.size();
-  if (desc->compute_dtype != 0) return set_error(RESIST_EUNSUPPORTED, "compute_dtype %d is not available in this build", desc->compute_dtype);
   if (batch < 1) return set_error(RESIST_EINVAL, "batch=%d", batch);
   if (nblocks < 0 || (nblocks > 0 && !blocks)) return set_error(RESIST_EINVAL, "blocks/nblocks");
   for (int i = 0; i < nblocks; ++i) {
@@ -94,6 +97,7 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
       return set_error(RESIST_ESHAPE, "first block %d of a stage is missing: the residual stream would change shape", f);
   P->batch = batch;
   const int N = batch;
+  const int es = esize(net.d.compute_dtype);
   Arena A(ws);
 
   P->layouts.resize(nblocks + 2);
@@ -106,7 +110,8 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
   auto track = [&](const ConvLayer &c, bool needs_dgrad) {
     max_act = std::max<int64_t>(max_act, c.M() * c.g.K);
     max_act = std::max<int64_t>(max_act, (int64_t)c.g.N * c.g.H * c.g.W * c.g.C);
-    if (needs_dgrad) max_filter = std::max<int64_t>(max_filter, (int64_t)c.g.K * c.g.R * c.g.S * c.g.C);
+    (void)needs_dgrad;
+    max_filter = std::max<int64_t>(max_filter, (int64_t)c.g.K * c.g.R * c.g.S * c.g.C);
     max_splitk = std::max<int64_t>(max_splitk, wgrad_scratch_floats(c.g));
     max_c = std::max(max_c, c.g.K);
   };
@@ -118,12 +123,12 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
     const int K0 = net.d.width[0];
     ConvLayer &s = P->stem;
     s = make_conv(P->layouts[0], 0, N, net.stem_h, net.stem_w, P->kpad, K0, 1, 1, 0);
-    P->col = A.take<float>(s.M() * P->kpad);
-    P->wpad = A.take<float>((int64_t)K0 * P->kpad);
+    P->col = A.take_act(s.M() * P->kpad, es);
+    P->wpad = A.take_act((int64_t)K0 * P->kpad, es);
     P->dwpad = A.take<float>((int64_t)K0 * P->kpad);
     s.in = P->col;
-    s.y = A.take<float>(s.M() * K0);
-    s.a = A.take<float>(s.M() * K0);
+    s.y = A.take_act(s.M() * K0, es);
+    s.a = A.take_act(s.M() * K0, es);
     s.mean = A.take<float>(K0);
     s.invstd = A.take<float>(K0);
     max_act = std::max<int64_t>(max_act, s.M() * K0);
@@ -131,11 +136,11 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
     max_c = std::max(max_c, K0);
     if (net.d.stem_kind == 1) {
       const int64_t n = (int64_t)N * net.body_h * net.body_w * K0;
-      P->stem_pool = A.take<float>(n);
+      P->stem_pool = A.take_act(n, es);
       P->stem_argmax = A.take<uint8_t>(n);
     }
   }
-  const float *cur = net.d.stem_kind == 1 ? P->stem_pool : P->stem.a;
+  const void *cur = net.d.stem_kind == 1 ? P->stem_pool : P->stem.a;
 
   // ---- residual blocks the sub-ResNet keeps
   P->blocks.resize(nblocks);
@@ -153,15 +158,15 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
       bp.convs.push_back(make_conv(L, 1, N, bs.h_in, bs.w_in, bs.width, bs.width, 3, bs.stride, 1));
       bp.convs.push_back(make_conv(L, 2, N, bs.h_out, bs.w_out, bs.width, bs.c_out, 1, 1, 0));
     }
-    const float *x = bp.in;
+    const void *x = bp.in;
     for (size_t j = 0; j < bp.convs.size(); ++j) {
       ConvLayer &c = bp.convs[j];
       c.in = x;
-      c.y = A.take<float>(c.M() * c.g.K);
+      c.y = A.take_act(c.M() * c.g.K, es);
       c.mean = A.take<float>(c.g.K);
       c.invstd = A.take<float>(c.g.K);
       if (j + 1 < bp.convs.size()) {
-        c.a = A.take<float>(c.M() * c.g.K);
+        c.a = A.take_act(c.M() * c.g.K, es);
         x = c.a;
       }
       track(c, true);
@@ -171,13 +176,13 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
       ConvLayer &d = bp.ds;
       d = make_conv(L, 3, N, bs.h_in, bs.w_in, bs.c_in, bs.c_out, 1, bs.stride, 0);
       d.in = bp.in;
-      d.y = A.take<float>(d.M() * d.g.K);
+      d.y = A.take_act(d.M() * d.g.K, es);
       d.mean = A.take<float>(d.g.K);
       d.invstd = A.take<float>(d.g.K);
       track(d, true);
     }
     bp.out_elems = (int64_t)N * bs.h_out * bs.w_out * bs.c_out;
-    bp.out = A.take<float>(bp.out_elems);
+    bp.out = A.take_act(bp.out_elems, es);
     cur = bp.out;
   }
 
@@ -195,13 +200,14 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
   }
 
   // ---- backward scratch shared by all layers (kernels are stream-ordered)
-  P->gbuf[0] = A.take<float>(max_act);
-  P->gbuf[1] = A.take<float>(max_act);
-  P->gm = A.take<float>(max_act);
-  P->dy0 = A.take<float>(max_act);
-  P->dy1 = A.take<float>(max_act);
-  P->da = A.take<float>(max_act);
-  P->wT = A.take<float>(max_filter);
+  P->gbuf[0] = A.take_act(max_act, es);
+  P->gbuf[1] = A.take_act(max_act, es);
+  P->gm = A.take_act(max_act, es);
+  P->dy0 = A.take_act(max_act, es);
+  P->dy1 = A.take_act(max_act, es);
+  P->da = A.take_act(max_act, es);
+  P->wT = A.take_act(max_filter, es);
+  if (net.d.compute_dtype == DT_BF16) P->wlp = A.take_act(max_filter, es);
   P->splitk = A.take<float>(max_splitk);
   P->bn_scratch = A.take<double>(bn_scratch_doubles(max_c));
   P->own_grads.resize(nblocks + 2);
@@ -262,87 +268,100 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
   auto params = [&](int slot) { return (float *)block_params[slot]; };
   auto grads = [&](int slot) { return block_grads ? (float *)block_grads[slot] : P.own_grads[slot]; };
 
+  const int dt = net.d.compute_dtype;
+  // the filter a convolution multiplies with: the fp32 master itself, or its bf16 copy made just before
+  auto fwd_filter = [&](const ConvLayer &c, const float *w, const void **out) -> int {
+    if (dt == DT_F32) { *out = w; return RESIST_OK; }
+    RESIST_TRY(prepare_filter(c.g, DT_F32, dt, w, P.wlp, nullptr, st));
+    *out = P.wlp;
+    return RESIST_OK;
+  };
+
   // ================= forward =================
   {
     ConvLayer &s = P.stem;
     const int K0 = net.d.width[0];
     const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
-    RESIST_TRY(stem_im2col_f32(x, P.col, N, net.d.in_c, net.d.in_h, net.d.in_w, net.stem_rs, net.stem_stride, net.stem_pad,
-                               net.stem_h, net.stem_w, P.kpad, st));
-    RESIST_TRY(pad_rows_f32(params(0) + s.w_off, P.wpad, K0, taps, P.kpad, st));
-    RESIST_TRY(conv_fwd_f32(s.g, P.col, P.wpad, s.y, st));
+    RESIST_TRY(stem_im2col(dt, x, P.col, N, net.d.in_c, net.d.in_h, net.d.in_w, net.stem_rs, net.stem_stride, net.stem_pad,
+                           net.stem_h, net.stem_w, P.kpad, st));
+    RESIST_TRY(pad_rows(dt, params(0) + s.w_off, P.wpad, K0, taps, P.kpad, st));
+    RESIST_TRY(conv_fwd(s.g, dt, P.col, P.wpad, s.y, st));
     BnBufs b = bn_bufs(s, params(0), grads(0));
-    RESIST_TRY(bn_stats_f32(s.y, s.M(), K0, b, eps, bnm, P.bn_scratch, st));
-    RESIST_TRY(bn_apply_f32(s.y, s.M(), K0, b, nullptr, nullptr, true, s.a, st));
+    RESIST_TRY(bn_stats(dt, s.y, s.M(), K0, b, eps, bnm, P.bn_scratch, st));
+    RESIST_TRY(bn_apply(dt, s.y, s.M(), K0, b, nullptr, nullptr, true, s.a, st));
     if (net.d.stem_kind == 1)
-      RESIST_TRY(maxpool_fwd_f32(s.a, P.stem_pool, P.stem_argmax, N, net.stem_h, net.stem_w, K0, net.body_h, net.body_w, st));
+      RESIST_TRY(maxpool_fwd(dt, s.a, P.stem_pool, P.stem_argmax, N, net.stem_h, net.stem_w, K0, net.body_h, net.body_w, st));
   }
   for (BlockPlan &bp : P.blocks) {
     float *pp = params(bp.slot), *gg = grads(bp.slot);
     for (size_t j = 0; j < bp.convs.size(); ++j) {
       ConvLayer &c = bp.convs[j];
-      RESIST_TRY(conv_fwd_f32(c.g, c.in, pp + c.w_off, c.y, st));
+      const void *wf;
+      RESIST_TRY(fwd_filter(c, pp + c.w_off, &wf));
+      RESIST_TRY(conv_fwd(c.g, dt, c.in, wf, c.y, st));
       BnBufs b = bn_bufs(c, pp, gg);
-      RESIST_TRY(bn_stats_f32(c.y, c.M(), c.g.K, b, eps, bnm, P.bn_scratch, st));
-      if (c.a) RESIST_TRY(bn_apply_f32(c.y, c.M(), c.g.K, b, nullptr, nullptr, true, c.a, st));
+      RESIST_TRY(bn_stats(dt, c.y, c.M(), c.g.K, b, eps, bnm, P.bn_scratch, st));
+      if (c.a) RESIST_TRY(bn_apply(dt, c.y, c.M(), c.g.K, b, nullptr, nullptr, true, c.a, st));
     }
     ConvLayer &last = bp.convs.back();
     BnBufs bl = bn_bufs(last, pp, gg);
     if (bp.has_ds) {
       ConvLayer &d = bp.ds;
-      RESIST_TRY(conv_fwd_f32(d.g, d.in, pp + d.w_off, d.y, st));
+      const void *wf;
+      RESIST_TRY(fwd_filter(d, pp + d.w_off, &wf));
+      RESIST_TRY(conv_fwd(d.g, dt, d.in, wf, d.y, st));
       BnBufs bd = bn_bufs(d, pp, gg);
-      RESIST_TRY(bn_stats_f32(d.y, d.M(), d.g.K, bd, eps, bnm, P.bn_scratch, st));
-      RESIST_TRY(bn_apply_f32(last.y, last.M(), last.g.K, bl, d.y, &bd, true, bp.out, st));
+      RESIST_TRY(bn_stats(dt, d.y, d.M(), d.g.K, bd, eps, bnm, P.bn_scratch, st));
+      RESIST_TRY(bn_apply(dt, last.y, last.M(), last.g.K, bl, d.y, &bd, true, bp.out, st));
     } else {
-      RESIST_TRY(bn_apply_f32(last.y, last.M(), last.g.K, bl, bp.in, nullptr, true, bp.out, st));
+      RESIST_TRY(bn_apply(dt, last.y, last.M(), last.g.K, bl, bp.in, nullptr, true, bp.out, st));
     }
   }
   const int J = net.d.num_classes, CH = net.head_c;
   const int hs = nslots - 1;
   const BlockLayout &HL = P.layouts[hs];
   float *fcw = params(hs) + HL.off(T_FCW, 0), *fcb = params(hs) + HL.off(T_FCB, 0);
-  RESIST_TRY(avgpool_fwd_f32(P.feat, P.pooled, N, P.feat_hw, CH, st));
+  RESIST_TRY(avgpool_fwd(dt, P.feat, P.pooled, N, P.feat_hw, CH, st));
   RESIST_TRY(fc_fwd_f32(P.pooled, fcw, fcb, P.z, N, CH, J, st));
   RESIST_TRY(softmax_ce_f32(P.z, labels, loss_out, P.dz, P.row_loss, N, J, st));
 
   // ================= backward =================
   RESIST_TRY(fc_bwd_f32(P.dz, P.pooled, fcw, P.dpooled, grads(hs) + HL.off(T_FCW, 0), grads(hs) + HL.off(T_FCB, 0), N, CH, J, st));
   int gi = 0;
-  float *G = P.gbuf[gi];
-  RESIST_TRY(avgpool_bwd_f32(P.dpooled, G, N, P.feat_hw, CH, st));
+  void *G = P.gbuf[gi];
+  RESIST_TRY(avgpool_bwd(dt, P.dpooled, G, N, P.feat_hw, CH, st));
   for (int bi = (int)P.blocks.size() - 1; bi >= 0; --bi) {
     BlockPlan &bp = P.blocks[bi];
     float *pp = params(bp.slot), *gg = grads(bp.slot);
-    float *Gn = P.gbuf[gi ^ 1];
+    void *Gn = P.gbuf[gi ^ 1];
     const int nc = (int)bp.convs.size();
     ConvLayer &last = bp.convs[nc - 1];
     BnBufs bl = bn_bufs(last, pp, gg);
     // through the final ReLU and the last BN of the residual branch
-    RESIST_TRY(bn_backward_f32(G, bp.out, last.y, last.M(), last.g.K, bl, P.dy0, bp.has_ds ? nullptr : P.gm, P.bn_scratch, st));
+    RESIST_TRY(bn_backward(dt, G, bp.out, last.y, last.M(), last.g.K, bl, P.dy0, bp.has_ds ? nullptr : P.gm, P.bn_scratch, st));
     if (bp.has_ds) {
       // shortcut branch: BN and 1x1 convolution; its data gradient initialises Gn
       ConvLayer &d = bp.ds;
       BnBufs bd = bn_bufs(d, pp, gg);
-      RESIST_TRY(bn_backward_f32(G, bp.out, d.y, d.M(), d.g.K, bd, P.gm, nullptr, P.bn_scratch, st));
-      RESIST_TRY(conv_wgrad_f32(d.g, P.gm, d.in, gg + d.w_off, P.splitk, st));
-      RESIST_TRY(transpose_filter_f32(d.g, pp + d.w_off, P.wT, st));
-      RESIST_TRY(conv_dgrad_f32(d.g, P.gm, P.wT, Gn, nullptr, st));
+      RESIST_TRY(bn_backward(dt, G, bp.out, d.y, d.M(), d.g.K, bd, P.gm, nullptr, P.bn_scratch, st));
+      RESIST_TRY(conv_wgrad(d.g, dt, P.gm, d.in, gg + d.w_off, P.splitk, st));
+      RESIST_TRY(prepare_filter(d.g, DT_F32, dt, pp + d.w_off, nullptr, P.wT, st));
+      RESIST_TRY(conv_dgrad(d.g, dt, P.gm, P.wT, Gn, nullptr, st));
     }
-    float *dy = P.dy0, *dy_other = P.dy1;
+    void *dy = P.dy0, *dy_other = P.dy1;
     for (int j = nc - 1; j >= 0; --j) {
       ConvLayer &c = bp.convs[j];
-      RESIST_TRY(conv_wgrad_f32(c.g, dy, c.in, gg + c.w_off, P.splitk, st));
-      RESIST_TRY(transpose_filter_f32(c.g, pp + c.w_off, P.wT, st));
+      RESIST_TRY(conv_wgrad(c.g, dt, dy, c.in, gg + c.w_off, P.splitk, st));
+      RESIST_TRY(prepare_filter(c.g, DT_F32, dt, pp + c.w_off, nullptr, P.wT, st));
       if (j > 0) {
         ConvLayer &prev = bp.convs[j - 1];
-        RESIST_TRY(conv_dgrad_f32(c.g, dy, P.wT, P.da, nullptr, st));
+        RESIST_TRY(conv_dgrad(c.g, dt, dy, P.wT, P.da, nullptr, st));
         BnBufs bp_ = bn_bufs(prev, pp, gg);
-        RESIST_TRY(bn_backward_f32(P.da, prev.a, prev.y, prev.M(), prev.g.K, bp_, dy_other, nullptr, P.bn_scratch, st));
+        RESIST_TRY(bn_backward(dt, P.da, prev.a, prev.y, prev.M(), prev.g.K, bp_, dy_other, nullptr, P.bn_scratch, st));
         std::swap(dy, dy_other);
       } else {
         // gradient w.r.t. the block input = branch + shortcut
-        RESIST_TRY(conv_dgrad_f32(c.g, dy, P.wT, Gn, bp.has_ds ? Gn : P.gm, st));
+        RESIST_TRY(conv_dgrad(c.g, dt, dy, P.wT, Gn, bp.has_ds ? Gn : P.gm, st));
       }
     }
     gi ^= 1;
@@ -352,14 +371,14 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     ConvLayer &s = P.stem;
     const int K0 = net.d.width[0];
     const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
-    const float *Gs = G;
+    const void *Gs = G;
     if (net.d.stem_kind == 1) {
-      RESIST_TRY(maxpool_bwd_f32(G, P.stem_argmax, P.da, N, net.stem_h, net.stem_w, K0, net.body_h, net.body_w, st));
+      RESIST_TRY(maxpool_bwd(dt, G, P.stem_argmax, P.da, N, net.stem_h, net.stem_w, K0, net.body_h, net.body_w, st));
       Gs = P.da;
     }
     BnBufs b = bn_bufs(s, params(0), grads(0));
-    RESIST_TRY(bn_backward_f32(Gs, s.a, s.y, s.M(), K0, b, P.dy0, nullptr, P.bn_scratch, st));
-    RESIST_TRY(conv_wgrad_f32(s.g, P.dy0, P.col, P.dwpad, P.splitk, st));
+    RESIST_TRY(bn_backward(dt, Gs, s.a, s.y, s.M(), K0, b, P.dy0, nullptr, P.bn_scratch, st));
+    RESIST_TRY(conv_wgrad(s.g, dt, P.dy0, P.col, P.dwpad, P.splitk, st));
     RESIST_TRY(unpad_rows_f32(P.dwpad, grads(0) + s.w_off, K0, taps, P.kpad, st));
   }
 

@@ -73,6 +73,66 @@ def test_conv_wgrad(case):
     assert_close(dw.cpu().numpy().transpose(0, 3, 1, 2), want, f"conv wgrad {case}")
 
 
+# ---- bf16 operands, fp32 accumulation ---------------------------------------------------------
+# Inputs are bfloat16 numbers, so the oracle's float64 result is the exact convolution of what the
+# kernel reads.  Outputs stored as bfloat16 carry half a bfloat16 ulp (2^-9 relative, 2^-8 of the
+# value's power of two) on top of the fp32 accumulation error; weight gradients are fp32.
+BF16_CASES = [c for c in CASES if c[3] % 8 == 0 and c[4] % 8 == 0]
+
+
+def _bf16_tensors(case, seed):
+    x, w, dy = _tensors(case, seed)
+    r = lambda a: torch.from_numpy(a).to(torch.bfloat16)
+    return r(x), r(w), r(dy)
+
+
+def _nhwc_t(t):
+    return t.permute(0, 2, 3, 1).contiguous().cuda()
+
+
+def _f64(t):
+    return t.to(torch.float64).numpy()
+
+
+@pytest.mark.parametrize("case", BF16_CASES)
+def test_conv_forward_bf16(case):
+    print("case", case, flush=True)
+    x, w, _ = _bf16_tensors(case, 3)
+    st, pad = case[6], case[7]
+    y = R.conv2d_forward(_nhwc_t(x), _nhwc_t(w), st, pad)
+    torch.cuda.synchronize()
+    assert y.dtype == torch.bfloat16
+    want = L.conv2d_fwd(_f64(x), _f64(w), st, pad)
+    assert_close(y.cpu().to(torch.float64).numpy().transpose(0, 3, 1, 2), want, f"bf16 conv fwd {case}",
+                 rtol=2.0 ** -8, atol=1e-5)
+
+
+@pytest.mark.parametrize("case", BF16_CASES)
+def test_conv_dgrad_bf16(case):
+    print("case", case, flush=True)
+    x, w, dy = _bf16_tensors(case, 4)
+    N, H, W, C, K, RS, st, pad = case
+    dx = R.conv2d_dgrad(_nhwc_t(dy), _nhwc_t(w), (N, H, W, C), st, pad)
+    torch.cuda.synchronize()
+    assert dx.dtype == torch.bfloat16
+    want = L.conv2d_dgrad(_f64(dy), _f64(w), tuple(x.shape), st, pad)
+    assert_close(dx.cpu().to(torch.float64).numpy().transpose(0, 3, 1, 2), want, f"bf16 conv dgrad {case}",
+                 rtol=2.0 ** -8, atol=1e-5)
+
+
+@pytest.mark.parametrize("case", BF16_CASES)
+def test_conv_wgrad_bf16(case):
+    print("case", case, flush=True)
+    x, w, dy = _bf16_tensors(case, 5)
+    N, H, W, C, K, RS, st, pad = case
+    dy = (dy.to(torch.float32) / float(np.sqrt(dy.shape[0] * dy.shape[2] * dy.shape[3]))).to(torch.bfloat16)
+    dw = R.conv2d_wgrad(_nhwc_t(dy), _nhwc_t(x), (K, RS, RS, C), st, pad)
+    torch.cuda.synchronize()
+    assert dw.dtype == torch.float32
+    want = L.conv2d_wgrad(_f64(dy), _f64(x), tuple(w.shape), st, pad)
+    assert_close(dw.cpu().numpy().transpose(0, 3, 1, 2), want, f"bf16 conv wgrad {case}")
+
+
 def test_conv_rejects_bad_shapes():
     x = torch.zeros((1, 4, 4, 6), device="cuda")
     w = torch.zeros((8, 3, 3, 6), device="cuda")

@@ -30,12 +30,23 @@ def _measured_traffic(kernel):
         return None
 
 
+def _describe(name, cfg, sub):
+    if name == "cfg1":
+        return "cfg1: tiny 2-block network"
+    shape = "ImageNet-shaped bottleneck" if cfg["model"]["block_kind"] == 1 else "CIFAR-shaped"
+    if cfg["S"] == 1:
+        return f"{name}: {shape} full model (S=1)"
+    return f"{name}: {shape} sub-ResNet {sub} of S={cfg['S']}"
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2", help="cfg1 | cfg2 | cfg3 | cfg5 (fp32 workloads)")
+    ap.add_argument("--workload", default="cfg2",
+                    help="cfg1 | cfg2 | cfg3 | cfg5 (fp32) | cfg4 | cfg5_bf16 (bf16 storage, fp32 accumulation)")
+    ap.add_argument("--sub", type=int, default=0, help="which sub-ResNet of the partition to step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=32)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -54,7 +65,7 @@ def main():
     cfg = get_config(args.workload)
     model, batch = cfg["model"], cfg["batch"]
     subs, _ = R.partition(model, cfg["S"], cfg["min_depth"], cfg["part_seed"], 0)
-    blocks = subs[0]
+    blocks = subs[args.sub]
     params = make_params(model, 0)
     sub = SubResNet(model, blocks, params, batch, keep_grads=False)
     x, y = make_batch(model, batch, cfg["data_seed"])
@@ -119,7 +130,7 @@ def main():
         from oracle import layers as OL
         from oracle import resnet as OR
         from resist_inputs import zeros_like_params
-        nb = min(args.cpu_sample_batch, batch)
+        nb = min(args.cpu_sample_batch if model["in_h"] <= 64 else max(1, args.cpu_sample_batch // 8), batch)
         xs, ys = make_batch(model, nb, cfg["data_seed"])
         OL._conv_lib()                         # build/load outside the timed region
         t2 = time.perf_counter()
@@ -137,8 +148,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
-        "config": {"workload": f"{args.workload}: CIFAR-shaped sub-ResNet 0 of S={cfg['S']}" if args.workload != "cfg1"
-                   else "cfg1: tiny 2-block network",
+        "config": {"workload": _describe(args.workload, cfg, args.sub),
                    "batch": batch, "blocks": blocks, "block_kind": "basic" if model["block_kind"] == 0 else "bottleneck",
                    "widths": model["widths"], "blocks_per_stage": model["blocks"], "classes": model["num_classes"]},
         "roofline": roof,

@@ -215,43 +215,56 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
     for (int i = 0; i < PB; ++i) *reinterpret_cast<f32x4 *>(&Bs[stage][i * RPP + lrow][kvec]) = rb[i];
   };
 
-  // prologue: chunk 0 into LDS stage 0, chunk 1 on its way in registers
+  // Pipeline.  Chunk `it` is multiplied out of LDS stage it&1, one k-step (2*VEC values of K) at a
+  // time; the fragments of a k-step are fetched from LDS during the MFMAs of the k-step before it,
+  // also across the chunk boundary.  In k-step KREFILL the registers holding chunk it+1 (requested
+  // from global memory one chunk of MFMA time earlier) go to the other stage and chunk it+2 is
+  // requested.  The one barrier per chunk sits at the start of the last k-step: by then every wave
+  // has all fragments of this stage in registers and has written its share of the next stage, so
+  // after it the first fragments of chunk it+1 can be fetched while the last MFMAs of chunk it run.
+  constexpr int KREFILL = NK / 2 - 1;
+  static_assert(NK % 2 == 0, "fragment double buffer parity");
+  const int lr = lane & 31, lk = (lane >> 5) * VEC;
+  f32x4 fa[2][TM], fb[2][TN];
+  auto load_frags = [&](int buf, int stage, int ks) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[buf][i] = *reinterpret_cast<const f32x4 *>(&As[stage][wm * WTM + i * 32 + lr][ks * 2 * VEC + lk]);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[buf][j] = *reinterpret_cast<const f32x4 *>(&Bs[stage][wn * WTN + j * 32 + lr][ks * 2 * VEC + lk]);
+  };
+  auto lds_barrier = [&]() {
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wave's LDS writes and reads are done
+    __builtin_amdgcn_s_barrier();
+  };
+
   load_global();
   store_lds(0);
   load_global();
-  __syncthreads();
+  lds_barrier();
+  load_frags(0, 0, 0);
+  __builtin_amdgcn_sched_barrier(0);
 
-  // Chunk `it` is multiplied out of stage it&1.  Half way through, the registers holding chunk it+1
-  // (requested one chunk of MFMA time earlier) go to the other stage and chunk it+2 is requested;
-  // fragments of k-step ks+1 are fetched from LDS before the MFMAs of k-step ks.
-  const int lr = lane & 31, lk = (lane >> 5) * VEC;
   for (int it = 0; it < nchunks; ++it) {
     const int stage = it & 1;
-    f32x4 fa[2][TM], fb[2][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) fa[0][i] = *reinterpret_cast<const f32x4 *>(&As[stage][wm * WTM + i * 32 + lr][lk]);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) fb[0][j] = *reinterpret_cast<const f32x4 *>(&Bs[stage][wn * WTN + j * 32 + lr][lk]);
 #pragma unroll
     for (int ks = 0; ks < NK; ++ks) {
       if (ks + 1 < NK) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-          fa[(ks + 1) & 1][i] = *reinterpret_cast<const f32x4 *>(&As[stage][wm * WTM + i * 32 + lr][(ks + 1) * 2 * VEC + lk]);
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          fb[(ks + 1) & 1][j] = *reinterpret_cast<const f32x4 *>(&Bs[stage][wn * WTN + j * 32 + lr][(ks + 1) * 2 * VEC + lk]);
+        load_frags((ks + 1) & 1, stage, ks + 1);
+      } else {
+        lds_barrier();
+        load_frags(0, stage ^ 1, 0);   // past the last chunk: zeros nobody uses
       }
-      if (ks == NK / 2) {
-        store_lds(stage ^ 1);   // past the last chunk this writes zeros nobody reads
+      __builtin_amdgcn_sched_barrier(0);   // keep the fetches ahead of this k-step's MFMAs
+      if (ks == KREFILL) {
+        store_lds(stage ^ 1);
         load_global();
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) E::mma(acc[i][j], fa[ks & 1][i], fb[ks & 1][j]);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __syncthreads();
   }
 
   // epilogue: lane holds column (lane%32), rows 8*(e/4) + 4*(lane/32) + e%4 of each 32x32 tile
@@ -524,28 +537,41 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
       if (i * RPB + brow < kWBK) ToLds<T>::store(&Bs[stage][i * RPB + brow][bcol], rb[i]);
   };
 
+  // same pipeline as the forward kernel: fragments one k-step ahead (also across chunks), refill of
+  // the other stage in k-step KREFILL, one barrier per chunk at the start of the last k-step
+  constexpr int KREFILL = NK / 2 - 1;
+  static_assert(NK % 2 == 0, "fragment double buffer parity");
+  const int lr = lane & 31, lh = lane >> 5;
+  float fa[2][TM], fb[2][TN];
+  auto load_frags = [&](int buf, int stage, int ks) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[buf][i] = As[stage][ks * 2 + lh][wm * WTM + i * 32 + lr];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[buf][j] = Bs[stage][ks * 2 + lh][wn * WTN + j * 32 + lr];
+  };
+  auto lds_barrier = [&]() {
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+  };
   load_global();
   store_lds(0);
   load_global();
-  __syncthreads();
-  const int lr = lane & 31, lh = lane >> 5;
+  lds_barrier();
+  load_frags(0, 0, 0);
+  __builtin_amdgcn_sched_barrier(0);
   for (int it = 0; it < nchunks; ++it) {
     const int stage = it & 1;
-    float fa[2][TM], fb[2][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) fa[0][i] = As[stage][lh][wm * WTM + i * 32 + lr];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) fb[0][j] = Bs[stage][lh][wn * WTN + j * 32 + lr];
 #pragma unroll
     for (int ks = 0; ks < NK; ++ks) {
       if (ks + 1 < NK) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[(ks + 1) & 1][i] = As[stage][(ks + 1) * 2 + lh][wm * WTM + i * 32 + lr];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[(ks + 1) & 1][j] = Bs[stage][(ks + 1) * 2 + lh][wn * WTN + j * 32 + lr];
+        load_frags((ks + 1) & 1, stage, ks + 1);
+      } else {
+        lds_barrier();
+        load_frags(0, stage ^ 1, 0);   // rows past mend were loaded as zeros
       }
-      if (ks == NK / 2) {
-        store_lds(stage ^ 1);   // rows past mend were loaded as zeros
+      __builtin_amdgcn_sched_barrier(0);
+      if (ks == KREFILL) {
+        store_lds(stage ^ 1);
         load_global();
       }
 #pragma unroll
@@ -553,8 +579,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __syncthreads();
   }
 
   float *out = a.out + (size_t)split * a.K * a.R * a.S * a.C;

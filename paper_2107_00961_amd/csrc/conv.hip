@@ -438,35 +438,16 @@ struct WgradArgs {
   FastDiv div_pq, div_q;
 };
 
-// 16 bytes of T -> fp32 values written to LDS
-template <typename T> struct ToLds;
-template <> struct ToLds<float> {
-  __device__ static inline void store(float *dst, const f32x4 &v) { *reinterpret_cast<f32x4 *>(dst) = v; }
-};
-template <> struct ToLds<__bf16> {
-  __device__ static inline void store(float *dst, const f32x4 &v) {
-    // a bf16 is the upper half of the fp32 with the same value
-    const unsigned *u = reinterpret_cast<const unsigned *>(&v);
-    f32x4 lo, hi;
-    lo[0] = __builtin_bit_cast(float, u[0] << 16); lo[1] = __builtin_bit_cast(float, u[0] & 0xffff0000u);
-    lo[2] = __builtin_bit_cast(float, u[1] << 16); lo[3] = __builtin_bit_cast(float, u[1] & 0xffff0000u);
-    hi[0] = __builtin_bit_cast(float, u[2] << 16); hi[1] = __builtin_bit_cast(float, u[2] & 0xffff0000u);
-    hi[2] = __builtin_bit_cast(float, u[3] << 16); hi[3] = __builtin_bit_cast(float, u[3] & 0xffff0000u);
-    *reinterpret_cast<f32x4 *>(dst) = lo;
-    *reinterpret_cast<f32x4 *>(dst + 4) = hi;
-  }
-};
-
 // Weight gradient: rows of the GEMM are output channels, columns are input channels of one filter
 // tap, the reduction runs over output pixels m (split across workgroups).  Both operand tiles arrive
 // "reduction-major" ([m][channel]) straight from the NHWC tensors.  Same pipeline as the forward
 // kernel: straight-line loop body, bounds-checked buffer loads, LDS refill in the middle of the
-// MFMAs, fragments fetched one k-step ahead.  bf16 inputs are widened to fp32 on their way into
-// LDS (exact), so the products and the accumulation are those of the fp32 matrix instruction.
-template <typename T, int BM, int BN, int WGM, int WGN>
+// MFMAs, fragments fetched one k-step ahead.  This is the fp32 kernel: the matrix instruction takes
+// one reduction index per lane, so fragments are single LDS words and no transpose is needed.
+template <int BM, int BN, int WGM, int WGN>
 __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
-  constexpr int VEC = Elem<T>::VEC;
-  constexpr int ES = (int)sizeof(T);
+  constexpr int VEC = 4;
+  constexpr int ES = 4;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int LDA = BM + 32, LDB = BN + 32;     // rows kk and kk+1 land on different bank halves
@@ -531,10 +512,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
   auto store_lds = [&](int stage) {
 #pragma unroll
     for (int i = 0; i < PA; ++i)
-      if (i * RPA + arow < kWBK) ToLds<T>::store(&As[stage][i * RPA + arow][acol], ra[i]);
+      if (i * RPA + arow < kWBK) *reinterpret_cast<f32x4 *>(&As[stage][i * RPA + arow][acol]) = ra[i];
 #pragma unroll
     for (int i = 0; i < PB; ++i)
-      if (i * RPB + brow < kWBK) ToLds<T>::store(&Bs[stage][i * RPB + brow][bcol], rb[i]);
+      if (i * RPB + brow < kWBK) *reinterpret_cast<f32x4 *>(&Bs[stage][i * RPB + brow][bcol]) = rb[i];
   };
 
   // same pipeline as the forward kernel: fragments one k-step ahead (also across chunks), refill of
@@ -597,14 +578,187 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
     }
 }
 
+// LDS transpose read (ds_read_b64_tr_b16).  Within each block of 16 lanes, lane s supplies the
+// address of 4 consecutive 16-bit values; lane j receives, as element e, the value number j%4 of
+// the four that lane 4*e + j/4 pointed at.  When lane s points at row s/4, columns 4*(s%4)..+3 of a
+// row-major tile, lane j therefore ends up with rows 0..3 of column j: a 4x16 -> 16x4 transpose.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ inline s16x4 lds_read_tr(const __bf16 *p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p));
+}
+
+// Weight gradient with bf16 operands on v_mfma_f32_32x32x16_bf16.  The matrix instruction wants 8
+// consecutive values of the reduction index (output pixels m) per lane, while both operands arrive
+// from memory with the channel index contiguous ([m][channel]); the tiles are therefore stored in LDS
+// as they arrive and read back through the LDS transpose read, two 4-deep reads per fragment.
+// WBK: pixels staged per chunk (a multiple of 32); otherwise the same pipeline as the fp32 kernel.
+template <int BM, int BN, int WBK>
+__global__ __launch_bounds__(kThreads) void wgrad_bf16_kernel(WgradArgs a) {
+  constexpr int WGM = 2, WGN = 2;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int LDA = BM + 32, LDB = BN + 32;     // row pitch = tile width + 64 bytes: 4 consecutive rows fall on disjoint banks
+  constexpr int TPRA = BM / 8, TPRB = BN / 8;     // threads per tile row (16 bytes each)
+  constexpr int RPA = kThreads / TPRA, RPB = kThreads / TPRB;
+  constexpr int PA = WBK / RPA, PB = WBK / RPB;
+  constexpr int NK = WBK / 16;
+  static_assert(WBK % RPA == 0 && WBK % RPB == 0 && NK % 2 == 0 && TM >= 1 && TN >= 1, "tile shape");
+  __shared__ __bf16 As[2][WBK][LDA];
+  __shared__ __bf16 Bs[2][WBK][LDB];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  int bid = blockIdx.x;
+  const int tile = bid % (a.tiles_k * a.tiles_c);
+  bid /= a.tiles_k * a.tiles_c;
+  const int tap = bid % (a.R * a.S), split = bid / (a.R * a.S);
+  const int tk = tile / a.tiles_c, tc = tile % a.tiles_c;
+  const int r = tap / a.S, s = tap - r * a.S;
+  const int k0 = tk * BM, c0 = tc * BN;
+  const int mbeg = split * a.rows_per_split;
+  const int mend = min(a.M, mbeg + a.rows_per_split);
+  const int nchunks = (mend - mbeg + WBK - 1) / WBK;
+
+  const int arow = tid / TPRA, acol = (tid % TPRA) * 8;
+  const int brow = tid / TPRB, bcol = (tid % TPRB) * 8;
+  const unsigned acolb = (k0 + acol) < a.K ? (unsigned)(k0 + acol) * 2u : kOOB;
+  const unsigned bcolb = (c0 + bcol) < a.C ? (unsigned)(c0 + bcol) * 2u : kOOB;
+  const __amdgpu_buffer_rsrc_t rdy = make_rsrc(a.dy, (unsigned)a.M * a.K * 2u);
+  const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (unsigned)a.N * a.H * a.W * a.C * 2u);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  f32x4 ra[PA], rb[PB];
+  int mc = mbeg;
+  auto load_global = [&]() {
+#pragma unroll
+    for (int i = 0; i < PA; ++i) {
+      const int m = mc + i * RPA + arow;
+      ra[i] = buffer_load_16B(rdy, m < mend ? (unsigned)m * (unsigned)a.K * 2u + acolb : kOOB);
+    }
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+      const int m = mc + i * RPB + brow;
+      const int n = fdiv(m, a.div_pq);
+      const int rem = m - n * (a.P * a.Q);
+      const int p = fdiv(rem, a.div_q), q = rem - p * a.Q;
+      const int ih = p * a.stride + r - a.pad, iw = q * a.stride + s - a.pad;
+      const bool ok = m < mend && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+      rb[i] = buffer_load_16B(rx, ok ? (unsigned)((n * a.H + ih) * a.W + iw) * (unsigned)a.C * 2u + bcolb : kOOB);
+    }
+    mc += WBK;
+  };
+  auto store_lds = [&](int stage) {
+#pragma unroll
+    for (int i = 0; i < PA; ++i) *reinterpret_cast<f32x4 *>(&As[stage][i * RPA + arow][acol]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < PB; ++i) *reinterpret_cast<f32x4 *>(&Bs[stage][i * RPB + brow][bcol]) = rb[i];
+  };
+
+  // fragment addressing of the transpose read: lane l supplies row 8*(l/32) + (l%16)/4 of a 16-row
+  // k-step and columns 16*((l/16)%2) + 4*(l%4) .. +3 of a 32-column tile; it receives column l%32,
+  // rows 8*(l/32) .. +3 (and +4 .. +7 from the second read)
+  const int frow = (lane >> 5) * 8 + ((lane & 15) >> 2);
+  const int fcol = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+  constexpr int KREFILL = NK / 2 - 1;
+  bf16x8 fa[2][TM], fb[2][TN];
+  auto load_frags = [&](int buf, int stage, int ks) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const s16x4 lo = lds_read_tr(&As[stage][ks * 16 + frow][wm * WTM + i * 32 + fcol]);
+      const s16x4 hi = lds_read_tr(&As[stage][ks * 16 + frow + 4][wm * WTM + i * 32 + fcol]);
+      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      fa[buf][i] = __builtin_bit_cast(bf16x8, v);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const s16x4 lo = lds_read_tr(&Bs[stage][ks * 16 + frow][wn * WTN + j * 32 + fcol]);
+      const s16x4 hi = lds_read_tr(&Bs[stage][ks * 16 + frow + 4][wn * WTN + j * 32 + fcol]);
+      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      fb[buf][j] = __builtin_bit_cast(bf16x8, v);
+    }
+  };
+  auto lds_barrier = [&]() {
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+  };
+  load_global();
+  store_lds(0);
+  load_global();
+  lds_barrier();
+  load_frags(0, 0, 0);
+  __builtin_amdgcn_sched_barrier(0);
+  for (int it = 0; it < nchunks; ++it) {
+    const int stage = it & 1;
+#pragma unroll
+    for (int ks = 0; ks < NK; ++ks) {
+      if (ks + 1 < NK) {
+        load_frags((ks + 1) & 1, stage, ks + 1);
+      } else {
+        lds_barrier();
+        load_frags(0, stage ^ 1, 0);   // rows past mend were loaded as zeros
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (ks == KREFILL) {
+        store_lds(stage ^ 1);
+        load_global();
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  const int lr = lane & 31, lh = lane >> 5;
+  float *out = a.out + (size_t)split * a.K * a.R * a.S * a.C;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int c = c0 + wn * WTN + j * 32 + lr;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int k = k0 + wm * WTM + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+        if (k < a.K && c < a.C) out[((size_t)k * a.R * a.S + tap) * a.C + c] = acc[i][j][e];
+      }
+    }
+}
+
+// Sum of the split partial results, in a fixed order (bit-stable from run to run): thread (x, g)
+// adds splits g, g+G, g+2G, ... of output vector x in ascending order, then the G partial sums are
+// added in ascending g.  G threads share one output vector so that many loads are in flight even
+// when the output is small and the number of splits large.
+template <int G>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part, float *__restrict__ out,
                                                             long long n4, int splits) {
-  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n4) return;
+  constexpr int X = 256 / G;
+  __shared__ f32x4 red[G][X];
+  const int x = threadIdx.x % X, g = threadIdx.x / X;
+  const long long i = (long long)blockIdx.x * X + x;
   const f32x4 *p = reinterpret_cast<const f32x4 *>(part);
-  f32x4 acc = p[i];
-  for (int z = 1; z < splits; ++z) acc += p[i + (long long)z * n4];
-  reinterpret_cast<f32x4 *>(out)[i] = acc;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  if (i < n4)
+    for (int z = g; z < splits; z += G) acc += p[i + (long long)z * n4];
+  if (G > 1) {
+    red[g][x] = acc;
+    __syncthreads();
+    if (g == 0) {
+#pragma unroll
+      for (int h = 1; h < G; ++h) acc += red[h][x];
+    }
+  }
+  if (g == 0 && i < n4) reinterpret_cast<f32x4 *>(out)[i] = acc;
 }
 
 struct WgradPlan { int bm, bn, splits, rows_per_split; };
@@ -652,22 +806,26 @@ int conv_wgrad(const ConvGeom &g, int dt, const void *dy, const void *x, float *
   {
     const double flops = 2.0 * a.M * g.K * g.C * g.R * g.S;
     const double bytes = esize(dt) * ((double)a.M * g.K + (double)g.N * g.H * g.W * g.C) + 4.0 * g.K * g.R * g.S * g.C;
-    const char *label = dt == DT_BF16 ? (p.bm == 128 ? "wgrad_bf16in_128x128" : "wgrad_bf16in_64x64")
+    const char *label = dt == DT_BF16 ? (p.bm == 128 ? "wgrad_bf16_128x128" : "wgrad_bf16_64x64")
                                       : (p.bm == 128 ? "wgrad_f32_128x128" : "wgrad_f32_64x64");
     prof::Scope ps(label, flops, bytes, st);
     if (dt == DT_BF16) {
-      if (p.bm == 128) hipLaunchKernelGGL((wgrad_kernel<__bf16, 128, 128, 2, 2>), grid, dim3(kThreads), 0, st, a);
-      else hipLaunchKernelGGL((wgrad_kernel<__bf16, 64, 64, 2, 2>), grid, dim3(kThreads), 0, st, a);
+      if (p.bm == 128) hipLaunchKernelGGL((wgrad_bf16_kernel<128, 128, 32>), grid, dim3(kThreads), 0, st, a);
+      else hipLaunchKernelGGL((wgrad_bf16_kernel<64, 64, 64>), grid, dim3(kThreads), 0, st, a);
     } else {
-      if (p.bm == 128) hipLaunchKernelGGL((wgrad_kernel<float, 128, 128, 2, 2>), grid, dim3(kThreads), 0, st, a);
-      else hipLaunchKernelGGL((wgrad_kernel<float, 64, 64, 2, 2>), grid, dim3(kThreads), 0, st, a);
+      if (p.bm == 128) hipLaunchKernelGGL((wgrad_kernel<128, 128, 2, 2>), grid, dim3(kThreads), 0, st, a);
+      else hipLaunchKernelGGL((wgrad_kernel<64, 64, 2, 2>), grid, dim3(kThreads), 0, st, a);
     }
   }
   RESIST_CHECK_LAUNCH("wgrad");
   if (p.splits > 1) {
     const long long n4 = (long long)g.K * g.R * g.S * g.C / 4;
     prof::Scope ps("splitk_reduce", 0, 16.0 * n4 * (p.splits + 1), st);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, partial, dw, n4, p.splits);
+    // enough threads per output vector that the launch has at least ~64k loads in flight
+    if (n4 * 4 >= 65536 || p.splits < 8)
+      hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3((unsigned)((n4 + 63) / 64)), dim3(256), 0, st, partial, dw, n4, p.splits);
+    else
+      hipLaunchKernelGGL(splitk_reduce_kernel<16>, dim3((unsigned)((n4 + 15) / 16)), dim3(256), 0, st, partial, dw, n4, p.splits);
     RESIST_CHECK_LAUNCH("splitk_reduce");
   }
   return RESIST_OK;

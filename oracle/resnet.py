@@ -79,6 +79,10 @@ class _Tape:
 
     def __init__(self):
         self.stats = {}      # (block, bn name) -> (mean, biased var, m)
+        self.relu_margin = np.inf   # smallest |input| any ReLU saw (how close a decision was to a tie)
+
+    def saw_relu_input(self, z):
+        self.relu_margin = min(self.relu_margin, float(np.abs(z).min()))
 
 
 def _conv_bn(x, p, conv, bn, stride, pad, eps, relu, tape, key, q):
@@ -90,6 +94,8 @@ def _conv_bn(x, p, conv, bn, stride, pad, eps, relu, tape, key, q):
     z, cache = L.bn_fwd(y, p[bn + "_g"].astype(np.float64), p[bn + "_b"].astype(np.float64), eps)
     m = y.shape[0] * y.shape[2] * y.shape[3]
     tape.stats[(key, bn)] = (cache[2], cache[3], m)
+    if relu:
+        tape.saw_relu_input(z)
     a = q(np.maximum(z, 0.0)) if relu else z
     return a, dict(x=x, cache=cache, z=z, conv=conv, bn=bn, stride=stride, pad=pad, relu=relu, wq=wq)
 
@@ -145,6 +151,7 @@ def forward_backward(model, blocks, params, x, labels, need_input_grad=False, ba
         else:
             sc, cd = inp, None
         pre = h + sc
+        tape.saw_relu_input(pre)
         a = q(np.maximum(pre, 0.0))
         ctxs.append((b, chain, cd, pre))
     feat_shape = a.shape

@@ -3,9 +3,11 @@
 //   forward   mean_c, var_c (biased) over the M rows; a = [relu](gamma*(y-mean)*invstd + beta [+ res])
 //   backward  gm = g*[mask>0]; dbeta = sum gm; dgamma = sum gm*xhat;
 //             dy = gamma*invstd*(gm - dbeta/M - xhat*dgamma/M)
-// These kernels are bound by HBM bandwidth.  Per-channel sums are accumulated in float64 (the
-// vector fp64 rate is far above what the memory stream needs), in a fixed order, so results are
-// bit-stable from run to run and free of the cancellation a float32 sum-of-squares would suffer.
+// These kernels are bound by HBM bandwidth.  The forward statistics arrive as per-row-tile fp32
+// column sums written by the convolution that produced y (at most 128 rows each) and are added up
+// in float64; the backward sums are accumulated in float64 throughout (the vector fp64 rate is far
+// above what the memory stream needs).  Every reduction has a fixed order, so results are bit-stable
+// from run to run.
 // Activations are stored as fp32 or bf16; a thread owns V = 4 (fp32) or 8 (bf16) consecutive channels
 // (one 16-byte access) and all arithmetic is fp32 / fp64.
 #include "elem.h"
@@ -45,56 +47,27 @@ inline int num_parts(int64_t M, const ColMap &m) {
   return (int)p;
 }
 
-// ---- forward statistics --------------------------------------------------------------------------
-// grid (parts, ctiles); scratch layout [2][parts][C] doubles: sum, sum of squares
-template <typename T>
-__global__ __launch_bounds__(kThreads) void bn_stats_partial_kernel(const T *__restrict__ y, long long M, int C,
-                                                                    int tpr, int rpp, double *__restrict__ scratch) {
-  constexpr int V = Vec<T>::N;
-  __shared__ double red[2][kThreads][V];
-  const int tid = threadIdx.x;
-  const int tc = tid % tpr, tr = tid / tpr;
-  const int c = (blockIdx.y * tpr + tc) * V;
-  const int parts = gridDim.x;
-  const long long rows_per_part = (M + parts - 1) / parts;
-  const long long r0 = blockIdx.x * rows_per_part;
-  long long r1 = r0 + rows_per_part;
-  if (r1 > M) r1 = M;
-  double s[V], q[V];
+// per-channel fp32 parameters of the V channels a thread owns (16-byte aligned by construction)
+template <int V>
+__device__ inline void load_params(const float *__restrict__ p, float (&v)[V]) {
 #pragma unroll
-  for (int e = 0; e < V; ++e) { s[e] = 0; q[e] = 0; }
-  for (long long r = r0 + tr; r < r1; r += rpp) {
-    float v[V];
-    Vec<T>::load(y + r * C + c, v);
-#pragma unroll
-    for (int e = 0; e < V; ++e) {
-      const double d = (double)v[e];
-      s[e] += d;
-      q[e] = fma(d, d, q[e]);
-    }
-  }
-#pragma unroll
-  for (int e = 0; e < V; ++e) { red[0][tid][e] = s[e]; red[1][tid][e] = q[e]; }
-  __syncthreads();
-  if (tr == 0) {
-    for (int j = 1; j < rpp; ++j)
-#pragma unroll
-      for (int e = 0; e < V; ++e) { s[e] += red[0][j * tpr + tc][e]; q[e] += red[1][j * tpr + tc][e]; }
-    double *ps = scratch + (size_t)blockIdx.x * C + c;
-    double *pq = scratch + (size_t)(parts + blockIdx.x) * C + c;
-#pragma unroll
-    for (int e = 0; e < V; ++e) { ps[e] = s[e]; pq[e] = q[e]; }
+  for (int e = 0; e < V; e += 4) {
+    const f32x4 t = *reinterpret_cast<const f32x4 *>(p + e);
+    v[e] = t[0]; v[e + 1] = t[1]; v[e + 2] = t[2]; v[e + 3] = t[3];
   }
 }
 
-// Final reduction over the row-slices: a workgroup owns 16 channels; 16 thread rows each sum every
-// 16th slice in index order, then thread row 0 adds the 16 partial sums in order.
-__device__ inline void reduce_parts(const double *__restrict__ scratch, int parts, int C, int c, int pl,
+// ---- forward statistics --------------------------------------------------------------------------
+// Reduction over `parts` partial sums per channel, layout [2][parts][C]: a workgroup owns 16
+// channels; 16 thread rows each sum every 16th part in index order, then thread row 0 adds the 16
+// partial sums in order.
+template <typename S>
+__device__ inline void reduce_parts(const S *__restrict__ scratch, int parts, int C, int c, int pl,
                                     double (*red)[16][16], double *out0, double *out1) {
   double s = 0, q = 0;
   for (int p = pl; p < parts; p += 16) {
-    s += scratch[(size_t)p * C + c];
-    q += scratch[(size_t)(parts + p) * C + c];
+    s += (double)scratch[(size_t)p * C + c];
+    q += (double)scratch[(size_t)(parts + p) * C + c];
   }
   const int cl = c & 15;
   red[0][pl][cl] = s;
@@ -107,20 +80,26 @@ __device__ inline void reduce_parts(const double *__restrict__ scratch, int part
   *out1 = q;
 }
 
-__global__ __launch_bounds__(kThreads) void bn_stats_final_kernel(const double *__restrict__ scratch, int parts, int C,
-                                                                  long long M, float eps, float momentum,
-                                                                  float *__restrict__ mean, float *__restrict__ invstd,
-                                                                  float *__restrict__ rmean, float *__restrict__ rvar) {
+__global__ __launch_bounds__(kThreads) void bn_finalize_kernel(const float *__restrict__ stats, int parts, int C,
+                                                               long long M, float eps, float momentum,
+                                                               const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                               float *__restrict__ mean, float *__restrict__ invstd,
+                                                               float *__restrict__ scale, float *__restrict__ shift,
+                                                               float *__restrict__ rmean, float *__restrict__ rvar) {
   __shared__ double red[2][16][16];
   const int c = blockIdx.x * 16 + (threadIdx.x & 15), pl = threadIdx.x >> 4;
   double s, q;
-  reduce_parts(scratch, parts, C, c, pl, red, &s, &q);
+  reduce_parts(stats, parts, C, c, pl, red, &s, &q);
   if (pl != 0) return;
   const double m = s / (double)M;
   double var = q / (double)M - m * m;
   if (var < 0) var = 0;
-  mean[c] = (float)m;
-  invstd[c] = (float)(1.0 / sqrt(var + (double)eps));
+  const float mf = (float)m, isf = (float)(1.0 / sqrt(var + (double)eps));
+  mean[c] = mf;
+  invstd[c] = isf;
+  const float sc = gamma[c] * isf;
+  scale[c] = sc;
+  shift[c] = beta[c] - mf * sc;
   if (rmean) {
     const double unb = M > 1 ? var * ((double)M / (double)(M - 1)) : var;
     rmean[c] = (float)((1.0 - momentum) * (double)rmean[c] + (double)momentum * m);
@@ -130,12 +109,14 @@ __global__ __launch_bounds__(kThreads) void bn_stats_final_kernel(const double *
 
 // ---- forward apply -------------------------------------------------------------------------------
 struct ApplyArgs {
-  const void *y; const float *gamma; const float *beta; const float *mean; const float *invstd;
+  const void *y; const float *scale; const float *shift;
   const void *res;                                        // raw residual or second pre-BN tensor
-  const float *rgamma; const float *rbeta; const float *rmean; const float *rinvstd;  // BN of res
+  const float *rscale; const float *rshift;               // BN of res (NULL: res is added as it is)
   void *a;
   long long M; int C; int tpr, rpp; int relu;
 };
+
+constexpr int kUnroll = 4;   // rows in flight per thread
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void bn_apply_kernel(ApplyArgs p) {
@@ -146,45 +127,61 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(ApplyArgs p) {
   const T *y = static_cast<const T *>(p.y), *res = static_cast<const T *>(p.res);
   T *a = static_cast<T *>(p.a);
   float sc[V], sh[V], rsc[V], rsh[V];
+  load_params<V>(p.scale + c, sc);
+  load_params<V>(p.shift + c, sh);
+  if (p.rscale) {
+    load_params<V>(p.rscale + c, rsc);
+    load_params<V>(p.rshift + c, rsh);
+  } else {
 #pragma unroll
-  for (int e = 0; e < V; ++e) {
-    sc[e] = p.gamma[c + e] * p.invstd[c + e];
-    sh[e] = p.beta[c + e] - p.mean[c + e] * sc[e];
-    if (p.rgamma) {
-      rsc[e] = p.rgamma[c + e] * p.rinvstd[c + e];
-      rsh[e] = p.rbeta[c + e] - p.rmean[c + e] * rsc[e];
-    } else {
-      rsc[e] = 1.f; rsh[e] = 0.f;
-    }
+    for (int e = 0; e < V; ++e) { rsc[e] = 1.f; rsh[e] = 0.f; }
   }
   const long long stride = (long long)gridDim.x * p.rpp;
-  for (long long r = (long long)blockIdx.x * p.rpp + tr; r < p.M; r += stride) {
-    const size_t off = (size_t)r * p.C + c;
-    float v[V], o[V];
-    Vec<T>::load(y + off, v);
+  for (long long r0 = (long long)blockIdx.x * p.rpp + tr; r0 < p.M; r0 += stride * kUnroll) {
+    float v[kUnroll][V], rv[kUnroll][V];
 #pragma unroll
-    for (int e = 0; e < V; ++e) o[e] = fmaf(v[e], sc[e], sh[e]);
-    if (res) {
-      float rv[V];
-      Vec<T>::load(res + off, rv);
-#pragma unroll
-      for (int e = 0; e < V; ++e) o[e] += fmaf(rv[e], rsc[e], rsh[e]);
+    for (int u = 0; u < kUnroll; ++u) {
+      const long long r = r0 + u * stride;
+      if (r < p.M) {
+        Vec<T>::load(y + (size_t)r * p.C + c, v[u]);
+        if (res) Vec<T>::load(res + (size_t)r * p.C + c, rv[u]);
+      }
     }
-    if (p.relu) {
 #pragma unroll
-      for (int e = 0; e < V; ++e) o[e] = o[e] > 0.f ? o[e] : 0.f;
+    for (int u = 0; u < kUnroll; ++u) {
+      const long long r = r0 + u * stride;
+      if (r < p.M) {
+        float o[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) o[e] = fmaf(v[u][e], sc[e], sh[e]);
+        if (res) {
+#pragma unroll
+          for (int e = 0; e < V; ++e) o[e] += fmaf(rv[u][e], rsc[e], rsh[e]);
+        }
+        if (p.relu) {
+#pragma unroll
+          for (int e = 0; e < V; ++e) o[e] = o[e] > 0.f ? o[e] : 0.f;
+        }
+        Vec<T>::store(a + (size_t)r * p.C + c, o);
+      }
     }
-    Vec<T>::store(a + off, o);
   }
 }
 
 // ---- backward ------------------------------------------------------------------------------------
+// mask modes: the gradient passes where ...
+constexpr int kMaskNone = 0;     // everywhere
+constexpr int kMaskTensor = 1;   // the given tensor is positive
+constexpr int kMaskSelf = 2;     // this BN's own output scale*y + shift is positive (its ReLU decision)
+
 // pass 1: per-channel sums of gm and gm*xhat; scratch [2][parts][C]
-template <typename T>
+template <typename T, int MASK>
 __global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const T *__restrict__ g, const T *__restrict__ mask,
                                                                   const T *__restrict__ y, long long M, int C, int tpr,
                                                                   int rpp, const float *__restrict__ mean,
                                                                   const float *__restrict__ invstd,
+                                                                  const float *__restrict__ scale,
+                                                                  const float *__restrict__ shift,
                                                                   double *__restrict__ scratch) {
   constexpr int V = Vec<T>::N;
   __shared__ double red[2][kThreads][V];
@@ -196,26 +193,39 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const T *__res
   const long long r0 = blockIdx.x * rows_per_part;
   long long r1 = r0 + rows_per_part;
   if (r1 > M) r1 = M;
-  float mu[V], is[V];
+  float mu[V], is[V], sc[V], sh[V];
+  load_params<V>(mean + c, mu);
+  load_params<V>(invstd + c, is);
+  if (MASK == kMaskSelf) { load_params<V>(scale + c, sc); load_params<V>(shift + c, sh); }
   double sb[V], sg[V];
 #pragma unroll
-  for (int e = 0; e < V; ++e) { mu[e] = mean[c + e]; is[e] = invstd[c + e]; sb[e] = 0; sg[e] = 0; }
-  for (long long r = r0 + tr; r < r1; r += rpp) {
-    const size_t off = (size_t)r * C + c;
-    float gv[V], yv[V];
-    Vec<T>::load(g + off, gv);
-    Vec<T>::load(y + off, yv);
-    if (mask) {
-      float mv[V];
-      Vec<T>::load(mask + off, mv);
+  for (int e = 0; e < V; ++e) { sb[e] = 0; sg[e] = 0; }
+  for (long long rr = r0 + tr; rr < r1; rr += 2 * rpp) {
+    float gv[2][V], yv[2][V], mv[2][V];
 #pragma unroll
-      for (int e = 0; e < V; ++e) gv[e] = mv[e] > 0.f ? gv[e] : 0.f;
+    for (int u = 0; u < 2; ++u) {
+      const long long r = rr + u * rpp;
+      if (r < r1) {
+        const size_t off = (size_t)r * C + c;
+        Vec<T>::load(g + off, gv[u]);
+        Vec<T>::load(y + off, yv[u]);
+        if (MASK == kMaskTensor) Vec<T>::load(mask + off, mv[u]);
+      }
     }
 #pragma unroll
-    for (int e = 0; e < V; ++e) {
-      const float xh = (yv[e] - mu[e]) * is[e];
-      sb[e] += (double)gv[e];
-      sg[e] = fma((double)gv[e], (double)xh, sg[e]);
+    for (int u = 0; u < 2; ++u) {
+      const long long r = rr + u * rpp;
+      if (r < r1) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          float gm = gv[u][e];
+          if (MASK == kMaskTensor) gm = mv[u][e] > 0.f ? gm : 0.f;
+          if (MASK == kMaskSelf) gm = fmaf(yv[u][e], sc[e], sh[e]) > 0.f ? gm : 0.f;
+          const float xh = (yv[u][e] - mu[e]) * is[e];
+          sb[e] += (double)gm;
+          sg[e] = fma((double)gm, (double)xh, sg[e]);
+        }
+      }
     }
   }
 #pragma unroll
@@ -245,12 +255,13 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const double *__
 
 struct BwdApplyArgs {
   const void *g; const void *mask; const void *y;
-  const float *gamma; const float *mean; const float *invstd; const float *dgamma; const float *dbeta;
+  const float *mean; const float *invstd; const float *scale; const float *shift;
+  const float *dgamma; const float *dbeta;
   void *dy; void *gm_out;
   long long M; int C; int tpr, rpp;
 };
 
-template <typename T>
+template <typename T, int MASK>
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BwdApplyArgs p) {
   constexpr int V = Vec<T>::N;
   const int tid = threadIdx.x;
@@ -259,33 +270,47 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BwdApplyArgs p) 
   const T *g = static_cast<const T *>(p.g), *mask = static_cast<const T *>(p.mask), *y = static_cast<const T *>(p.y);
   T *dy = static_cast<T *>(p.dy), *gm_out = static_cast<T *>(p.gm_out);
   const float invM = 1.0f / (float)p.M;
-  float mu[V], is[V], k0[V], k1[V], k2[V];
+  float mu[V], is[V], k0[V], sh[V], k1[V], k2[V];
+  load_params<V>(p.mean + c, mu);
+  load_params<V>(p.invstd + c, is);
+  load_params<V>(p.scale + c, k0);          // gamma * invstd
+  load_params<V>(p.shift + c, sh);
+  load_params<V>(p.dbeta + c, k1);
+  load_params<V>(p.dgamma + c, k2);
 #pragma unroll
-  for (int e = 0; e < V; ++e) {
-    mu[e] = p.mean[c + e]; is[e] = p.invstd[c + e];
-    k0[e] = p.gamma[c + e] * is[e];          // scale
-    k1[e] = p.dbeta[c + e] * invM;           // mean of gm
-    k2[e] = p.dgamma[c + e] * invM;          // mean of gm*xhat
-  }
+  for (int e = 0; e < V; ++e) { k1[e] *= invM; k2[e] *= invM; }   // means of gm and of gm*xhat
   const long long stride = (long long)gridDim.x * p.rpp;
-  for (long long r = (long long)blockIdx.x * p.rpp + tr; r < p.M; r += stride) {
-    const size_t off = (size_t)r * p.C + c;
-    float gv[V], yv[V], o[V];
-    Vec<T>::load(g + off, gv);
-    Vec<T>::load(y + off, yv);
-    if (mask) {
-      float mv[V];
-      Vec<T>::load(mask + off, mv);
+  for (long long r0 = (long long)blockIdx.x * p.rpp + tr; r0 < p.M; r0 += stride * 2) {
+    float gv[2][V], yv[2][V], mv[2][V];
 #pragma unroll
-      for (int e = 0; e < V; ++e) gv[e] = mv[e] > 0.f ? gv[e] : 0.f;
+    for (int u = 0; u < 2; ++u) {
+      const long long r = r0 + u * stride;
+      if (r < p.M) {
+        const size_t off = (size_t)r * p.C + c;
+        Vec<T>::load(g + off, gv[u]);
+        Vec<T>::load(y + off, yv[u]);
+        if (MASK == kMaskTensor) Vec<T>::load(mask + off, mv[u]);
+      }
     }
 #pragma unroll
-    for (int e = 0; e < V; ++e) {
-      const float xh = (yv[e] - mu[e]) * is[e];
-      o[e] = k0[e] * (gv[e] - k1[e] - xh * k2[e]);
+    for (int u = 0; u < 2; ++u) {
+      const long long r = r0 + u * stride;
+      if (r < p.M) {
+        const size_t off = (size_t)r * p.C + c;
+        float o[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          float gm = gv[u][e];
+          if (MASK == kMaskTensor) gm = mv[u][e] > 0.f ? gm : 0.f;
+          if (MASK == kMaskSelf) gm = fmaf(yv[u][e], k0[e], sh[e]) > 0.f ? gm : 0.f;
+          gv[u][e] = gm;
+          const float xh = (yv[u][e] - mu[e]) * is[e];
+          o[e] = k0[e] * (gm - k1[e] - xh * k2[e]);
+        }
+        Vec<T>::store(dy + off, o);
+        if (gm_out) Vec<T>::store(gm_out + off, gv[u]);   // exact: gm is g or zero
+      }
     }
-    Vec<T>::store(dy + off, o);
-    if (gm_out) Vec<T>::store(gm_out + off, gv);   // exact: gm is g or zero
   }
 }
 
@@ -295,33 +320,44 @@ int check_bn(int dt, int64_t M, int C) {
   return RESIST_OK;
 }
 
-unsigned apply_grid_x(int64_t M, const ColMap &m) {
-  int64_t want = 4096 / m.ctiles;
+// workgroups along the rows for the streaming kernels: every thread gets about `rows_per_thread`
+// rows, at most 4096 workgroups in total
+unsigned apply_grid_x(int64_t M, const ColMap &m, int rows_per_thread) {
+  int64_t want = (M + (int64_t)m.rpp * rows_per_thread - 1) / ((int64_t)m.rpp * rows_per_thread);
+  const int64_t cap = 4096 / m.ctiles > 0 ? 4096 / m.ctiles : 1;
+  if (want > cap) want = cap;
   if (want < 1) want = 1;
-  const int64_t maxb = (M + m.rpp - 1) / m.rpp;
-  return (unsigned)(want < maxb ? want : maxb);
+  return (unsigned)want;
 }
 
 inline int vec_of(int dt) { return dt == DT_BF16 ? 8 : 4; }
+
+template <typename T>
+void launch_bwd(int mode, dim3 gp, dim3 ga, hipStream_t st, const void *g, const void *mask, const void *y, int64_t M, int C,
+                const ColMap &m, const BnBufs &b, double *scratch, const BwdApplyArgs &p, int parts) {
+  const T *gg = (const T *)g, *mm = (const T *)mask, *yy = (const T *)y;
+#define RESIST_BN_BWD(MODE)                                                                                              \
+  hipLaunchKernelGGL((bn_bwd_partial_kernel<T, MODE>), gp, dim3(kThreads), 0, st, gg, mm, yy, (long long)M, C, m.tpr, m.rpp, \
+                     b.mean, b.invstd, b.scale, b.shift, scratch);                                                      \
+  hipLaunchKernelGGL(bn_bwd_final_kernel, dim3(C / 16), dim3(kThreads), 0, st, scratch, parts, C, b.dgamma, b.dbeta);     \
+  hipLaunchKernelGGL((bn_bwd_apply_kernel<T, MODE>), ga, dim3(kThreads), 0, st, p);
+  if (mode == kMaskTensor) { RESIST_BN_BWD(kMaskTensor) }
+  else if (mode == kMaskSelf) { RESIST_BN_BWD(kMaskSelf) }
+  else { RESIST_BN_BWD(kMaskNone) }
+#undef RESIST_BN_BWD
+}
 
 }  // namespace
 
 int64_t bn_scratch_doubles(int C) { return (int64_t)2 * kMaxParts * C; }
 
-int bn_stats(int dt, const void *y, int64_t M, int C, const BnBufs &b, float eps, float momentum, double *scratch,
-             hipStream_t st) {
-  RESIST_TRY(check_bn(dt, M, C));
-  const ColMap m = col_map(C, vec_of(dt));
-  const int parts = num_parts(M, m);
-  prof::Scope ps("bn_stats", 0, (double)esize(dt) * M * C, st);
-  if (dt == DT_BF16)
-    hipLaunchKernelGGL(bn_stats_partial_kernel<__bf16>, dim3(parts, m.ctiles), dim3(kThreads), 0, st, (const __bf16 *)y, (long long)M, C, m.tpr, m.rpp, scratch);
-  else
-    hipLaunchKernelGGL(bn_stats_partial_kernel<float>, dim3(parts, m.ctiles), dim3(kThreads), 0, st, (const float *)y, (long long)M, C, m.tpr, m.rpp, scratch);
-  RESIST_CHECK_LAUNCH("bn_stats_partial");
-  hipLaunchKernelGGL(bn_stats_final_kernel, dim3(C / 16), dim3(kThreads), 0, st, scratch, parts, C,
-                     (long long)M, eps, momentum, b.mean, b.invstd, b.rmean, b.rvar);
-  RESIST_CHECK_LAUNCH("bn_stats_final");
+int bn_finalize(const float *stats, int parts, int64_t M, int C, const BnBufs &b, float eps, float momentum, hipStream_t st) {
+  RESIST_TRY(check_bn(DT_F32, M, C));
+  if (parts < 1 || !stats) return set_error(RESIST_EINVAL, "bn_finalize: no partial sums");
+  prof::Scope ps("bn_finalize", 0, 8.0 * parts * C, st);
+  hipLaunchKernelGGL(bn_finalize_kernel, dim3(C / 16), dim3(kThreads), 0, st, stats, parts, C, (long long)M, eps, momentum,
+                     b.gamma, b.beta, b.mean, b.invstd, b.scale, b.shift, b.rmean, b.rvar);
+  RESIST_CHECK_LAUNCH("bn_finalize");
   return RESIST_OK;
 }
 
@@ -330,40 +366,34 @@ int bn_apply(int dt, const void *y, int64_t M, int C, const BnBufs &b, const voi
   RESIST_TRY(check_bn(dt, M, C));
   const ColMap m = col_map(C, vec_of(dt));
   ApplyArgs p{};
-  p.y = y; p.gamma = b.gamma; p.beta = b.beta; p.mean = b.mean; p.invstd = b.invstd;
+  p.y = y; p.scale = b.scale; p.shift = b.shift;
   p.res = res;
-  if (res_bn) { p.rgamma = res_bn->gamma; p.rbeta = res_bn->beta; p.rmean = res_bn->mean; p.rinvstd = res_bn->invstd; }
+  if (res_bn) { p.rscale = res_bn->scale; p.rshift = res_bn->shift; }
   p.a = a; p.M = M; p.C = C; p.tpr = m.tpr; p.rpp = m.rpp; p.relu = relu ? 1 : 0;
   prof::Scope ps("bn_apply", 0, (double)esize(dt) * M * C * (res ? 3 : 2), st);
-  if (dt == DT_BF16) hipLaunchKernelGGL(bn_apply_kernel<__bf16>, dim3(apply_grid_x(M, m), m.ctiles), dim3(kThreads), 0, st, p);
-  else hipLaunchKernelGGL(bn_apply_kernel<float>, dim3(apply_grid_x(M, m), m.ctiles), dim3(kThreads), 0, st, p);
+  const dim3 grid(apply_grid_x(M, m, 2 * kUnroll), m.ctiles);
+  if (dt == DT_BF16) hipLaunchKernelGGL(bn_apply_kernel<__bf16>, grid, dim3(kThreads), 0, st, p);
+  else hipLaunchKernelGGL(bn_apply_kernel<float>, grid, dim3(kThreads), 0, st, p);
   RESIST_CHECK_LAUNCH("bn_apply");
   return RESIST_OK;
 }
 
-int bn_backward(int dt, const void *g, const void *mask, const void *y, int64_t M, int C, const BnBufs &b, void *dy,
-                void *gm_out, double *scratch, hipStream_t st) {
+int bn_backward(int dt, const void *g, const void *mask, bool relu_of_self, const void *y, int64_t M, int C, const BnBufs &b,
+                void *dy, void *gm_out, double *scratch, hipStream_t st) {
   RESIST_TRY(check_bn(dt, M, C));
   const ColMap m = col_map(C, vec_of(dt));
   const int parts = num_parts(M, m);
-  prof::Scope ps("bn_backward", 0, (double)esize(dt) * M * C * ((mask ? 3 : 2) + (mask ? 4 : 3) + (gm_out ? 1 : 0)), st);
-  if (dt == DT_BF16)
-    hipLaunchKernelGGL(bn_bwd_partial_kernel<__bf16>, dim3(parts, m.ctiles), dim3(kThreads), 0, st, (const __bf16 *)g,
-                       (const __bf16 *)mask, (const __bf16 *)y, (long long)M, C, m.tpr, m.rpp, b.mean, b.invstd, scratch);
-  else
-    hipLaunchKernelGGL(bn_bwd_partial_kernel<float>, dim3(parts, m.ctiles), dim3(kThreads), 0, st, (const float *)g,
-                       (const float *)mask, (const float *)y, (long long)M, C, m.tpr, m.rpp, b.mean, b.invstd, scratch);
-  RESIST_CHECK_LAUNCH("bn_bwd_partial");
-  hipLaunchKernelGGL(bn_bwd_final_kernel, dim3(C / 16), dim3(kThreads), 0, st, scratch, parts, C,
-                     b.dgamma, b.dbeta);
-  RESIST_CHECK_LAUNCH("bn_bwd_final");
+  const int mode = mask ? kMaskTensor : (relu_of_self ? kMaskSelf : kMaskNone);
+  const int reads = mask ? 3 : 2;
+  prof::Scope ps("bn_backward", 0, (double)esize(dt) * M * C * (2 * reads + 1 + (gm_out ? 1 : 0)), st);
   BwdApplyArgs p{};
-  p.g = g; p.mask = mask; p.y = y; p.gamma = b.gamma; p.mean = b.mean; p.invstd = b.invstd;
+  p.g = g; p.mask = mask; p.y = y; p.mean = b.mean; p.invstd = b.invstd; p.scale = b.scale; p.shift = b.shift;
   p.dgamma = b.dgamma; p.dbeta = b.dbeta; p.dy = dy; p.gm_out = gm_out;
   p.M = M; p.C = C; p.tpr = m.tpr; p.rpp = m.rpp;
-  if (dt == DT_BF16) hipLaunchKernelGGL(bn_bwd_apply_kernel<__bf16>, dim3(apply_grid_x(M, m), m.ctiles), dim3(kThreads), 0, st, p);
-  else hipLaunchKernelGGL(bn_bwd_apply_kernel<float>, dim3(apply_grid_x(M, m), m.ctiles), dim3(kThreads), 0, st, p);
-  RESIST_CHECK_LAUNCH("bn_bwd_apply");
+  const dim3 gp(parts, m.ctiles), ga(apply_grid_x(M, m, 4), m.ctiles);
+  if (dt == DT_BF16) launch_bwd<__bf16>(mode, gp, ga, st, g, mask, y, M, C, m, b, scratch, p, parts);
+  else launch_bwd<float>(mode, gp, ga, st, g, mask, y, M, C, m, b, scratch, p, parts);
+  RESIST_CHECK_LAUNCH("bn_backward");
   return RESIST_OK;
 }
 

@@ -52,6 +52,7 @@ struct IgemmArgs {
   const void *wt;      // [OC][R][S][IC]
   void *out;           // [N][OH][OW][OC]
   const void *addend;  // optional, indexed like out
+  float *stats;        // optional [2][tiles_m][OC]: per row-tile column sums and sums of squares of out
   int N, IH, IW, IC;
   int OH, OW, OC;
   int R, S, stride, pad;
@@ -270,6 +271,9 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
   // epilogue: lane holds column (lane%32), rows 8*(e/4) + 4*(lane/32) + e%4 of each 32x32 tile
   T *out = static_cast<T *>(a.out);
   const T *addend = static_cast<const T *>(a.addend);
+  float s1[TN], s2[TN];   // column sums of the values as stored (batch-norm statistics of this row tile)
+#pragma unroll
+  for (int j = 0; j < TN; ++j) { s1[j] = 0.f; s2[j] = 0.f; }
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -283,15 +287,46 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
           const size_t off = (size_t)ro * a.OC + col;
           float v = acc[i][j][e];
           if (addend) v += E::to_f32(addend[off]);
-          out[off] = E::from_f32(v);
+          const T stored = E::from_f32(v);
+          out[off] = stored;
+          if (MODE == kFwd) {
+            const float sv = E::to_f32(stored);
+            s1[j] += sv;
+            s2[j] = fmaf(sv, sv, s2[j]);
+          }
         }
       }
     }
+  if (MODE == kFwd && a.stats) {
+    // lanes l and l+32 hold the same column; then the WGM waves that share a column range add up in
+    // wave order.  Every step has a fixed order, so the sums are bit-stable from run to run.
+    __shared__ float red[2][WGM][BN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      s1[j] += __shfl_xor(s1[j], 32, 64);
+      s2[j] += __shfl_xor(s2[j], 32, 64);
+      if (lane < 32) {
+        red[0][wm][wn * WTN + j * 32 + lr] = s1[j];
+        red[1][wm][wn * WTN + j * 32 + lr] = s2[j];
+      }
+    }
+    __syncthreads();
+    for (int c = tid; c < BN; c += kThreads) {
+      if (n0 + c < a.OC) {
+        float t1 = red[0][0][c], t2 = red[1][0][c];
+#pragma unroll
+        for (int w = 1; w < WGM; ++w) { t1 += red[0][w][c]; t2 += red[1][w][c]; }
+        a.stats[(size_t)tm * a.OC + n0 + c] = t1;
+        a.stats[((size_t)a.tiles_m + tm) * a.OC + n0 + c] = t2;
+      }
+    }
+  }
 }
 
 template <typename T, int BM, int BN, int BK, int WGM, int WGN, int MODE>
-int launch_igemm(IgemmArgs a, hipStream_t st) {
+int launch_igemm(IgemmArgs a, hipStream_t st, int *tiles_m_out) {
   a.tiles_m = (a.Mrows + BM - 1) / BM;
+  if (tiles_m_out) *tiles_m_out = a.tiles_m;
   a.tiles_n = (a.OC + BN - 1) / BN;
   const long long grid = (long long)a.tiles_m * a.tiles_n * a.cls * a.cls;
   if (grid <= 0 || grid > 0x7fffffffLL) return set_error(RESIST_ESHAPE, "igemm grid %lld", grid);
@@ -310,17 +345,17 @@ int launch_igemm(IgemmArgs a, hipStream_t st) {
 }
 
 template <typename T, int MODE>
-int dispatch_igemm(const IgemmArgs &a, hipStream_t st) {
+int dispatch_igemm(const IgemmArgs &a, hipStream_t st, int *tiles_m_out = nullptr) {
   // pick the largest tile that still yields enough workgroups to cover the 256 compute units
   constexpr int V = Elem<T>::VEC;   // K-chunks of 8*V and 16*V elements: 128 and 256 bytes per tile row
   const long long classes = (long long)a.cls * a.cls;
   auto tiles = [&](int bm, int bn) {
     return (long long)((a.Mrows + bm - 1) / bm) * ((a.OC + bn - 1) / bn) * classes;
   };
-  if (a.OC > 64 && tiles(128, 128) >= 512) return launch_igemm<T, 128, 128, 8 * V, 2, 2, MODE>(a, st);
-  if (tiles(128, 64) >= 512) return launch_igemm<T, 128, 64, 8 * V, 2, 2, MODE>(a, st);
-  if (a.IC % (16 * V) == 0) return launch_igemm<T, 64, 64, 16 * V, 2, 2, MODE>(a, st);
-  return launch_igemm<T, 64, 64, 8 * V, 2, 2, MODE>(a, st);
+  if (a.OC > 64 && tiles(128, 128) >= 512) return launch_igemm<T, 128, 128, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);
+  if (tiles(128, 64) >= 512) return launch_igemm<T, 128, 64, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);
+  if (a.IC % (16 * V) == 0) return launch_igemm<T, 64, 64, 16 * V, 2, 2, MODE>(a, st, tiles_m_out);
+  return launch_igemm<T, 64, 64, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);
 }
 
 int check_geom(const ConvGeom &g, int dt) {
@@ -342,16 +377,22 @@ int check_geom(const ConvGeom &g, int dt) {
 
 }  // namespace
 
-int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, hipStream_t st) {
+int64_t conv_stats_floats(const ConvGeom &g) {
+  // the smallest row tile any forward kernel uses is 64
+  return (int64_t)2 * (((int64_t)g.N * g.P * g.Q + 63) / 64) * g.K;
+}
+
+int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, float *stats, int *stat_parts, hipStream_t st) {
   RESIST_TRY(check_geom(g, dt));
+  if (stats && !stat_parts) return set_error(RESIST_EINVAL, "conv_fwd: stats without stat_parts");
   IgemmArgs a{};
-  a.in = x; a.wt = w; a.out = y; a.addend = nullptr;
+  a.in = x; a.wt = w; a.out = y; a.addend = nullptr; a.stats = stats;
   a.N = g.N; a.IH = g.H; a.IW = g.W; a.IC = g.C;
   a.OH = g.P; a.OW = g.Q; a.OC = g.K;
   a.R = g.R; a.S = g.S; a.stride = g.stride; a.pad = g.pad;
   a.cls = 1; a.OHc = g.P; a.OWc = g.Q;
   a.Mrows = g.N * g.P * g.Q;
-  return dt == DT_BF16 ? dispatch_igemm<__bf16, kFwd>(a, st) : dispatch_igemm<float, kFwd>(a, st);
+  return dt == DT_BF16 ? dispatch_igemm<__bf16, kFwd>(a, st, stat_parts) : dispatch_igemm<float, kFwd>(a, st, stat_parts);
 }
 
 int conv_dgrad(const ConvGeom &g, int dt, const void *dy, const void *wT, void *dx, const void *addend, hipStream_t st) {

@@ -102,7 +102,11 @@ enum { DT_F32 = 0, DT_BF16 = 1 };
 inline int esize(int dt) { return dt == DT_BF16 ? 2 : 4; }
 
 // implicit-GEMM convolution family (conv.hip); dt selects fp32 or bf16 tensors (fp32 accumulation)
-int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, hipStream_t st);
+// stats (optional): per row-tile column sums and sums of squares of y as stored, [2][*stat_parts][K]
+// floats (capacity conv_stats_floats(g)); input of bn_finalize
+int64_t conv_stats_floats(const ConvGeom &g);
+int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, float *stats, int *stat_parts,
+             hipStream_t st);
 // dx = dgrad(dy, wT) [+ addend]; wT is the [C][R][S][K] transpose made by prepare_filter
 int conv_dgrad(const ConvGeom &g, int dt, const void *dy, const void *wT, void *dx, const void *addend,
                hipStream_t st);
@@ -122,19 +126,24 @@ int unpad_rows_f32(const float *src, float *dst, int rows, int n, int npad, hipS
 // BatchNorm on [M][C] activations in dt, fp32 arithmetic (bn.hip)
 struct BnBufs {
   const float *gamma, *beta;
-  float *rmean, *rvar;       // running statistics (updated by stats)
+  float *rmean, *rvar;       // running statistics (updated by bn_finalize)
   float *mean, *invstd;      // [C] saved batch statistics
+  float *scale, *shift;      // [C] gamma*invstd and beta - mean*gamma*invstd (written by bn_finalize)
   float *dgamma, *dbeta;     // [C] gradient outputs
 };
-int64_t bn_scratch_doubles(int C);   // partial-sum scratch for one BN call
-int bn_stats(int dt, const void *y, int64_t M, int C, const BnBufs &b, float eps, float momentum,
-             double *scratch, hipStream_t st);
-// a = [relu]( gamma*xhat(y)+beta [+ res] )            res: raw tensor, or BN(res_y) if res_bn given
+int64_t bn_scratch_doubles(int C);   // partial-sum scratch for one bn_backward call
+// batch statistics from the per-tile sums a convolution left behind: mean, 1/sqrt(var+eps), the
+// affine map of bn_apply, and the running statistics
+int bn_finalize(const float *stats, int parts, int64_t M, int C, const BnBufs &b, float eps, float momentum,
+                hipStream_t st);
+// a = [relu]( scale*y + shift [+ res] )            res: raw tensor, or BN(res_y) if res_bn given
 int bn_apply(int dt, const void *y, int64_t M, int C, const BnBufs &b, const void *res,
              const BnBufs *res_bn, bool relu, void *a, hipStream_t st);
-// gm = g * [mask>0] (mask may be NULL: no masking); dbeta = sum gm; dgamma = sum gm*xhat(y);
+// gm = g * [mask>0]; dbeta = sum gm; dgamma = sum gm*xhat(y);
 // dy = gamma*invstd*(gm - dbeta/M - xhat*dgamma/M); optionally stores gm to gm_out.
-int bn_backward(int dt, const void *g, const void *mask, const void *y, int64_t M, int C,
+// The mask is the tensor `mask` if given; else, if relu_of_self, the sign of this BN's own output
+// scale*y + shift (the forward ReLU decision recomputed with the same arithmetic); else none.
+int bn_backward(int dt, const void *g, const void *mask, bool relu_of_self, const void *y, int64_t M, int C,
                 const BnBufs &b, void *dy, void *gm_out, double *scratch, hipStream_t st);
 
 // pooling / head / loss (head.hip); pooled features, logits and the loss stay fp32

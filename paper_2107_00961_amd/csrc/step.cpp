@@ -31,7 +31,7 @@ struct ConvLayer {
   const void *in = nullptr;  // activations are stored in the model's compute type (fp32 or bf16)
   void *y = nullptr;         // pre-BN output
   void *a = nullptr;         // post-BN(+ReLU) output; NULL for the layer that ends a block
-  float *mean = nullptr, *invstd = nullptr;
+  float *mean = nullptr, *invstd = nullptr, *scale = nullptr, *shift = nullptr;   // [K] each
   int64_t M() const { return (int64_t)g.N * g.P * g.Q; }
 };
 
@@ -65,6 +65,7 @@ struct StepPlan {
   void *gbuf[2] = {nullptr, nullptr}, *gm = nullptr, *dy0 = nullptr, *dy1 = nullptr, *da = nullptr;
   void *wT = nullptr, *wlp = nullptr;     // transposed filter; low-precision copy of a filter (bf16 mode)
   float *splitk = nullptr;
+  float *stats = nullptr;             // per-tile column sums left by a forward convolution
   double *bn_scratch = nullptr;
   std::vector<float *> own_grads;     // per slot, when the caller passes no gradient buffers
   int64_t bytes = 0;
@@ -105,7 +106,12 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
   for (int i = 0; i < nblocks; ++i) RESIST_TRY(block_layout(net, blocks[i], &P->layouts[i + 1]));
   RESIST_TRY(block_layout(net, B, &P->layouts[nblocks + 1]));
 
-  int64_t max_act = 0, max_filter = 0, max_splitk = 0;
+  int64_t max_act = 0, max_filter = 0, max_splitk = 0, max_stats = 0;
+  auto take_bn = [&](ConvLayer &c) {
+    float *p = A.take<float>((int64_t)4 * c.g.K);
+    c.mean = p; c.invstd = p + c.g.K; c.scale = p + 2 * c.g.K; c.shift = p + 3 * c.g.K;
+    max_stats = std::max<int64_t>(max_stats, conv_stats_floats(c.g));
+  };
   int max_c = 16;
   auto track = [&](const ConvLayer &c, bool needs_dgrad) {
     max_act = std::max<int64_t>(max_act, c.M() * c.g.K);
@@ -129,8 +135,7 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
     s.in = P->col;
     s.y = A.take_act(s.M() * K0, es);
     s.a = A.take_act(s.M() * K0, es);
-    s.mean = A.take<float>(K0);
-    s.invstd = A.take<float>(K0);
+    take_bn(s);
     max_act = std::max<int64_t>(max_act, s.M() * K0);
     max_splitk = std::max<int64_t>(max_splitk, wgrad_scratch_floats(s.g));
     max_c = std::max(max_c, K0);
@@ -163,8 +168,7 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
       ConvLayer &c = bp.convs[j];
       c.in = x;
       c.y = A.take_act(c.M() * c.g.K, es);
-      c.mean = A.take<float>(c.g.K);
-      c.invstd = A.take<float>(c.g.K);
+      take_bn(c);
       if (j + 1 < bp.convs.size()) {
         c.a = A.take_act(c.M() * c.g.K, es);
         x = c.a;
@@ -177,8 +181,7 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
       d = make_conv(L, 3, N, bs.h_in, bs.w_in, bs.c_in, bs.c_out, 1, bs.stride, 0);
       d.in = bp.in;
       d.y = A.take_act(d.M() * d.g.K, es);
-      d.mean = A.take<float>(d.g.K);
-      d.invstd = A.take<float>(d.g.K);
+      take_bn(d);
       track(d, true);
     }
     bp.out_elems = (int64_t)N * bs.h_out * bs.w_out * bs.c_out;
@@ -209,6 +212,7 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
   P->wT = A.take_act(max_filter, es);
   if (net.d.compute_dtype == DT_BF16) P->wlp = A.take_act(max_filter, es);
   P->splitk = A.take<float>(max_splitk);
+  P->stats = A.take<float>(max_stats);
   P->bn_scratch = A.take<double>(bn_scratch_doubles(max_c));
   P->own_grads.resize(nblocks + 2);
   for (int i = 0; i < nblocks + 2; ++i) P->own_grads[i] = A.take<float>(P->layouts[i].n_trainable);
@@ -224,6 +228,8 @@ BnBufs bn_bufs(const ConvLayer &c, float *params, float *grads) {
   b.rvar = params + c.rvar_off;
   b.mean = c.mean;
   b.invstd = c.invstd;
+  b.scale = c.scale;
+  b.shift = c.shift;
   b.dgamma = grads + c.gamma_off;
   b.dbeta = grads + c.beta_off;
   return b;
@@ -285,9 +291,10 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     RESIST_TRY(stem_im2col(dt, x, P.col, N, net.d.in_c, net.d.in_h, net.d.in_w, net.stem_rs, net.stem_stride, net.stem_pad,
                            net.stem_h, net.stem_w, P.kpad, st));
     RESIST_TRY(pad_rows(dt, params(0) + s.w_off, P.wpad, K0, taps, P.kpad, st));
-    RESIST_TRY(conv_fwd(s.g, dt, P.col, P.wpad, s.y, st));
+    int parts = 0;
+    RESIST_TRY(conv_fwd(s.g, dt, P.col, P.wpad, s.y, P.stats, &parts, st));
     BnBufs b = bn_bufs(s, params(0), grads(0));
-    RESIST_TRY(bn_stats(dt, s.y, s.M(), K0, b, eps, bnm, P.bn_scratch, st));
+    RESIST_TRY(bn_finalize(P.stats, parts, s.M(), K0, b, eps, bnm, st));
     RESIST_TRY(bn_apply(dt, s.y, s.M(), K0, b, nullptr, nullptr, true, s.a, st));
     if (net.d.stem_kind == 1)
       RESIST_TRY(maxpool_fwd(dt, s.a, P.stem_pool, P.stem_argmax, N, net.stem_h, net.stem_w, K0, net.body_h, net.body_w, st));
@@ -298,9 +305,10 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
       ConvLayer &c = bp.convs[j];
       const void *wf;
       RESIST_TRY(fwd_filter(c, pp + c.w_off, &wf));
-      RESIST_TRY(conv_fwd(c.g, dt, c.in, wf, c.y, st));
+      int parts = 0;
+      RESIST_TRY(conv_fwd(c.g, dt, c.in, wf, c.y, P.stats, &parts, st));
       BnBufs b = bn_bufs(c, pp, gg);
-      RESIST_TRY(bn_stats(dt, c.y, c.M(), c.g.K, b, eps, bnm, P.bn_scratch, st));
+      RESIST_TRY(bn_finalize(P.stats, parts, c.M(), c.g.K, b, eps, bnm, st));
       if (c.a) RESIST_TRY(bn_apply(dt, c.y, c.M(), c.g.K, b, nullptr, nullptr, true, c.a, st));
     }
     ConvLayer &last = bp.convs.back();
@@ -309,9 +317,10 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
       ConvLayer &d = bp.ds;
       const void *wf;
       RESIST_TRY(fwd_filter(d, pp + d.w_off, &wf));
-      RESIST_TRY(conv_fwd(d.g, dt, d.in, wf, d.y, st));
+      int parts = 0;
+      RESIST_TRY(conv_fwd(d.g, dt, d.in, wf, d.y, P.stats, &parts, st));
       BnBufs bd = bn_bufs(d, pp, gg);
-      RESIST_TRY(bn_stats(dt, d.y, d.M(), d.g.K, bd, eps, bnm, P.bn_scratch, st));
+      RESIST_TRY(bn_finalize(P.stats, parts, d.M(), d.g.K, bd, eps, bnm, st));
       RESIST_TRY(bn_apply(dt, last.y, last.M(), last.g.K, bl, d.y, &bd, true, bp.out, st));
     } else {
       RESIST_TRY(bn_apply(dt, last.y, last.M(), last.g.K, bl, bp.in, nullptr, true, bp.out, st));
@@ -338,12 +347,12 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     ConvLayer &last = bp.convs[nc - 1];
     BnBufs bl = bn_bufs(last, pp, gg);
     // through the final ReLU and the last BN of the residual branch
-    RESIST_TRY(bn_backward(dt, G, bp.out, last.y, last.M(), last.g.K, bl, P.dy0, bp.has_ds ? nullptr : P.gm, P.bn_scratch, st));
+    RESIST_TRY(bn_backward(dt, G, bp.out, false, last.y, last.M(), last.g.K, bl, P.dy0, bp.has_ds ? nullptr : P.gm, P.bn_scratch, st));
     if (bp.has_ds) {
       // shortcut branch: BN and 1x1 convolution; its data gradient initialises Gn
       ConvLayer &d = bp.ds;
       BnBufs bd = bn_bufs(d, pp, gg);
-      RESIST_TRY(bn_backward(dt, G, bp.out, d.y, d.M(), d.g.K, bd, P.gm, nullptr, P.bn_scratch, st));
+      RESIST_TRY(bn_backward(dt, G, bp.out, false, d.y, d.M(), d.g.K, bd, P.gm, nullptr, P.bn_scratch, st));
       RESIST_TRY(conv_wgrad(d.g, dt, P.gm, d.in, gg + d.w_off, P.splitk, st));
       RESIST_TRY(prepare_filter(d.g, DT_F32, dt, pp + d.w_off, nullptr, P.wT, st));
       RESIST_TRY(conv_dgrad(d.g, dt, P.gm, P.wT, Gn, nullptr, st));
@@ -357,7 +366,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
         ConvLayer &prev = bp.convs[j - 1];
         RESIST_TRY(conv_dgrad(c.g, dt, dy, P.wT, P.da, nullptr, st));
         BnBufs bp_ = bn_bufs(prev, pp, gg);
-        RESIST_TRY(bn_backward(dt, P.da, prev.a, prev.y, prev.M(), prev.g.K, bp_, dy_other, nullptr, P.bn_scratch, st));
+        RESIST_TRY(bn_backward(dt, P.da, nullptr, true, prev.y, prev.M(), prev.g.K, bp_, dy_other, nullptr, P.bn_scratch, st));
         std::swap(dy, dy_other);
       } else {
         // gradient w.r.t. the block input = branch + shortcut
@@ -377,7 +386,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
       Gs = P.da;
     }
     BnBufs b = bn_bufs(s, params(0), grads(0));
-    RESIST_TRY(bn_backward(dt, Gs, s.a, s.y, s.M(), K0, b, P.dy0, nullptr, P.bn_scratch, st));
+    RESIST_TRY(bn_backward(dt, Gs, nullptr, true, s.y, s.M(), K0, b, P.dy0, nullptr, P.bn_scratch, st));
     RESIST_TRY(conv_wgrad(s.g, dt, P.dy0, P.col, P.dwpad, P.splitk, st));
     RESIST_TRY(unpad_rows_f32(P.dwpad, grads(0) + s.w_off, K0, taps, P.kpad, st));
   }

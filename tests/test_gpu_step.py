@@ -139,9 +139,12 @@ def _full_size_check(cfg_name, what):
     a pre-activation within rounding distance of zero flips its ReLU decision, which moves the
     weight gradients of that layer and of every earlier layer by a few 1e-3 of their norm
     (tests/test_oracle_sensitivity.py measures the same response in the float64 oracle itself).
-    The element-wise fp32 bound is therefore applied to the loss and to the tensors no ReLU
-    decision stands behind (head, tail of the last block); every other gradient tensor and the
-    applied update are bounded in relative L2 norm by 2e-2.
+    The element-wise fp32 bound is therefore applied to the loss, the running statistics and the
+    tensors no ReLU decision stands behind (the head: a flipped decision belongs to an activation
+    that is zero to rounding either way, so forward quantities are continuous in it).  The tail of
+    the last block has exactly one ReLU layer behind it (the block's output, 1 M decisions, each
+    within fp32 accumulation error of zero with probability ~4e-6): bound 2e-3 in relative L2 norm.
+    Every other gradient tensor and the applied update are bounded in relative L2 norm by 2e-2.
     """
     cfg = get_config(cfg_name)
     model = cfg["model"]
@@ -166,11 +169,11 @@ def _full_size_check(cfg_name, what):
     for k in sub.keys:
         for name, g in grads[k].items():
             a = got_g[k][name].astype(np.float64)
-            exact = k == nb or (k == last and name.startswith((tail, tail_bn)))
-            if exact:
+            if k == nb:
                 assert_close(a, g, f"{what} grad block {k} {name}")
             rel = np.linalg.norm(a - g) / np.linalg.norm(g)
-            assert rel <= 2e-2, f"{what} grad block {k} {name}: relative L2 error {rel:.3e}"
+            bar = 2e-3 if (k == last and name.startswith((tail, tail_bn))) else 2e-2
+            assert rel <= bar, f"{what} grad block {k} {name}: relative L2 error {rel:.3e}"
             upd = params[k][name].astype(np.float64) - new_p[k][name]
             err = got_p[k][name].astype(np.float64) - new_p[k][name]
             assert np.linalg.norm(err) <= 2e-2 * np.linalg.norm(upd) + 1e-7 * np.linalg.norm(new_p[k][name]), \
@@ -286,7 +289,22 @@ def test_cfg2_full_size_step():
 
 
 def test_cfg2_widths_reduced_depth_strict():
-    """Same channel widths and tile shapes as the benchmark network at a depth and batch where no
-    ReLU decision is within rounding distance: the strict element-wise bound applies throughout."""
+    """Same channel widths and tile shapes as the benchmark network, strict element-wise bound.
+
+    The bound can only hold where no ReLU decision is within fp32 rounding distance of a tie, and
+    with z ~ N(0,1) pre-activations a network with D decisions has about 0.8*D*m of them within m of
+    zero.  The case is therefore kept small (batch 2, 16x16 images, ~0.5 M decisions) and the data
+    seed is the first one for which the oracle's closest decision is at least 1e-5 away from a tie
+    (fp32 accumulation over up to 4608 terms moves a normalised value by ~1e-6)."""
     model = dict(get_config("cfg2")["model"], blocks=[2, 2, 3, 2], in_h=16, in_w=16)
-    _run_steps(model, [0, 1, 2, 4, 6, 7, 8], 8, steps=1, lr=0.1, mu=0.9, wd=5e-4, perturb_bn=False)
+    blocks, batch = [0, 1, 2, 4, 6, 7, 8], 2
+    params = make_params(model, 0, perturb_bn=False)
+    for seed in range(40):
+        x, y = make_batch(model, batch, 100 * seed)
+        _, _, tape, _ = OR.forward_backward(model, blocks, params, x, y, backward=False)
+        print(f"seed {seed}: closest ReLU decision {tape.relu_margin:.2e}", flush=True)
+        if tape.relu_margin >= 1e-5:
+            break
+    else:
+        pytest.fail("no seed with a clear ReLU margin")
+    _run_steps(model, blocks, batch, steps=1, lr=0.1, mu=0.9, wd=5e-4, seed=seed, perturb_bn=False)

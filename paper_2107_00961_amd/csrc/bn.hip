@@ -80,7 +80,32 @@ __device__ inline void reduce_parts(const S *__restrict__ scratch, int parts, in
   *out1 = q;
 }
 
-__global__ __launch_bounds__(kThreads) void bn_finalize_kernel(const float *__restrict__ stats, int parts, int C,
+// first level for long lists of parts: workgroup (x, z) adds parts [z*kSlice, (z+1)*kSlice) of 16
+// channels in float64; output [2][Z][C]
+constexpr int kSlice = 64;
+__global__ __launch_bounds__(kThreads) void bn_stats_reduce_kernel(const float *__restrict__ stats, int parts, int C,
+                                                                   double *__restrict__ out) {
+  __shared__ double red[2][16][16];
+  const int c = blockIdx.x * 16 + (threadIdx.x & 15), pl = threadIdx.x >> 4;
+  const int z = blockIdx.y, Z = gridDim.y;
+  const int p0 = z * kSlice, p1 = min(parts, p0 + kSlice);
+  double s = 0, q = 0;
+  for (int p = p0 + pl; p < p1; p += 16) {
+    s += (double)stats[(size_t)p * C + c];
+    q += (double)stats[(size_t)(parts + p) * C + c];
+  }
+  const int cl = c & 15;
+  red[0][pl][cl] = s;
+  red[1][pl][cl] = q;
+  __syncthreads();
+  if (pl != 0) return;
+  for (int j = 1; j < 16; ++j) { s += red[0][j][cl]; q += red[1][j][cl]; }
+  out[(size_t)z * C + c] = s;
+  out[(size_t)(Z + z) * C + c] = q;
+}
+
+template <typename S>
+__global__ __launch_bounds__(kThreads) void bn_finalize_kernel(const S *__restrict__ stats, int parts, int C,
                                                                long long M, float eps, float momentum,
                                                                const float *__restrict__ gamma, const float *__restrict__ beta,
                                                                float *__restrict__ mean, float *__restrict__ invstd,
@@ -351,12 +376,22 @@ void launch_bwd(int mode, dim3 gp, dim3 ga, hipStream_t st, const void *g, const
 
 int64_t bn_scratch_doubles(int C) { return (int64_t)2 * kMaxParts * C; }
 
-int bn_finalize(const float *stats, int parts, int64_t M, int C, const BnBufs &b, float eps, float momentum, hipStream_t st) {
+int bn_finalize(const float *stats, int parts, int64_t M, int C, const BnBufs &b, float eps, float momentum, double *scratch,
+                hipStream_t st) {
   RESIST_TRY(check_bn(DT_F32, M, C));
   if (parts < 1 || !stats) return set_error(RESIST_EINVAL, "bn_finalize: no partial sums");
   prof::Scope ps("bn_finalize", 0, 8.0 * parts * C, st);
-  hipLaunchKernelGGL(bn_finalize_kernel, dim3(C / 16), dim3(kThreads), 0, st, stats, parts, C, (long long)M, eps, momentum,
-                     b.gamma, b.beta, b.mean, b.invstd, b.scale, b.shift, b.rmean, b.rvar);
+  if (parts > 2 * kSlice) {
+    const int Z = (parts + kSlice - 1) / kSlice;
+    if (Z > kMaxParts || !scratch) return set_error(RESIST_ESHAPE, "bn_finalize: %d partial sums", parts);
+    hipLaunchKernelGGL(bn_stats_reduce_kernel, dim3(C / 16, Z), dim3(kThreads), 0, st, stats, parts, C, scratch);
+    RESIST_CHECK_LAUNCH("bn_stats_reduce");
+    hipLaunchKernelGGL(bn_finalize_kernel<double>, dim3(C / 16), dim3(kThreads), 0, st, (const double *)scratch, Z, C,
+                       (long long)M, eps, momentum, b.gamma, b.beta, b.mean, b.invstd, b.scale, b.shift, b.rmean, b.rvar);
+  } else {
+    hipLaunchKernelGGL(bn_finalize_kernel<float>, dim3(C / 16), dim3(kThreads), 0, st, stats, parts, C, (long long)M, eps,
+                       momentum, b.gamma, b.beta, b.mean, b.invstd, b.scale, b.shift, b.rmean, b.rvar);
+  }
   RESIST_CHECK_LAUNCH("bn_finalize");
   return RESIST_OK;
 }

@@ -437,6 +437,75 @@ __global__ __launch_bounds__(256) void prepare_filter_kernel(const S *__restrict
 }
 }  // namespace
 
+// All filters of a step in one launch (or a few: the table travels in the kernel arguments).
+namespace {
+constexpr int kPrepSegs = 48;
+struct PrepTable {
+  const float *w[kPrepSegs];
+  void *wlp[kPrepSegs];
+  void *wT[kPrepSegs];
+  int K[kPrepSegs], RS[kPrepSegs], C[kPrepSegs];
+  int first_wg[kPrepSegs + 1];
+  int nseg;
+};
+template <typename T>
+__global__ __launch_bounds__(256) void prepare_filters_kernel(PrepTable t) {
+  __shared__ float tile[32][33];
+  int seg = 0;
+  while (seg + 1 < t.nseg && (int)blockIdx.x >= t.first_wg[seg + 1]) ++seg;
+  const int K = t.K[seg], RS = t.RS[seg], C = t.C[seg];
+  const int ct = (C + 31) / 32, kt = (K + 31) / 32;
+  int id = blockIdx.x - t.first_wg[seg];
+  const int c0 = (id % ct) * 32;
+  id /= ct;
+  const int k0 = (id % kt) * 32, tap = id / kt;
+  const float *__restrict__ w = t.w[seg];
+  T *__restrict__ wlp = static_cast<T *>(t.wlp[seg]);
+  T *__restrict__ wT = static_cast<T *>(t.wT[seg]);
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int i = ty; i < 32; i += 8) {
+    const int k = k0 + i, c = c0 + tx;
+    float v = 0.f;
+    if (k < K && c < C) {
+      v = w[((size_t)k * RS + tap) * C + c];
+      if (wlp) wlp[((size_t)k * RS + tap) * C + c] = Elem<T>::from_f32(v);
+    }
+    tile[i][tx] = v;
+  }
+  __syncthreads();
+  if (wT)
+    for (int i = ty; i < 32; i += 8) {
+      const int c = c0 + i, k = k0 + tx;
+      if (k < K && c < C) wT[((size_t)c * RS + tap) * K + k] = Elem<T>::from_f32(tile[tx][i]);
+    }
+}
+}  // namespace
+
+int prepare_filters(const std::vector<FilterPrep> &items, int dt, hipStream_t st) {
+  size_t i = 0;
+  while (i < items.size()) {
+    PrepTable t{};
+    int wg = 0;
+    double bytes = 0;
+    while (i < items.size() && t.nseg < kPrepSegs) {
+      const FilterPrep &f = items[i++];
+      const int n = t.nseg++;
+      t.w[n] = f.w; t.wlp[n] = f.w_lp; t.wT[n] = f.wT;
+      t.K[n] = f.g.K; t.RS[n] = f.g.R * f.g.S; t.C[n] = f.g.C;
+      t.first_wg[n] = wg;
+      wg += ((f.g.C + 31) / 32) * ((f.g.K + 31) / 32) * f.g.R * f.g.S;
+      bytes += (4.0 + (f.w_lp ? esize(dt) : 0) + (f.wT ? esize(dt) : 0)) * f.g.K * f.g.R * f.g.S * f.g.C;
+    }
+    t.first_wg[t.nseg] = wg;
+    if (wg == 0) continue;
+    prof::Scope ps("prepare_filters", 0, bytes, st);
+    if (dt == DT_BF16) hipLaunchKernelGGL(prepare_filters_kernel<__bf16>, dim3(wg), dim3(256), 0, st, t);
+    else hipLaunchKernelGGL(prepare_filters_kernel<float>, dim3(wg), dim3(256), 0, st, t);
+    RESIST_CHECK_LAUNCH("prepare_filters");
+  }
+  return RESIST_OK;
+}
+
 int prepare_filter(const ConvGeom &g, int src_dt, int dt, const void *w, void *w_lp, void *wT, hipStream_t st) {
   if (src_dt == DT_BF16 && dt != DT_BF16) return set_error(RESIST_EINVAL, "prepare_filter: bf16 source needs a bf16 target");
   dim3 grid((g.C + 31) / 32, (g.K + 31) / 32, g.R * g.S);

@@ -112,6 +112,9 @@ int conv_dgrad(const ConvGeom &g, int dt, const void *dy, const void *wT, void *
                hipStream_t st);
 // from a filter stored in src_dt: optional copy in dt (w_lp) and optional transpose in dt (wT)
 int prepare_filter(const ConvGeom &g, int src_dt, int dt, const void *w, void *w_lp, void *wT, hipStream_t st);
+// the same for many filters at once (fp32 masters -> copies and transposes in dt)
+struct FilterPrep { ConvGeom g; const float *w; void *w_lp; void *wT; };
+int prepare_filters(const std::vector<FilterPrep> &items, int dt, hipStream_t st);
 // dw (fp32) = wgrad(dy, x); partial: split-reduction scratch of wgrad_scratch_floats(g) floats
 int64_t wgrad_scratch_floats(const ConvGeom &g);
 int conv_wgrad(const ConvGeom &g, int dt, const void *dy, const void *x, float *dw, float *partial,
@@ -131,11 +134,11 @@ struct BnBufs {
   float *scale, *shift;      // [C] gamma*invstd and beta - mean*gamma*invstd (written by bn_finalize)
   float *dgamma, *dbeta;     // [C] gradient outputs
 };
-int64_t bn_scratch_doubles(int C);   // partial-sum scratch for one bn_backward call
+int64_t bn_scratch_doubles(int C);   // partial-sum scratch for one bn_finalize or bn_backward call
 // batch statistics from the per-tile sums a convolution left behind: mean, 1/sqrt(var+eps), the
 // affine map of bn_apply, and the running statistics
 int bn_finalize(const float *stats, int parts, int64_t M, int C, const BnBufs &b, float eps, float momentum,
-                hipStream_t st);
+                double *scratch, hipStream_t st);
 // a = [relu]( scale*y + shift [+ res] )            res: raw tensor, or BN(res_y) if res_bn given
 int bn_apply(int dt, const void *y, int64_t M, int C, const BnBufs &b, const void *res,
              const BnBufs *res_bn, bool relu, void *a, hipStream_t st);

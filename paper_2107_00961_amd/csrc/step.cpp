@@ -32,6 +32,8 @@ struct ConvLayer {
   void *y = nullptr;         // pre-BN output
   void *a = nullptr;         // post-BN(+ReLU) output; NULL for the layer that ends a block
   float *mean = nullptr, *invstd = nullptr, *scale = nullptr, *shift = nullptr;   // [K] each
+  void *wlp = nullptr;       // the filter in the compute type (bf16 mode; fp32 mode multiplies the master)
+  void *wT = nullptr;        // [C][R][S][K] transpose in the compute type, for the data gradient
   int64_t M() const { return (int64_t)g.N * g.P * g.Q; }
 };
 
@@ -63,7 +65,6 @@ struct StepPlan {
   int feat_hw = 0;
   // shared scratch
   void *gbuf[2] = {nullptr, nullptr}, *gm = nullptr, *dy0 = nullptr, *dy1 = nullptr, *da = nullptr;
-  void *wT = nullptr, *wlp = nullptr;     // transposed filter; low-precision copy of a filter (bf16 mode)
   float *splitk = nullptr;
   float *stats = nullptr;             // per-tile column sums left by a forward convolution
   double *bn_scratch = nullptr;
@@ -106,7 +107,12 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
   for (int i = 0; i < nblocks; ++i) RESIST_TRY(block_layout(net, blocks[i], &P->layouts[i + 1]));
   RESIST_TRY(block_layout(net, B, &P->layouts[nblocks + 1]));
 
-  int64_t max_act = 0, max_filter = 0, max_splitk = 0, max_stats = 0;
+  int64_t max_act = 0, max_splitk = 0, max_stats = 0;
+  auto take_filters = [&](ConvLayer &c) {
+    const int64_t n = (int64_t)c.g.K * c.g.R * c.g.S * c.g.C;
+    c.wT = A.take_act(n, es);
+    if (net.d.compute_dtype == DT_BF16) c.wlp = A.take_act(n, es);
+  };
   auto take_bn = [&](ConvLayer &c) {
     float *p = A.take<float>((int64_t)4 * c.g.K);
     c.mean = p; c.invstd = p + c.g.K; c.scale = p + 2 * c.g.K; c.shift = p + 3 * c.g.K;
@@ -117,7 +123,6 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
     max_act = std::max<int64_t>(max_act, c.M() * c.g.K);
     max_act = std::max<int64_t>(max_act, (int64_t)c.g.N * c.g.H * c.g.W * c.g.C);
     (void)needs_dgrad;
-    max_filter = std::max<int64_t>(max_filter, (int64_t)c.g.K * c.g.R * c.g.S * c.g.C);
     max_splitk = std::max<int64_t>(max_splitk, wgrad_scratch_floats(c.g));
     max_c = std::max(max_c, c.g.K);
   };
@@ -169,6 +174,7 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
       c.in = x;
       c.y = A.take_act(c.M() * c.g.K, es);
       take_bn(c);
+      take_filters(c);
       if (j + 1 < bp.convs.size()) {
         c.a = A.take_act(c.M() * c.g.K, es);
         x = c.a;
@@ -182,6 +188,7 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
       d.in = bp.in;
       d.y = A.take_act(d.M() * d.g.K, es);
       take_bn(d);
+      take_filters(d);
       track(d, true);
     }
     bp.out_elems = (int64_t)N * bs.h_out * bs.w_out * bs.c_out;
@@ -209,8 +216,6 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
   P->dy0 = A.take_act(max_act, es);
   P->dy1 = A.take_act(max_act, es);
   P->da = A.take_act(max_act, es);
-  P->wT = A.take_act(max_filter, es);
-  if (net.d.compute_dtype == DT_BF16) P->wlp = A.take_act(max_filter, es);
   P->splitk = A.take<float>(max_splitk);
   P->stats = A.take<float>(max_stats);
   P->bn_scratch = A.take<double>(bn_scratch_doubles(max_c));
@@ -275,13 +280,18 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
   auto grads = [&](int slot) { return block_grads ? (float *)block_grads[slot] : P.own_grads[slot]; };
 
   const int dt = net.d.compute_dtype;
-  // the filter a convolution multiplies with: the fp32 master itself, or its bf16 copy made just before
-  auto fwd_filter = [&](const ConvLayer &c, const float *w, const void **out) -> int {
-    if (dt == DT_F32) { *out = w; return RESIST_OK; }
-    RESIST_TRY(prepare_filter(c.g, DT_F32, dt, w, P.wlp, nullptr, st));
-    *out = P.wlp;
-    return RESIST_OK;
-  };
+  // every filter once, up front: the transpose the data gradient reads and, in bf16 mode, the copy
+  // the forward convolution multiplies with (fp32 mode multiplies the master itself)
+  {
+    std::vector<FilterPrep> prep;
+    for (BlockPlan &bp : P.blocks) {
+      float *pp = params(bp.slot);
+      for (ConvLayer &c : bp.convs) prep.push_back(FilterPrep{c.g, pp + c.w_off, c.wlp, c.wT});
+      if (bp.has_ds) prep.push_back(FilterPrep{bp.ds.g, pp + bp.ds.w_off, bp.ds.wlp, bp.ds.wT});
+    }
+    RESIST_TRY(prepare_filters(prep, dt, st));
+  }
+  auto fwd_filter = [&](const ConvLayer &c, const float *w) -> const void * { return dt == DT_F32 ? (const void *)w : c.wlp; };
 
   // ================= forward =================
   {
@@ -294,7 +304,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     int parts = 0;
     RESIST_TRY(conv_fwd(s.g, dt, P.col, P.wpad, s.y, P.stats, &parts, st));
     BnBufs b = bn_bufs(s, params(0), grads(0));
-    RESIST_TRY(bn_finalize(P.stats, parts, s.M(), K0, b, eps, bnm, st));
+    RESIST_TRY(bn_finalize(P.stats, parts, s.M(), K0, b, eps, bnm, P.bn_scratch, st));
     RESIST_TRY(bn_apply(dt, s.y, s.M(), K0, b, nullptr, nullptr, true, s.a, st));
     if (net.d.stem_kind == 1)
       RESIST_TRY(maxpool_fwd(dt, s.a, P.stem_pool, P.stem_argmax, N, net.stem_h, net.stem_w, K0, net.body_h, net.body_w, st));
@@ -303,24 +313,20 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     float *pp = params(bp.slot), *gg = grads(bp.slot);
     for (size_t j = 0; j < bp.convs.size(); ++j) {
       ConvLayer &c = bp.convs[j];
-      const void *wf;
-      RESIST_TRY(fwd_filter(c, pp + c.w_off, &wf));
       int parts = 0;
-      RESIST_TRY(conv_fwd(c.g, dt, c.in, wf, c.y, P.stats, &parts, st));
+      RESIST_TRY(conv_fwd(c.g, dt, c.in, fwd_filter(c, pp + c.w_off), c.y, P.stats, &parts, st));
       BnBufs b = bn_bufs(c, pp, gg);
-      RESIST_TRY(bn_finalize(P.stats, parts, c.M(), c.g.K, b, eps, bnm, st));
+      RESIST_TRY(bn_finalize(P.stats, parts, c.M(), c.g.K, b, eps, bnm, P.bn_scratch, st));
       if (c.a) RESIST_TRY(bn_apply(dt, c.y, c.M(), c.g.K, b, nullptr, nullptr, true, c.a, st));
     }
     ConvLayer &last = bp.convs.back();
     BnBufs bl = bn_bufs(last, pp, gg);
     if (bp.has_ds) {
       ConvLayer &d = bp.ds;
-      const void *wf;
-      RESIST_TRY(fwd_filter(d, pp + d.w_off, &wf));
       int parts = 0;
-      RESIST_TRY(conv_fwd(d.g, dt, d.in, wf, d.y, P.stats, &parts, st));
+      RESIST_TRY(conv_fwd(d.g, dt, d.in, fwd_filter(d, pp + d.w_off), d.y, P.stats, &parts, st));
       BnBufs bd = bn_bufs(d, pp, gg);
-      RESIST_TRY(bn_finalize(P.stats, parts, d.M(), d.g.K, bd, eps, bnm, st));
+      RESIST_TRY(bn_finalize(P.stats, parts, d.M(), d.g.K, bd, eps, bnm, P.bn_scratch, st));
       RESIST_TRY(bn_apply(dt, last.y, last.M(), last.g.K, bl, d.y, &bd, true, bp.out, st));
     } else {
       RESIST_TRY(bn_apply(dt, last.y, last.M(), last.g.K, bl, bp.in, nullptr, true, bp.out, st));
@@ -354,23 +360,21 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
       BnBufs bd = bn_bufs(d, pp, gg);
       RESIST_TRY(bn_backward(dt, G, bp.out, false, d.y, d.M(), d.g.K, bd, P.gm, nullptr, P.bn_scratch, st));
       RESIST_TRY(conv_wgrad(d.g, dt, P.gm, d.in, gg + d.w_off, P.splitk, st));
-      RESIST_TRY(prepare_filter(d.g, DT_F32, dt, pp + d.w_off, nullptr, P.wT, st));
-      RESIST_TRY(conv_dgrad(d.g, dt, P.gm, P.wT, Gn, nullptr, st));
+      RESIST_TRY(conv_dgrad(d.g, dt, P.gm, d.wT, Gn, nullptr, st));
     }
     void *dy = P.dy0, *dy_other = P.dy1;
     for (int j = nc - 1; j >= 0; --j) {
       ConvLayer &c = bp.convs[j];
       RESIST_TRY(conv_wgrad(c.g, dt, dy, c.in, gg + c.w_off, P.splitk, st));
-      RESIST_TRY(prepare_filter(c.g, DT_F32, dt, pp + c.w_off, nullptr, P.wT, st));
       if (j > 0) {
         ConvLayer &prev = bp.convs[j - 1];
-        RESIST_TRY(conv_dgrad(c.g, dt, dy, P.wT, P.da, nullptr, st));
+        RESIST_TRY(conv_dgrad(c.g, dt, dy, c.wT, P.da, nullptr, st));
         BnBufs bp_ = bn_bufs(prev, pp, gg);
         RESIST_TRY(bn_backward(dt, P.da, nullptr, true, prev.y, prev.M(), prev.g.K, bp_, dy_other, nullptr, P.bn_scratch, st));
         std::swap(dy, dy_other);
       } else {
         // gradient w.r.t. the block input = branch + shortcut
-        RESIST_TRY(conv_dgrad(c.g, dt, dy, P.wT, Gn, bp.has_ds ? Gn : P.gm, st));
+        RESIST_TRY(conv_dgrad(c.g, dt, dy, c.wT, Gn, bp.has_ds ? Gn : P.gm, st));
       }
     }
     gi ^= 1;

@@ -39,6 +39,66 @@ def _describe(name, cfg, sub):
     return f"{name}: {shape} sub-ResNet {sub} of S={cfg['S']}"
 
 
+def _bench_round(args, cfg, subs):
+    """One synchronisation round on one GPU: S sub-ResNets x local_iters steps, then aggregation."""
+    import torch
+    import paper_2107_00961_amd as R
+    from paper_2107_00961_amd.harness import DeviceModel, SubResNet, to_device_batch
+    from resist_inputs import make_batch, make_params
+
+    model, batch, S = cfg["model"], cfg["batch"], cfg["S"]
+    iters = cfg.get("local_iters", 50)
+    params = make_params(model, 0)
+    nb = R.num_blocks(model)
+    workers = [SubResNet(model, subs[s], params, batch, keep_grads=False) for s in range(S)]
+    glob = DeviceModel(model, list(range(nb)), params)
+    lr, mu, wd = cfg["lr"], cfg["momentum"], cfg["weight_decay"]
+    batches = [[to_device_batch(*make_batch(model, batch, cfg["data_seed"] + 1000 * s + it)) for it in range(iters)]
+               for s in range(S)]
+    stream = torch.cuda.current_stream()
+    for s in range(S):                                   # warm-up: one step each (weights restored below)
+        workers[s].step(*batches[s][0], lr * 0.0, mu, wd, stream)
+    torch.cuda.synchronize()
+    workers = [SubResNet(model, subs[s], params, batch, keep_grads=False) for s in range(S)]
+    torch.cuda.synchronize()
+    step_ms = []
+    t_round = time.perf_counter()
+    for s in range(S):
+        t0 = time.perf_counter()
+        for it in range(iters):
+            workers[s].step(*batches[s][it], lr, mu, wd, stream)
+        torch.cuda.synchronize()
+        step_ms.append((time.perf_counter() - t0) / iters * 1e3)
+    t_steps = time.perf_counter() - t_round
+    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    agg_ms = []
+    for rep in range(5):
+        a0.record(stream)
+        R.aggregate(model, subs, [w.params for w in workers], glob.params, stream)
+        a1.record(stream)
+        torch.cuda.synchronize()
+        agg_ms.append(a0.elapsed_time(a1))
+    agg = min(agg_ms[1:])
+    n_glob = sum(p.numel() for p in glob.params)
+    n_read = sum(p.numel() for w in workers for p in w.params)
+    agg_bytes = 4.0 * (n_glob + n_read)
+    ms = t_steps / (S * iters) * 1e3
+    losses = [float(w.loss.cpu()[0]) for w in workers]
+    out = {
+        "metric": "images/sec per sub-ResNet local SGD step",
+        "value": round(batch / (ms * 1e-3), 1), "unit": "images/s", "n_gpus": 1, "steps": S * iters, "warmup": S,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if model.get("compute_dtype", 0) == 1 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: full round, {S} sub-ResNets x {iters} local steps, then aggregation",
+                   "batch": batch, "blocks": subs, "classes": model["num_classes"]},
+        "round": {"ms_per_step_by_sub": [round(v, 4) for v in step_ms], "aggregate_ms": round(agg, 4),
+                  "aggregate_bytes": agg_bytes, "aggregate_GBps": round(agg_bytes / (agg * 1e-3) / 1e9, 1),
+                  "aggregate_frac_of_hbm_peak": round(agg_bytes / (agg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                  "round_ms": round(t_steps * 1e3 + agg, 2), "final_losses": losses},
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -47,6 +107,9 @@ def main():
     ap.add_argument("--workload", default="cfg2",
                     help="cfg1 | cfg2 | cfg3 | cfg5 (fp32) | cfg4 | cfg5_bf16 (bf16 storage, fp32 accumulation)")
     ap.add_argument("--sub", type=int, default=0, help="which sub-ResNet of the partition to step")
+    ap.add_argument("--round", action="store_true",
+                    help="time one full round instead: every sub-ResNet runs its local iterations on fresh "
+                         "batches, one after the other, then resist_aggregate rebuilds the global model")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=32)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -65,6 +128,8 @@ def main():
     cfg = get_config(args.workload)
     model, batch = cfg["model"], cfg["batch"]
     subs, _ = R.partition(model, cfg["S"], cfg["min_depth"], cfg["part_seed"], 0)
+    if args.round:
+        return _bench_round(args, cfg, subs)
     blocks = subs[args.sub]
     params = make_params(model, 0)
     sub = SubResNet(model, blocks, params, batch, keep_grads=False)

@@ -13,6 +13,7 @@
 // grid of 32x32 accumulator tiles held in registers.
 #include <type_traits>
 
+#include "elem.h"
 #include "internal.h"
 
 namespace resist {
@@ -107,8 +108,15 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
   constexpr int PA = BM / RPP, PB = BN / RPP;    // load passes
   constexpr int NK = BK / (2 * VEC);             // k-steps per chunk
   static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1 && PA >= 1 && PB >= 1 && NK >= 2, "tile shape");
-  __shared__ T As[kStages][BM][LDK];
-  __shared__ T Bs[kStages][BN][LDK];
+  // one LDS block: the operand stages during the K loop, the fp32 output tile afterwards
+  constexpr int LDC = BN + 8;   // output tile pitch (floats): lanes l and l+32 (4 rows apart) hit disjoint banks
+  constexpr size_t kOperandBytes = sizeof(T) * kStages * (BM + BN) * LDK;
+  constexpr size_t kTileBytes = sizeof(float) * BM * LDC;
+  static_assert(kTileBytes <= kOperandBytes, "output tile must fit in the operand stages");
+  __shared__ __attribute__((aligned(16))) char lds_raw[kOperandBytes];
+  T (*As)[BM][LDK] = reinterpret_cast<T (*)[BM][LDK]>(lds_raw);
+  T (*Bs)[BN][LDK] = reinterpret_cast<T (*)[BN][LDK]>(lds_raw + sizeof(T) * kStages * BM * LDK);
+  float (*Cs)[LDC] = reinterpret_cast<float (*)[LDC]>(lds_raw);
   __shared__ int row_off[BM];
 
   const int tid = threadIdx.x;
@@ -268,7 +276,10 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
     }
   }
 
-  // epilogue: lane holds column (lane%32), rows 8*(e/4) + 4*(lane/32) + e%4 of each 32x32 tile
+  // epilogue.  A lane holds column (lane%32) and rows 8*(e/4) + 4*(lane/32) + e%4 of each 32x32
+  // tile.  The tile goes through LDS (the operand stages are free after the last barrier: every
+  // fragment a wave uses was fetched before it) so that global memory sees 16-byte accesses along
+  // the channel axis; the optional addend is added in fp32 before the one rounding to T.
   T *out = static_cast<T *>(a.out);
   const T *addend = static_cast<const T *>(a.addend);
   float s1[TN], s2[TN];   // column sums of the values as stored (batch-norm statistics of this row tile)
@@ -278,25 +289,48 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int col = n0 + wn * WTN + j * 32 + lr;
+      const int cl = wn * WTN + j * 32 + lr;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int row = wm * WTM + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        const int ro = row_off[row];
-        if (ro >= 0 && col < a.OC) {
-          const size_t off = (size_t)ro * a.OC + col;
-          float v = acc[i][j][e];
-          if (addend) v += E::to_f32(addend[off]);
-          const T stored = E::from_f32(v);
-          out[off] = stored;
-          if (MODE == kFwd) {
-            const float sv = E::to_f32(stored);
-            s1[j] += sv;
-            s2[j] = fmaf(sv, sv, s2[j]);
-          }
+        const float v = acc[i][j][e];
+        Cs[row][cl] = v;
+        if (MODE == kFwd) {   // rows and columns outside the tensor hold exact zeros
+          const float sv = E::to_f32(E::from_f32(v));
+          s1[j] += sv;
+          s2[j] = fmaf(sv, sv, s2[j]);
         }
       }
     }
+  __syncthreads();
+  {
+    constexpr int CV = BN / VEC;            // 16-byte pieces per tile row
+    constexpr int RPS = kThreads / CV;      // rows per pass
+    const int cv = (tid % CV) * VEC, r0 = tid / CV;
+    const bool col_ok = n0 + cv < a.OC;     // OC is a multiple of VEC
+    static_assert(BM % RPS == 0, "output tile rows per pass");
+#pragma unroll
+    for (int pass = 0; pass < BM / RPS; ++pass) {
+      const int r = r0 + pass * RPS;
+      const int ro = row_off[r];
+      if (ro >= 0 && col_ok) {
+        const size_t off = (size_t)ro * a.OC + n0 + cv;
+        float v[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; e += 4) {
+          const f32x4 t = *reinterpret_cast<const f32x4 *>(&Cs[r][cv + e]);
+          v[e] = t[0]; v[e + 1] = t[1]; v[e + 2] = t[2]; v[e + 3] = t[3];
+        }
+        if (addend) {
+          float ad[VEC];
+          Vec<T>::load(addend + off, ad);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) v[e] += ad[e];
+        }
+        Vec<T>::store(out + off, v);
+      }
+    }
+  }
   if (MODE == kFwd && a.stats) {
     // lanes l and l+32 hold the same column; then the WGM waves that share a column range add up in
     // wave order.  Every step has a fixed order, so the sums are bit-stable from run to run.

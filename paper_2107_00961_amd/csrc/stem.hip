@@ -9,25 +9,34 @@
 namespace resist {
 namespace {
 
+// one thread writes V consecutive columns of one row (a 16-byte store); kpad is a multiple of 32
 template <typename T>
 __global__ __launch_bounds__(256) void stem_im2col_kernel(const float *__restrict__ x, T *__restrict__ col, int N, int C,
                                                           int H, int W, int R, int stride, int pad, int P, int Q, int kpad) {
-  const long long total = (long long)N * P * Q * kpad;
+  constexpr int V = Vec<T>::N;
+  const int vpr = kpad / V;
+  const long long total = (long long)N * P * Q * vpr;
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
-  const int j = (int)(i % kpad);
-  long long m = i / kpad;
-  float v = 0.f;
-  if (j < R * R * C) {
-    const int c = j % C, tap = j / C;
-    const int r = tap / R, s = tap % R;
-    const int q = (int)(m % Q); m /= Q;
-    const int p = (int)(m % P);
-    const int n = (int)(m / P);
-    const int ih = p * stride + r - pad, iw = q * stride + s - pad;
-    if (ih >= 0 && ih < H && iw >= 0 && iw < W) v = x[((size_t)(n * C + c) * H + ih) * W + iw];
+  const int j0 = (int)(i % vpr) * V;
+  long long m = i / vpr;
+  const int q = (int)(m % Q); m /= Q;
+  const int p = (int)(m % P);
+  const int n = (int)(m / P);
+  float v[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) {
+    const int j = j0 + e;
+    float t = 0.f;
+    if (j < R * R * C) {
+      const int c = j % C, tap = j / C;
+      const int r = tap / R, s = tap % R;
+      const int ih = p * stride + r - pad, iw = q * stride + s - pad;
+      if (ih >= 0 && ih < H && iw >= 0 && iw < W) t = x[((size_t)(n * C + c) * H + ih) * W + iw];
+    }
+    v[e] = t;
   }
-  Vec<T>::put(col + i, v);
+  Vec<T>::store(col + i * V, v);
 }
 
 template <typename T>
@@ -47,7 +56,9 @@ int stem_im2col(int dt, const float *x, void *col, int N, int C, int H, int W, i
   const long long total = (long long)N * P * Q * kpad;
   if (total > 0x7fffffffLL * 256) return set_error(RESIST_ESHAPE, "im2col too large");
   prof::Scope ps("stem_im2col", 0, 4.0 * N * C * H * W + (double)esize(dt) * total, st);
-  const dim3 grid((unsigned)((total + 255) / 256));
+  const int V = dt == DT_BF16 ? 8 : 4;
+  if (kpad % 32) return set_error(RESIST_ESHAPE, "im2col row length %d is not a multiple of 32", kpad);
+  const dim3 grid((unsigned)((total / V + 255) / 256));
   if (dt == DT_BF16)
     hipLaunchKernelGGL(stem_im2col_kernel<__bf16>, grid, dim3(256), 0, st, x, (__bf16 *)col, N, C, H, W, R, stride, pad, P, Q, kpad);
   else

@@ -13,8 +13,7 @@ namespace {
 
 constexpr int kChunk = 4096;  // floats per workgroup (256 threads x 4 float4)
 constexpr int kSgdSegs = 48;
-constexpr int kAggSegs = 16;
-constexpr int kAggSrc = 16;
+constexpr int kAggSrc = 16;   // most sub-ResNets that may hold one block
 
 struct SgdTable {
   float *w[kSgdSegs];
@@ -61,16 +60,20 @@ __global__ __launch_bounds__(256) void sgd_kernel(SgdTable t) {
   }
 }
 
-struct AggTable {
-  float *dst[kAggSegs];
-  const float *src[kAggSegs][kAggSrc];
-  long long n[kAggSegs];
-  int count[kAggSegs];
-  int first_wg[kAggSegs + 1];
+// The segment table travels in the kernel arguments (4 KB at most), so the number of segments one
+// launch covers depends on how many sources a segment may have: 56 / 36 / 20 for up to 4 / 8 / 16.
+template <int NSRC> struct AggTable {
+  static constexpr int kSegs = NSRC <= 4 ? 56 : (NSRC <= 8 ? 36 : 20);
+  float *dst[kSegs];
+  const float *src[kSegs][NSRC];
+  long long n[kSegs];
+  int count[kSegs];
+  int first_wg[kSegs + 1];
   int nseg;
 };
 
-__global__ __launch_bounds__(256) void aggregate_kernel(AggTable t) {
+template <int NSRC>
+__global__ __launch_bounds__(256) void aggregate_kernel(AggTable<NSRC> t) {
   int seg = 0;
   while (seg + 1 < t.nseg && (int)blockIdx.x >= t.first_wg[seg + 1]) ++seg;
   const long long base = (long long)(blockIdx.x - t.first_wg[seg]) * kChunk;
@@ -134,15 +137,17 @@ int sgd_momentum_f32(const std::vector<SgdSeg> &segs, float lr, float mu, float 
   return RESIST_OK;
 }
 
-int aggregate_f32(const std::vector<AggSeg> &segs, hipStream_t st) {
+namespace {
+template <int NSRC>
+int aggregate_launch(const std::vector<AggSeg> &segs, hipStream_t st) {
   size_t i = 0;
   while (i < segs.size()) {
-    AggTable t{};
+    AggTable<NSRC> t{};
+    static_assert(sizeof(t) <= 4096, "kernel argument limit");
     int wg = 0;
-    while (i < segs.size() && t.nseg < kAggSegs) {
+    while (i < segs.size() && t.nseg < AggTable<NSRC>::kSegs) {
       const AggSeg &s = segs[i++];
       if (s.n <= 0 || s.count <= 0) continue;
-      if (s.count > kAggSrc) return set_error(RESIST_EUNSUPPORTED, "a block is held by %d sub-ResNets; at most %d supported", s.count, kAggSrc);
       t.dst[t.nseg] = s.dst;
       for (int k = 0; k < s.count; ++k) t.src[t.nseg][k] = s.src[k];
       t.n[t.nseg] = s.n; t.count[t.nseg] = s.count;
@@ -155,10 +160,20 @@ int aggregate_f32(const std::vector<AggSeg> &segs, hipStream_t st) {
     double nb = 0;
     for (int k = 0; k < t.nseg; ++k) nb += 4.0 * t.n[k] * (t.count[k] + 1);
     prof::Scope ps("aggregate", 0, nb, st);
-    hipLaunchKernelGGL(aggregate_kernel, dim3(wg), dim3(256), 0, st, t);
+    hipLaunchKernelGGL(aggregate_kernel<NSRC>, dim3(wg), dim3(256), 0, st, t);
     RESIST_CHECK_LAUNCH("aggregate");
   }
   return RESIST_OK;
+}
+}  // namespace
+
+int aggregate_f32(const std::vector<AggSeg> &segs, hipStream_t st) {
+  int most = 0;
+  for (const AggSeg &s : segs) most = s.count > most ? s.count : most;
+  if (most > kAggSrc) return set_error(RESIST_EUNSUPPORTED, "a block is held by %d sub-ResNets; at most %d supported", most, kAggSrc);
+  if (most <= 4) return aggregate_launch<4>(segs, st);
+  if (most <= 8) return aggregate_launch<8>(segs, st);
+  return aggregate_launch<16>(segs, st);
 }
 
 int fill_zero_f32(float *p, int64_t n, hipStream_t st) {

@@ -20,12 +20,13 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # dense MFMA peaks of MI355X
 PEAK_HBM_GBS = 8000.0
 
 
-def _measured_traffic(kernel):
-    """HBM bytes per launch of `kernel` from committed rocprofv3 --pmc runs, if recorded."""
+def _measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` in `workload` from the committed rocprofv3 --pmc runs
+    (FETCH_SIZE and WRITE_SIZE, scaled by a copy of known size), if recorded."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(kernel)
+            return json.load(f).get(workload, {}).get(kernel)
     except (OSError, ValueError):
         return None
 
@@ -179,12 +180,12 @@ def main():
         roof = dict(bound="mfma", kernel=dom["name"], achieved=round(ach, 2), peak=PEAK_TFLOPS[dtype],
                     unit="TFLOP/s", frac=round(ach / PEAK_TFLOPS[dtype], 4),
                     avg_launch_us=round(dom["ms"] / dom["launches"] * 1e3, 2),
-                    traffic=_measured_traffic(dom["name"]))
+                    traffic=_measured_traffic(args.workload, dom["name"]))
     else:
         ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
         roof = dict(bound="hbm", kernel=dom["name"], achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                     frac=round(ach / PEAK_HBM_GBS, 4), avg_launch_us=round(dom["ms"] / dom["launches"] * 1e3, 2),
-                    traffic=_measured_traffic(dom["name"]))
+                    traffic=_measured_traffic(args.workload, dom["name"]))
     conv_flops = sum(s["flops"] for s in stats)
     conv_ms = sum(s["ms"] for s in stats if s["flops"])
     roof["all_conv_tflops"] = round(conv_flops / (conv_ms * 1e-3) / 1e12, 2) if conv_ms else None

@@ -18,7 +18,7 @@ namespace resist {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMaxParts = 512;  // row-slices per channel tile
+constexpr int kMaxParts = 512;  // most row-slices per channel tile (scratch capacity)
 
 struct ColMap {
   int tpr;       // threads per row (each owns V consecutive channels)

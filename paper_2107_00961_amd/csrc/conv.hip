@@ -604,7 +604,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  // order: tile fastest, then filter tap, then reduction split
+  // order: tile fastest, then filter tap, then reduction split (hardware round-robin over the XCDs:
+  // this MFMA-bound kernel measured faster that way than with one contiguous range per XCD)
   int bid = blockIdx.x;
   const int tile = bid % (a.tiles_k * a.tiles_c);
   bid /= a.tiles_k * a.tiles_c;
@@ -752,7 +753,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_bf16_kernel(WgradArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  int bid = blockIdx.x;
+  // every XCD gets a contiguous range of (tile, tap, split) ids, so the workgroups that read the same
+  // pixels (all tiles and taps of one split) share an L2: this kernel is bound by memory traffic
+  int bid = xcd_contiguous(blockIdx.x, gridDim.x);
   const int tile = bid % (a.tiles_k * a.tiles_c);
   bid /= a.tiles_k * a.tiles_c;
   const int tap = bid % (a.R * a.S), split = bid / (a.R * a.S);

@@ -141,14 +141,33 @@ __global__ __launch_bounds__(64) void fc_fwd_kernel(const float *__restrict__ x,
   if (lane == 0) z[(size_t)n * J + j] = acc + b[j];
 }
 
+// dx[n][c] = sum_j dz[n][j] * w[j][c].  A workgroup owns one sample and 256 channels: 64 threads
+// cover the channels (4 each), the 4 waves take every 4th class and their partial sums are added in
+// wave order.  C is a multiple of 4; channels past C are skipped.
 __global__ __launch_bounds__(256) void fc_bwd_dx_kernel(const float *__restrict__ dz, const float *__restrict__ w,
                                                         float *__restrict__ dx, int N, int C, int J) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= N * C) return;
-  const int c = i % C, n = i / C;
-  float acc = 0.f;
-  for (int j = 0; j < J; ++j) acc = fmaf(dz[(size_t)n * J + j], w[(size_t)j * C + c], acc);
-  dx[i] = acc;
+  __shared__ f32x4 red[4][64];
+  const int n = blockIdx.y, tx = threadIdx.x & 63, jg = threadIdx.x >> 6;
+  const int c = blockIdx.x * 256 + tx * 4;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  if (c < C) {
+    const float *dzr = dz + (size_t)n * J;
+#pragma unroll 4
+    for (int j = jg; j < J; j += 4) {
+      const f32x4 wv = *reinterpret_cast<const f32x4 *>(w + (size_t)j * C + c);
+      const float d = dzr[j];
+      acc[0] = fmaf(d, wv[0], acc[0]); acc[1] = fmaf(d, wv[1], acc[1]);
+      acc[2] = fmaf(d, wv[2], acc[2]); acc[3] = fmaf(d, wv[3], acc[3]);
+    }
+  }
+  red[jg][tx] = acc;
+  __syncthreads();
+  if (jg == 0 && c < C) {
+    acc += red[1][tx];
+    acc += red[2][tx];
+    acc += red[3][tx];
+    *reinterpret_cast<f32x4 *>(dx + (size_t)n * C + c) = acc;
+  }
 }
 
 __global__ __launch_bounds__(256) void fc_bwd_dw_kernel(const float *__restrict__ dz, const float *__restrict__ x,
@@ -256,7 +275,8 @@ int fc_fwd_f32(const float *x, const float *w, const float *b, float *z, int N, 
 }
 int fc_bwd_f32(const float *dz, const float *x, const float *w, float *dx, float *dw, float *db, int N, int C, int J, hipStream_t st) {
   prof::Scope ps("fc_bwd", 0, 0, st);
-  hipLaunchKernelGGL(fc_bwd_dx_kernel, dim3(blocks_for((long long)N * C)), dim3(256), 0, st, dz, w, dx, N, C, J);
+  if (C % 4) return set_error(RESIST_ESHAPE, "fully connected layer: C=%d must be a multiple of 4", C);
+  hipLaunchKernelGGL(fc_bwd_dx_kernel, dim3((C + 255) / 256, N), dim3(256), 0, st, dz, w, dx, N, C, J);
   RESIST_CHECK_LAUNCH("fc_bwd_dx");
   hipLaunchKernelGGL(fc_bwd_dw_kernel, dim3(blocks_for((long long)J * C)), dim3(256), 0, st, dz, x, dw, N, C, J);
   RESIST_CHECK_LAUNCH("fc_bwd_dw");

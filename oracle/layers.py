@@ -67,6 +67,72 @@ def conv2d_wgrad(dy, x, w_shape, stride, pad):
     return dw
 
 
+# ---- single outputs of a convolution, straight from the definition ------------------------
+# For tensors too large to run the whole oracle on: one output element at a time, float64, on
+# channels-last arrays (x [N,H,W,C], w [K,R,S,C], y / dy [N,P,Q,K]) so that a test can hand over the
+# tensors as the library lays them out.  Pinned against the full-tensor functions above.
+
+def conv2d_fwd_points(x, w, stride, pad, points):
+    """y[n,p,q,k] = sum_{r,s,c} x[n, p*stride+r-pad, q*stride+s-pad, c] * w[k,r,s,c] for each (n,p,q,k)."""
+    N, H, W, C = x.shape
+    K, R, S, _ = w.shape
+    out = []
+    for n, p, q, k in points:
+        acc = 0.0
+        for r in range(R):
+            ih = p * stride + r - pad
+            if ih < 0 or ih >= H:
+                continue
+            for s in range(S):
+                iw = q * stride + s - pad
+                if iw < 0 or iw >= W:
+                    continue
+                acc += float(np.dot(x[n, ih, iw, :].astype(np.float64), w[k, r, s, :].astype(np.float64)))
+        out.append(acc)
+    return np.array(out)
+
+
+def conv2d_dgrad_points(dy, w, stride, pad, points):
+    """dx[n,h,w_,c] = sum over (k,r,s) and the (p,q) with h = p*stride+r-pad, w_ = q*stride+s-pad of
+    dy[n,p,q,k] * w[k,r,s,c], for each (n,h,w_,c)."""
+    N, P, Q, K = dy.shape
+    _, R, S, _ = w.shape
+    out = []
+    for n, h, ww, c in points:
+        acc = 0.0
+        for r in range(R):
+            t = h + pad - r
+            if t % stride or t < 0 or t // stride >= P:
+                continue
+            for s in range(S):
+                u = ww + pad - s
+                if u % stride or u < 0 or u // stride >= Q:
+                    continue
+                acc += float(np.dot(dy[n, t // stride, u // stride, :].astype(np.float64),
+                                    w[:, r, s, c].astype(np.float64)))
+        out.append(acc)
+    return np.array(out)
+
+
+def conv2d_wgrad_points(dy, x, stride, pad, R, S, points):
+    """dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n, p*stride+r-pad, q*stride+s-pad, c] for each (k,r,s,c)."""
+    N, P, Q, K = dy.shape
+    _, H, W, C = x.shape
+    out = []
+    for k, r, s, c in points:
+        ps = [p for p in range(P) if 0 <= p * stride + r - pad < H]
+        qs = [q for q in range(Q) if 0 <= q * stride + s - pad < W]
+        if not ps or not qs:
+            out.append(0.0)
+            continue
+        ih = np.array(ps) * stride + r - pad
+        iw = np.array(qs) * stride + s - pad
+        a = dy[:, ps[0]:ps[-1] + 1, qs[0]:qs[-1] + 1, k].astype(np.float64)
+        b = x[:, ih[0]:ih[-1] + 1:stride, iw[0]:iw[-1] + 1:stride, c].astype(np.float64)
+        out.append(float((a * b).sum()))
+    return np.array(out)
+
+
 # ---- batch normalisation, training mode -------------------------------------------------
 
 def bn_fwd(x, gamma, beta, eps):

@@ -1,0 +1,82 @@
+"""GPU parity at the benchmark's full sizes: every distinct convolution shape of the CIFAR-shaped
+(fp32) and ImageNet-shaped (bf16) sub-ResNets at the benchmark batch size, in the launch
+configuration bench.py times, on sampled outputs that the oracle computes one by one from the
+definition (the full-tensor oracle would take minutes per layer at these sizes)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2107_00961_amd as R
+from oracle import layers as L
+from resist_inputs import get_config, model_blocks
+
+pytestmark = pytest.mark.gpu
+
+NPTS = 48
+
+
+def _shapes(cfg_name):
+    """Distinct (H, C, K, R, stride, pad) of the block convolutions of the configuration's network."""
+    cfg = get_config(cfg_name)
+    m = cfg["model"]
+    h = m["in_h"] if m["stem_kind"] == 0 else m["in_h"] // 4
+    out = []
+    for blk in model_blocks(m):
+        s = blk["stride"]
+        if m["block_kind"] == 0:
+            convs = [(h, blk["c_in"], blk["width"], 3, s, 1), (h // s, blk["width"], blk["c_out"], 3, 1, 1)]
+        else:
+            convs = [(h, blk["c_in"], blk["width"], 1, 1, 0), (h, blk["width"], blk["width"], 3, s, 1),
+                     (h // s, blk["width"], blk["c_out"], 1, 1, 0)]
+        if blk["has_ds"]:
+            convs.append((h, blk["c_in"], blk["c_out"], 1, s, 0))
+        for c in convs:
+            if c not in out:
+                out.append(c)
+        h //= s
+    return cfg["batch"], out
+
+
+def _cases():
+    cases = []
+    for name, dt in (("cfg2", torch.float32), ("cfg4", torch.bfloat16)):
+        batch, shapes = _shapes(name)
+        cases += [pytest.param(name, dt, batch, s, id=f"{name}-H{s[0]}-C{s[1]}-K{s[2]}-R{s[3]}-s{s[4]}") for s in shapes]
+    return cases
+
+
+@pytest.mark.parametrize("name,dt,N,shape", _cases())
+def test_full_size_conv_sampled(name, dt, N, shape):
+    H, C, K, RS, st, pad = shape
+    print(f"{name} N={N} shape={shape} dtype={dt}", flush=True)
+    P = (H + 2 * pad - RS) // st + 1
+    g = torch.Generator(device="cuda").manual_seed(1234)
+    x = torch.randn((N, H, H, C), generator=g, device="cuda").to(dt)
+    w = (torch.randn((K, RS, RS, C), generator=g, device="cuda") / float(np.sqrt(C * RS * RS))).to(dt)
+    dy = torch.randn((N, P, P, K), generator=g, device="cuda").to(dt)
+    dyw = (dy.float() / float(np.sqrt(N * P * P))).to(dt)          # keeps weight-gradient sums O(1)
+    y = R.conv2d_forward(x, w, st, pad)
+    dx = R.conv2d_dgrad(dy, w, (N, H, H, C), st, pad)
+    dw = R.conv2d_wgrad(dyw, x, (K, RS, RS, C), st, pad)
+    torch.cuda.synchronize()
+    xh, wh, dyh, dywh = (t.float().cpu().numpy() for t in (x, w, dy, dyw))
+    yh, dxh, dwh = y.float().cpu().numpy(), dx.float().cpu().numpy(), dw.cpu().numpy()
+    rng = np.random.default_rng(5)
+    # bf16 outputs carry half a bfloat16 ulp on top of the fp32 accumulation error
+    rtol, atol = (2.0 ** -8, 1e-5) if dt == torch.bfloat16 else (1e-4, 1e-5)
+
+    def check(got, want, what):
+        err = np.abs(got - want)
+        tol = atol + rtol * np.abs(want)
+        assert np.all(err <= tol), f"{what} {name} {shape}: worst {np.max(err / tol):.2f} x tolerance"
+
+    pts = [(rng.integers(N), rng.integers(P), rng.integers(P), rng.integers(K)) for _ in range(NPTS)]
+    pts += [(0, 0, 0, 0), (N - 1, P - 1, P - 1, K - 1), (N - 1, 0, P - 1, K // 2)]
+    check(np.array([yh[p] for p in pts]), L.conv2d_fwd_points(xh, wh, st, pad, pts), "fwd")
+    pts = [(rng.integers(N), rng.integers(H), rng.integers(H), rng.integers(C)) for _ in range(NPTS)]
+    pts += [(0, 0, 0, 0), (N - 1, H - 1, H - 1, C - 1), (N // 2, H - 1, 0, C // 2)]
+    check(np.array([dxh[p] for p in pts]), L.conv2d_dgrad_points(dyh, wh, st, pad, pts), "dgrad")
+    pts = [(rng.integers(K), rng.integers(RS), rng.integers(RS), rng.integers(C)) for _ in range(NPTS // 2)]
+    pts += [(0, 0, 0, 0), (K - 1, RS - 1, RS - 1, C - 1)]
+    rtol, atol = 1e-4, 1e-5                                           # weight gradients are fp32 in both modes
+    check(np.array([dwh[p] for p in pts]), L.conv2d_wgrad_points(dywh, xh, st, pad, RS, RS, pts), "wgrad")

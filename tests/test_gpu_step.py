@@ -283,6 +283,17 @@ def test_cfg4_shape_reduced_bf16():
                      what="cfg4 reduced", perturb_bn=False)
 
 
+def test_cfg4_full_depth_small_batch_bf16():
+    """The ImageNet-shaped configuration itself -- 224x224 images, 1000 classes, its own partition
+    (seed 2, S=2, sub-ResNet 0: ten bottleneck blocks), bf16 storage -- at batch 4 instead of 64 so
+    that the oracle finishes in seconds."""
+    cfg = get_config("cfg4")
+    model = cfg["model"]
+    subs, _ = R.partition(model, cfg["S"], cfg["min_depth"], cfg["part_seed"], 0)
+    _bf16_step_check(model, subs[0], 4, cfg["lr"], cfg["momentum"], cfg["weight_decay"], seed=0,
+                     what="cfg4 batch 4", perturb_bn=False)
+
+
 def test_cfg2_full_size_step():
     """The benchmark configuration itself: CIFAR-shaped sub-ResNet 0 of S=4, batch 128."""
     _full_size_check("cfg2", "cfg2")

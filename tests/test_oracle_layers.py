@@ -174,3 +174,24 @@ def test_ce_closed_forms(classes):
     # shift invariance and large logits (stable log-sum-exp)
     loss2, _ = L.softmax_ce(z + 1000.0, labels)
     assert math.isclose(loss, loss2, rel_tol=1e-10)
+
+
+def test_single_output_functions_match_full_convolutions():
+    """The one-output-at-a-time functions (used on full-size tensors) against the full-tensor oracle."""
+    rng = np.random.default_rng(7)
+    for (N, H, W, C, K, RS, st, pad) in [(2, 7, 6, 5, 4, 3, 1, 1), (2, 8, 8, 3, 6, 3, 2, 1), (3, 6, 6, 4, 5, 1, 2, 0),
+                                         (1, 9, 9, 2, 3, 7, 2, 3)]:
+        x = rng.standard_normal((N, C, H, W))
+        w = rng.standard_normal((K, C, RS, RS))
+        y = L.conv2d_fwd(x, w, st, pad)
+        dy = rng.standard_normal(y.shape)
+        dx = L.conv2d_dgrad(dy, w, x.shape, st, pad)
+        dw = L.conv2d_wgrad(dy, x, w.shape, st, pad)
+        xl, wl, dyl = x.transpose(0, 2, 3, 1), w.transpose(0, 2, 3, 1), dy.transpose(0, 2, 3, 1)
+        P, Q = y.shape[2], y.shape[3]
+        pts = [(rng.integers(N), rng.integers(P), rng.integers(Q), rng.integers(K)) for _ in range(20)] + [(0, 0, 0, 0), (N - 1, P - 1, Q - 1, K - 1)]
+        np.testing.assert_allclose(L.conv2d_fwd_points(xl, wl, st, pad, pts), [y[n, k, p, q] for n, p, q, k in pts], rtol=1e-12, atol=1e-12)
+        pts = [(rng.integers(N), rng.integers(H), rng.integers(W), rng.integers(C)) for _ in range(20)] + [(0, 0, 0, 0), (N - 1, H - 1, W - 1, C - 1)]
+        np.testing.assert_allclose(L.conv2d_dgrad_points(dyl, wl, st, pad, pts), [dx[n, c, h, v] for n, h, v, c in pts], rtol=1e-12, atol=1e-12)
+        pts = [(rng.integers(K), rng.integers(RS), rng.integers(RS), rng.integers(C)) for _ in range(20)] + [(0, 0, 0, 0), (K - 1, RS - 1, RS - 1, C - 1)]
+        np.testing.assert_allclose(L.conv2d_wgrad_points(dyl, xl, st, pad, RS, RS, pts), [dw[k, c, r, s] for k, r, s, c in pts], rtol=1e-12, atol=1e-12)

@@ -20,6 +20,21 @@ class DeviceModel:
         self.params = [torch.from_numpy(B.pack_block(model, k, logical_params[k])).to(device)
                        for k in self.keys]
 
+    @classmethod
+    def from_device(cls, model, blocks, source, **kw):
+        """The blocks `blocks` of another DeviceModel (device-to-device copies of its buffers)."""
+        self = cls.__new__(cls)
+        self._init_from_tensors(model, blocks, {k: p.clone() for k, p in zip(source.keys, source.params)}, **kw)
+        return self
+
+    def _init_from_tensors(self, model, blocks, by_key):
+        self.model = model
+        self.blocks = list(blocks)
+        self.nb = B.num_blocks(model)
+        self.keys = [-1] + self.blocks + [self.nb]
+        self.params = [by_key[k] for k in self.keys]
+        self.device = self.params[0].device
+
     def download(self):
         """-> {key: {name: logical array}} of the current parameter buffers."""
         return {k: B.unpack_block(self.model, k, p.cpu().numpy()) for k, p in zip(self.keys, self.params)}
@@ -30,6 +45,14 @@ class SubResNet(DeviceModel):
 
     def __init__(self, model, blocks, logical_params, batch, device="cuda", keep_grads=True):
         super().__init__(model, blocks, logical_params, device)
+        self._alloc(batch, keep_grads)
+
+    def _init_from_tensors(self, model, blocks, by_key, batch=None, keep_grads=False):
+        super()._init_from_tensors(model, blocks, by_key)
+        self._alloc(batch, keep_grads)
+
+    def _alloc(self, batch, keep_grads):
+        model, device = self.model, self.device
         self.batch = batch
         sizes = [B.block_param_count(model, k)[1] for k in self.keys]
         self.momentum = [torch.zeros(n, dtype=torch.float32, device=device) for n in sizes]
@@ -59,3 +82,31 @@ class SubResNet(DeviceModel):
 def to_device_batch(x, labels, device="cuda"):
     return (torch.from_numpy(np.ascontiguousarray(x, np.float32)).to(device),
             torch.from_numpy(np.ascontiguousarray(labels, np.int32)).to(device))
+
+
+def run_round(model, glob, S, min_depth, seed, rnd, local_iters, batch_fn, batch, lr, mu, wd,
+              partitionable=None, stream=None):
+    """One synchronisation round of Algorithm 1 on one GPU: split the global model (a DeviceModel
+    holding every block) into S sub-ResNets for round `rnd`, run `local_iters` local steps of each, one
+    sub-ResNet after the other, from the current global parameters and with fresh (zero) momentum,
+    then reassemble the global model in place.  batch_fn(rnd, s, it) -> device (x, labels).
+    Returns the partition and the workers (their loss buffers hold the last local loss)."""
+    subs, owner = B.partition(model, S, min_depth, seed, rnd, partitionable)
+    workers = []
+    for s in range(S):
+        w = SubResNet.from_device(model, subs[s], _Select(glob, subs[s]), batch=batch, keep_grads=False)
+        for it in range(local_iters):
+            x, y = batch_fn(rnd, s, it)
+            w.step(x, y, lr, mu, wd, stream)
+        workers.append(w)
+    B.aggregate(model, subs, [w.params for w in workers], glob.params, stream)
+    return subs, owner, workers
+
+
+class _Select:
+    """View of a DeviceModel restricted to stem, the given blocks and head."""
+
+    def __init__(self, glob, blocks):
+        idx = {k: i for i, k in enumerate(glob.keys)}
+        self.keys = [-1] + list(blocks) + [glob.nb]
+        self.params = [glob.params[idx[k]] for k in self.keys]

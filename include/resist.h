@@ -138,6 +138,28 @@ int resist_local_step(const resist_model_desc *desc, const int32_t *blocks, int3
                       int64_t workspace_bytes, float *loss_out, void *hip_stream);
 
 /*
+ * Test-time forward pass (Sec. 2.6, "Scaling Activations"): logits of a batch through the stem, the
+ * listed blocks and the head, with BN normalising by the running statistics stored in the block
+ * buffers and the residual branch of blocks[i] multiplied by branch_scale[i] before the shortcut is
+ * added:  out = ReLU(shortcut + branch_scale[i] * BN(last convolution of the branch)).  The paper
+ * scales the partitioned blocks by 1/S when the reassembled global model uses all of them at once;
+ * blocks every sub-ResNet trained get 1.  Nothing is written to the parameter buffers.
+ *   blocks         host [nblocks] ascending, must contain the first block of every stage
+ *   block_params   host array [nblocks+2] of device fp32 buffers: stem, blocks..., head
+ *   branch_scale   host [nblocks] floats, or NULL = all 1
+ *   x              device [batch,in_c,in_h,in_w] fp32
+ *   workspace      device, at least resist_forward_workspace_bytes()
+ *   logits_out     device [batch][num_classes] fp32
+ *   labels, loss_out  both NULL, or device [batch] int32 and device 1 float (mean cross-entropy)
+ */
+int resist_forward_workspace_bytes(const resist_model_desc *desc, const int32_t *blocks,
+                                   int32_t nblocks, int32_t batch, int64_t *bytes);
+int resist_forward(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks,
+                   void *const *block_params, const float *branch_scale, const float *x,
+                   int32_t batch, void *workspace, int64_t workspace_bytes, float *logits_out,
+                   const int32_t *labels, float *loss_out, void *hip_stream);
+
+/*
  * Reassembly (Sec. 2.3; Appendix B: W = sum_v W_v M_v / sum_v M_v, last layer a = sum_v a_v / S):
  * every float of every block buffer of the global model (running statistics included) becomes the
  * mean over the sub-ResNets that hold the block -- fp32 sum in ascending sub-ResNet order, then one

@@ -224,3 +224,49 @@ def local_step(model, blocks, params, momentum_buf, x, labels, lr, mu, wd, emula
                                      mean, var, m, mom)
         new_p[b][bn + "_rm"], new_p[b][bn + "_rv"] = rm, rv
     return loss, grads, new_p, new_v
+
+
+def forward_eval(model, blocks, params, x, branch_scale=None, labels=None):
+    """Test-time forward pass (Sec. 2.6, "Scaling Activations"): BN normalises with the running
+    statistics stored with each block, and the residual branch of block blocks[i] is multiplied by
+    branch_scale[i] before the shortcut is added -- the paper scales the output of the partitioned
+    blocks by 1/S when all of them are used together; blocks that every sub-ResNet trained get 1.
+        out = ReLU(shortcut + branch_scale * BN(last conv of the branch))
+    Returns the logits [N, classes] (and the mean cross-entropy if labels are given).  float64, no
+    rounding anywhere."""
+    tab = block_table(model)
+    B = len(tab)
+    eps = model["bn_eps"]
+    if branch_scale is None:
+        branch_scale = [1.0] * len(blocks)
+
+    def cbn(a, p, conv, bn, stride, pad, relu, scale=1.0):
+        y = L.conv2d_fwd(a, p[conv + "_w"], stride, pad)
+        g, b = p[bn + "_g"].astype(np.float64), p[bn + "_b"].astype(np.float64)
+        rm, rv = p[bn + "_rm"].astype(np.float64), p[bn + "_rv"].astype(np.float64)
+        z = (y - rm[None, :, None, None]) / np.sqrt(rv + eps)[None, :, None, None] * g[None, :, None, None] \
+            + b[None, :, None, None]
+        z = scale * z
+        return np.maximum(z, 0.0) if relu else z
+
+    a = np.asarray(x, np.float64)
+    if model["stem_kind"] == 0:
+        a = cbn(a, params[-1], "conv", "bn", 1, 1, True)
+    else:
+        a, _ = L.maxpool_fwd(cbn(a, params[-1], "conv", "bn", 2, 3, True), 3, 2, 1)
+    for b, sc in zip(blocks, branch_scale):
+        t, p = tab[b], params[b]
+        if model["block_kind"] == 0:
+            h = cbn(a, p, "conv1", "bn1", t["stride"], 1, True)
+            h = cbn(h, p, "conv2", "bn2", 1, 1, False, sc)
+        else:
+            h = cbn(a, p, "conv1", "bn1", 1, 0, True)
+            h = cbn(h, p, "conv2", "bn2", t["stride"], 1, True)
+            h = cbn(h, p, "conv3", "bn3", 1, 0, False, sc)
+        short = cbn(a, p, "ds", "dsbn", t["stride"], 0, False) if t["has_ds"] else a
+        a = np.maximum(h + short, 0.0)
+    z = L.fc_fwd(L.avgpool_fwd(a), params[B]["fc_w"].astype(np.float64), params[B]["fc_b"].astype(np.float64))
+    if labels is None:
+        return z
+    loss, _ = L.softmax_ce(z, np.asarray(labels))
+    return z, loss

@@ -6,11 +6,11 @@ buffer layout.  There is no CPU fallback: importing works without a GPU (host-on
 as `partition` run anywhere), device calls need the built library and a gfx950 device.
 """
 from .binding import (ResistError, aggregate, block_layout, block_param_count, conv2d_dgrad,
-                      conv2d_forward, conv2d_wgrad, lib, local_step, model_desc, num_blocks,
+                      conv2d_forward, conv2d_wgrad, forward, forward_workspace_bytes, lib, local_step, model_desc, num_blocks,
                       pack_block, partition, profile_enable, profile_read, unpack_block,
                       workspace_bytes)
 
 __all__ = ["ResistError", "aggregate", "block_layout", "block_param_count", "conv2d_dgrad",
-           "conv2d_forward", "conv2d_wgrad", "lib", "local_step", "model_desc", "num_blocks",
+           "conv2d_forward", "conv2d_wgrad", "forward", "forward_workspace_bytes", "lib", "local_step", "model_desc", "num_blocks",
            "pack_block", "partition", "profile_enable", "profile_read", "unpack_block",
            "workspace_bytes"]

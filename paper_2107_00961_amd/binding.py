@@ -45,7 +45,8 @@ def lib():
         L.resist_last_error.restype = C.c_char_p
         for name in ("resist_num_blocks", "resist_partition", "resist_block_param_count",
                      "resist_block_layout", "resist_workspace_bytes", "resist_local_step",
-                     "resist_aggregate", "resist_conv2d_workspace_bytes", "resist_conv2d_forward",
+                     "resist_aggregate", "resist_forward", "resist_forward_workspace_bytes",
+                     "resist_conv2d_workspace_bytes", "resist_conv2d_forward",
                      "resist_conv2d_dgrad", "resist_conv2d_wgrad", "resist_profile_enable",
                      "resist_profile_read"):
             getattr(L, name).restype = C.c_int
@@ -56,6 +57,10 @@ def lib():
         L.resist_aggregate.argtypes = [
             C.POINTER(_ModelDesc), C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
             C.POINTER(C.POINTER(C.c_void_p)), C.POINTER(C.c_void_p), C.c_void_p]
+        L.resist_forward.argtypes = [
+            C.POINTER(_ModelDesc), C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_void_p),
+            C.POINTER(C.c_float), C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+            C.c_void_p, C.c_void_p]
         L.resist_partition.argtypes = [
             C.POINTER(_ModelDesc), C.POINTER(C.c_uint8), C.c_int32, C.c_int32, C.c_uint64,
             C.c_uint64, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32)]
@@ -204,6 +209,26 @@ def local_step(model, blocks, params, momentum, grads, x, labels, lr, mu, wd, wo
         _ptr_array(grads) if grads is not None else None, x.data_ptr(), labels.data_ptr(),
         x.shape[0], lr, mu, wd, workspace.data_ptr(), workspace.numel() * workspace.element_size(),
         loss_out.data_ptr(), _stream_ptr(stream)))
+
+
+def forward_workspace_bytes(model, blocks, batch):
+    n = C.c_int64()
+    arr = (C.c_int32 * len(blocks))(*blocks)
+    _check(lib().resist_forward_workspace_bytes(C.byref(model_desc(model)), arr, len(blocks), batch, C.byref(n)))
+    return n.value
+
+
+def forward(model, blocks, params, x, logits_out, workspace, branch_scale=None, labels=None, loss_out=None,
+            stream=None):
+    """Test-time forward pass: params = device float32 tensors [stem, blocks..., head]; x [N,C,H,W]
+    float32; logits_out [N, classes] float32 (written); branch_scale: one float per block or None."""
+    arr = (C.c_int32 * len(blocks))(*blocks)
+    sc = (C.c_float * len(blocks))(*branch_scale) if branch_scale is not None else None
+    _check(lib().resist_forward(
+        C.byref(model_desc(model)), arr, len(blocks), _ptr_array(params), sc, x.data_ptr(), x.shape[0],
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), logits_out.data_ptr(),
+        labels.data_ptr() if labels is not None else None,
+        loss_out.data_ptr() if loss_out is not None else None, _stream_ptr(stream)))
 
 
 def aggregate(model, subs, sub_params, global_params, stream=None):

@@ -132,6 +132,19 @@ __global__ __launch_bounds__(kThreads) void bn_finalize_kernel(const S *__restri
   }
 }
 
+// evaluation mode: the affine map from the running statistics, times a scalar `s` (the test-time
+// scaling of a residual branch): scale = s*gamma/sqrt(rvar+eps), shift = s*(beta - rmean*gamma/sqrt(rvar+eps))
+__global__ __launch_bounds__(kThreads) void bn_eval_affine_kernel(const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                                  const float *__restrict__ rmean, const float *__restrict__ rvar,
+                                                                  float eps, float s, float *__restrict__ scale,
+                                                                  float *__restrict__ shift, int C) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  const double k = (double)gamma[c] / sqrt((double)rvar[c] + (double)eps);
+  scale[c] = (float)((double)s * k);
+  shift[c] = (float)((double)s * ((double)beta[c] - (double)rmean[c] * k));
+}
+
 // ---- forward apply -------------------------------------------------------------------------------
 struct ApplyArgs {
   const void *y; const float *scale; const float *shift;
@@ -393,6 +406,15 @@ int bn_finalize(const float *stats, int parts, int64_t M, int C, const BnBufs &b
                        momentum, b.gamma, b.beta, b.mean, b.invstd, b.scale, b.shift, b.rmean, b.rvar);
   }
   RESIST_CHECK_LAUNCH("bn_finalize");
+  return RESIST_OK;
+}
+
+int bn_eval_affine(int C, const BnBufs &b, float eps, float s, hipStream_t st) {
+  if (C < 1) return set_error(RESIST_ESHAPE, "bn_eval_affine: C=%d", C);
+  prof::Scope ps("bn_eval_affine", 0, 24.0 * C, st);
+  hipLaunchKernelGGL(bn_eval_affine_kernel, dim3((C + kThreads - 1) / kThreads), dim3(kThreads), 0, st, b.gamma, b.beta, b.rmean,
+                     b.rvar, eps, s, b.scale, b.shift, C);
+  RESIST_CHECK_LAUNCH("bn_eval_affine");
   return RESIST_OK;
 }
 

@@ -139,6 +139,8 @@ int64_t bn_scratch_doubles(int C);   // partial-sum scratch for one bn_finalize 
 // affine map of bn_apply, and the running statistics
 int bn_finalize(const float *stats, int parts, int64_t M, int C, const BnBufs &b, float eps, float momentum,
                 double *scratch, hipStream_t st);
+// evaluation mode: scale/shift from the running statistics, both multiplied by s
+int bn_eval_affine(int C, const BnBufs &b, float eps, float s, hipStream_t st);
 // a = [relu]( scale*y + shift [+ res] )            res: raw tensor, or BN(res_y) if res_bn given
 int bn_apply(int dt, const void *y, int64_t M, int C, const BnBufs &b, const void *res,
              const BnBufs *res_bn, bool relu, void *a, hipStream_t st);

@@ -83,10 +83,7 @@ ConvLayer make_conv(const BlockLayout &L, int layer, int N, int H, int W, int C,
   return c;
 }
 
-int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks, int32_t batch, void *ws,
-               StepPlan *P) {
-  RESIST_TRY(build_net(desc, &P->net));
-  const Net &net = P->net;
+int check_block_list(const Net &net, const int32_t *blocks, int32_t nblocks, int32_t batch) {
   const int B = (int)net.blocks.size();
   if (batch < 1) return set_error(RESIST_EINVAL, "batch=%d", batch);
   if (nblocks < 0 || (nblocks > 0 && !blocks)) return set_error(RESIST_EINVAL, "blocks/nblocks");
@@ -97,6 +94,15 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
   for (int f : net.stage_first)
     if (!std::binary_search(blocks, blocks + nblocks, f))
       return set_error(RESIST_ESHAPE, "first block %d of a stage is missing: the residual stream would change shape", f);
+  return RESIST_OK;
+}
+
+int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks, int32_t batch, void *ws,
+               StepPlan *P) {
+  RESIST_TRY(build_net(desc, &P->net));
+  const Net &net = P->net;
+  RESIST_TRY(check_block_list(net, blocks, nblocks, batch));
+  const int B = (int)net.blocks.size();
   P->batch = batch;
   const int N = batch;
   const int es = esize(net.d.compute_dtype);
@@ -223,6 +229,125 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
   for (int i = 0; i < nblocks + 2; ++i) P->own_grads[i] = A.take<float>(P->layouts[i].n_trainable);
   P->bytes = (A.off + 255) & ~(int64_t)255;
   return RESIST_OK;
+}
+
+// ---- test-time forward: nothing is kept, so every convolution output goes to one shared buffer and
+// the activations alternate between two
+struct ForwardPlan {
+  Net net;
+  std::vector<BlockLayout> layouts;
+  int kpad = 0;
+  ConvLayer stem;
+  void *col = nullptr, *wpad = nullptr, *stem_pool = nullptr;
+  uint8_t *stem_argmax = nullptr;
+  std::vector<BlockPlan> blocks;
+  float *affine[2] = {nullptr, nullptr};   // scale/shift scratch of the branch BN and the shortcut BN: [2][max_c] each
+  float *pooled = nullptr, *dz = nullptr, *row_loss = nullptr;
+  const void *feat = nullptr;
+  int feat_hw = 0;
+  int64_t bytes = 0;
+};
+
+int build_forward_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks, int32_t batch, void *ws,
+                       ForwardPlan *P) {
+  RESIST_TRY(build_net(desc, &P->net));
+  const Net &net = P->net;
+  RESIST_TRY(check_block_list(net, blocks, nblocks, batch));
+  const int B = (int)net.blocks.size();
+  const int N = batch, es = esize(net.d.compute_dtype);
+  Arena A(ws);
+  P->layouts.resize(nblocks + 2);
+  RESIST_TRY(block_layout(net, -1, &P->layouts[0]));
+  for (int i = 0; i < nblocks; ++i) RESIST_TRY(block_layout(net, blocks[i], &P->layouts[i + 1]));
+  RESIST_TRY(block_layout(net, B, &P->layouts[nblocks + 1]));
+
+  // geometry first (to size the shared buffers), pointers afterwards
+  const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
+  P->kpad = (taps + 31) / 32 * 32;
+  const int K0 = net.d.width[0];
+  P->stem = make_conv(P->layouts[0], 0, N, net.stem_h, net.stem_w, P->kpad, K0, 1, 1, 0);
+  int64_t max_act = P->stem.M() * K0;
+  int max_c = K0;
+  P->blocks.resize(nblocks);
+  for (int i = 0; i < nblocks; ++i) {
+    const BlockShape &bs = net.blocks[blocks[i]];
+    const BlockLayout &L = P->layouts[i + 1];
+    BlockPlan &bp = P->blocks[i];
+    bp.slot = i + 1;
+    if (net.d.block_kind == 0) {
+      bp.convs.push_back(make_conv(L, 0, N, bs.h_in, bs.w_in, bs.c_in, bs.width, 3, bs.stride, 1));
+      bp.convs.push_back(make_conv(L, 1, N, bs.h_out, bs.w_out, bs.width, bs.c_out, 3, 1, 1));
+    } else {
+      bp.convs.push_back(make_conv(L, 0, N, bs.h_in, bs.w_in, bs.c_in, bs.width, 1, 1, 0));
+      bp.convs.push_back(make_conv(L, 1, N, bs.h_in, bs.w_in, bs.width, bs.width, 3, bs.stride, 1));
+      bp.convs.push_back(make_conv(L, 2, N, bs.h_out, bs.w_out, bs.width, bs.c_out, 1, 1, 0));
+    }
+    bp.has_ds = bs.has_ds;
+    if (bs.has_ds) bp.ds = make_conv(L, 3, N, bs.h_in, bs.w_in, bs.c_in, bs.c_out, 1, bs.stride, 0);
+    for (const ConvLayer &c : bp.convs) {
+      max_act = std::max<int64_t>(max_act, c.M() * c.g.K);
+      max_c = std::max(max_c, c.g.K);
+    }
+    bp.out_elems = (int64_t)N * bs.h_out * bs.w_out * bs.c_out;
+  }
+  P->col = A.take_act(P->stem.M() * P->kpad, es);
+  P->wpad = A.take_act((int64_t)K0 * P->kpad, es);
+  void *ybuf = A.take_act(max_act, es), *ydsbuf = A.take_act(max_act, es);
+  void *abuf[2] = {A.take_act(max_act, es), A.take_act(max_act, es)};
+  void *obuf[2] = {A.take_act(max_act, es), A.take_act(max_act, es)};
+  P->stem.in = P->col;
+  P->stem.y = ybuf;
+  P->stem.a = obuf[0];
+  const void *cur = obuf[0];
+  int oi = 1;
+  if (net.d.stem_kind == 1) {
+    const int64_t n = (int64_t)N * net.body_h * net.body_w * K0;
+    P->stem_pool = obuf[1];
+    P->stem_argmax = A.take<uint8_t>(n);
+    cur = obuf[1];
+    oi = 0;
+  }
+  for (BlockPlan &bp : P->blocks) {
+    bp.in = cur;
+    const void *x = cur;
+    for (size_t j = 0; j < bp.convs.size(); ++j) {
+      ConvLayer &c = bp.convs[j];
+      c.in = x;
+      c.y = ybuf;
+      if (net.d.compute_dtype == DT_BF16) c.wlp = A.take_act((int64_t)c.g.K * c.g.R * c.g.S * c.g.C, es);
+      if (j + 1 < bp.convs.size()) { c.a = abuf[j & 1]; x = c.a; }
+    }
+    if (bp.has_ds) {
+      bp.ds.in = bp.in;
+      bp.ds.y = ydsbuf;
+      if (net.d.compute_dtype == DT_BF16) bp.ds.wlp = A.take_act((int64_t)bp.ds.g.K * bp.ds.g.C, es);
+    }
+    bp.out = obuf[oi];
+    cur = bp.out;
+    oi ^= 1;
+  }
+  P->feat = cur;
+  const BlockShape &last = net.blocks[blocks[nblocks - 1]];
+  P->feat_hw = last.h_out * last.w_out;
+  P->affine[0] = A.take<float>((int64_t)2 * max_c);
+  P->affine[1] = A.take<float>((int64_t)2 * max_c);
+  P->pooled = A.take<float>((int64_t)N * net.head_c);
+  P->dz = A.take<float>((int64_t)N * net.d.num_classes);
+  P->row_loss = A.take<float>(N);
+  P->bytes = (A.off + 255) & ~(int64_t)255;
+  return RESIST_OK;
+}
+
+// running statistics and affine parameters of a BN inside a block buffer, scale/shift in `affine`
+BnBufs bn_eval_bufs(const ConvLayer &c, float *params, float *affine) {
+  BnBufs b{};
+  b.gamma = params + c.gamma_off;
+  b.beta = params + c.beta_off;
+  b.rmean = params + c.rmean_off;
+  b.rvar = params + c.rvar_off;
+  b.scale = affine;
+  b.shift = affine + c.g.K;
+  return b;
 }
 
 BnBufs bn_bufs(const ConvLayer &c, float *params, float *grads) {
@@ -400,6 +525,92 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
   for (int i = 0; i < nslots; ++i)
     segs.push_back(SgdSeg{params(i), (float *)block_momentum[i], grads(i), P.layouts[i].n_trainable});
   RESIST_TRY(sgd_momentum_f32(segs, lr, momentum, weight_decay, st));
+  return RESIST_OK;
+}
+
+extern "C" int resist_forward_workspace_bytes(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks,
+                                              int32_t batch, int64_t *bytes) {
+  if (!bytes) return set_error(RESIST_EINVAL, "bytes is NULL");
+  ForwardPlan P;
+  RESIST_TRY(build_forward_plan(desc, blocks, nblocks, batch, nullptr, &P));
+  *bytes = P.bytes;
+  return RESIST_OK;
+}
+
+extern "C" int resist_forward(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks,
+                              void *const *block_params, const float *branch_scale, const float *x, int32_t batch,
+                              void *workspace, int64_t workspace_bytes, float *logits_out, const int32_t *labels,
+                              float *loss_out, void *hip_stream) {
+  if (!block_params || !x || !workspace || !logits_out) return set_error(RESIST_EINVAL, "NULL argument");
+  if ((labels == nullptr) != (loss_out == nullptr)) return set_error(RESIST_EINVAL, "labels and loss_out go together");
+  if (((uintptr_t)workspace & 15) || ((uintptr_t)x & 15) || ((uintptr_t)logits_out & 15))
+    return set_error(RESIST_EINVAL, "workspace, x and logits_out must be 16-byte aligned");
+  ForwardPlan P;
+  RESIST_TRY(build_forward_plan(desc, blocks, nblocks, batch, workspace, &P));
+  if (workspace_bytes < P.bytes) return set_error(RESIST_EWORKSPACE, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes, (long long)P.bytes);
+  const int nslots = nblocks + 2;
+  for (int i = 0; i < nslots; ++i)
+    if (!block_params[i] || ((uintptr_t)block_params[i] & 15)) return set_error(RESIST_EINVAL, "buffer %d is NULL or not 16-byte aligned", i);
+  hipStream_t st = (hipStream_t)hip_stream;
+  const Net &net = P.net;
+  const int N = batch, dt = net.d.compute_dtype;
+  const float eps = net.d.bn_eps;
+  auto params = [&](int slot) { return (float *)block_params[slot]; };
+  if (dt == DT_BF16) {
+    std::vector<FilterPrep> prep;
+    for (BlockPlan &bp : P.blocks) {
+      float *pp = params(bp.slot);
+      for (ConvLayer &c : bp.convs) prep.push_back(FilterPrep{c.g, pp + c.w_off, c.wlp, nullptr});
+      if (bp.has_ds) prep.push_back(FilterPrep{bp.ds.g, pp + bp.ds.w_off, bp.ds.wlp, nullptr});
+    }
+    RESIST_TRY(prepare_filters(prep, dt, st));
+  }
+  auto filter = [&](const ConvLayer &c, const float *w) -> const void * { return dt == DT_F32 ? (const void *)w : c.wlp; };
+  {
+    ConvLayer &s = P.stem;
+    const int K0 = net.d.width[0];
+    const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
+    RESIST_TRY(stem_im2col(dt, x, P.col, N, net.d.in_c, net.d.in_h, net.d.in_w, net.stem_rs, net.stem_stride, net.stem_pad,
+                           net.stem_h, net.stem_w, P.kpad, st));
+    RESIST_TRY(pad_rows(dt, params(0) + s.w_off, P.wpad, K0, taps, P.kpad, st));
+    RESIST_TRY(conv_fwd(s.g, dt, P.col, P.wpad, s.y, nullptr, nullptr, st));
+    BnBufs b = bn_eval_bufs(s, params(0), P.affine[0]);
+    RESIST_TRY(bn_eval_affine(K0, b, eps, 1.f, st));
+    RESIST_TRY(bn_apply(dt, s.y, s.M(), K0, b, nullptr, nullptr, true, s.a, st));
+    if (net.d.stem_kind == 1)
+      RESIST_TRY(maxpool_fwd(dt, s.a, P.stem_pool, P.stem_argmax, N, net.stem_h, net.stem_w, K0, net.body_h, net.body_w, st));
+  }
+  for (size_t bi = 0; bi < P.blocks.size(); ++bi) {
+    BlockPlan &bp = P.blocks[bi];
+    float *pp = params(bp.slot);
+    const float scale = branch_scale ? branch_scale[bi] : 1.f;
+    const size_t nc = bp.convs.size();
+    BnBufs bl{};
+    for (size_t j = 0; j < nc; ++j) {
+      ConvLayer &c = bp.convs[j];
+      RESIST_TRY(conv_fwd(c.g, dt, c.in, filter(c, pp + c.w_off), c.y, nullptr, nullptr, st));
+      BnBufs b = bn_eval_bufs(c, pp, P.affine[0]);
+      RESIST_TRY(bn_eval_affine(c.g.K, b, eps, j + 1 == nc ? scale : 1.f, st));
+      if (c.a) RESIST_TRY(bn_apply(dt, c.y, c.M(), c.g.K, b, nullptr, nullptr, true, c.a, st));
+      else bl = b;
+    }
+    ConvLayer &last = bp.convs.back();
+    if (bp.has_ds) {
+      ConvLayer &d = bp.ds;
+      RESIST_TRY(conv_fwd(d.g, dt, d.in, filter(d, pp + d.w_off), d.y, nullptr, nullptr, st));
+      BnBufs bd = bn_eval_bufs(d, pp, P.affine[1]);
+      RESIST_TRY(bn_eval_affine(d.g.K, bd, eps, 1.f, st));
+      RESIST_TRY(bn_apply(dt, last.y, last.M(), last.g.K, bl, d.y, &bd, true, bp.out, st));
+    } else {
+      RESIST_TRY(bn_apply(dt, last.y, last.M(), last.g.K, bl, bp.in, nullptr, true, bp.out, st));
+    }
+  }
+  const int J = net.d.num_classes, CH = net.head_c;
+  const BlockLayout &HL = P.layouts[nslots - 1];
+  float *fcw = params(nslots - 1) + HL.off(T_FCW, 0), *fcb = params(nslots - 1) + HL.off(T_FCB, 0);
+  RESIST_TRY(avgpool_fwd(dt, P.feat, P.pooled, N, P.feat_hw, CH, st));
+  RESIST_TRY(fc_fwd_f32(P.pooled, fcw, fcb, logits_out, N, CH, J, st));
+  if (labels) RESIST_TRY(softmax_ce_f32(logits_out, labels, loss_out, P.dz, P.row_loss, N, J, st));
   return RESIST_OK;
 }
 

@@ -35,6 +35,16 @@ class DeviceModel:
         self.params = [by_key[k] for k in self.keys]
         self.device = self.params[0].device
 
+    def predict(self, x, branch_scale=None, labels=None, stream=None):
+        """Test-time forward pass of these blocks (BN running statistics; the residual branch of block i
+        times branch_scale[i]).  x: device float32 [N,C,H,W].  -> logits [N, classes] (and the loss)."""
+        n = x.shape[0]
+        ws = torch.empty(B.forward_workspace_bytes(self.model, self.blocks, n), dtype=torch.uint8, device=x.device)
+        logits = torch.empty((n, self.model["num_classes"]), dtype=torch.float32, device=x.device)
+        loss = torch.zeros(1, dtype=torch.float32, device=x.device) if labels is not None else None
+        B.forward(self.model, self.blocks, self.params, x, logits, ws, branch_scale, labels, loss, stream)
+        return (logits, loss) if labels is not None else logits
+
     def download(self):
         """-> {key: {name: logical array}} of the current parameter buffers."""
         return {k: B.unpack_block(self.model, k, p.cpu().numpy()) for k, p in zip(self.keys, self.params)}

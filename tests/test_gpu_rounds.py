@@ -49,3 +49,47 @@ def test_two_rounds_paper_mode_partition():
         for n in want[k]:
             rel = np.linalg.norm(got[k][n] - want[k][n]) / max(np.linalg.norm(want[k][n]), 1e-30)
             assert rel <= 2e-3, f"after {rounds} rounds: block {k} {n}: relative L2 error {rel:.3e}"
+
+
+@pytest.mark.parametrize("kind", ["basic", "bottleneck", "bottleneck_bf16"])
+def test_forward_eval_with_branch_scaling(kind):
+    """resist_forward: evaluation-mode BN (running statistics) and 1/S scaling of the partitioned
+    blocks' residual branches (Sec. 2.6), against the oracle; and after a reassembly, as in the method."""
+    from oracle import resnet as OR
+    base = get_config("cfg1")["model"]
+    if kind == "basic":
+        model = dict(base, widths=[16, 32, 64], blocks=[2, 2, 4], in_h=16, in_w=16, num_classes=10)
+    else:
+        model = dict(base, block_kind=1, stem_kind=1, widths=[16, 32], blocks=[2, 3], in_h=40, in_w=40, num_classes=12,
+                     compute_dtype=1 if kind.endswith("bf16") else 0)
+    nb = R.num_blocks(model)
+    S = 4
+    first = {0, model["blocks"][0], model["blocks"][0] + model["blocks"][1]} if kind == "basic" else {0, model["blocks"][0]}
+    scale = [1.0 if b in first else 1.0 / S for b in range(nb)]
+    params = make_params(model, 9, perturb_bn=True)          # non-trivial running statistics
+    x, y = make_batch(model, 7, 3)
+    glob = DeviceModel(model, list(range(nb)), params)
+    xd, yd = to_device_batch(x, y)
+    logits, loss = glob.predict(xd, branch_scale=scale, labels=yd)
+    torch.cuda.synchronize()
+    want_z, want_loss = OR.forward_eval(model, list(range(nb)), params, x, branch_scale=scale, labels=y)
+    if model["compute_dtype"] == 1:
+        # forward only, bf16 storage: ~2^-9 per stored activation, a few dozen of them in sequence
+        rel = np.linalg.norm(logits.cpu().numpy() - want_z) / np.linalg.norm(want_z)
+        assert rel <= 2e-2, f"bf16 logits: relative L2 error {rel:.3e}"
+        assert abs(float(loss.cpu()[0]) - want_loss) <= 2e-2 * abs(want_loss)
+    else:
+        assert_close(logits.cpu().numpy(), want_z, f"{kind} logits")
+        assert_close(loss.cpu().numpy()[0], want_loss, f"{kind} loss")
+    # a sub-ResNet's own forward (scale 1, some blocks absent), without labels
+    sub_blocks = [b for b in range(nb) if b in first or b % 2 == 1]
+    sub = DeviceModel(model, sub_blocks, params)
+    z2 = sub.predict(xd).cpu().numpy()
+    want2 = OR.forward_eval(model, sub_blocks, params, x)
+    if model["compute_dtype"] == 1:
+        assert np.linalg.norm(z2 - want2) / np.linalg.norm(want2) <= 2e-2
+    else:
+        assert_close(z2, want2, f"{kind} sub-ResNet logits")
+    # nothing was written to the parameters
+    for k, p in zip(glob.keys, glob.params):
+        assert np.array_equal(p.cpu().numpy(), R.pack_block(model, k, params[k]))

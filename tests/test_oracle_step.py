@@ -198,3 +198,68 @@ def test_param_count_matches_tensors():
             n_all = sum(v.size for v in p.values())
             assert OR.param_count(model, b) == n_train
             assert OR.param_count(model, b, trainable_only=False) == n_all
+
+
+# ---- test-time forward (Sec. 2.6 "Scaling Activations") ---------------------------------------------
+
+@pytest.mark.parametrize("name", ["basic", "strided", "bottleneck"])
+def test_forward_eval_pins(name):
+    model = _tiny_models()[name]
+    B = sum(model["blocks"])
+    blocks = list(range(B))
+    params = make_params(model, 6, perturb_bn=True)
+    x, y = make_batch(model, 5, 7)
+    z, loss = OR.forward_eval(model, blocks, params, x, branch_scale=None, labels=y)
+
+    # (1) an autograd library's evaluation-mode batch norm as third opinion
+    tab = OR.block_table(model)
+    tp = {b: {k: torch.tensor(np.asarray(v, np.float64)) for k, v in p.items()} for b, p in params.items()}
+    eps = model["bn_eps"]
+
+    def cbn(a, p, conv, bn, stride, pad, relu):
+        h = F.conv2d(a, p[conv + "_w"], stride=stride, padding=pad)
+        h = F.batch_norm(h, p[bn + "_rm"], p[bn + "_rv"], p[bn + "_g"], p[bn + "_b"], False, 0.1, eps)
+        return F.relu(h) if relu else h
+
+    a = torch.tensor(np.asarray(x, np.float64))
+    if model["stem_kind"] == 0:
+        a = cbn(a, tp[-1], "conv", "bn", 1, 1, True)
+    else:
+        a = F.max_pool2d(cbn(a, tp[-1], "conv", "bn", 2, 3, True), 3, 2, 1)
+    for b in blocks:
+        t, p = tab[b], tp[b]
+        if model["block_kind"] == 0:
+            h = cbn(cbn(a, p, "conv1", "bn1", t["stride"], 1, True), p, "conv2", "bn2", 1, 1, False)
+        else:
+            h = cbn(a, p, "conv1", "bn1", 1, 0, True)
+            h = cbn(cbn(h, p, "conv2", "bn2", t["stride"], 1, True), p, "conv3", "bn3", 1, 0, False)
+        sc = cbn(a, p, "ds", "dsbn", t["stride"], 0, False) if t["has_ds"] else a
+        a = F.relu(h + sc)
+    zt = F.linear(a.mean(dim=(2, 3)), tp[B]["fc_w"], tp[B]["fc_b"])
+    np.testing.assert_allclose(z, zt.numpy(), rtol=1e-10, atol=1e-12)
+    assert math.isclose(loss, float(F.cross_entropy(zt, torch.tensor(y, dtype=torch.long))), rel_tol=1e-12)
+
+    # (2) with the running statistics set to this batch's own statistics, the evaluation-mode pass is
+    #     the training-mode pass (whose loss the finite-difference tests pin)
+    tr_loss, _, tape, _ = OR.forward_backward(model, blocks, params, x, y, backward=False)
+    p2 = copy.deepcopy(params)
+    for (b, bn), (mean, var, m) in tape.stats.items():
+        p2[b][bn + "_rm"], p2[b][bn + "_rv"] = mean, var
+    _, loss2 = OR.forward_eval(model, blocks, p2, x, labels=y)
+    assert math.isclose(loss2, tr_loss, rel_tol=1e-12)
+
+    # (3) a branch scaled by zero is an absent block (identity shortcuts; Appendix B, mask 0), and the
+    #     scale is linear in the branch: scaling gamma and beta of the last BN by s is the same thing
+    drop = 1                                              # a non-first block in every tiny model
+    scale = [1.0] * B
+    scale[drop] = 0.0
+    z0 = OR.forward_eval(model, blocks, params, x, branch_scale=scale)
+    z1 = OR.forward_eval(model, [b for b in blocks if b != drop], params, x)
+    np.testing.assert_allclose(z0, z1, rtol=1e-12, atol=1e-13)
+    scale[drop] = 0.25
+    p3 = copy.deepcopy(params)
+    last = "bn3" if model["block_kind"] == 1 else "bn2"
+    p3[drop][last + "_g"] = params[drop][last + "_g"] * 0.25
+    p3[drop][last + "_b"] = params[drop][last + "_b"] * 0.25
+    np.testing.assert_allclose(OR.forward_eval(model, blocks, params, x, branch_scale=scale),
+                               OR.forward_eval(model, blocks, p3, x), rtol=1e-12, atol=1e-13)

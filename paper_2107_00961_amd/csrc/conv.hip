@@ -386,8 +386,9 @@ int dispatch_igemm(const IgemmArgs &a, hipStream_t st, int *tiles_m_out = nullpt
   auto tiles = [&](int bm, int bn) {
     return (long long)((a.Mrows + bm - 1) / bm) * ((a.OC + bn - 1) / bn) * classes;
   };
-  if (a.OC > 64 && tiles(128, 128) >= 512) return launch_igemm<T, 128, 128, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);
-  if (tiles(128, 64) >= 512) return launch_igemm<T, 128, 64, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);
+  constexpr long long kMin = 512;   // measured: 256 or fewer workgroups of a larger tile are slower on every layer shape
+  if (a.OC > 64 && tiles(128, 128) >= kMin) return launch_igemm<T, 128, 128, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);
+  if (tiles(128, 64) >= kMin) return launch_igemm<T, 128, 64, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);
   if (a.IC % (16 * V) == 0) return launch_igemm<T, 64, 64, 16 * V, 2, 2, MODE>(a, st, tiles_m_out);
   return launch_igemm<T, 64, 64, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);
 }

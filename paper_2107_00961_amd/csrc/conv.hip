@@ -282,9 +282,6 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
   // the channel axis; the optional addend is added in fp32 before the one rounding to T.
   T *out = static_cast<T *>(a.out);
   const T *addend = static_cast<const T *>(a.addend);
-  float s1[TN], s2[TN];   // column sums of the values as stored (batch-norm statistics of this row tile)
-#pragma unroll
-  for (int j = 0; j < TN; ++j) { s1[j] = 0.f; s2[j] = 0.f; }
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -293,63 +290,68 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int row = wm * WTM + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        const float v = acc[i][j][e];
-        Cs[row][cl] = v;
-        if (MODE == kFwd) {   // rows and columns outside the tensor hold exact zeros
-          const float sv = E::to_f32(E::from_f32(v));
-          s1[j] += sv;
-          s2[j] = fmaf(sv, sv, s2[j]);
-        }
+        Cs[row][cl] = acc[i][j][e];
       }
     }
   __syncthreads();
-  {
-    constexpr int CV = BN / VEC;            // 16-byte pieces per tile row
-    constexpr int RPS = kThreads / CV;      // rows per pass
-    const int cv = (tid % CV) * VEC, r0 = tid / CV;
-    const bool col_ok = n0 + cv < a.OC;     // OC is a multiple of VEC
-    static_assert(BM % RPS == 0, "output tile rows per pass");
+  constexpr int CV = BN / VEC;            // 16-byte pieces per tile row
+  constexpr int RPS = kThreads / CV;      // rows per pass
+  static_assert(BM % RPS == 0 && CV <= 32, "output tile rows per pass");
+  const int cv = (tid % CV) * VEC, row0 = tid / CV;
+  const bool col_ok = n0 + cv < a.OC;     // OC is a multiple of VEC
+  float s1[VEC], s2[VEC];   // column sums of the values as stored (batch-norm statistics of this row tile)
 #pragma unroll
-    for (int pass = 0; pass < BM / RPS; ++pass) {
-      const int r = r0 + pass * RPS;
-      const int ro = row_off[r];
-      if (ro >= 0 && col_ok) {
-        const size_t off = (size_t)ro * a.OC + n0 + cv;
-        float v[VEC];
+  for (int e = 0; e < VEC; ++e) { s1[e] = 0.f; s2[e] = 0.f; }
 #pragma unroll
-        for (int e = 0; e < VEC; e += 4) {
-          const f32x4 t = *reinterpret_cast<const f32x4 *>(&Cs[r][cv + e]);
-          v[e] = t[0]; v[e + 1] = t[1]; v[e + 2] = t[2]; v[e + 3] = t[3];
+  for (int pass = 0; pass < BM / RPS; ++pass) {
+    const int r = row0 + pass * RPS;
+    const int ro = row_off[r];
+    if (ro >= 0 && col_ok) {
+      const size_t off = (size_t)ro * a.OC + n0 + cv;
+      float v[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; e += 4) {
+        const f32x4 t = *reinterpret_cast<const f32x4 *>(&Cs[r][cv + e]);
+        v[e] = t[0]; v[e + 1] = t[1]; v[e + 2] = t[2]; v[e + 3] = t[3];
+      }
+      if (addend) {
+        float ad[VEC];
+        Vec<T>::load(addend + off, ad);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] += ad[e];
+      }
+      Vec<T>::store(out + off, v);
+      if (MODE == kFwd) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const float sv = E::to_f32(E::from_f32(v[e]));
+          s1[e] += sv;
+          s2[e] = fmaf(sv, sv, s2[e]);
         }
-        if (addend) {
-          float ad[VEC];
-          Vec<T>::load(addend + off, ad);
-#pragma unroll
-          for (int e = 0; e < VEC; ++e) v[e] += ad[e];
-        }
-        Vec<T>::store(out + off, v);
       }
     }
   }
   if (MODE == kFwd && a.stats) {
-    // lanes l and l+32 hold the same column; then the WGM waves that share a column range add up in
-    // wave order.  Every step has a fixed order, so the sums are bit-stable from run to run.
-    __shared__ float red[2][WGM][BN];
+    // A wave holds 64/CV rows of every column piece: butterfly over those lanes, then the 4 waves add
+    // up in wave order.  Every step has a fixed order, so the sums are bit-stable from run to run.
+    __shared__ float red[2][4][BN];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      s1[j] += __shfl_xor(s1[j], 32, 64);
-      s2[j] += __shfl_xor(s2[j], 32, 64);
-      if (lane < 32) {
-        red[0][wm][wn * WTN + j * 32 + lr] = s1[j];
-        red[1][wm][wn * WTN + j * 32 + lr] = s2[j];
+    for (int e = 0; e < VEC; ++e) {
+#pragma unroll
+      for (int o = CV; o < 64; o <<= 1) {
+        s1[e] += __shfl_xor(s1[e], o, 64);
+        s2[e] += __shfl_xor(s2[e], o, 64);
       }
+    }
+    if (lane < CV) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) { red[0][wave][cv + e] = s1[e]; red[1][wave][cv + e] = s2[e]; }
     }
     __syncthreads();
     for (int c = tid; c < BN; c += kThreads) {
       if (n0 + c < a.OC) {
-        float t1 = red[0][0][c], t2 = red[1][0][c];
-#pragma unroll
-        for (int w = 1; w < WGM; ++w) { t1 += red[0][w][c]; t2 += red[1][w][c]; }
+        const float t1 = ((red[0][0][c] + red[0][1][c]) + red[0][2][c]) + red[0][3][c];
+        const float t2 = ((red[1][0][c] + red[1][1][c]) + red[1][2][c]) + red[1][3][c];
         a.stats[(size_t)tm * a.OC + n0 + c] = t1;
         a.stats[((size_t)a.tiles_m + tm) * a.OC + n0 + c] = t2;
       }
@@ -417,11 +419,12 @@ int64_t conv_stats_floats(const ConvGeom &g) {
   return (int64_t)2 * (((int64_t)g.N * g.P * g.Q + 63) / 64) * g.K;
 }
 
-int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, float *stats, int *stat_parts, hipStream_t st) {
+int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, const void *addend, float *stats, int *stat_parts,
+             hipStream_t st) {
   RESIST_TRY(check_geom(g, dt));
   if (stats && !stat_parts) return set_error(RESIST_EINVAL, "conv_fwd: stats without stat_parts");
   IgemmArgs a{};
-  a.in = x; a.wt = w; a.out = y; a.addend = nullptr; a.stats = stats;
+  a.in = x; a.wt = w; a.out = y; a.addend = addend; a.stats = stats;
   a.N = g.N; a.IH = g.H; a.IW = g.W; a.IC = g.C;
   a.OH = g.P; a.OW = g.Q; a.OC = g.K;
   a.R = g.R; a.S = g.S; a.stride = g.stride; a.pad = g.pad;

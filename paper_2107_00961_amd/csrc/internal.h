@@ -102,11 +102,11 @@ enum { DT_F32 = 0, DT_BF16 = 1 };
 inline int esize(int dt) { return dt == DT_BF16 ? 2 : 4; }
 
 // implicit-GEMM convolution family (conv.hip); dt selects fp32 or bf16 tensors (fp32 accumulation)
-// stats (optional): per row-tile column sums and sums of squares of y as stored, [2][*stat_parts][K]
-// floats (capacity conv_stats_floats(g)); input of bn_finalize
+// y = conv(x, w) [+ addend].  stats (optional): per row-tile column sums and sums of squares of y as
+// stored, [2][*stat_parts][K] floats (capacity conv_stats_floats(g)); input of bn_finalize
 int64_t conv_stats_floats(const ConvGeom &g);
-int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, float *stats, int *stat_parts,
-             hipStream_t st);
+int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, const void *addend, float *stats,
+             int *stat_parts, hipStream_t st);
 // dx = dgrad(dy, wT) [+ addend]; wT is the [C][R][S][K] transpose made by prepare_filter
 int conv_dgrad(const ConvGeom &g, int dt, const void *dy, const void *wT, void *dx, const void *addend,
                hipStream_t st);

@@ -32,7 +32,7 @@ extern "C" int resist_conv2d_forward(const resist_conv_shape *s, const void *x, 
   RESIST_TRY(to_geom(s, &g));
   if (!x || !w || !y) return set_error(RESIST_EINVAL, "NULL tensor");
   (void)workspace; (void)workspace_bytes;
-  return conv_fwd(g, s->dtype, x, w, y, nullptr, nullptr, (hipStream_t)hip_stream);
+  return conv_fwd(g, s->dtype, x, w, y, nullptr, nullptr, nullptr, (hipStream_t)hip_stream);
 }
 
 extern "C" int resist_conv2d_dgrad(const resist_conv_shape *s, const void *dy, const void *w, void *dx, void *workspace,

@@ -427,7 +427,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
                            net.stem_h, net.stem_w, P.kpad, st));
     RESIST_TRY(pad_rows(dt, params(0) + s.w_off, P.wpad, K0, taps, P.kpad, st));
     int parts = 0;
-    RESIST_TRY(conv_fwd(s.g, dt, P.col, P.wpad, s.y, P.stats, &parts, st));
+    RESIST_TRY(conv_fwd(s.g, dt, P.col, P.wpad, s.y, nullptr, P.stats, &parts, st));
     BnBufs b = bn_bufs(s, params(0), grads(0));
     RESIST_TRY(bn_finalize(P.stats, parts, s.M(), K0, b, eps, bnm, P.bn_scratch, st));
     RESIST_TRY(bn_apply(dt, s.y, s.M(), K0, b, nullptr, nullptr, true, s.a, st));
@@ -439,7 +439,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     for (size_t j = 0; j < bp.convs.size(); ++j) {
       ConvLayer &c = bp.convs[j];
       int parts = 0;
-      RESIST_TRY(conv_fwd(c.g, dt, c.in, fwd_filter(c, pp + c.w_off), c.y, P.stats, &parts, st));
+      RESIST_TRY(conv_fwd(c.g, dt, c.in, fwd_filter(c, pp + c.w_off), c.y, nullptr, P.stats, &parts, st));
       BnBufs b = bn_bufs(c, pp, gg);
       RESIST_TRY(bn_finalize(P.stats, parts, c.M(), c.g.K, b, eps, bnm, P.bn_scratch, st));
       if (c.a) RESIST_TRY(bn_apply(dt, c.y, c.M(), c.g.K, b, nullptr, nullptr, true, c.a, st));
@@ -449,7 +449,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     if (bp.has_ds) {
       ConvLayer &d = bp.ds;
       int parts = 0;
-      RESIST_TRY(conv_fwd(d.g, dt, d.in, fwd_filter(d, pp + d.w_off), d.y, P.stats, &parts, st));
+      RESIST_TRY(conv_fwd(d.g, dt, d.in, fwd_filter(d, pp + d.w_off), d.y, nullptr, P.stats, &parts, st));
       BnBufs bd = bn_bufs(d, pp, gg);
       RESIST_TRY(bn_finalize(P.stats, parts, d.M(), d.g.K, bd, eps, bnm, P.bn_scratch, st));
       RESIST_TRY(bn_apply(dt, last.y, last.M(), last.g.K, bl, d.y, &bd, true, bp.out, st));
@@ -573,7 +573,7 @@ extern "C" int resist_forward(const resist_model_desc *desc, const int32_t *bloc
     RESIST_TRY(stem_im2col(dt, x, P.col, N, net.d.in_c, net.d.in_h, net.d.in_w, net.stem_rs, net.stem_stride, net.stem_pad,
                            net.stem_h, net.stem_w, P.kpad, st));
     RESIST_TRY(pad_rows(dt, params(0) + s.w_off, P.wpad, K0, taps, P.kpad, st));
-    RESIST_TRY(conv_fwd(s.g, dt, P.col, P.wpad, s.y, nullptr, nullptr, st));
+    RESIST_TRY(conv_fwd(s.g, dt, P.col, P.wpad, s.y, nullptr, nullptr, nullptr, st));
     BnBufs b = bn_eval_bufs(s, params(0), P.affine[0]);
     RESIST_TRY(bn_eval_affine(K0, b, eps, 1.f, st));
     RESIST_TRY(bn_apply(dt, s.y, s.M(), K0, b, nullptr, nullptr, true, s.a, st));
@@ -588,7 +588,7 @@ extern "C" int resist_forward(const resist_model_desc *desc, const int32_t *bloc
     BnBufs bl{};
     for (size_t j = 0; j < nc; ++j) {
       ConvLayer &c = bp.convs[j];
-      RESIST_TRY(conv_fwd(c.g, dt, c.in, filter(c, pp + c.w_off), c.y, nullptr, nullptr, st));
+      RESIST_TRY(conv_fwd(c.g, dt, c.in, filter(c, pp + c.w_off), c.y, nullptr, nullptr, nullptr, st));
       BnBufs b = bn_eval_bufs(c, pp, P.affine[0]);
       RESIST_TRY(bn_eval_affine(c.g.K, b, eps, j + 1 == nc ? scale : 1.f, st));
       if (c.a) RESIST_TRY(bn_apply(dt, c.y, c.M(), c.g.K, b, nullptr, nullptr, true, c.a, st));
@@ -597,7 +597,7 @@ extern "C" int resist_forward(const resist_model_desc *desc, const int32_t *bloc
     ConvLayer &last = bp.convs.back();
     if (bp.has_ds) {
       ConvLayer &d = bp.ds;
-      RESIST_TRY(conv_fwd(d.g, dt, d.in, filter(d, pp + d.w_off), d.y, nullptr, nullptr, st));
+      RESIST_TRY(conv_fwd(d.g, dt, d.in, filter(d, pp + d.w_off), d.y, nullptr, nullptr, nullptr, st));
       BnBufs bd = bn_eval_bufs(d, pp, P.affine[1]);
       RESIST_TRY(bn_eval_affine(d.g.K, bd, eps, 1.f, st));
       RESIST_TRY(bn_apply(dt, last.y, last.M(), last.g.K, bl, d.y, &bd, true, bp.out, st));

@@ -6,12 +6,22 @@ A block that is absent contributes nothing: the residual stream passes through u
 (Appendix B, forward recursion with mask M = 0; with M = 1 everywhere the sub-ResNet is the
 global ResNet).
 
-Network (post-activation blocks, the benchmark configurations' layer list):
+block_kind 0 / 1: post-activation basic / bottleneck blocks (the benchmark configurations' layer list);
+block_kind 2 / 3: pre-activation basic / bottleneck blocks (the architecture the paper prefers, Sec. 2.1 and
+Fig. 2: BN -> ReLU -> conv, twice, identity added without a ReLU after it), see the second list.
+
+Network (post-activation blocks):
   stem   conv (3x3 s1 p1 | 7x7 s2 p3) -> BN -> ReLU [-> maxpool 3x3 s2 p1]
   basic  conv3x3(stride) -> BN -> ReLU -> conv3x3 -> BN ; + shortcut ; ReLU
   bottle conv1x1 -> BN -> ReLU -> conv3x3(stride) -> BN -> ReLU -> conv1x1(x4) -> BN ; + shortcut ; ReLU
   shortcut: identity, or conv1x1(stride) -> BN in the first block of a stage when shape changes
   head   global mean pool -> FC + bias -> softmax cross-entropy, mean over the batch
+Network (pre-activation blocks; what the paper leaves open is read as in the pre-activation ResNet it cites):
+  stem   conv 3x3 s1 p1 only
+  basic  BN -> ReLU -> conv3x3(stride) -> BN -> ReLU -> conv3x3 ; + shortcut        (no ReLU after the add)
+  bottle BN -> ReLU -> conv1x1 -> BN -> ReLU -> conv3x3(stride) -> BN -> ReLU -> conv1x1(x4) ; + shortcut
+  shortcut: identity, or conv1x1(stride) applied to the block's first ReLU output (no BN) where shape changes
+  head   BN -> ReLU -> global mean pool -> FC + bias -> softmax cross-entropy
 Update (momentum per the paper's experimental section; form is the usual one):
   g <- g + wd*w ; v <- mu*v + g ; w <- w - lr*v   (every trainable parameter alike)
 Parameters are dicts keyed -1 (stem), b (block), B (head) of logical-layout arrays.
@@ -31,8 +41,12 @@ from . import layers as L
 from . import quant as Q
 
 
+def is_preact(model):
+    return model["block_kind"] >= 2
+
+
 def block_table(model):
-    exp = 4 if model["block_kind"] == 1 else 1
+    exp = 4 if model["block_kind"] in (1, 3) else 1
     tab, c_in = [], model["widths"][0]
     for si, (w, nb) in enumerate(zip(model["widths"], model["blocks"])):
         for bi in range(nb):
@@ -57,6 +71,18 @@ def param_count(model, block, trainable_only=True):
     tab = block_table(model)
     B = len(tab)
     bn = (lambda c: 2 * c) if trainable_only else (lambda c: 4 * c)
+    if is_preact(model):
+        if block == -1:
+            return model["widths"][0] * model["in_c"] * 9
+        if block == B:
+            return model["num_classes"] * tab[-1]["c_out"] + model["num_classes"] + bn(tab[-1]["c_out"])
+        t = tab[block]
+        if model["block_kind"] == 2:
+            n = bn(t["c_in"]) + t["width"] * t["c_in"] * 9 + bn(t["width"]) + t["c_out"] * t["width"] * 9
+        else:
+            n = (bn(t["c_in"]) + t["width"] * t["c_in"] + bn(t["width"]) + t["width"] * t["width"] * 9
+                 + bn(t["width"]) + t["c_out"] * t["width"])
+        return n + (t["c_out"] * t["c_in"] if t["has_ds"] else 0)
     if block == -1:
         rs = 3 if model["stem_kind"] == 0 else 7
         w0 = model["widths"][0]
@@ -119,6 +145,8 @@ def forward_backward(model, blocks, params, x, labels, need_input_grad=False, ba
     Returns loss, grads (same keys as params, trainable tensors only), tape (batch statistics),
     and the input gradient if asked.  backward=False stops after the loss (grads = None).
     """
+    if is_preact(model):
+        return _forward_backward_preact(model, blocks, params, x, labels, need_input_grad, backward, emulate_bf16)
     tab = block_table(model)
     B = len(tab)
     eps = model["bn_eps"]
@@ -192,6 +220,98 @@ def forward_backward(model, blocks, params, x, labels, need_input_grad=False, ba
     if need_input_grad:
         dx = L.conv2d_dgrad(dy, w, stem_ctx["x"].shape, stem_ctx["stride"], stem_ctx["pad"])
     return loss, grads, tape, dx
+
+
+def _preact_layers(model, t):
+    """(bn name, conv name, kernel, stride, pad) of the BN-ReLU-conv units of a pre-activation block."""
+    if model["block_kind"] == 2:
+        return [("bn1", "conv1", 3, t["stride"], 1), ("bn2", "conv2", 3, 1, 1)]
+    return [("bn1", "conv1", 1, 1, 0), ("bn2", "conv2", 3, t["stride"], 1), ("bn3", "conv3", 1, 1, 0)]
+
+
+def _forward_backward_preact(model, blocks, params, x, labels, need_input_grad, backward, emulate_bf16):
+    """forward_backward for pre-activation blocks (block_kind 2, 3).  In a block with units
+    j = 1..n:  a_j = ReLU(BN_j(u_j)), h_j = conv_j(a_j), u_1 = x, u_j = h_{j-1};  out = h_n + shortcut.
+    With bf16 emulation everything stored is rounded: a_j, h_j (j < n), the shortcut convolution's
+    output, out (the sum, rounded once), and the matching gradients on the way back."""
+    tab = block_table(model)
+    B = len(tab)
+    eps = model["bn_eps"]
+    tape = _Tape()
+    q = Q.round_bf16 if emulate_bf16 else Q.identity
+    if model["stem_kind"] != 0:
+        raise ValueError("pre-activation networks use the 3x3 stem")
+
+    def bn_relu(u, p, bn, key):
+        z, cache = L.bn_fwd(u, p[bn + "_g"].astype(np.float64), p[bn + "_b"].astype(np.float64), eps)
+        tape.stats[(key, bn)] = (cache[2], cache[3], u.shape[0] * u.shape[2] * u.shape[3])
+        tape.saw_relu_input(z)
+        return q(np.maximum(z, 0.0)), (z, cache)
+
+    # ---- forward
+    ximg = q(np.asarray(x, np.float64))
+    wstem = q(params[-1]["conv_w"])
+    u = q(L.conv2d_fwd(ximg, wstem, 1, 1))
+    ctxs = []
+    for b in blocks:
+        t, p = tab[b], params[b]
+        xin, units = u, []
+        for bn, conv, k, stride, pad in _preact_layers(model, t):
+            a, (z, cache) = bn_relu(u, p, bn, b)
+            wq = q(p[conv + "_w"])
+            h = L.conv2d_fwd(a, wq, stride, pad)
+            units.append(dict(bn=bn, conv=conv, stride=stride, pad=pad, a=a, z=z, cache=cache, wq=wq, u_shape=u.shape))
+            u = q(h) if conv != units_last_name(model) else h
+        ds = None
+        if t["has_ds"]:
+            wd_ = q(p["ds_w"])
+            sc = q(L.conv2d_fwd(units[0]["a"], wd_, t["stride"], 0))
+            ds = dict(wq=wd_)
+        else:
+            sc = xin
+        u = q(u + sc)
+        ctxs.append((b, units, ds))
+    hd = params[B]
+    f, (zf, cachef) = bn_relu(u, hd, "bn", B)
+    feat_shape = f.shape
+    pooled = L.avgpool_fwd(f)
+    z = L.fc_fwd(pooled, hd["fc_w"].astype(np.float64), hd["fc_b"].astype(np.float64))
+    loss, dz = L.softmax_ce(z, np.asarray(labels))
+    if not backward:
+        return loss, None, tape, None
+    # ---- backward
+    grads = {}
+    dpooled, dw, db = L.fc_bwd(dz, pooled, hd["fc_w"].astype(np.float64))
+    gf = q(L.avgpool_bwd(dpooled, feat_shape))
+    du, dg, dbt = L.bn_bwd(gf * (zf > 0), cachef, hd["bn_g"].astype(np.float64))
+    grads[B] = {"fc_w": dw, "fc_b": db, "bn_g": dg, "bn_b": dbt}
+    g = q(du)
+    for b, units, ds in reversed(ctxs):
+        t, p = tab[b], params[b]
+        gb = {}
+        gcur = g
+        for j in range(len(units) - 1, -1, -1):
+            un = units[j]
+            gb[un["conv"] + "_w"] = L.conv2d_wgrad(gcur, un["a"], un["wq"].shape, un["stride"], un["pad"])
+            da = L.conv2d_dgrad(gcur, un["wq"], un["a"].shape, un["stride"], un["pad"])
+            if j == 0 and ds is not None:
+                gb["ds_w"] = L.conv2d_wgrad(g, un["a"], ds["wq"].shape, t["stride"], 0)
+                da = da + q(L.conv2d_dgrad(g, ds["wq"], un["a"].shape, t["stride"], 0))
+            da = q(da)
+            du, dgam, dbet = L.bn_bwd(da * (un["z"] > 0), un["cache"], p[un["bn"] + "_g"].astype(np.float64))
+            gb[un["bn"] + "_g"], gb[un["bn"] + "_b"] = dgam, dbet
+            if j > 0:
+                gcur = q(du)
+            else:
+                g = q(du + g) if ds is None else q(du)
+        grads[b] = gb
+    grads[-1] = {"conv_w": L.conv2d_wgrad(g, ximg, wstem.shape, 1, 1)}
+    dx = L.conv2d_dgrad(g, wstem, ximg.shape, 1, 1) if need_input_grad else None
+    return loss, grads, tape, dx
+
+
+def units_last_name(model):
+    return "conv2" if model["block_kind"] == 2 else "conv3"
 
 
 def sgd_update(params, momentum_buf, grads, lr, mu, wd):

@@ -293,6 +293,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const double *__
 
 struct BwdApplyArgs {
   const void *g; const void *mask; const void *y;
+  const void *addend;   // optional: added to dy in fp32 before it is stored
   const float *mean; const float *invstd; const float *scale; const float *shift;
   const float *dgamma; const float *dbeta;
   void *dy; void *gm_out;
@@ -307,6 +308,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BwdApplyArgs p) 
   const int c = (blockIdx.y * p.tpr + tc) * V;
   const T *g = static_cast<const T *>(p.g), *mask = static_cast<const T *>(p.mask), *y = static_cast<const T *>(p.y);
   T *dy = static_cast<T *>(p.dy), *gm_out = static_cast<T *>(p.gm_out);
+  const T *addend = static_cast<const T *>(p.addend);
   const float invM = 1.0f / (float)p.M;
   float mu[V], is[V], k0[V], sh[V], k1[V], k2[V];
   load_params<V>(p.mean + c, mu);
@@ -344,6 +346,12 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BwdApplyArgs p) 
           gv[u][e] = gm;
           const float xh = (yv[u][e] - mu[e]) * is[e];
           o[e] = k0[e] * (gm - k1[e] - xh * k2[e]);
+        }
+        if (addend) {
+          float ad[V];
+          Vec<T>::load(addend + off, ad);
+#pragma unroll
+          for (int e = 0; e < V; ++e) o[e] += ad[e];
         }
         Vec<T>::store(dy + off, o);
         if (gm_out) Vec<T>::store(gm_out + off, gv[u]);   // exact: gm is g or zero
@@ -436,15 +444,15 @@ int bn_apply(int dt, const void *y, int64_t M, int C, const BnBufs &b, const voi
 }
 
 int bn_backward(int dt, const void *g, const void *mask, bool relu_of_self, const void *y, int64_t M, int C, const BnBufs &b,
-                void *dy, void *gm_out, double *scratch, hipStream_t st) {
+                void *dy, void *gm_out, const void *addend, double *scratch, hipStream_t st) {
   RESIST_TRY(check_bn(dt, M, C));
   const ColMap m = col_map(C, vec_of(dt));
   const int parts = num_parts(M, m);
   const int mode = mask ? kMaskTensor : (relu_of_self ? kMaskSelf : kMaskNone);
   const int reads = mask ? 3 : 2;
-  prof::Scope ps("bn_backward", 0, (double)esize(dt) * M * C * (2 * reads + 1 + (gm_out ? 1 : 0)), st);
+  prof::Scope ps("bn_backward", 0, (double)esize(dt) * M * C * (2 * reads + 1 + (gm_out ? 1 : 0) + (addend ? 1 : 0)), st);
   BwdApplyArgs p{};
-  p.g = g; p.mask = mask; p.y = y; p.mean = b.mean; p.invstd = b.invstd; p.scale = b.scale; p.shift = b.shift;
+  p.g = g; p.mask = mask; p.y = y; p.addend = addend; p.mean = b.mean; p.invstd = b.invstd; p.scale = b.scale; p.shift = b.shift;
   p.dgamma = b.dgamma; p.dbeta = b.dbeta; p.dy = dy; p.gm_out = gm_out;
   p.M = M; p.C = C; p.tpr = m.tpr; p.rpp = m.rpp;
   const dim3 gp(parts, m.ctiles), ga(apply_grid_x(M, m, 4), m.ctiles);

@@ -145,11 +145,11 @@ int bn_eval_affine(int C, const BnBufs &b, float eps, float s, hipStream_t st);
 int bn_apply(int dt, const void *y, int64_t M, int C, const BnBufs &b, const void *res,
              const BnBufs *res_bn, bool relu, void *a, hipStream_t st);
 // gm = g * [mask>0]; dbeta = sum gm; dgamma = sum gm*xhat(y);
-// dy = gamma*invstd*(gm - dbeta/M - xhat*dgamma/M); optionally stores gm to gm_out.
+// dy = gamma*invstd*(gm - dbeta/M - xhat*dgamma/M) [+ addend]; optionally stores gm to gm_out.
 // The mask is the tensor `mask` if given; else, if relu_of_self, the sign of this BN's own output
 // scale*y + shift (the forward ReLU decision recomputed with the same arithmetic); else none.
 int bn_backward(int dt, const void *g, const void *mask, bool relu_of_self, const void *y, int64_t M, int C,
-                const BnBufs &b, void *dy, void *gm_out, double *scratch, hipStream_t st);
+                const BnBufs &b, void *dy, void *gm_out, const void *addend, double *scratch, hipStream_t st);
 
 // pooling / head / loss (head.hip); pooled features, logits and the loss stay fp32
 int maxpool_fwd(int dt, const void *x, void *y, uint8_t *argmax, int N, int H, int W, int C, int P,

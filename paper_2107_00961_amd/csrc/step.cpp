@@ -478,12 +478,12 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     ConvLayer &last = bp.convs[nc - 1];
     BnBufs bl = bn_bufs(last, pp, gg);
     // through the final ReLU and the last BN of the residual branch
-    RESIST_TRY(bn_backward(dt, G, bp.out, false, last.y, last.M(), last.g.K, bl, P.dy0, bp.has_ds ? nullptr : P.gm, P.bn_scratch, st));
+    RESIST_TRY(bn_backward(dt, G, bp.out, false, last.y, last.M(), last.g.K, bl, P.dy0, bp.has_ds ? nullptr : P.gm, nullptr, P.bn_scratch, st));
     if (bp.has_ds) {
       // shortcut branch: BN and 1x1 convolution; its data gradient initialises Gn
       ConvLayer &d = bp.ds;
       BnBufs bd = bn_bufs(d, pp, gg);
-      RESIST_TRY(bn_backward(dt, G, bp.out, false, d.y, d.M(), d.g.K, bd, P.gm, nullptr, P.bn_scratch, st));
+      RESIST_TRY(bn_backward(dt, G, bp.out, false, d.y, d.M(), d.g.K, bd, P.gm, nullptr, nullptr, P.bn_scratch, st));
       RESIST_TRY(conv_wgrad(d.g, dt, P.gm, d.in, gg + d.w_off, P.splitk, st));
       RESIST_TRY(conv_dgrad(d.g, dt, P.gm, d.wT, Gn, nullptr, st));
     }
@@ -495,7 +495,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
         ConvLayer &prev = bp.convs[j - 1];
         RESIST_TRY(conv_dgrad(c.g, dt, dy, c.wT, P.da, nullptr, st));
         BnBufs bp_ = bn_bufs(prev, pp, gg);
-        RESIST_TRY(bn_backward(dt, P.da, nullptr, true, prev.y, prev.M(), prev.g.K, bp_, dy_other, nullptr, P.bn_scratch, st));
+        RESIST_TRY(bn_backward(dt, P.da, nullptr, true, prev.y, prev.M(), prev.g.K, bp_, dy_other, nullptr, nullptr, P.bn_scratch, st));
         std::swap(dy, dy_other);
       } else {
         // gradient w.r.t. the block input = branch + shortcut
@@ -515,7 +515,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
       Gs = P.da;
     }
     BnBufs b = bn_bufs(s, params(0), grads(0));
-    RESIST_TRY(bn_backward(dt, Gs, nullptr, true, s.y, s.M(), K0, b, P.dy0, nullptr, P.bn_scratch, st));
+    RESIST_TRY(bn_backward(dt, Gs, nullptr, true, s.y, s.M(), K0, b, P.dy0, nullptr, nullptr, P.bn_scratch, st));
     RESIST_TRY(conv_wgrad(s.g, dt, P.dy0, P.col, P.dwpad, P.splitk, st));
     RESIST_TRY(unpad_rows_f32(P.dwpad, grads(0) + s.w_off, K0, taps, P.kpad, st));
   }

@@ -1,7 +1,8 @@
 """The benchmark workloads as plain data (no arithmetic of the method).
 
 A model description is a dict with the keys
-  block_kind   0 = basic block (3x3, 3x3), 1 = bottleneck (1x1, 3x3, 1x1, expansion 4)
+  block_kind   0 = basic block (3x3, 3x3), 1 = bottleneck (1x1, 3x3, 1x1, expansion 4);
+               2, 3 = the same two in pre-activation form (BN-ReLU before every convolution)
   stem_kind    0 = conv3x3 stride 1 pad 1;  1 = conv7x7 stride 2 pad 3 + maxpool 3x3 stride 2 pad 1
   in_c,in_h,in_w, widths (per stage), blocks (per stage), num_classes,
   compute_dtype 0 = fp32, 1 = bf16 operands with fp32 accumulation
@@ -50,7 +51,7 @@ def model_blocks(model):
 
     Pure bookkeeping (channel counts, strides), used only to size random tensors.
     """
-    exp = 4 if model["block_kind"] == 1 else 1
+    exp = 4 if model["block_kind"] in (1, 3) else 1
     out = []
     c_in = model["widths"][0]
     for si, (w, nb) in enumerate(zip(model["widths"], model["blocks"])):

@@ -38,6 +38,8 @@ def make_params(model, seed, perturb_bn=False):
     Conv weights [K,C,R,S] Kaiming-normal; BN gamma=1, beta=0, running mean 0 / var 1;
     FC weight/bias uniform in +-1/sqrt(fan_in).  All float32.
     """
+    if model["block_kind"] >= 2:
+        return _make_params_preact(model, seed, perturb_bn)
     rng = np.random.default_rng(seed)
     blocks = model_blocks(model)
     params = {}
@@ -71,6 +73,37 @@ def make_params(model, seed, perturb_bn=False):
         "fc_w": rng.uniform(-bound, bound, size=(nc, c_last)).astype(np.float32),
         "fc_b": rng.uniform(-bound, bound, size=(nc,)).astype(np.float32),
     }
+    return params
+
+
+def _make_params_preact(model, seed, perturb_bn):
+    """Pre-activation networks: the stem is a bare 3x3 convolution, every BN sits before its
+    convolution (so it has that convolution's input channels), the shortcut convolution has no BN,
+    and the head starts with a BN."""
+    rng = np.random.default_rng(seed)
+    blocks = model_blocks(model)
+    w0 = model["widths"][0]
+    params = {-1: {"conv_w": _conv_w(rng, w0, model["in_c"], 3, 3)}}
+    for b, blk in enumerate(blocks):
+        p = {}
+        if model["block_kind"] == 2:
+            units = [("bn1", "conv1", blk["c_in"], blk["width"], 3), ("bn2", "conv2", blk["width"], blk["c_out"], 3)]
+        else:
+            units = [("bn1", "conv1", blk["c_in"], blk["width"], 1), ("bn2", "conv2", blk["width"], blk["width"], 3),
+                     ("bn3", "conv3", blk["width"], blk["c_out"], 1)]
+        for bn, conv, c, k, r in units:
+            p.update(_bn(rng, bn, c, perturb_bn))
+            p[conv + "_w"] = _conv_w(rng, k, c, r, r)
+        if blk["has_ds"]:
+            p["ds_w"] = _conv_w(rng, blk["c_out"], blk["c_in"], 1, 1)
+        params[b] = p
+    c_last = blocks[-1]["c_out"]
+    bound = 1.0 / float(np.sqrt(c_last))
+    nc = model["num_classes"]
+    head = _bn(rng, "bn", c_last, perturb_bn)
+    head["fc_w"] = rng.uniform(-bound, bound, size=(nc, c_last)).astype(np.float32)
+    head["fc_b"] = rng.uniform(-bound, bound, size=(nc,)).astype(np.float32)
+    params[len(blocks)] = head
     return params
 
 

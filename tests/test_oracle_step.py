@@ -263,3 +263,103 @@ def test_forward_eval_pins(name):
     p3[drop][last + "_b"] = params[drop][last + "_b"] * 0.25
     np.testing.assert_allclose(OR.forward_eval(model, blocks, params, x, branch_scale=scale),
                                OR.forward_eval(model, blocks, p3, x), rtol=1e-12, atol=1e-13)
+
+
+# ---- pre-activation blocks (Sec. 2.1, Fig. 2: BN -> ReLU -> conv) ---------------------------------------
+
+def _preact_models():
+    basic = get_config("cfg1")["model"]
+    return {"preact_basic": dict(basic, block_kind=2, widths=[8, 16], blocks=[2, 2], in_h=8, in_w=8, num_classes=5),
+            "preact_bottleneck": dict(basic, block_kind=3, widths=[4, 8], blocks=[2, 2], in_h=8, in_w=8, num_classes=6)}
+
+
+def _torch_loss_preact(model, blocks, params, x, labels):
+    """The pre-activation network written with a float64 autograd library (library special case)."""
+    tab = OR.block_table(model)
+    B = len(tab)
+    tp = {b: {k: torch.tensor(np.asarray(v, np.float64), requires_grad=OR.is_trainable(k))
+              for k, v in p.items()} for b, p in params.items()}
+    eps = model["bn_eps"]
+
+    def bnrelu(u, p, bn):
+        return F.relu(F.batch_norm(u, None, None, p[bn + "_g"], p[bn + "_b"], True, 0.1, eps))
+
+    u = F.conv2d(torch.tensor(np.asarray(x, np.float64)), tp[-1]["conv_w"], stride=1, padding=1)
+    for b in blocks:
+        t, p = tab[b], tp[b]
+        a1 = bnrelu(u, p, "bn1")
+        if model["block_kind"] == 2:
+            h = F.conv2d(a1, p["conv1_w"], stride=t["stride"], padding=1)
+            h = F.conv2d(bnrelu(h, p, "bn2"), p["conv2_w"], stride=1, padding=1)
+        else:
+            h = F.conv2d(a1, p["conv1_w"])
+            h = F.conv2d(bnrelu(h, p, "bn2"), p["conv2_w"], stride=t["stride"], padding=1)
+            h = F.conv2d(bnrelu(h, p, "bn3"), p["conv3_w"])
+        sc = F.conv2d(a1, p["ds_w"], stride=t["stride"]) if t["has_ds"] else u
+        u = h + sc
+    f = bnrelu(u, tp[B], "bn")
+    z = F.linear(f.mean(dim=(2, 3)), tp[B]["fc_w"], tp[B]["fc_b"])
+    return F.cross_entropy(z, torch.tensor(np.asarray(labels), dtype=torch.long)), tp
+
+
+@pytest.mark.parametrize("name", ["preact_basic", "preact_bottleneck"])
+@pytest.mark.parametrize("drop", [False, True])
+def test_preact_gradients_match_autograd_library(name, drop):
+    model = _preact_models()[name]
+    B = sum(model["blocks"])
+    blocks = [b for b in range(B) if not (drop and b == 1)]
+    params = make_params(model, 3, perturb_bn=True)
+    x, y = make_batch(model, 4, 5)
+    loss, grads, _, _ = OR.forward_backward(model, blocks, params, x, y)
+    tl, tp = _torch_loss_preact(model, blocks, params, x, y)
+    tl.backward()
+    assert math.isclose(loss, float(tl.detach()), rel_tol=1e-12)
+    assert set(grads.keys()) == set([-1, B] + blocks)
+    for b in grads:
+        assert set(grads[b]) == {k for k in params[b] if OR.is_trainable(k)}
+        for k, g in grads[b].items():
+            np.testing.assert_allclose(g, tp[b][k].grad.numpy(), rtol=1e-8, atol=1e-11, err_msg=f"block {b} {k}")
+
+
+@pytest.mark.parametrize("name", ["preact_basic", "preact_bottleneck"])
+def test_preact_finite_differences_sampled(name):
+    model = _preact_models()[name]
+    blocks = [0, 2, 3]
+    params = {b: {k: v.astype(np.float64) for k, v in p.items()}
+              for b, p in make_params(model, 11, perturb_bn=True).items()}
+    x, y = make_batch(model, 3, 12)
+    loss, grads, _, dx = OR.forward_backward(model, blocks, params, x, y, need_input_grad=True)
+    rng = np.random.default_rng(0)
+    h = 1e-5
+    for b, gb in grads.items():
+        for k, g in gb.items():
+            flat = params[b][k].reshape(-1)
+            for i in rng.choice(flat.size, size=min(6, flat.size), replace=False):
+                old = flat[i]
+                flat[i] = old + h
+                lp = OR.forward_backward(model, blocks, params, x, y, backward=False)[0]
+                flat[i] = old - h
+                lm = OR.forward_backward(model, blocks, params, x, y, backward=False)[0]
+                flat[i] = old
+                fd = (lp - lm) / (2 * h)
+                assert abs(fd - g.reshape(-1)[i]) <= 1e-7 + 1e-5 * abs(fd), f"block {b} {k}[{i}]"
+    xd = x.astype(np.float64)
+    for idx in [(0, 0, 3, 3), (2, 2, 7, 1)]:
+        e = np.zeros_like(xd)
+        e[idx] = h
+        fd = (OR.forward_backward(model, blocks, params, xd + e, y, backward=False)[0]
+              - OR.forward_backward(model, blocks, params, xd - e, y, backward=False)[0]) / (2 * h)
+        assert abs(fd - dx[idx]) <= 1e-7 + 1e-5 * abs(fd)
+
+
+def test_preact_step_updates_every_tensor_and_running_statistics():
+    model = _preact_models()["preact_basic"]
+    params = make_params(model, 2)
+    x, y = make_batch(model, 4, 3)
+    _, grads, new_p, _ = OR.local_step(model, [0, 2], params, zeros_like_params(params), x, y, 0.1, 0.9, 1e-3)
+    assert OR.param_count(model, -1) == params[-1]["conv_w"].size
+    for b in (-1, 0, 2, 4):
+        assert sum(g.size for g in grads[b].values()) == OR.param_count(model, b)
+        for k in params[b]:
+            assert not np.array_equal(new_p[b][k], params[b][k]), (b, k)      # running stats included
+    assert 1 not in new_p and 3 not in new_p

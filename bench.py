@@ -35,6 +35,8 @@ def _describe(name, cfg, sub):
     if name == "cfg1":
         return "cfg1: tiny 2-block network"
     shape = "ImageNet-shaped bottleneck" if cfg["model"]["block_kind"] == 1 else "CIFAR-shaped"
+    if cfg["model"]["block_kind"] >= 2:
+        shape += " pre-activation"
     if cfg["S"] == 1:
         return f"{name}: {shape} full model (S=1)"
     return f"{name}: {shape} sub-ResNet {sub} of S={cfg['S']}"
@@ -106,7 +108,7 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2",
-                    help="cfg1 | cfg2 | cfg3 | cfg5 (fp32) | cfg4 | cfg5_bf16 (bf16 storage, fp32 accumulation)")
+                    help="cfg1 | cfg2 | cfg2_preact | cfg3 | cfg5 (fp32) | cfg4 | cfg5_bf16 (bf16 storage, fp32 accumulation)")
     ap.add_argument("--sub", type=int, default=0, help="which sub-ResNet of the partition to step")
     ap.add_argument("--round", action="store_true",
                     help="time one full round instead: every sub-ResNet runs its local iterations on fresh "
@@ -215,7 +217,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": _describe(args.workload, cfg, args.sub),
-                   "batch": batch, "blocks": blocks, "block_kind": "basic" if model["block_kind"] == 0 else "bottleneck",
+                   "batch": batch, "blocks": blocks, "block_kind": ["basic", "bottleneck", "pre-activation basic", "pre-activation bottleneck"][model["block_kind"]],
                    "widths": model["widths"], "blocks_per_stage": model["blocks"], "classes": model["num_classes"]},
         "roofline": roof,
         "cpu_baseline": cpu,

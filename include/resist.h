@@ -21,7 +21,9 @@
  *     [ trainable tensors ... | BN running statistics ... ]
  *   trainable part, in order: conv1 W, bn1 gamma, bn1 beta, conv2 W, bn2 gamma, bn2 beta,
  *   [conv3 W, bn3 gamma, bn3 beta,] [downsample W, its gamma, its beta]; stem: conv W, gamma,
- *   beta; head: fc W [classes][C], fc bias.  Then running mean, running var of each BN in the
+ *   beta; head: fc W [classes][C], fc bias.  Pre-activation kinds: bn1 gamma, beta, conv1 W, bn2
+ *   gamma, beta, conv2 W, [bn3 gamma, beta, conv3 W,] [downsample W]; stem: conv W; head: bn
+ *   gamma, beta, fc W, fc bias.  Then running mean, running var of each BN in the
  *   same order.  Each tensor starts at a multiple of 4 floats (zero padding after it if needed).
  *   Convolution weights are stored [K][R][S][C] (output channel, filter row, filter column, input
  *   channel; C fastest), i.e. element (k,c,r,s) of the logical [K,C,R,S] filter sits at
@@ -52,7 +54,12 @@ typedef enum {
 /* The GLOBAL ResNet (Sec. 2.1: sections of blocks of equal channel width).  Plain data. */
 typedef struct {
   int32_t block_kind;    /* 0 basic: conv3x3-BN-ReLU-conv3x3-BN, +shortcut, ReLU
-                            1 bottleneck: conv1x1-BN-ReLU-conv3x3-BN-ReLU-conv1x1(x4)-BN, +, ReLU */
+                            1 bottleneck: conv1x1-BN-ReLU-conv3x3-BN-ReLU-conv1x1(x4)-BN, +, ReLU
+                            2, 3: the same two in pre-activation form (Sec. 2.1, Fig. 2):
+                               BN-ReLU before every convolution, shortcut added without a ReLU;
+                               the stem is the bare convolution (stem_kind 0 only), the head starts
+                               with BN-ReLU, a shape-changing shortcut is conv1x1(stride) applied to
+                               the block's first ReLU output, without BN                          */
   int32_t stem_kind;     /* 0: conv3x3 stride 1 pad 1, BN, ReLU
                             1: conv7x7 stride 2 pad 3, BN, ReLU, maxpool 3x3 stride 2 pad 1       */
   int32_t in_c, in_h, in_w;

@@ -137,7 +137,7 @@ def _tensor_name(block, B, t):
         return "fc_w"
     if t["kind"] == 6:
         return "fc_b"
-    if block == -1:
+    if block == -1 or block == B:
         return ("conv" if t["kind"] == 0 else "bn") + _KIND_SUFFIX[t["kind"]]
     conv = ["conv1", "conv2", "conv3", "ds"][t["layer"]]
     bn = ["bn1", "bn2", "bn3", "dsbn"][t["layer"]]

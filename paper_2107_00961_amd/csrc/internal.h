@@ -76,6 +76,8 @@ struct Net {
   int body_h, body_w;               // after optional max-pool
   int head_c;                       // channels entering the head
   int expansion;
+  bool preact;       // BN-ReLU before every convolution, no ReLU after the add (block_kind 2, 3)
+  bool bottleneck;   // 1x1-3x3-1x1 blocks with expansion 4 (block_kind 1, 3)
 };
 
 int build_net(const resist_model_desc *desc, Net *net);          // validates

@@ -23,7 +23,9 @@ static int out_dim(int in, int k, int stride, int pad) { return (in + 2 * pad - 
 
 int build_net(const resist_model_desc *d, Net *net) {
   if (!d) return set_error(RESIST_EINVAL, "model description is NULL");
-  if (d->block_kind < 0 || d->block_kind > 1) return set_error(RESIST_EINVAL, "block_kind %d", d->block_kind);
+  if (d->block_kind < 0 || d->block_kind > 3) return set_error(RESIST_EINVAL, "block_kind %d", d->block_kind);
+  if (d->block_kind >= 2 && d->stem_kind != 0)
+    return set_error(RESIST_EUNSUPPORTED, "pre-activation networks take the 3x3 stem (stem_kind 0)");
   if (d->stem_kind < 0 || d->stem_kind > 1) return set_error(RESIST_EINVAL, "stem_kind %d", d->stem_kind);
   if (d->compute_dtype < 0 || d->compute_dtype > 1) return set_error(RESIST_EINVAL, "compute_dtype %d", d->compute_dtype);
   if (d->num_stages < 1 || d->num_stages > RESIST_MAX_STAGES) return set_error(RESIST_EINVAL, "num_stages %d", d->num_stages);
@@ -35,7 +37,9 @@ int build_net(const resist_model_desc *d, Net *net) {
     if (d->blocks[i] < 1) return set_error(RESIST_ESHAPE, "blocks[%d]=%d", i, d->blocks[i]);
   }
   net->d = *d;
-  net->expansion = d->block_kind == 1 ? 4 : 1;
+  net->preact = d->block_kind >= 2;
+  net->bottleneck = (d->block_kind & 1) != 0;
+  net->expansion = net->bottleneck ? 4 : 1;
   net->stem_rs = d->stem_kind == 0 ? 3 : 7;
   net->stem_stride = d->stem_kind == 0 ? 1 : 2;
   net->stem_pad = d->stem_kind == 0 ? 1 : 3;
@@ -88,14 +92,43 @@ int block_layout(const Net &net, int block, BlockLayout *L) {
     push(L, T_BETA, layer, K, K);
     bns.push_back({layer, K});
   };
-  if (block == -1) {
+  // pre-activation: the BN of layer j sits before convolution j and has its input channels
+  auto bn_conv = [&](int layer, int K, int R, int C) {
+    push(L, T_GAMMA, layer, C, C);
+    push(L, T_BETA, layer, C, C);
+    push(L, T_CONVW, layer, (int64_t)K * R * R * C, K, R, R, C);
+    bns.push_back({layer, C});
+  };
+  if (net.preact) {
+    if (block == -1) {
+      push(L, T_CONVW, 0, (int64_t)net.d.width[0] * net.stem_rs * net.stem_rs * net.d.in_c, net.d.width[0], net.stem_rs,
+           net.stem_rs, net.d.in_c);
+    } else if (block == B) {
+      push(L, T_GAMMA, 0, net.head_c, net.head_c);
+      push(L, T_BETA, 0, net.head_c, net.head_c);
+      bns.push_back({0, net.head_c});
+      push(L, T_FCW, 0, (int64_t)net.d.num_classes * net.head_c, net.d.num_classes, net.head_c);
+      push(L, T_FCB, 0, net.d.num_classes, net.d.num_classes);
+    } else {
+      const BlockShape &b = net.blocks[block];
+      if (!net.bottleneck) {
+        bn_conv(0, b.width, 3, b.c_in);
+        bn_conv(1, b.c_out, 3, b.width);
+      } else {
+        bn_conv(0, b.width, 1, b.c_in);
+        bn_conv(1, b.width, 3, b.width);
+        bn_conv(2, b.c_out, 1, b.width);
+      }
+      if (b.has_ds) push(L, T_CONVW, 3, (int64_t)b.c_out * b.c_in, b.c_out, 1, 1, b.c_in);
+    }
+  } else if (block == -1) {
     conv_bn(0, net.d.width[0], net.stem_rs, net.d.in_c);
   } else if (block == B) {
     push(L, T_FCW, 0, (int64_t)net.d.num_classes * net.head_c, net.d.num_classes, net.head_c);
     push(L, T_FCB, 0, net.d.num_classes, net.d.num_classes);
   } else {
     const BlockShape &b = net.blocks[block];
-    if (net.d.block_kind == 0) {
+    if (!net.bottleneck) {
       conv_bn(0, b.width, 3, b.c_in);
       conv_bn(1, b.c_out, 3, b.width);
     } else {

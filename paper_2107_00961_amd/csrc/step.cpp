@@ -166,7 +166,7 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
     BlockPlan &bp = P->blocks[i];
     bp.slot = i + 1;
     bp.in = cur;
-    if (net.d.block_kind == 0) {
+    if (!net.bottleneck) {
       bp.convs.push_back(make_conv(L, 0, N, bs.h_in, bs.w_in, bs.c_in, bs.width, 3, bs.stride, 1));
       bp.convs.push_back(make_conv(L, 1, N, bs.h_out, bs.w_out, bs.width, bs.c_out, 3, 1, 1));
     } else {
@@ -252,6 +252,7 @@ int build_forward_plan(const resist_model_desc *desc, const int32_t *blocks, int
                        ForwardPlan *P) {
   RESIST_TRY(build_net(desc, &P->net));
   const Net &net = P->net;
+  if (net.preact) return set_error(RESIST_EUNSUPPORTED, "the test-time forward pass covers post-activation networks only");
   RESIST_TRY(check_block_list(net, blocks, nblocks, batch));
   const int B = (int)net.blocks.size();
   const int N = batch, es = esize(net.d.compute_dtype);
@@ -274,7 +275,7 @@ int build_forward_plan(const resist_model_desc *desc, const int32_t *blocks, int
     const BlockLayout &L = P->layouts[i + 1];
     BlockPlan &bp = P->blocks[i];
     bp.slot = i + 1;
-    if (net.d.block_kind == 0) {
+    if (!net.bottleneck) {
       bp.convs.push_back(make_conv(L, 0, N, bs.h_in, bs.w_in, bs.c_in, bs.width, 3, bs.stride, 1));
       bp.convs.push_back(make_conv(L, 1, N, bs.h_out, bs.w_out, bs.width, bs.c_out, 3, 1, 1));
     } else {
@@ -350,6 +351,285 @@ BnBufs bn_eval_bufs(const ConvLayer &c, float *params, float *affine) {
   return b;
 }
 
+// ---- pre-activation networks (block_kind 2, 3) -------------------------------------------------------
+// A block is a chain of units  a_j = ReLU(BN_j(u_j)), h_j = conv_j(a_j)  with u_1 = the block input and
+// u_j = h_{j-1};  out = h_n + shortcut, shortcut = input or conv1x1(stride)(a_1).  The statistics of a
+// tensor are taken by the convolution that writes it (the stem convolution, or a block's last
+// convolution after the shortcut has been added), so every BN starts from per-tile sums.
+struct PreUnit {
+  ConvGeom g;
+  int64_t w_off, gamma_off, beta_off, rmean_off, rvar_off;
+  const void *u = nullptr;   // BN input
+  void *a = nullptr;         // ReLU(BN(u)): the convolution's input, kept for the backward pass
+  void *h = nullptr;         // convolution output (the block output for the last unit)
+  float *mean = nullptr, *invstd = nullptr, *scale = nullptr, *shift = nullptr;   // [g.C] each
+  void *wlp = nullptr, *wT = nullptr;
+  int64_t rows() const { return (int64_t)g.N * g.H * g.W; }   // rows of the BN input
+};
+
+struct PreBlock {
+  int slot;
+  const void *x = nullptr;
+  std::vector<PreUnit> units;
+  bool has_ds = false;
+  ConvGeom dsg;
+  int64_t ds_w_off = 0;
+  void *ds_wlp = nullptr, *ds_wT = nullptr;
+  void *out = nullptr;
+};
+
+struct PrePlan {
+  Net net;
+  std::vector<BlockLayout> layouts;
+  int kpad = 0;
+  ConvGeom stem;
+  int64_t stem_w_off = 0;
+  void *col = nullptr, *wpad = nullptr, *x0 = nullptr;
+  float *dwpad = nullptr;
+  std::vector<PreBlock> blocks;
+  // head: BN-ReLU, mean pool, FC
+  int64_t head_rows = 0;
+  float *hmean = nullptr, *hinvstd = nullptr, *hscale = nullptr, *hshift = nullptr;
+  float *pooled = nullptr, *z = nullptr, *dz = nullptr, *row_loss = nullptr, *dpooled = nullptr;
+  const void *feat_in = nullptr;
+  int feat_hw = 0;
+  void *gbuf[2] = {nullptr, nullptr}, *sc = nullptr, *dsgrad = nullptr, *dy0 = nullptr, *dy1 = nullptr, *da = nullptr;
+  float *splitk = nullptr, *stats = nullptr;
+  double *bn_scratch = nullptr;
+  std::vector<float *> own_grads;
+  int64_t bytes = 0;
+};
+
+int build_preact_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks, int32_t batch, void *ws, PrePlan *P) {
+  RESIST_TRY(build_net(desc, &P->net));
+  const Net &net = P->net;
+  RESIST_TRY(check_block_list(net, blocks, nblocks, batch));
+  const int B = (int)net.blocks.size();
+  const int N = batch, es = esize(net.d.compute_dtype);
+  const bool lp = net.d.compute_dtype == DT_BF16;
+  Arena A(ws);
+  P->layouts.resize(nblocks + 2);
+  RESIST_TRY(block_layout(net, -1, &P->layouts[0]));
+  for (int i = 0; i < nblocks; ++i) RESIST_TRY(block_layout(net, blocks[i], &P->layouts[i + 1]));
+  RESIST_TRY(block_layout(net, B, &P->layouts[nblocks + 1]));
+  int64_t max_act = 0, max_splitk = 0, max_stats = 0;
+  int max_c = 16;
+  auto track = [&](const ConvGeom &g, bool stats) {
+    max_act = std::max<int64_t>(max_act, (int64_t)g.N * g.P * g.Q * g.K);
+    max_act = std::max<int64_t>(max_act, (int64_t)g.N * g.H * g.W * g.C);
+    max_splitk = std::max<int64_t>(max_splitk, wgrad_scratch_floats(g));
+    if (stats) max_stats = std::max<int64_t>(max_stats, conv_stats_floats(g));
+    max_c = std::max(max_c, std::max(g.K, g.C));
+  };
+  const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
+  P->kpad = (taps + 31) / 32 * 32;
+  const int K0 = net.d.width[0];
+  P->stem = make_geom(N, net.stem_h, net.stem_w, P->kpad, K0, 1, 1, 0);
+  P->stem_w_off = P->layouts[0].off(T_CONVW, 0);
+  const int64_t M0 = (int64_t)N * net.stem_h * net.stem_w;
+  P->col = A.take_act(M0 * P->kpad, es);
+  P->wpad = A.take_act((int64_t)K0 * P->kpad, es);
+  P->dwpad = A.take<float>((int64_t)K0 * P->kpad);
+  P->x0 = A.take_act(M0 * K0, es);
+  track(P->stem, true);
+  const void *cur = P->x0;
+  P->blocks.resize(nblocks);
+  for (int i = 0; i < nblocks; ++i) {
+    const BlockShape &bs = net.blocks[blocks[i]];
+    const BlockLayout &L = P->layouts[i + 1];
+    PreBlock &pb = P->blocks[i];
+    pb.slot = i + 1;
+    pb.x = cur;
+    std::vector<ConvGeom> gs;
+    if (!net.bottleneck) {
+      gs.push_back(make_geom(N, bs.h_in, bs.w_in, bs.c_in, bs.width, 3, bs.stride, 1));
+      gs.push_back(make_geom(N, bs.h_out, bs.w_out, bs.width, bs.c_out, 3, 1, 1));
+    } else {
+      gs.push_back(make_geom(N, bs.h_in, bs.w_in, bs.c_in, bs.width, 1, 1, 0));
+      gs.push_back(make_geom(N, bs.h_in, bs.w_in, bs.width, bs.width, 3, bs.stride, 1));
+      gs.push_back(make_geom(N, bs.h_out, bs.w_out, bs.width, bs.c_out, 1, 1, 0));
+    }
+    const void *u = cur;
+    for (size_t j = 0; j < gs.size(); ++j) {
+      PreUnit un;
+      un.g = gs[j];
+      un.w_off = L.off(T_CONVW, (int)j);
+      un.gamma_off = L.off(T_GAMMA, (int)j);
+      un.beta_off = L.off(T_BETA, (int)j);
+      un.rmean_off = L.off(T_RMEAN, (int)j);
+      un.rvar_off = L.off(T_RVAR, (int)j);
+      un.u = u;
+      un.a = A.take_act(un.rows() * un.g.C, es);
+      un.h = A.take_act((int64_t)N * un.g.P * un.g.Q * un.g.K, es);
+      float *p = A.take<float>((int64_t)4 * un.g.C);
+      un.mean = p; un.invstd = p + un.g.C; un.scale = p + 2 * un.g.C; un.shift = p + 3 * un.g.C;
+      const int64_t nf = (int64_t)un.g.K * un.g.R * un.g.S * un.g.C;
+      un.wT = A.take_act(nf, es);
+      if (lp) un.wlp = A.take_act(nf, es);
+      track(un.g, true);
+      u = un.h;
+      pb.units.push_back(un);
+    }
+    pb.has_ds = bs.has_ds;
+    if (bs.has_ds) {
+      pb.dsg = make_geom(N, bs.h_in, bs.w_in, bs.c_in, bs.c_out, 1, bs.stride, 0);
+      pb.ds_w_off = L.off(T_CONVW, 3);
+      const int64_t nf = (int64_t)bs.c_out * bs.c_in;
+      pb.ds_wT = A.take_act(nf, es);
+      if (lp) pb.ds_wlp = A.take_act(nf, es);
+      track(pb.dsg, false);
+    }
+    pb.out = pb.units.back().h;
+    cur = pb.out;
+  }
+  const BlockShape &last = net.blocks[blocks[nblocks - 1]];
+  P->feat_in = cur;
+  P->feat_hw = last.h_out * last.w_out;
+  P->head_rows = (int64_t)N * P->feat_hw;
+  {
+    float *p = A.take<float>((int64_t)4 * net.head_c);
+    P->hmean = p; P->hinvstd = p + net.head_c; P->hscale = p + 2 * net.head_c; P->hshift = p + 3 * net.head_c;
+    max_c = std::max(max_c, net.head_c);
+    const int J = net.d.num_classes;
+    P->pooled = A.take<float>((int64_t)N * net.head_c);
+    P->dpooled = A.take<float>((int64_t)N * net.head_c);
+    P->z = A.take<float>((int64_t)N * J);
+    P->dz = A.take<float>((int64_t)N * J);
+    P->row_loss = A.take<float>(N);
+  }
+  P->gbuf[0] = A.take_act(max_act, es);
+  P->gbuf[1] = A.take_act(max_act, es);
+  P->sc = A.take_act(max_act, es);
+  P->dsgrad = A.take_act(max_act, es);
+  P->dy0 = A.take_act(max_act, es);
+  P->dy1 = A.take_act(max_act, es);
+  P->da = A.take_act(max_act, es);
+  P->splitk = A.take<float>(max_splitk);
+  P->stats = A.take<float>(max_stats);
+  P->bn_scratch = A.take<double>(bn_scratch_doubles(max_c));
+  P->own_grads.resize(nblocks + 2);
+  for (int i = 0; i < nblocks + 2; ++i) P->own_grads[i] = A.take<float>(P->layouts[i].n_trainable);
+  P->bytes = (A.off + 255) & ~(int64_t)255;
+  return RESIST_OK;
+}
+
+BnBufs pre_bn_bufs(const PreUnit &un, float *params, float *grads) {
+  BnBufs b{};
+  b.gamma = params + un.gamma_off;
+  b.beta = params + un.beta_off;
+  b.rmean = params + un.rmean_off;
+  b.rvar = params + un.rvar_off;
+  b.mean = un.mean; b.invstd = un.invstd; b.scale = un.scale; b.shift = un.shift;
+  b.dgamma = grads + un.gamma_off;
+  b.dbeta = grads + un.beta_off;
+  return b;
+}
+
+int local_step_preact(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks, void *const *block_params,
+                      void *const *block_momentum, void *const *block_grads, const float *x, const int32_t *labels,
+                      int32_t batch, float lr, float momentum, float weight_decay, void *workspace, int64_t workspace_bytes,
+                      float *loss_out, hipStream_t st) {
+  PrePlan P;
+  RESIST_TRY(build_preact_plan(desc, blocks, nblocks, batch, workspace, &P));
+  if (workspace_bytes < P.bytes) return set_error(RESIST_EWORKSPACE, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes, (long long)P.bytes);
+  const Net &net = P.net;
+  const int nslots = nblocks + 2, N = batch, dt = net.d.compute_dtype;
+  const float eps = net.d.bn_eps, bnm = net.d.bn_momentum;
+  auto params = [&](int slot) { return (float *)block_params[slot]; };
+  auto grads = [&](int slot) { return block_grads ? (float *)block_grads[slot] : P.own_grads[slot]; };
+  {
+    std::vector<FilterPrep> prep;
+    for (PreBlock &pb : P.blocks) {
+      float *pp = params(pb.slot);
+      for (PreUnit &un : pb.units) prep.push_back(FilterPrep{un.g, pp + un.w_off, un.wlp, un.wT});
+      if (pb.has_ds) prep.push_back(FilterPrep{pb.dsg, pp + pb.ds_w_off, pb.ds_wlp, pb.ds_wT});
+    }
+    RESIST_TRY(prepare_filters(prep, dt, st));
+  }
+  auto fwd_filter = [&](const float *w, const void *wlp) -> const void * { return dt == DT_F32 ? (const void *)w : wlp; };
+
+  // ================= forward =================
+  const int K0 = net.d.width[0];
+  const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
+  int parts = 0;   // number of per-tile sums the last statistics-taking convolution left in P.stats
+  RESIST_TRY(stem_im2col(dt, x, P.col, N, net.d.in_c, net.d.in_h, net.d.in_w, net.stem_rs, net.stem_stride, net.stem_pad,
+                         net.stem_h, net.stem_w, P.kpad, st));
+  RESIST_TRY(pad_rows(dt, params(0) + P.stem_w_off, P.wpad, K0, taps, P.kpad, st));
+  RESIST_TRY(conv_fwd(P.stem, dt, P.col, P.wpad, P.x0, nullptr, P.stats, &parts, st));
+  for (PreBlock &pb : P.blocks) {
+    float *pp = params(pb.slot), *gg = grads(pb.slot);
+    const size_t n = pb.units.size();
+    for (size_t j = 0; j < n; ++j) {
+      PreUnit &un = pb.units[j];
+      BnBufs b = pre_bn_bufs(un, pp, gg);
+      RESIST_TRY(bn_finalize(P.stats, parts, un.rows(), un.g.C, b, eps, bnm, P.bn_scratch, st));
+      RESIST_TRY(bn_apply(dt, un.u, un.rows(), un.g.C, b, nullptr, nullptr, true, un.a, st));
+      if (j == 0 && pb.has_ds)
+        RESIST_TRY(conv_fwd(pb.dsg, dt, un.a, fwd_filter(pp + pb.ds_w_off, pb.ds_wlp), P.sc, nullptr, nullptr, nullptr, st));
+      const void *addend = j + 1 == n ? (pb.has_ds ? (const void *)P.sc : pb.x) : nullptr;
+      RESIST_TRY(conv_fwd(un.g, dt, un.a, fwd_filter(pp + un.w_off, un.wlp), un.h, addend, P.stats, &parts, st));
+    }
+  }
+  const int J = net.d.num_classes, CH = net.head_c;
+  const int hs = nslots - 1;
+  const BlockLayout &HL = P.layouts[hs];
+  float *hp = params(hs), *hg = grads(hs);
+  BnBufs hb{};
+  hb.gamma = hp + HL.off(T_GAMMA, 0); hb.beta = hp + HL.off(T_BETA, 0);
+  hb.rmean = hp + HL.off(T_RMEAN, 0); hb.rvar = hp + HL.off(T_RVAR, 0);
+  hb.mean = P.hmean; hb.invstd = P.hinvstd; hb.scale = P.hscale; hb.shift = P.hshift;
+  hb.dgamma = hg + HL.off(T_GAMMA, 0); hb.dbeta = hg + HL.off(T_BETA, 0);
+  float *fcw = hp + HL.off(T_FCW, 0), *fcb = hp + HL.off(T_FCB, 0);
+  RESIST_TRY(bn_finalize(P.stats, parts, P.head_rows, CH, hb, eps, bnm, P.bn_scratch, st));
+  RESIST_TRY(bn_apply(dt, P.feat_in, P.head_rows, CH, hb, nullptr, nullptr, true, P.da, st));
+  RESIST_TRY(avgpool_fwd(dt, P.da, P.pooled, N, P.feat_hw, CH, st));
+  RESIST_TRY(fc_fwd_f32(P.pooled, fcw, fcb, P.z, N, CH, J, st));
+  RESIST_TRY(softmax_ce_f32(P.z, labels, loss_out, P.dz, P.row_loss, N, J, st));
+
+  // ================= backward =================
+  RESIST_TRY(fc_bwd_f32(P.dz, P.pooled, fcw, P.dpooled, hg + HL.off(T_FCW, 0), hg + HL.off(T_FCB, 0), N, CH, J, st));
+  RESIST_TRY(avgpool_bwd(dt, P.dpooled, P.da, N, P.feat_hw, CH, st));
+  int gi = 0;
+  RESIST_TRY(bn_backward(dt, P.da, nullptr, true, P.feat_in, P.head_rows, CH, hb, P.gbuf[gi], nullptr, nullptr, P.bn_scratch, st));
+  for (int bi = (int)P.blocks.size() - 1; bi >= 0; --bi) {
+    PreBlock &pb = P.blocks[bi];
+    float *pp = params(pb.slot), *gg = grads(pb.slot);
+    void *G = P.gbuf[gi], *Gn = P.gbuf[gi ^ 1];
+    const void *gcur = G;
+    void *dy = P.dy0, *dy_other = P.dy1;
+    for (int j = (int)pb.units.size() - 1; j >= 0; --j) {
+      PreUnit &un = pb.units[j];
+      RESIST_TRY(conv_wgrad(un.g, dt, gcur, un.a, gg + un.w_off, P.splitk, st));
+      const void *addend = nullptr;
+      if (j == 0 && pb.has_ds) {
+        // the shortcut convolution reads the same a_1: its data gradient joins the branch's
+        RESIST_TRY(conv_wgrad(pb.dsg, dt, G, un.a, gg + pb.ds_w_off, P.splitk, st));
+        RESIST_TRY(conv_dgrad(pb.dsg, dt, G, pb.ds_wT, P.dsgrad, nullptr, st));
+        addend = P.dsgrad;
+      }
+      RESIST_TRY(conv_dgrad(un.g, dt, gcur, un.wT, P.da, addend, st));
+      BnBufs b = pre_bn_bufs(un, pp, gg);
+      if (j > 0) {
+        RESIST_TRY(bn_backward(dt, P.da, nullptr, true, un.u, un.rows(), un.g.C, b, dy, nullptr, nullptr, P.bn_scratch, st));
+        gcur = dy;
+        std::swap(dy, dy_other);
+      } else {
+        // gradient w.r.t. the block input: through BN_1, plus the identity shortcut's share
+        RESIST_TRY(bn_backward(dt, P.da, nullptr, true, un.u, un.rows(), un.g.C, b, Gn, nullptr, pb.has_ds ? nullptr : G, P.bn_scratch, st));
+      }
+    }
+    gi ^= 1;
+  }
+  RESIST_TRY(conv_wgrad(P.stem, dt, P.gbuf[gi], P.col, P.dwpad, P.splitk, st));
+  RESIST_TRY(unpad_rows_f32(P.dwpad, grads(0) + P.stem_w_off, K0, taps, P.kpad, st));
+
+  // ================= update =================
+  std::vector<SgdSeg> segs;
+  for (int i = 0; i < nslots; ++i)
+    segs.push_back(SgdSeg{params(i), (float *)block_momentum[i], grads(i), P.layouts[i].n_trainable});
+  return sgd_momentum_f32(segs, lr, momentum, weight_decay, st);
+}
+
 BnBufs bn_bufs(const ConvLayer &c, float *params, float *grads) {
   BnBufs b;
   b.gamma = params + c.gamma_off;
@@ -373,6 +653,12 @@ using namespace resist;
 extern "C" int resist_workspace_bytes(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks,
                                       int32_t batch, int64_t *bytes) {
   if (!bytes) return set_error(RESIST_EINVAL, "bytes is NULL");
+  if (desc && desc->block_kind >= 2) {
+    PrePlan Q;
+    RESIST_TRY(build_preact_plan(desc, blocks, nblocks, batch, nullptr, &Q));
+    *bytes = Q.bytes;
+    return RESIST_OK;
+  }
   StepPlan P;
   RESIST_TRY(build_plan(desc, blocks, nblocks, batch, nullptr, &P));
   *bytes = P.bytes;
@@ -387,6 +673,17 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
   if (!block_params || !block_momentum || !x || !labels || !workspace || !loss_out)
     return set_error(RESIST_EINVAL, "NULL argument");
   if (((uintptr_t)workspace & 15) || ((uintptr_t)x & 15)) return set_error(RESIST_EINVAL, "workspace and x must be 16-byte aligned");
+  if (desc && desc->block_kind >= 2) {
+    if (nblocks < 0) return set_error(RESIST_EINVAL, "nblocks");
+    for (int i = 0; i < nblocks + 2; ++i) {
+      if (!block_params[i] || !block_momentum[i] || (block_grads && !block_grads[i]))
+        return set_error(RESIST_EINVAL, "buffer %d is NULL", i);
+      if (((uintptr_t)block_params[i] & 15) || ((uintptr_t)block_momentum[i] & 15) || (block_grads && ((uintptr_t)block_grads[i] & 15)))
+        return set_error(RESIST_EINVAL, "buffer %d is not 16-byte aligned", i);
+    }
+    return local_step_preact(desc, blocks, nblocks, block_params, block_momentum, block_grads, x, labels, batch, lr, momentum,
+                             weight_decay, workspace, workspace_bytes, loss_out, (hipStream_t)hip_stream);
+  }
   StepPlan P;
   RESIST_TRY(build_plan(desc, blocks, nblocks, batch, workspace, &P));
   if (workspace_bytes < P.bytes) return set_error(RESIST_EWORKSPACE, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes, (long long)P.bytes);

@@ -24,6 +24,9 @@ CONFIGS = {
     # CIFAR-shaped sub-ResNet (the configuration the metric is quoted on)
     "cfg2": dict(model=_model(0, 0, 32, [64, 128, 256, 512], [3, 4, 23, 3], 10), batch=128, S=4,
                  part_seed=1, data_seed=0, lr=0.1, momentum=0.9, weight_decay=5e-4, min_depth=0),
+    # the same sub-ResNet with pre-activation blocks (the architecture the paper prefers)
+    "cfg2_preact": dict(model=_model(2, 0, 32, [64, 128, 256, 512], [3, 4, 23, 3], 10), batch=128, S=4,
+                        part_seed=1, data_seed=0, lr=0.1, momentum=0.9, weight_decay=5e-4, min_depth=0),
     # CIFAR-shaped full round: S=4 x 50 local iterations, 100 classes, then aggregation
     "cfg3": dict(model=_model(0, 0, 32, [64, 128, 256, 512], [3, 4, 23, 3], 100), batch=128, S=4,
                  part_seed=1, data_seed=0, lr=0.1, momentum=0.9, weight_decay=5e-4, min_depth=0,

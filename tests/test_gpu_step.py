@@ -25,6 +25,13 @@ def _small_models():
         "bottleneck_sub": (dict(basic, block_kind=1, stem_kind=1, widths=[16, 32], blocks=[2, 3], in_h=40, in_w=40,
                                 num_classes=12), [0, 2, 4], 5),  # 7x7 stem + max-pool, bottlenecks
         "ragged": (dict(basic, widths=[16, 32], blocks=[2, 2], in_h=12, in_w=12, num_classes=3), [0, 1, 2, 3], 3),
+        # pre-activation blocks (the paper's preferred architecture, Sec. 2.1)
+        "preact_sub": (dict(basic, block_kind=2, widths=[16, 32, 64], blocks=[2, 3, 2], in_h=16, in_w=16, num_classes=10),
+                       [0, 2, 3, 5], 6),
+        "preact_bottleneck_sub": (dict(basic, block_kind=3, widths=[16, 32], blocks=[2, 3], in_h=12, in_w=12, num_classes=7),
+                                  [0, 2, 4], 5),
+        "preact_full": (dict(basic, block_kind=2, widths=[16, 32], blocks=[2, 2], in_h=12, in_w=12, num_classes=3),
+                        [0, 1, 2, 3], 3),
     }
 
 
@@ -48,10 +55,14 @@ def _run_steps(model, blocks, batch, steps, lr, mu, wd, seed=0, perturb_bn=True)
     return sub
 
 
-@pytest.mark.parametrize("name", ["cfg1", "strided_sub", "bottleneck_sub", "ragged"])
+@pytest.mark.parametrize("name", ["cfg1", "strided_sub", "bottleneck_sub", "ragged", "preact_sub", "preact_bottleneck_sub",
+                                  "preact_full"])
 def test_local_step_small(name):
     model, blocks, batch = _small_models()[name]
-    _run_steps(model, blocks, batch, steps=2, lr=0.1, mu=0.9, wd=5e-4)
+    # data seeds for which the oracle's closest ReLU decision is > 1e-5 from a tie (seed 0 of
+    # "preact_full" has one at 1.6e-8: no fp32 evaluation can be expected to decide it the same way)
+    seed = {"preact_full": 1}.get(name, 0)
+    _run_steps(model, blocks, batch, steps=2, lr=0.1, mu=0.9, wd=5e-4, seed=seed)
 
 
 def test_cfg1_exact_config():
@@ -256,19 +267,20 @@ def _bf16_step_check(model, blocks, batch, lr, mu, wd, seed, what, perturb_bn=Tr
     return sub
 
 
-@pytest.mark.parametrize("name", ["cfg1", "strided_sub", "bottleneck_sub", "ragged"])
+@pytest.mark.parametrize("name", ["cfg1", "strided_sub", "bottleneck_sub", "ragged", "preact_sub", "preact_bottleneck_sub"])
 def test_local_step_small_bf16(name):
     model, blocks, batch = _small_models()[name]
     _bf16_step_check(model, blocks, batch, 0.1, 0.9, 5e-4, seed=1, what=f"bf16 {name}")
 
 
-@pytest.mark.parametrize("name", ["basic", "strided", "bottleneck"])
+@pytest.mark.parametrize("name", ["basic", "strided", "bottleneck", "preact"])
 def test_local_step_shallow_bf16_matches_emulation(name):
     basic = get_config("cfg1")["model"]
     model, blocks, batch, bar = {
         "basic": (dict(basic, widths=[64], blocks=[1], in_h=16, in_w=16), [0], 16, 5e-3),
         "strided": (dict(basic, widths=[32, 64], blocks=[1, 1], in_h=16, in_w=16), [0, 1], 16, 5e-3),
         "bottleneck": (dict(basic, block_kind=1, stem_kind=1, widths=[32], blocks=[1], in_h=32, in_w=32), [0], 16, 2e-2),
+        "preact": (dict(basic, block_kind=2, widths=[32, 64], blocks=[1, 1], in_h=16, in_w=16), [0, 1], 16, 5e-3),
     }[name]
     _bf16_step_check(model, blocks, batch, 0.1, 0.9, 5e-4, seed=3, what=f"bf16 shallow {name}", emu_bar=bar)
 

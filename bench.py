@@ -169,14 +169,20 @@ def main():
     stats = R.profile_read()
     R.profile_enable(False)
     stats.sort(key=lambda s: -s["ms"])
-    kernels = [dict(name=s["name"], launches_per_step=s["launches"] / psteps,
-                    ms_per_step=round(s["ms"] / psteps, 4),
-                    avg_us=round(s["ms"] / s["launches"] * 1e3, 2),
-                    tflops=round(s["flops"] / (s["ms"] * 1e-3) / 1e12, 2) if s["flops"] else None,
-                    gbs=round(s["bytes"] / (s["ms"] * 1e-3) / 1e9, 1) if s["bytes"] else None)
-               for s in stats]
-    dom = stats[0]
     dtype = "bf16" if model.get("compute_dtype", 0) == 1 else "f32"
+    kernels = []
+    for s in stats:
+        tf = s["flops"] / (s["ms"] * 1e-3) / 1e12 if s["flops"] else None
+        gb = s["bytes"] / (s["ms"] * 1e-3) / 1e9 if s["bytes"] else None
+        kernels.append(dict(name=s["name"], launches_per_step=s["launches"] / psteps,
+                            ms_per_step=round(s["ms"] / psteps, 4),
+                            avg_us=round(s["ms"] / s["launches"] * 1e3, 2),
+                            tflops=round(tf, 2) if tf else None,
+                            frac_of_mfma_peak=round(tf / PEAK_TFLOPS[dtype], 4) if tf else None,
+                            gbs=round(gb, 1) if gb else None,
+                            frac_of_hbm_peak=round(gb / PEAK_HBM_GBS, 4) if gb else None,
+                            measured_hbm_bytes_per_launch=_measured_traffic(args.workload, s["name"])))
+    dom = stats[0]
     if dom["flops"] > 0:
         ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
         roof = dict(bound="mfma", kernel=dom["name"], achieved=round(ach, 2), peak=PEAK_TFLOPS[dtype],

@@ -359,6 +359,8 @@ def forward_eval(model, blocks, params, x, branch_scale=None, labels=None):
     eps = model["bn_eps"]
     if branch_scale is None:
         branch_scale = [1.0] * len(blocks)
+    if is_preact(model):
+        return _forward_eval_preact(model, blocks, params, x, branch_scale, labels)
 
     def cbn(a, p, conv, bn, stride, pad, relu, scale=1.0):
         y = L.conv2d_fwd(a, p[conv + "_w"], stride, pad)
@@ -386,6 +388,37 @@ def forward_eval(model, blocks, params, x, branch_scale=None, labels=None):
         short = cbn(a, p, "ds", "dsbn", t["stride"], 0, False) if t["has_ds"] else a
         a = np.maximum(h + short, 0.0)
     z = L.fc_fwd(L.avgpool_fwd(a), params[B]["fc_w"].astype(np.float64), params[B]["fc_b"].astype(np.float64))
+    if labels is None:
+        return z
+    loss, _ = L.softmax_ce(z, np.asarray(labels))
+    return z, loss
+
+
+def _forward_eval_preact(model, blocks, params, x, branch_scale, labels):
+    """forward_eval for pre-activation blocks:  out = shortcut + branch_scale * (last convolution of the branch)."""
+    tab = block_table(model)
+    B = len(tab)
+    eps = model["bn_eps"]
+
+    def bn_relu(u, p, bn):
+        g, b = p[bn + "_g"].astype(np.float64), p[bn + "_b"].astype(np.float64)
+        rm, rv = p[bn + "_rm"].astype(np.float64), p[bn + "_rv"].astype(np.float64)
+        z = (u - rm[None, :, None, None]) / np.sqrt(rv + eps)[None, :, None, None] * g[None, :, None, None] \
+            + b[None, :, None, None]
+        return np.maximum(z, 0.0)
+
+    u = L.conv2d_fwd(np.asarray(x, np.float64), params[-1]["conv_w"], 1, 1)
+    for b, sc in zip(blocks, branch_scale):
+        t, p = tab[b], params[b]
+        xin, a1, h = u, None, u
+        for bn, conv, k, stride, pad in _preact_layers(model, t):
+            a = bn_relu(h, p, bn)
+            a1 = a if a1 is None else a1
+            h = L.conv2d_fwd(a, p[conv + "_w"], stride, pad)
+        short = L.conv2d_fwd(a1, p["ds_w"], t["stride"], 0) if t["has_ds"] else xin
+        u = short + sc * h
+    f = bn_relu(u, params[B], "bn")
+    z = L.fc_fwd(L.avgpool_fwd(f), params[B]["fc_w"].astype(np.float64), params[B]["fc_b"].astype(np.float64))
     if labels is None:
         return z
     loss, _ = L.softmax_ce(z, np.asarray(labels))

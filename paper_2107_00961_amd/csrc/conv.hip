@@ -483,6 +483,7 @@ struct PrepTable {
   void *wlp[kPrepSegs];
   void *wT[kPrepSegs];
   int K[kPrepSegs], RS[kPrepSegs], C[kPrepSegs];
+  float scale[kPrepSegs];
   int first_wg[kPrepSegs + 1];
   int nseg;
 };
@@ -498,6 +499,7 @@ __global__ __launch_bounds__(256) void prepare_filters_kernel(PrepTable t) {
   id /= ct;
   const int k0 = (id % kt) * 32, tap = id / kt;
   const float *__restrict__ w = t.w[seg];
+  const float sc = t.scale[seg];
   T *__restrict__ wlp = static_cast<T *>(t.wlp[seg]);
   T *__restrict__ wT = static_cast<T *>(t.wT[seg]);
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
@@ -505,7 +507,7 @@ __global__ __launch_bounds__(256) void prepare_filters_kernel(PrepTable t) {
     const int k = k0 + i, c = c0 + tx;
     float v = 0.f;
     if (k < K && c < C) {
-      v = w[((size_t)k * RS + tap) * C + c];
+      v = w[((size_t)k * RS + tap) * C + c] * sc;
       if (wlp) wlp[((size_t)k * RS + tap) * C + c] = Elem<T>::from_f32(v);
     }
     tile[i][tx] = v;
@@ -530,6 +532,7 @@ int prepare_filters(const std::vector<FilterPrep> &items, int dt, hipStream_t st
       const int n = t.nseg++;
       t.w[n] = f.w; t.wlp[n] = f.w_lp; t.wT[n] = f.wT;
       t.K[n] = f.g.K; t.RS[n] = f.g.R * f.g.S; t.C[n] = f.g.C;
+      t.scale[n] = f.scale;
       t.first_wg[n] = wg;
       wg += ((f.g.C + 31) / 32) * ((f.g.K + 31) / 32) * f.g.R * f.g.S;
       bytes += (4.0 + (f.w_lp ? esize(dt) : 0) + (f.wT ? esize(dt) : 0)) * f.g.K * f.g.R * f.g.S * f.g.C;

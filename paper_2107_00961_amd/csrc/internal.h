@@ -114,8 +114,8 @@ int conv_dgrad(const ConvGeom &g, int dt, const void *dy, const void *wT, void *
                hipStream_t st);
 // from a filter stored in src_dt: optional copy in dt (w_lp) and optional transpose in dt (wT)
 int prepare_filter(const ConvGeom &g, int src_dt, int dt, const void *w, void *w_lp, void *wT, hipStream_t st);
-// the same for many filters at once (fp32 masters -> copies and transposes in dt)
-struct FilterPrep { ConvGeom g; const float *w; void *w_lp; void *wT; };
+// the same for many filters at once (fp32 masters -> copies and transposes in dt, times `scale`)
+struct FilterPrep { ConvGeom g; const float *w; void *w_lp; void *wT; float scale = 1.f; };
 int prepare_filters(const std::vector<FilterPrep> &items, int dt, hipStream_t st);
 // dw (fp32) = wgrad(dy, x); partial: split-reduction scratch of wgrad_scratch_floats(g) floats
 int64_t wgrad_scratch_floats(const ConvGeom &g);

@@ -252,7 +252,6 @@ int build_forward_plan(const resist_model_desc *desc, const int32_t *blocks, int
                        ForwardPlan *P) {
   RESIST_TRY(build_net(desc, &P->net));
   const Net &net = P->net;
-  if (net.preact) return set_error(RESIST_EUNSUPPORTED, "the test-time forward pass covers post-activation networks only");
   RESIST_TRY(check_block_list(net, blocks, nblocks, batch));
   const int B = (int)net.blocks.size();
   const int N = batch, es = esize(net.d.compute_dtype);
@@ -825,9 +824,193 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
   return RESIST_OK;
 }
 
+namespace resist {
+namespace {
+
+// test-time forward of a pre-activation network: out = shortcut + s * conv_n(a_n); the scale is folded
+// into a copy of the last convolution's filter
+struct PreForwardPlan {
+  Net net;
+  std::vector<BlockLayout> layouts;
+  int kpad = 0;
+  ConvGeom stem;
+  void *col = nullptr, *wpad = nullptr;
+  std::vector<PreBlock> blocks;
+  void *abuf = nullptr, *sc = nullptr;
+  float *affine = nullptr, *pooled = nullptr, *dz = nullptr, *row_loss = nullptr;
+  const void *feat_in = nullptr;
+  int feat_hw = 0;
+  int64_t bytes = 0;
+};
+
+int build_preact_forward_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks, int32_t batch, void *ws,
+                              PreForwardPlan *P) {
+  RESIST_TRY(build_net(desc, &P->net));
+  const Net &net = P->net;
+  RESIST_TRY(check_block_list(net, blocks, nblocks, batch));
+  const int B = (int)net.blocks.size();
+  const int N = batch, es = esize(net.d.compute_dtype);
+  Arena A(ws);
+  P->layouts.resize(nblocks + 2);
+  RESIST_TRY(block_layout(net, -1, &P->layouts[0]));
+  for (int i = 0; i < nblocks; ++i) RESIST_TRY(block_layout(net, blocks[i], &P->layouts[i + 1]));
+  RESIST_TRY(block_layout(net, B, &P->layouts[nblocks + 1]));
+  const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
+  P->kpad = (taps + 31) / 32 * 32;
+  const int K0 = net.d.width[0];
+  P->stem = make_geom(N, net.stem_h, net.stem_w, P->kpad, K0, 1, 1, 0);
+  int64_t max_act = (int64_t)N * net.stem_h * net.stem_w * K0;
+  int max_c = std::max(K0, net.head_c);
+  P->blocks.resize(nblocks);
+  for (int i = 0; i < nblocks; ++i) {
+    const BlockShape &bs = net.blocks[blocks[i]];
+    const BlockLayout &L = P->layouts[i + 1];
+    PreBlock &pb = P->blocks[i];
+    pb.slot = i + 1;
+    std::vector<ConvGeom> gs;
+    if (!net.bottleneck) {
+      gs.push_back(make_geom(N, bs.h_in, bs.w_in, bs.c_in, bs.width, 3, bs.stride, 1));
+      gs.push_back(make_geom(N, bs.h_out, bs.w_out, bs.width, bs.c_out, 3, 1, 1));
+    } else {
+      gs.push_back(make_geom(N, bs.h_in, bs.w_in, bs.c_in, bs.width, 1, 1, 0));
+      gs.push_back(make_geom(N, bs.h_in, bs.w_in, bs.width, bs.width, 3, bs.stride, 1));
+      gs.push_back(make_geom(N, bs.h_out, bs.w_out, bs.width, bs.c_out, 1, 1, 0));
+    }
+    for (size_t j = 0; j < gs.size(); ++j) {
+      PreUnit un;
+      un.g = gs[j];
+      un.w_off = L.off(T_CONVW, (int)j);
+      un.gamma_off = L.off(T_GAMMA, (int)j);
+      un.beta_off = L.off(T_BETA, (int)j);
+      un.rmean_off = L.off(T_RMEAN, (int)j);
+      un.rvar_off = L.off(T_RVAR, (int)j);
+      // a copy of the filter in the compute type; the last unit's always (it carries the branch scale)
+      if (net.d.compute_dtype == DT_BF16 || j + 1 == gs.size())
+        un.wlp = A.take_act((int64_t)un.g.K * un.g.R * un.g.S * un.g.C, es);
+      max_act = std::max<int64_t>(max_act, (int64_t)N * un.g.P * un.g.Q * un.g.K);
+      max_act = std::max<int64_t>(max_act, un.rows() * un.g.C);
+      max_c = std::max(max_c, std::max(un.g.C, un.g.K));
+      pb.units.push_back(un);
+    }
+    pb.has_ds = bs.has_ds;
+    if (bs.has_ds) {
+      pb.dsg = make_geom(N, bs.h_in, bs.w_in, bs.c_in, bs.c_out, 1, bs.stride, 0);
+      pb.ds_w_off = L.off(T_CONVW, 3);
+      if (net.d.compute_dtype == DT_BF16) pb.ds_wlp = A.take_act((int64_t)bs.c_out * bs.c_in, es);
+    }
+  }
+  P->col = A.take_act((int64_t)N * net.stem_h * net.stem_w * P->kpad, es);
+  P->wpad = A.take_act((int64_t)K0 * P->kpad, es);
+  // the residual stream alternates between two buffers, the branch between two more
+  void *ubuf[2] = {A.take_act(max_act, es), A.take_act(max_act, es)};
+  void *hbuf[2] = {A.take_act(max_act, es), A.take_act(max_act, es)};
+  P->abuf = A.take_act(max_act, es);
+  P->sc = A.take_act(max_act, es);
+  const void *cur = ubuf[0];
+  int ui = 1;
+  for (PreBlock &pb : P->blocks) {
+    pb.x = cur;
+    const void *u = cur;
+    for (size_t j = 0; j < pb.units.size(); ++j) {
+      PreUnit &un = pb.units[j];
+      un.u = u;
+      un.a = P->abuf;
+      un.h = j + 1 == pb.units.size() ? ubuf[ui] : hbuf[j & 1];
+      u = un.h;
+    }
+    pb.out = ubuf[ui];
+    cur = pb.out;
+    ui ^= 1;
+  }
+  P->feat_in = cur;
+  const BlockShape &last = net.blocks[blocks[nblocks - 1]];
+  P->feat_hw = last.h_out * last.w_out;
+  P->affine = A.take<float>((int64_t)2 * max_c);
+  P->pooled = A.take<float>((int64_t)N * net.head_c);
+  P->dz = A.take<float>((int64_t)N * net.d.num_classes);
+  P->row_loss = A.take<float>(N);
+  P->bytes = (A.off + 255) & ~(int64_t)255;
+  return RESIST_OK;
+}
+
+int forward_preact(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks, void *const *block_params,
+                   const float *branch_scale, const float *x, int32_t batch, void *workspace, int64_t workspace_bytes,
+                   float *logits_out, const int32_t *labels, float *loss_out, hipStream_t st) {
+  PreForwardPlan P;
+  RESIST_TRY(build_preact_forward_plan(desc, blocks, nblocks, batch, workspace, &P));
+  if (workspace_bytes < P.bytes) return set_error(RESIST_EWORKSPACE, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes, (long long)P.bytes);
+  const Net &net = P.net;
+  const int nslots = nblocks + 2, N = batch, dt = net.d.compute_dtype;
+  const float eps = net.d.bn_eps;
+  auto params = [&](int slot) { return (float *)block_params[slot]; };
+  {
+    std::vector<FilterPrep> prep;
+    for (size_t bi = 0; bi < P.blocks.size(); ++bi) {
+      PreBlock &pb = P.blocks[bi];
+      float *pp = params(pb.slot);
+      for (size_t j = 0; j < pb.units.size(); ++j) {
+        PreUnit &un = pb.units[j];
+        if (!un.wlp) continue;
+        FilterPrep f{un.g, pp + un.w_off, un.wlp, nullptr};
+        if (j + 1 == pb.units.size() && branch_scale) f.scale = branch_scale[bi];
+        prep.push_back(f);
+      }
+      if (pb.ds_wlp) prep.push_back(FilterPrep{pb.dsg, pp + pb.ds_w_off, pb.ds_wlp, nullptr});
+    }
+    RESIST_TRY(prepare_filters(prep, dt, st));
+  }
+  const int K0 = net.d.width[0];
+  const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
+  RESIST_TRY(stem_im2col(dt, x, P.col, N, net.d.in_c, net.d.in_h, net.d.in_w, net.stem_rs, net.stem_stride, net.stem_pad,
+                         net.stem_h, net.stem_w, P.kpad, st));
+  RESIST_TRY(pad_rows(dt, params(0) + P.layouts[0].off(T_CONVW, 0), P.wpad, K0, taps, P.kpad, st));
+  RESIST_TRY(conv_fwd(P.stem, dt, P.col, P.wpad, const_cast<void *>(P.blocks[0].x), nullptr, nullptr, nullptr, st));
+  for (PreBlock &pb : P.blocks) {
+    float *pp = params(pb.slot);
+    const size_t n = pb.units.size();
+    for (size_t j = 0; j < n; ++j) {
+      PreUnit &un = pb.units[j];
+      BnBufs b{};
+      b.gamma = pp + un.gamma_off; b.beta = pp + un.beta_off; b.rmean = pp + un.rmean_off; b.rvar = pp + un.rvar_off;
+      b.scale = P.affine; b.shift = P.affine + un.g.C;
+      RESIST_TRY(bn_eval_affine(un.g.C, b, eps, 1.f, st));
+      RESIST_TRY(bn_apply(dt, un.u, un.rows(), un.g.C, b, nullptr, nullptr, true, un.a, st));
+      if (j == 0 && pb.has_ds) {
+        const void *wd = dt == DT_F32 ? (const void *)(pp + pb.ds_w_off) : pb.ds_wlp;
+        RESIST_TRY(conv_fwd(pb.dsg, dt, un.a, wd, P.sc, nullptr, nullptr, nullptr, st));
+      }
+      const void *wf = un.wlp ? un.wlp : (const void *)(pp + un.w_off);
+      const void *addend = j + 1 == n ? (pb.has_ds ? (const void *)P.sc : pb.x) : nullptr;
+      RESIST_TRY(conv_fwd(un.g, dt, un.a, wf, un.h, addend, nullptr, nullptr, st));
+    }
+  }
+  const int J = net.d.num_classes, CH = net.head_c;
+  const BlockLayout &HL = P.layouts[nslots - 1];
+  float *hp = params(nslots - 1);
+  BnBufs hb{};
+  hb.gamma = hp + HL.off(T_GAMMA, 0); hb.beta = hp + HL.off(T_BETA, 0);
+  hb.rmean = hp + HL.off(T_RMEAN, 0); hb.rvar = hp + HL.off(T_RVAR, 0);
+  hb.scale = P.affine; hb.shift = P.affine + CH;
+  RESIST_TRY(bn_eval_affine(CH, hb, eps, 1.f, st));
+  RESIST_TRY(bn_apply(dt, P.feat_in, (int64_t)N * P.feat_hw, CH, hb, nullptr, nullptr, true, P.abuf, st));
+  RESIST_TRY(avgpool_fwd(dt, P.abuf, P.pooled, N, P.feat_hw, CH, st));
+  RESIST_TRY(fc_fwd_f32(P.pooled, hp + HL.off(T_FCW, 0), hp + HL.off(T_FCB, 0), logits_out, N, CH, J, st));
+  if (labels) RESIST_TRY(softmax_ce_f32(logits_out, labels, loss_out, P.dz, P.row_loss, N, J, st));
+  return RESIST_OK;
+}
+
+}  // namespace
+}  // namespace resist
+
 extern "C" int resist_forward_workspace_bytes(const resist_model_desc *desc, const int32_t *blocks, int32_t nblocks,
                                               int32_t batch, int64_t *bytes) {
   if (!bytes) return set_error(RESIST_EINVAL, "bytes is NULL");
+  if (desc && desc->block_kind >= 2) {
+    PreForwardPlan Q;
+    RESIST_TRY(build_preact_forward_plan(desc, blocks, nblocks, batch, nullptr, &Q));
+    *bytes = Q.bytes;
+    return RESIST_OK;
+  }
   ForwardPlan P;
   RESIST_TRY(build_forward_plan(desc, blocks, nblocks, batch, nullptr, &P));
   *bytes = P.bytes;
@@ -842,6 +1025,13 @@ extern "C" int resist_forward(const resist_model_desc *desc, const int32_t *bloc
   if ((labels == nullptr) != (loss_out == nullptr)) return set_error(RESIST_EINVAL, "labels and loss_out go together");
   if (((uintptr_t)workspace & 15) || ((uintptr_t)x & 15) || ((uintptr_t)logits_out & 15))
     return set_error(RESIST_EINVAL, "workspace, x and logits_out must be 16-byte aligned");
+  if (desc && desc->block_kind >= 2) {
+    if (nblocks < 0) return set_error(RESIST_EINVAL, "nblocks");
+    for (int i = 0; i < nblocks + 2; ++i)
+      if (!block_params[i] || ((uintptr_t)block_params[i] & 15)) return set_error(RESIST_EINVAL, "buffer %d is NULL or not 16-byte aligned", i);
+    return forward_preact(desc, blocks, nblocks, block_params, branch_scale, x, batch, workspace, workspace_bytes, logits_out,
+                          labels, loss_out, (hipStream_t)hip_stream);
+  }
   ForwardPlan P;
   RESIST_TRY(build_forward_plan(desc, blocks, nblocks, batch, workspace, &P));
   if (workspace_bytes < P.bytes) return set_error(RESIST_EWORKSPACE, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes, (long long)P.bytes);

@@ -51,20 +51,24 @@ def test_two_rounds_paper_mode_partition():
             assert rel <= 2e-3, f"after {rounds} rounds: block {k} {n}: relative L2 error {rel:.3e}"
 
 
-@pytest.mark.parametrize("kind", ["basic", "bottleneck", "bottleneck_bf16"])
+@pytest.mark.parametrize("kind", ["basic", "bottleneck", "bottleneck_bf16", "preact", "preact_bottleneck_bf16"])
 def test_forward_eval_with_branch_scaling(kind):
     """resist_forward: evaluation-mode BN (running statistics) and 1/S scaling of the partitioned
     blocks' residual branches (Sec. 2.6), against the oracle; and after a reassembly, as in the method."""
     from oracle import resnet as OR
     base = get_config("cfg1")["model"]
-    if kind == "basic":
-        model = dict(base, widths=[16, 32, 64], blocks=[2, 2, 4], in_h=16, in_w=16, num_classes=10)
+    if kind in ("basic", "preact"):
+        model = dict(base, block_kind=2 if kind == "preact" else 0, widths=[16, 32, 64], blocks=[2, 2, 4], in_h=16, in_w=16,
+                     num_classes=10)
+    elif kind == "preact_bottleneck_bf16":
+        model = dict(base, block_kind=3, widths=[16, 32], blocks=[2, 3], in_h=16, in_w=16, num_classes=12, compute_dtype=1)
     else:
         model = dict(base, block_kind=1, stem_kind=1, widths=[16, 32], blocks=[2, 3], in_h=40, in_w=40, num_classes=12,
                      compute_dtype=1 if kind.endswith("bf16") else 0)
     nb = R.num_blocks(model)
     S = 4
-    first = {0, model["blocks"][0], model["blocks"][0] + model["blocks"][1]} if kind == "basic" else {0, model["blocks"][0]}
+    first = ({0, model["blocks"][0], model["blocks"][0] + model["blocks"][1]} if len(model["blocks"]) == 3
+             else {0, model["blocks"][0]})
     scale = [1.0 if b in first else 1.0 / S for b in range(nb)]
     params = make_params(model, 9, perturb_bn=True)          # non-trivial running statistics
     x, y = make_batch(model, 7, 3)

@@ -363,3 +363,32 @@ def test_preact_step_updates_every_tensor_and_running_statistics():
         for k in params[b]:
             assert not np.array_equal(new_p[b][k], params[b][k]), (b, k)      # running stats included
     assert 1 not in new_p and 3 not in new_p
+
+
+@pytest.mark.parametrize("name", ["preact_basic", "preact_bottleneck"])
+def test_preact_forward_eval_pins(name):
+    """Evaluation-mode forward of the pre-activation network: equals the training-mode forward when the
+    running statistics are this batch's own; a branch scaled by zero is an absent block; the scale is
+    linear in the last convolution's filter."""
+    model = _preact_models()[name]
+    B = sum(model["blocks"])
+    blocks = list(range(B))
+    params = make_params(model, 6, perturb_bn=True)
+    x, y = make_batch(model, 5, 7)
+    tr_loss, _, tape, _ = OR.forward_backward(model, blocks, params, x, y, backward=False)
+    p2 = copy.deepcopy(params)
+    for (b, bn), (mean, var, m) in tape.stats.items():
+        p2[b][bn + "_rm"], p2[b][bn + "_rv"] = mean, var
+    _, loss2 = OR.forward_eval(model, blocks, p2, x, labels=y)
+    assert math.isclose(loss2, tr_loss, rel_tol=1e-12)
+    drop = 1
+    scale = [1.0] * B
+    scale[drop] = 0.0
+    np.testing.assert_allclose(OR.forward_eval(model, blocks, params, x, branch_scale=scale),
+                               OR.forward_eval(model, [b for b in blocks if b != drop], params, x), rtol=1e-12, atol=1e-13)
+    scale[drop] = 0.25
+    p3 = copy.deepcopy(params)
+    last = OR.units_last_name(model)
+    p3[drop][last + "_w"] = params[drop][last + "_w"] * 0.25
+    np.testing.assert_allclose(OR.forward_eval(model, blocks, params, x, branch_scale=scale),
+                               OR.forward_eval(model, blocks, p3, x), rtol=1e-12, atol=1e-13)

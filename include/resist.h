@@ -148,7 +148,8 @@ int resist_local_step(const resist_model_desc *desc, const int32_t *blocks, int3
  * Test-time forward pass (Sec. 2.6, "Scaling Activations"): logits of a batch through the stem, the
  * listed blocks and the head, with BN normalising by the running statistics stored in the block
  * buffers and the residual branch of blocks[i] multiplied by branch_scale[i] before the shortcut is
- * added:  out = ReLU(shortcut + branch_scale[i] * BN(last convolution of the branch)).  The paper
+ * added:  out = ReLU(shortcut + branch_scale[i] * BN(last convolution of the branch)); for the
+ * pre-activation kinds  out = shortcut + branch_scale[i] * (last convolution of the branch).  The paper
  * scales the partitioned blocks by 1/S when the reassembled global model uses all of them at once;
  * blocks every sub-ResNet trained get 1.  Nothing is written to the parameter buffers.
  *   blocks         host [nblocks] ascending, must contain the first block of every stage

@@ -191,24 +191,19 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
   // loop state of the chunk that will be requested next (uniform across the workgroup)
   int tr = r0, ts = s0, tc = 0, issued = 0;
   f32x4 ra[PA], rb[PB];
-  auto load_global = [&]() {
+  // scalars of the chunk being requested (set by begin_chunk, used by request)
+  int q_dh = 0, q_dw = 0, q_adelta = 0, q_bdelta = 0;
+  bool q_kok = false;
+  auto begin_chunk = [&]() {
     // tap scalars: source pixel displacement and the byte deltas of activation and filter
-    int dh, dw;
-    if (MODE == kFwd) { dh = tr; dw = ts; }
-    else if (a.stride == 1) { dh = -tr; dw = -ts; }
-    else { dh = (ph + a.pad - tr) >> 1; dw = (pw + a.pad - ts) >> 1; }   // even by construction
+    if (MODE == kFwd) { q_dh = tr; q_dw = ts; }
+    else if (a.stride == 1) { q_dh = -tr; q_dw = -ts; }
+    else { q_dh = (ph + a.pad - tr) >> 1; q_dw = (pw + a.pad - ts) >> 1; }   // even by construction
     const bool live = issued < nchunks;
     const int c0 = tc * BK;
-    const int adelta = ((dh * a.IW + dw) * a.IC + c0) * ES;
-    const int bdelta = ((tr * a.S + ts) * a.IC + c0) * ES;
-    const bool kok = live && (c0 + kvec) < a.IC;
-#pragma unroll
-    for (int i = 0; i < PA; ++i) {
-      const bool ok = kok && (unsigned)(hc[i] + dh) < (unsigned)a.IH && (unsigned)(wc[i] + dw) < (unsigned)a.IW;
-      ra[i] = buffer_load_16B(rin, ok ? (unsigned)(aoff[i] + adelta) : kOOB);
-    }
-#pragma unroll
-    for (int i = 0; i < PB; ++i) rb[i] = buffer_load_16B(rwt, kok ? (unsigned)(boff[i] + bdelta) : kOOB);
+    q_adelta = ((q_dh * a.IW + q_dw) * a.IC + c0) * ES;
+    q_bdelta = ((tr * a.S + ts) * a.IC + c0) * ES;
+    q_kok = live && (c0 + kvec) < a.IC;
     // advance (tap, channel chunk) without branches
     ++issued;
     const bool cwrap = (tc + 1 == cchunks);
@@ -217,21 +212,39 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
     ts = cwrap ? (swrap ? s0 : ts + tstep) : ts;
     tr = swrap ? tr + tstep : tr;
   };
+  // register `part` (0..PA-1: activation rows, PA..PA+PB-1: filter rows) of the chunk begun last
+  auto request = [&](int part) {
+    if (part < PA) {
+      const int i = part;
+      const bool ok = q_kok && (unsigned)(hc[i] + q_dh) < (unsigned)a.IH && (unsigned)(wc[i] + q_dw) < (unsigned)a.IW;
+      ra[i] = buffer_load_16B(rin, ok ? (unsigned)(aoff[i] + q_adelta) : kOOB);
+    } else {
+      const int i = part - PA;
+      rb[i] = buffer_load_16B(rwt, q_kok ? (unsigned)(boff[i] + q_bdelta) : kOOB);
+    }
+  };
+  auto store_part = [&](int stage, int part) {
+    if (part < PA) *reinterpret_cast<f32x4 *>(&As[stage][part * RPP + lrow][kvec]) = ra[part];
+    else *reinterpret_cast<f32x4 *>(&Bs[stage][(part - PA) * RPP + lrow][kvec]) = rb[part - PA];
+  };
+  auto load_global = [&]() {
+    begin_chunk();
+#pragma unroll
+    for (int p = 0; p < PA + PB; ++p) request(p);
+  };
   auto store_lds = [&](int stage) {
 #pragma unroll
-    for (int i = 0; i < PA; ++i) *reinterpret_cast<f32x4 *>(&As[stage][i * RPP + lrow][kvec]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < PB; ++i) *reinterpret_cast<f32x4 *>(&Bs[stage][i * RPP + lrow][kvec]) = rb[i];
+    for (int p = 0; p < PA + PB; ++p) store_part(stage, p);
   };
 
   // Pipeline.  Chunk `it` is multiplied out of LDS stage it&1, one k-step (2*VEC values of K) at a
   // time; the fragments of a k-step are fetched from LDS during the MFMAs of the k-step before it,
-  // also across the chunk boundary.  In k-step KREFILL the registers holding chunk it+1 (requested
-  // from global memory one chunk of MFMA time earlier) go to the other stage and chunk it+2 is
-  // requested.  The one barrier per chunk sits at the start of the last k-step: by then every wave
-  // has all fragments of this stage in registers and has written its share of the next stage, so
-  // after it the first fragments of chunk it+1 can be fetched while the last MFMAs of chunk it run.
-  constexpr int KREFILL = NK / 2 - 1;
+  // also across the chunk boundary.  The registers holding chunk it+1 (requested from global memory
+  // one chunk of MFMA time earlier) go to the other stage, and chunk it+2 is requested into them,
+  // a few registers per k-step over k-steps 0 .. NK-2, so that neither the LDS nor the memory
+  // pipeline sees a burst.  The one barrier per chunk sits at the start of the last k-step: by then
+  // every wave has all fragments of this stage in registers and has written its share of the next
+  // stage, so after it the first fragments of chunk it+1 can be fetched while the last MFMAs run.
   static_assert(NK % 2 == 0, "fragment double buffer parity");
   const int lr = lane & 31, lk = (lane >> 5) * VEC;
   f32x4 fa[2][TM], fb[2][TN];
@@ -264,10 +277,13 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
         load_frags(0, stage ^ 1, 0);   // past the last chunk: zeros nobody uses
       }
       __builtin_amdgcn_sched_barrier(0);   // keep the fetches ahead of this k-step's MFMAs
-      if (ks == KREFILL) {
-        store_lds(stage ^ 1);
-        load_global();
-      }
+      if (ks == 0) begin_chunk();
+#pragma unroll
+      for (int p = 0; p < PA + PB; ++p)
+        if ((p * (NK - 1)) / (PA + PB) == ks) {   // parts spread evenly over k-steps 0 .. NK-2
+          store_part(stage ^ 1, p);
+          request(p);
+        }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -640,16 +656,15 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   f32x4 ra[PA], rb[PB];
-  int mc = mbeg;   // first reduction row of the chunk requested next
-  auto load_global = [&]() {
-#pragma unroll
-    for (int i = 0; i < PA; ++i) {
-      const int row = i * RPA + arow;
+  int mc = mbeg;   // first reduction row of the chunk being requested
+  // register `part` (0..PA-1: rows of dy, PA..PA+PB-1: rows of x) of the chunk starting at row mc
+  auto request = [&](int part) {
+    if (part < PA) {
+      const int row = part * RPA + arow;
       const int m = mc + row;
-      ra[i] = buffer_load_16B(rdy, (m < mend && row < kWBK) ? (unsigned)m * (unsigned)a.K * ES + acolb : kOOB);
-    }
-#pragma unroll
-    for (int i = 0; i < PB; ++i) {
+      ra[part] = buffer_load_16B(rdy, (m < mend && row < kWBK) ? (unsigned)m * (unsigned)a.K * ES + acolb : kOOB);
+    } else {
+      const int i = part - PA;
       const int row = i * RPB + brow;
       const int m = mc + row;
       const int n = fdiv(m, a.div_pq);
@@ -659,20 +674,27 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
       const bool ok = m < mend && row < kWBK && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
       rb[i] = buffer_load_16B(rx, ok ? (unsigned)((n * a.H + ih) * a.W + iw) * (unsigned)a.C * ES + bcolb : kOOB);
     }
+  };
+  auto store_part = [&](int stage, int part) {
+    if (part < PA) {
+      if (part * RPA + arow < kWBK) *reinterpret_cast<f32x4 *>(&As[stage][part * RPA + arow][acol]) = ra[part];
+    } else {
+      const int i = part - PA;
+      if (i * RPB + brow < kWBK) *reinterpret_cast<f32x4 *>(&Bs[stage][i * RPB + brow][bcol]) = rb[i];
+    }
+  };
+  auto load_global = [&]() {
+#pragma unroll
+    for (int p = 0; p < PA + PB; ++p) request(p);
     mc += kWBK;
   };
   auto store_lds = [&](int stage) {
 #pragma unroll
-    for (int i = 0; i < PA; ++i)
-      if (i * RPA + arow < kWBK) *reinterpret_cast<f32x4 *>(&As[stage][i * RPA + arow][acol]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < PB; ++i)
-      if (i * RPB + brow < kWBK) *reinterpret_cast<f32x4 *>(&Bs[stage][i * RPB + brow][bcol]) = rb[i];
+    for (int p = 0; p < PA + PB; ++p) store_part(stage, p);
   };
 
   // same pipeline as the forward kernel: fragments one k-step ahead (also across chunks), refill of
-  // the other stage in k-step KREFILL, one barrier per chunk at the start of the last k-step
-  constexpr int KREFILL = NK / 2 - 1;
+  // the other stage spread over k-steps 0 .. NK-2, one barrier per chunk at the start of the last k-step
   static_assert(NK % 2 == 0, "fragment double buffer parity");
   const int lr = lane & 31, lh = lane >> 5;
   float fa[2][TM], fb[2][TN];
@@ -703,10 +725,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
         load_frags(0, stage ^ 1, 0);   // rows past mend were loaded as zeros
       }
       __builtin_amdgcn_sched_barrier(0);
-      if (ks == KREFILL) {
-        store_lds(stage ^ 1);
-        load_global();
-      }
+#pragma unroll
+      for (int p = 0; p < PA + PB; ++p)
+        if ((p * (NK - 1)) / (PA + PB) == ks) {   // refill spread evenly over k-steps 0 .. NK-2
+          store_part(stage ^ 1, p);
+          request(p);
+        }
+      if (ks == NK - 2) mc += kWBK;
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -789,15 +814,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_bf16_kernel(WgradArgs a) {
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   f32x4 ra[PA], rb[PB];
-  int mc = mbeg;
-  auto load_global = [&]() {
-#pragma unroll
-    for (int i = 0; i < PA; ++i) {
-      const int m = mc + i * RPA + arow;
-      ra[i] = buffer_load_16B(rdy, m < mend ? (unsigned)m * (unsigned)a.K * 2u + acolb : kOOB);
-    }
-#pragma unroll
-    for (int i = 0; i < PB; ++i) {
+  int mc = mbeg;   // first reduction row of the chunk being requested
+  auto request = [&](int part) {
+    if (part < PA) {
+      const int m = mc + part * RPA + arow;
+      ra[part] = buffer_load_16B(rdy, m < mend ? (unsigned)m * (unsigned)a.K * 2u + acolb : kOOB);
+    } else {
+      const int i = part - PA;
       const int m = mc + i * RPB + brow;
       const int n = fdiv(m, a.div_pq);
       const int rem = m - n * (a.P * a.Q);
@@ -806,13 +829,19 @@ __global__ __launch_bounds__(kThreads) void wgrad_bf16_kernel(WgradArgs a) {
       const bool ok = m < mend && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
       rb[i] = buffer_load_16B(rx, ok ? (unsigned)((n * a.H + ih) * a.W + iw) * (unsigned)a.C * 2u + bcolb : kOOB);
     }
+  };
+  auto store_part = [&](int stage, int part) {
+    if (part < PA) *reinterpret_cast<f32x4 *>(&As[stage][part * RPA + arow][acol]) = ra[part];
+    else *reinterpret_cast<f32x4 *>(&Bs[stage][(part - PA) * RPB + brow][bcol]) = rb[part - PA];
+  };
+  auto load_global = [&]() {
+#pragma unroll
+    for (int p = 0; p < PA + PB; ++p) request(p);
     mc += WBK;
   };
   auto store_lds = [&](int stage) {
 #pragma unroll
-    for (int i = 0; i < PA; ++i) *reinterpret_cast<f32x4 *>(&As[stage][i * RPA + arow][acol]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < PB; ++i) *reinterpret_cast<f32x4 *>(&Bs[stage][i * RPB + brow][bcol]) = rb[i];
+    for (int p = 0; p < PA + PB; ++p) store_part(stage, p);
   };
 
   // fragment addressing of the transpose read: lane l supplies row 8*(l/32) + (l%16)/4 of a 16-row
@@ -820,7 +849,6 @@ __global__ __launch_bounds__(kThreads) void wgrad_bf16_kernel(WgradArgs a) {
   // rows 8*(l/32) .. +3 (and +4 .. +7 from the second read)
   const int frow = (lane >> 5) * 8 + ((lane & 15) >> 2);
   const int fcol = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-  constexpr int KREFILL = NK / 2 - 1;
   bf16x8 fa[2][TM], fb[2][TN];
   auto load_frags = [&](int buf, int stage, int ks) {
 #pragma unroll
@@ -861,10 +889,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_bf16_kernel(WgradArgs a) {
         load_frags(0, stage ^ 1, 0);   // rows past mend were loaded as zeros
       }
       __builtin_amdgcn_sched_barrier(0);
-      if (ks == KREFILL) {
-        store_lds(stage ^ 1);
-        load_global();
-      }
+#pragma unroll
+      for (int p = 0; p < PA + PB; ++p)
+        if ((p * (NK - 1)) / (PA + PB) == ks) {   // refill spread evenly over k-steps 0 .. NK-2
+          store_part(stage ^ 1, p);
+          request(p);
+        }
+      if (ks == NK - 2) mc += WBK;
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll

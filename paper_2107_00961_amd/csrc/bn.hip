@@ -65,7 +65,19 @@ template <typename S>
 __device__ inline void reduce_parts(const S *__restrict__ scratch, int parts, int C, int c, int pl,
                                     double (*red)[16][16], double *out0, double *out1) {
   double s = 0, q = 0;
-  for (int p = pl; p < parts; p += 16) {
+  int p = pl;
+  // eight loads of each sum in flight per thread; the additions keep their order
+  for (; p + 7 * 16 < parts; p += 8 * 16) {
+    S vs[8], vq[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      vs[u] = scratch[(size_t)(p + 16 * u) * C + c];
+      vq[u] = scratch[(size_t)(parts + p + 16 * u) * C + c];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { s += (double)vs[u]; q += (double)vq[u]; }
+  }
+  for (; p < parts; p += 16) {
     s += (double)scratch[(size_t)p * C + c];
     q += (double)scratch[(size_t)(parts + p) * C + c];
   }

@@ -430,6 +430,8 @@ int check_geom(const ConvGeom &g, int dt) {
 
 }  // namespace
 
+int conv_check(const ConvGeom &g, int dt) { return check_geom(g, dt); }
+
 int64_t conv_stats_floats(const ConvGeom &g) {
   // the smallest row tile any forward kernel uses is 64
   return (int64_t)2 * (((int64_t)g.N * g.P * g.Q + 63) / 64) * g.K;

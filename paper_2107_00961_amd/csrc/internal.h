@@ -104,6 +104,8 @@ enum { DT_F32 = 0, DT_BF16 = 1 };
 inline int esize(int dt) { return dt == DT_BF16 ? 2 : 4; }
 
 // implicit-GEMM convolution family (conv.hip); dt selects fp32 or bf16 tensors (fp32 accumulation)
+// shape limits of the convolution kernels (channel multiples, filter sizes, tensors below 2 GiB); host only
+int conv_check(const ConvGeom &g, int dt);
 // y = conv(x, w) [+ addend].  stats (optional): per row-tile column sums and sums of squares of y as
 // stored, [2][*stat_parts][K] floats (capacity conv_stats_floats(g)); input of bn_finalize
 int64_t conv_stats_floats(const ConvGeom &g);

@@ -125,7 +125,9 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
     max_stats = std::max<int64_t>(max_stats, conv_stats_floats(c.g));
   };
   int max_c = 16;
+  int shape_rc = RESIST_OK;   // every convolution is checked here, before anything is launched
   auto track = [&](const ConvLayer &c, bool needs_dgrad) {
+    if (shape_rc == RESIST_OK) shape_rc = conv_check(c.g, net.d.compute_dtype);
     max_act = std::max<int64_t>(max_act, c.M() * c.g.K);
     max_act = std::max<int64_t>(max_act, (int64_t)c.g.N * c.g.H * c.g.W * c.g.C);
     (void)needs_dgrad;
@@ -147,6 +149,7 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
     s.y = A.take_act(s.M() * K0, es);
     s.a = A.take_act(s.M() * K0, es);
     take_bn(s);
+    RESIST_TRY(conv_check(s.g, net.d.compute_dtype));
     max_act = std::max<int64_t>(max_act, s.M() * K0);
     max_splitk = std::max<int64_t>(max_splitk, wgrad_scratch_floats(s.g));
     max_c = std::max(max_c, K0);
@@ -202,6 +205,7 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
     cur = bp.out;
   }
 
+  RESIST_TRY(shape_rc);
   // ---- head
   {
     const BlockShape &last = net.blocks[blocks[nblocks - 1]];
@@ -266,6 +270,7 @@ int build_forward_plan(const resist_model_desc *desc, const int32_t *blocks, int
   P->kpad = (taps + 31) / 32 * 32;
   const int K0 = net.d.width[0];
   P->stem = make_conv(P->layouts[0], 0, N, net.stem_h, net.stem_w, P->kpad, K0, 1, 1, 0);
+  RESIST_TRY(conv_check(P->stem.g, net.d.compute_dtype));
   int64_t max_act = P->stem.M() * K0;
   int max_c = K0;
   P->blocks.resize(nblocks);
@@ -285,9 +290,11 @@ int build_forward_plan(const resist_model_desc *desc, const int32_t *blocks, int
     bp.has_ds = bs.has_ds;
     if (bs.has_ds) bp.ds = make_conv(L, 3, N, bs.h_in, bs.w_in, bs.c_in, bs.c_out, 1, bs.stride, 0);
     for (const ConvLayer &c : bp.convs) {
+      RESIST_TRY(conv_check(c.g, net.d.compute_dtype));
       max_act = std::max<int64_t>(max_act, c.M() * c.g.K);
       max_c = std::max(max_c, c.g.K);
     }
+    if (bs.has_ds) RESIST_TRY(conv_check(bp.ds.g, net.d.compute_dtype));
     bp.out_elems = (int64_t)N * bs.h_out * bs.w_out * bs.c_out;
   }
   P->col = A.take_act(P->stem.M() * P->kpad, es);
@@ -413,7 +420,9 @@ int build_preact_plan(const resist_model_desc *desc, const int32_t *blocks, int3
   RESIST_TRY(block_layout(net, B, &P->layouts[nblocks + 1]));
   int64_t max_act = 0, max_splitk = 0, max_stats = 0;
   int max_c = 16;
+  int shape_rc = RESIST_OK;   // every convolution is checked here, before anything is launched
   auto track = [&](const ConvGeom &g, bool stats) {
+    if (shape_rc == RESIST_OK) shape_rc = conv_check(g, net.d.compute_dtype);
     max_act = std::max<int64_t>(max_act, (int64_t)g.N * g.P * g.Q * g.K);
     max_act = std::max<int64_t>(max_act, (int64_t)g.N * g.H * g.W * g.C);
     max_splitk = std::max<int64_t>(max_splitk, wgrad_scratch_floats(g));
@@ -481,6 +490,7 @@ int build_preact_plan(const resist_model_desc *desc, const int32_t *blocks, int3
     pb.out = pb.units.back().h;
     cur = pb.out;
   }
+  RESIST_TRY(shape_rc);
   const BlockShape &last = net.blocks[blocks[nblocks - 1]];
   P->feat_in = cur;
   P->feat_hw = last.h_out * last.w_out;
@@ -859,6 +869,7 @@ int build_preact_forward_plan(const resist_model_desc *desc, const int32_t *bloc
   P->kpad = (taps + 31) / 32 * 32;
   const int K0 = net.d.width[0];
   P->stem = make_geom(N, net.stem_h, net.stem_w, P->kpad, K0, 1, 1, 0);
+  RESIST_TRY(conv_check(P->stem, net.d.compute_dtype));
   int64_t max_act = (int64_t)N * net.stem_h * net.stem_w * K0;
   int max_c = std::max(K0, net.head_c);
   P->blocks.resize(nblocks);
@@ -887,6 +898,7 @@ int build_preact_forward_plan(const resist_model_desc *desc, const int32_t *bloc
       // a copy of the filter in the compute type; the last unit's always (it carries the branch scale)
       if (net.d.compute_dtype == DT_BF16 || j + 1 == gs.size())
         un.wlp = A.take_act((int64_t)un.g.K * un.g.R * un.g.S * un.g.C, es);
+      RESIST_TRY(conv_check(un.g, net.d.compute_dtype));
       max_act = std::max<int64_t>(max_act, (int64_t)N * un.g.P * un.g.Q * un.g.K);
       max_act = std::max<int64_t>(max_act, un.rows() * un.g.C);
       max_c = std::max(max_c, std::max(un.g.C, un.g.K));

@@ -107,3 +107,86 @@ def test_workspace_and_step_argument_errors():
     rc = R.lib().resist_local_step(ctypes.byref(d), blocks, 4, None, None, None, None, None, 8, 0.1, 0.9, 0.0,
                                    None, 0, None, None)
     assert rc == -1
+
+
+@pytest.mark.parametrize("kind", [2, 3])
+def test_preactivation_layouts(kind):
+    model = dict(get_config("cfg2")["model"], block_kind=kind)
+    nb = R.num_blocks(model)
+    params = make_params(model, 0, perturb_bn=True)
+    for b in (-1, 0, 1, 3, nb - 1, nb):
+        lay = R.block_layout(model, b)
+        assert sum(t["count"] for t in lay if t["kind"] not in (3, 4)) == OR.param_count(model, b)
+        assert sum(t["count"] for t in lay) == OR.param_count(model, b, trainable_only=False)
+        back = R.unpack_block(model, b, R.pack_block(model, b, params[b]))
+        assert set(back) == set(params[b])
+        for k in back:
+            np.testing.assert_array_equal(back[k], params[b][k])
+    # a BN of a pre-activation block has its convolution's INPUT channels
+    first_of_stage2 = model["blocks"][0]
+    lay = {(t["kind"], t["layer"]): t for t in R.block_layout(model, first_of_stage2)}
+    assert lay[(1, 0)]["dims"][0] == lay[(0, 0)]["dims"][3]
+    assert (1, 3) not in lay and (0, 3) in lay            # the shortcut convolution has no BN
+    with pytest.raises(R.ResistError, match="stem"):
+        R.num_blocks(dict(model, stem_kind=1))
+    assert R.workspace_bytes(model, [0, 3, 7, 30], 8) > 0
+
+
+def test_forward_and_aggregate_argument_errors():
+    """Validation happens before any kernel is launched, so the error paths run without a GPU."""
+    model = get_config("cfg2")["model"]
+    d = R.model_desc(model)
+    lib = R.lib()
+    blocks = (ctypes.c_int32 * 4)(0, 3, 7, 30)
+    n = ctypes.c_int64()
+    assert lib.resist_forward_workspace_bytes(ctypes.byref(d), blocks, 4, 8, ctypes.byref(n)) == 0 and n.value > 0
+    assert lib.resist_forward_workspace_bytes(ctypes.byref(d), blocks, 3, 8, ctypes.byref(n)) == -2      # stage 4's first block missing
+    assert lib.resist_forward_workspace_bytes(ctypes.byref(d), blocks, 4, 8, None) == -1
+    rc = lib.resist_forward(ctypes.byref(d), blocks, 4, None, None, None, 8, None, 0, None, None, None, None)
+    assert rc == -1
+    # labels without a loss buffer (fake, never dereferenced: the call fails before that)
+    fake = (ctypes.c_void_p * 6)(*([16] * 6))
+    rc = lib.resist_forward(ctypes.byref(d), blocks, 4, fake, None, ctypes.c_void_p(16), 8, ctypes.c_void_p(16), 1 << 40,
+                            ctypes.c_void_p(16), ctypes.c_void_p(16), None, None)
+    assert rc == -1 and b"labels" in lib.resist_last_error()
+    # workspace too small
+    rc = lib.resist_forward(ctypes.byref(d), blocks, 4, fake, None, ctypes.c_void_p(16), 8, ctypes.c_void_p(16), 1024,
+                            ctypes.c_void_p(16), None, None, None)
+    assert rc == -3
+    # misaligned parameter buffer
+    bad = (ctypes.c_void_p * 6)(16, 16, 20, 16, 16, 16)
+    rc = lib.resist_forward(ctypes.byref(d), blocks, 4, bad, None, ctypes.c_void_p(16), 8, ctypes.c_void_p(16), 1 << 40,
+                            ctypes.c_void_p(16), None, None, None)
+    assert rc == -1
+    # aggregate: S < 1, too many holders, block index out of range
+    nb = R.num_blocks(model)
+    offs = (ctypes.c_int32 * 2)(0, 4)
+    glob = (ctypes.c_void_p * (nb + 2))(*([16] * (nb + 2)))
+    one = (ctypes.POINTER(ctypes.c_void_p) * 1)(ctypes.cast(fake, ctypes.POINTER(ctypes.c_void_p)))
+    assert lib.resist_aggregate(ctypes.byref(d), 0, offs, blocks, one, glob, None) == -1
+    assert lib.resist_aggregate(ctypes.byref(d), 17, offs, blocks, one, glob, None) == -5
+    badblocks = (ctypes.c_int32 * 4)(0, 3, 7, 99)
+    assert lib.resist_aggregate(ctypes.byref(d), 1, offs, badblocks, one, glob, None) == -1
+    # bf16 layer entry points refuse channel counts that are not multiples of 8
+    from paper_2107_00961_amd.binding import _conv_shape
+    sh = _conv_shape(1, 4, 4, 12, 16, 3, 1, 1, 1)
+    rc = lib.resist_conv2d_forward(ctypes.byref(sh), ctypes.c_void_p(16), ctypes.c_void_p(16), ctypes.c_void_p(16), None, 0, None)
+    assert rc == -2
+
+
+def test_tensors_beyond_two_gib_are_refused_up_front():
+    """The kernels address a tensor with 32-bit byte offsets: a batch that would push any activation
+    past 2 GiB is refused when the plan is made (maximum sizes), in fp32 earlier than in bf16."""
+    model = get_config("cfg2")["model"]                     # stem output: batch x 32 x 32 x 64 floats
+    blocks = [0, 3, 7, 30]
+    assert R.workspace_bytes(model, blocks, 8191) > 0      # 8191 * 65536 * 4 B just under 2 GiB
+    with pytest.raises(R.ResistError, match="2 GiB"):
+        R.workspace_bytes(model, blocks, 8192)
+    bf = dict(model, compute_dtype=1)
+    assert R.workspace_bytes(bf, blocks, 8192) > 0
+    with pytest.raises(R.ResistError, match="2 GiB"):
+        R.workspace_bytes(bf, blocks, 16384)
+    with pytest.raises(R.ResistError, match="2 GiB"):
+        R.forward_workspace_bytes(model, blocks, 8192)
+    with pytest.raises(R.ResistError, match="2 GiB"):
+        R.workspace_bytes(dict(model, block_kind=2), blocks, 8192)

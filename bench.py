@@ -50,7 +50,7 @@ def _bench_round(args, cfg, subs):
     from resist_inputs import make_batch, make_params
 
     model, batch, S = cfg["model"], cfg["batch"], cfg["S"]
-    iters = cfg.get("local_iters", 50)
+    iters = args.local_iters or cfg.get("local_iters", 50)
     params = make_params(model, 0)
     nb = R.num_blocks(model)
     workers = [SubResNet(model, subs[s], params, batch, keep_grads=False) for s in range(S)]
@@ -74,19 +74,49 @@ def _bench_round(args, cfg, subs):
         step_ms.append((time.perf_counter() - t0) / iters * 1e3)
     t_steps = time.perf_counter() - t_round
     a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    agg_ms = []
-    for rep in range(5):
-        a0.record(stream)
-        R.aggregate(model, subs, [w.params for w in workers], glob.params, stream)
-        a1.record(stream)
-        torch.cuda.synchronize()
-        agg_ms.append(a0.elapsed_time(a1))
-    agg = min(agg_ms[1:])
+    INNER = 5      # calls between two events: the event pair's own cost (~20 us) is spread over them
+
+    def timed(fn, reps=4):
+        best = None
+        for rep in range(reps + 1):
+            a0.record(stream)
+            for _ in range(INNER):
+                fn()
+            a1.record(stream)
+            torch.cuda.synchronize()
+            if rep > 0:
+                ms = a0.elapsed_time(a1) / INNER
+                best = ms if best is None else min(best, ms)
+        return best
+
+    agg = timed(lambda: R.aggregate(model, subs, [w.params for w in workers], glob.params, stream))
     n_glob = sum(p.numel() for p in glob.params)
     n_read = sum(p.numel() for w in workers for p in w.params)
     agg_bytes = 4.0 * (n_glob + n_read)
     ms = t_steps / (S * iters) * 1e3
     losses = [float(w.loss.cpu()[0]) for w in workers]
+    compressed = None
+    if args.compress_bits:
+        # the same reassembly from b-bit compressed copies: each worker compresses its blocks (read 2 x 4 B,
+        # write one code per parameter), the global model is rebuilt from the codes (read count codes, write 4 B)
+        bits = args.compress_bits
+        cb = 0.5 if bits <= 4 else 1.0
+        comp = [w.compress(bits, stream) for w in workers]
+        def compress_all():
+            for w, (cd, rg) in zip(workers, comp):
+                R.compress_blocks(model, w.keys, bits, w.params, cd, rg, stream)
+
+        c_best = timed(compress_all)
+        q_best = timed(lambda: R.aggregate_compressed(model, subs, bits, [c for c, _ in comp], [r for _, r in comp],
+                                                      glob.params, stream))
+        c_bytes = n_read * (8.0 + cb)
+        q_bytes = n_read * cb + 4.0 * n_glob
+        compressed = {"bits": bits, "compress_ms": round(c_best, 4), "compress_bytes": c_bytes,
+                      "compress_GBps": round(c_bytes / (c_best * 1e-3) / 1e9, 1),
+                      "aggregate_ms": round(q_best, 4), "aggregate_bytes": q_bytes,
+                      "aggregate_GBps": round(q_bytes / (q_best * 1e-3) / 1e9, 1),
+                      "aggregate_frac_of_hbm_peak": round(q_bytes / (q_best * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                      "bytes_vs_fp32_aggregate": round(q_bytes / agg_bytes, 4)}
     out = {
         "metric": "images/sec per sub-ResNet local SGD step",
         "value": round(batch / (ms * 1e-3), 1), "unit": "images/s", "n_gpus": 1, "steps": S * iters, "warmup": S,
@@ -99,6 +129,8 @@ def _bench_round(args, cfg, subs):
                   "aggregate_frac_of_hbm_peak": round(agg_bytes / (agg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                   "round_ms": round(t_steps * 1e3 + agg, 2), "final_losses": losses},
     }
+    if compressed:
+        out["round"]["compressed"] = compressed
     print(json.dumps(out))
 
 
@@ -110,6 +142,10 @@ def main():
     ap.add_argument("--workload", default="cfg2",
                     help="cfg1 | cfg2 | cfg2_preact | cfg3 | cfg5 (fp32) | cfg4 | cfg5_bf16 (bf16 storage, fp32 accumulation)")
     ap.add_argument("--sub", type=int, default=0, help="which sub-ResNet of the partition to step")
+    ap.add_argument("--compress-bits", type=int, default=0,
+                    help="with --round: also time b-bit compression of the workers' blocks and the reassembly "
+                         "from the compressed copies (2..8; 0 = off)")
+    ap.add_argument("--local-iters", type=int, default=0, help="with --round: override the local iterations per sub-ResNet")
     ap.add_argument("--round", action="store_true",
                     help="time one full round instead: every sub-ResNet runs its local iterations on fresh "
                          "batches, one after the other, then resist_aggregate rebuilds the global model")

@@ -183,6 +183,47 @@ int resist_aggregate(const resist_model_desc *desc, int32_t S, const int32_t *su
                      void *const *global_block_params, void *hip_stream);
 
 /*
+ * Compressed communication (appendix "ResIST and Quantization/Sparse Gradients", Table 9: all
+ * communicated parameters compressed to b bits, b = 8 ... 4).  The paper names no quantiser; the
+ * library uses the uniform min-max one on every tensor of a block buffer separately:
+ *     lo = min w, hi = max w, delta = (hi - lo) / (2^b - 1),
+ *     code = round-half-even((w - lo) / delta) in 0 .. 2^b - 1   (all zero when delta == 0),
+ *     decoded value lo + code * delta                          (fp32 throughout).
+ * A compressed block is (a) a header of one resist_qrange per tensor, in the order of
+ * resist_block_layout(), begin/end in floats from the start of the block buffer (alignment padding
+ * between tensors belongs to no record: its code is 0 and it decodes to 0), and (b) one code per
+ * float of the buffer: a byte each for b = 5..8; for b = 2..4 two per byte, float 2j in the low
+ * nibble of byte j.
+ *
+ * resist_compressed_block_size: bytes of the code array and number of header records of `block`
+ *   (-1 stem, 0..B-1, B head).  host.
+ * resist_compress_blocks: compresses nkeys block buffers in a few launches.
+ *   keys    host [nkeys] block keys (-1 stem, 0..B-1, B head)
+ *   params  host [nkeys] device fp32 block buffers (read)
+ *   codes   host [nkeys] device code arrays (written), 4-byte aligned
+ *   ranges  host [nkeys] device arrays of n_tensors resist_qrange (written), 16-byte aligned
+ * resist_aggregate_compressed: resist_aggregate with every source a compressed block: each float of
+ *   the global model becomes the fp32 mean, in ascending sub-ResNet order, of the decoded copies (a
+ *   single holder: its decoded copy; no holder: untouched).  sub_codes[s] / sub_ranges[s] are host
+ *   arrays [n_s + 2] of device pointers laid out like sub_block_params of resist_aggregate; every
+ *   copy must have been written by resist_compress_blocks with the same desc and bits.
+ * Both are asynchronous on hip_stream; bits outside 2..8 is RESIST_EINVAL.
+ */
+typedef struct {
+  float lo, delta;
+  int32_t begin, end;
+} resist_qrange;
+int resist_compressed_block_size(const resist_model_desc *desc, int32_t block, int32_t bits,
+                                 int64_t *code_bytes, int32_t *n_tensors);
+int resist_compress_blocks(const resist_model_desc *desc, int32_t nkeys, const int32_t *keys,
+                           int32_t bits, void *const *params, void *const *codes,
+                           void *const *ranges, void *hip_stream);
+int resist_aggregate_compressed(const resist_model_desc *desc, int32_t S, const int32_t *sub_offsets,
+                                const int32_t *sub_blocks, int32_t bits,
+                                void *const *const *sub_codes, void *const *const *sub_ranges,
+                                void *const *global_block_params, void *hip_stream);
+
+/*
  * Optional per-kernel timing, for benchmarks (not a step of the paper's method).  While enabled,
  * every kernel launch is bracketed by two HIP events on the stream it is launched on.
  * resist_profile_enable(on) clears the statistics and switches timing on or off (off by default);

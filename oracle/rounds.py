@@ -13,12 +13,13 @@ per round).
 import numpy as np
 
 from . import aggregate as OA
+from . import compress as OC
 from . import partition as OP
 from . import resnet as OR
 
 
 def run_rounds(model, global_params, S, min_depth, seed, rounds, local_iters, batch_fn, lr, mu, wd,
-               partitionable=None, first_round=0):
+               partitionable=None, first_round=0, compress_bits=0):
     """batch_fn(round, s, it) -> (x, labels).  Returns (new global params, log) where log[t] holds
     the partition of round t and the losses of every local step."""
     g = {k: {n: np.asarray(v) for n, v in p.items()} for k, p in global_params.items()}
@@ -38,6 +39,12 @@ def run_rounds(model, global_params, S, min_depth, seed, rounds, local_iters, ba
                 ls.append(loss)
             sub_params.append(p)
             losses.append(ls)
-        g = OA.aggregate(g, subs, sub_params)
+        if compress_bits:
+            # appendix on quantised communication: the workers' parameters travel as b-bit codes
+            sq = [{k: OC.quantize_block({n: np.asarray(a, np.float32) for n, a in t.items()}, compress_bits)
+                   for k, t in p.items()} for p in sub_params]
+            g = OC.aggregate_quantized(g, subs, sq)
+        else:
+            g = OA.aggregate(g, subs, sub_params)
         log.append(dict(subs=subs, owner=owner, losses=losses))
     return g, log

@@ -48,7 +48,8 @@ def lib():
                      "resist_aggregate", "resist_forward", "resist_forward_workspace_bytes",
                      "resist_conv2d_workspace_bytes", "resist_conv2d_forward",
                      "resist_conv2d_dgrad", "resist_conv2d_wgrad", "resist_profile_enable",
-                     "resist_profile_read"):
+                     "resist_profile_read", "resist_compressed_block_size",
+                     "resist_compress_blocks", "resist_aggregate_compressed"):
             getattr(L, name).restype = C.c_int
         L.resist_local_step.argtypes = [
             C.POINTER(_ModelDesc), C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_void_p),
@@ -57,6 +58,15 @@ def lib():
         L.resist_aggregate.argtypes = [
             C.POINTER(_ModelDesc), C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
             C.POINTER(C.POINTER(C.c_void_p)), C.POINTER(C.c_void_p), C.c_void_p]
+        L.resist_compressed_block_size.argtypes = [
+            C.POINTER(_ModelDesc), C.c_int32, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
+        L.resist_compress_blocks.argtypes = [
+            C.POINTER(_ModelDesc), C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_void_p),
+            C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p]
+        L.resist_aggregate_compressed.argtypes = [
+            C.POINTER(_ModelDesc), C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32,
+            C.POINTER(C.POINTER(C.c_void_p)), C.POINTER(C.POINTER(C.c_void_p)), C.POINTER(C.c_void_p),
+            C.c_void_p]
         L.resist_forward.argtypes = [
             C.POINTER(_ModelDesc), C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_void_p),
             C.POINTER(C.c_float), C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
@@ -246,6 +256,41 @@ def aggregate(model, subs, sub_params, global_params, stream=None):
     outer = (C.POINTER(C.c_void_p) * S)(*[C.cast(k, C.POINTER(C.c_void_p)) for k in keep])
     _check(lib().resist_aggregate(C.byref(model_desc(model)), S, offs_a, flat_a, outer,
                                   _ptr_array(global_params), _stream_ptr(stream)))
+
+
+def compressed_block_size(model, block, bits):
+    """-> (bytes of the code array, number of header records) of `block` (-1 stem, 0..B-1, B head)."""
+    nb, nt = C.c_int64(), C.c_int32()
+    _check(lib().resist_compressed_block_size(C.byref(model_desc(model)), block, bits, C.byref(nb), C.byref(nt)))
+    return nb.value, nt.value
+
+
+def compress_blocks(model, keys, bits, params, codes, ranges, stream=None):
+    """keys: block keys; params: device fp32 block buffers; codes: device uint8 tensors of
+    compressed_block_size()[0] bytes; ranges: device tensors of 16 bytes per header record."""
+    n = len(keys)
+    keys_a = (C.c_int32 * max(n, 1))(*keys)
+    _check(lib().resist_compress_blocks(C.byref(model_desc(model)), n, keys_a, bits, _ptr_array(params),
+                                        _ptr_array(codes), _ptr_array(ranges), _stream_ptr(stream)))
+
+
+def aggregate_compressed(model, subs, bits, sub_codes, sub_ranges, global_params, stream=None):
+    """aggregate() with every source a compressed block: sub_codes[s] / sub_ranges[s] are device
+    tensors [stem, blocks of s..., head] as written by compress_blocks."""
+    S = len(subs)
+    offs = [0]
+    flat = []
+    for s in subs:
+        flat += list(s)
+        offs.append(len(flat))
+    offs_a = (C.c_int32 * (S + 1))(*offs)
+    flat_a = (C.c_int32 * max(len(flat), 1))(*flat)
+    keep_c = [_ptr_array(p) for p in sub_codes]
+    keep_r = [_ptr_array(p) for p in sub_ranges]
+    outer_c = (C.POINTER(C.c_void_p) * S)(*[C.cast(k, C.POINTER(C.c_void_p)) for k in keep_c])
+    outer_r = (C.POINTER(C.c_void_p) * S)(*[C.cast(k, C.POINTER(C.c_void_p)) for k in keep_r])
+    _check(lib().resist_aggregate_compressed(C.byref(model_desc(model)), S, offs_a, flat_a, bits, outer_c,
+                                             outer_r, _ptr_array(global_params), _stream_ptr(stream)))
 
 
 def profile_enable(on):

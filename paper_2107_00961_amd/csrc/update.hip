@@ -25,9 +25,17 @@ struct SgdTable {
   float lr, mu, wd;
 };
 
+// Segment of this workgroup: first_wg is ascending, so the segment index is the number of segment
+// starts at or below blockIdx.x.  One lane per candidate and a ballot: a single round trip to the
+// kernel arguments instead of a chain of dependent loads.  nseg <= 64.
+__device__ inline int find_seg(const int *first_wg, int nseg) {
+  const int lane = threadIdx.x & 63;
+  const bool past = lane + 1 < nseg && (int)blockIdx.x >= first_wg[lane + 1];
+  return __popcll(__ballot(past));
+}
+
 __global__ __launch_bounds__(256) void sgd_kernel(SgdTable t) {
-  int seg = 0;
-  while (seg + 1 < t.nseg && (int)blockIdx.x >= t.first_wg[seg + 1]) ++seg;
+  const int seg = find_seg(t.first_wg, t.nseg);
   const long long base = (long long)(blockIdx.x - t.first_wg[seg]) * kChunk;
   float *w = t.w[seg];
   float *v = t.v[seg];
@@ -74,33 +82,52 @@ template <int NSRC> struct AggTable {
 
 template <int NSRC>
 __global__ __launch_bounds__(256) void aggregate_kernel(AggTable<NSRC> t) {
-  int seg = 0;
-  while (seg + 1 < t.nseg && (int)blockIdx.x >= t.first_wg[seg + 1]) ++seg;
+  // the segment index is the same in every lane; telling the compiler so keeps the table lookups scalar
+  const int seg = __builtin_amdgcn_readfirstlane(find_seg(t.first_wg, t.nseg));
   const long long base = (long long)(blockIdx.x - t.first_wg[seg]) * kChunk;
   float *dst = t.dst[seg];
   const long long n = t.n[seg];
   const int count = t.count[seg];
   const float fc = (float)count;
+  if (base + kChunk <= n) {
+    // whole chunk: every load of the workgroup is issued before the first sum; the only branches are
+    // the uniform "source s present" ones
+    constexpr int UB = NSRC <= 4 ? 4 : (NSRC <= 8 ? 2 : 1);   // vectors in flight per thread and source
 #pragma unroll
+    for (int u0 = 0; u0 < 4; u0 += UB) {
+      f32x4 v[UB][NSRC];
+#pragma unroll
+      for (int s = 0; s < NSRC; ++s)
+        if (s < count) {
+          const float *src = t.src[seg][s];
+#pragma unroll
+          for (int u = 0; u < UB; ++u) v[u][s] = *reinterpret_cast<const f32x4 *>(src + base + ((u0 + u) * 256 + threadIdx.x) * 4);
+        }
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        f32x4 acc = v[u][0];
+#pragma unroll
+        for (int s = 1; s < NSRC; ++s)
+          if (s < count) acc += v[u][s];      // ascending sub-ResNet order
+        if (count > 1) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[e] = acc[e] / fc;
+        }
+        *reinterpret_cast<f32x4 *>(dst + base + ((u0 + u) * 256 + threadIdx.x) * 4) = acc;
+      }
+    }
+    return;
+  }
+  // ragged last chunk of a buffer
   for (int u = 0; u < 4; ++u) {
     const long long i = base + (u * 256 + threadIdx.x) * 4;
-    if (i + 3 < n) {
-      f32x4 acc = *reinterpret_cast<const f32x4 *>(t.src[seg][0] + i);
+    for (long long k = i; k < i + 4 && k < n; ++k) {
+      float acc = t.src[seg][0][k];
       if (count > 1) {
-        for (int s = 1; s < count; ++s) acc += *reinterpret_cast<const f32x4 *>(t.src[seg][s] + i);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] = acc[e] / fc;
+        for (int s = 1; s < count; ++s) acc += t.src[seg][s][k];
+        acc = acc / fc;
       }
-      *reinterpret_cast<f32x4 *>(dst + i) = acc;
-    } else {
-      for (long long k = i; k < n; ++k) {
-        float acc = t.src[seg][0][k];
-        if (count > 1) {
-          for (int s = 1; s < count; ++s) acc += t.src[seg][s][k];
-          acc = acc / fc;
-        }
-        dst[k] = acc;
-      }
+      dst[k] = acc;
     }
   }
 }

@@ -45,6 +45,16 @@ class DeviceModel:
         B.forward(self.model, self.blocks, self.params, x, logits, ws, branch_scale, labels, loss, stream)
         return (logits, loss) if labels is not None else logits
 
+    def compress(self, bits, stream=None):
+        """b-bit compressed copies of all block buffers -> (codes, ranges): per buffer a uint8 tensor of
+        codes and an int32 tensor [n_tensors, 4] holding the header records (lo and delta are the float32
+        bit patterns of columns 0 and 1)."""
+        sizes = [B.compressed_block_size(self.model, k, bits) for k in self.keys]
+        codes = [torch.empty(nb, dtype=torch.uint8, device=self.device) for nb, _ in sizes]
+        ranges = [torch.empty((nt, 4), dtype=torch.int32, device=self.device) for _, nt in sizes]
+        B.compress_blocks(self.model, self.keys, bits, self.params, codes, ranges, stream)
+        return codes, ranges
+
     def download(self):
         """-> {key: {name: logical array}} of the current parameter buffers."""
         return {k: B.unpack_block(self.model, k, p.cpu().numpy()) for k, p in zip(self.keys, self.params)}
@@ -95,11 +105,13 @@ def to_device_batch(x, labels, device="cuda"):
 
 
 def run_round(model, glob, S, min_depth, seed, rnd, local_iters, batch_fn, batch, lr, mu, wd,
-              partitionable=None, stream=None):
+              partitionable=None, stream=None, compress_bits=0):
     """One synchronisation round of Algorithm 1 on one GPU: split the global model (a DeviceModel
     holding every block) into S sub-ResNets for round `rnd`, run `local_iters` local steps of each, one
     sub-ResNet after the other, from the current global parameters and with fresh (zero) momentum,
     then reassemble the global model in place.  batch_fn(rnd, s, it) -> device (x, labels).
+    With compress_bits = b in 2..8 every worker sends its blocks back compressed to b bits and the
+    global model is reassembled from the compressed copies.
     Returns the partition and the workers (their loss buffers hold the last local loss)."""
     subs, owner = B.partition(model, S, min_depth, seed, rnd, partitionable)
     workers = []
@@ -109,7 +121,11 @@ def run_round(model, glob, S, min_depth, seed, rnd, local_iters, batch_fn, batch
             x, y = batch_fn(rnd, s, it)
             w.step(x, y, lr, mu, wd, stream)
         workers.append(w)
-    B.aggregate(model, subs, [w.params for w in workers], glob.params, stream)
+    if compress_bits:
+        comp = [w.compress(compress_bits, stream) for w in workers]
+        B.aggregate_compressed(model, subs, compress_bits, [c for c, _ in comp], [r for _, r in comp], glob.params, stream)
+    else:
+        B.aggregate(model, subs, [w.params for w in workers], glob.params, stream)
     return subs, owner, workers
 
 

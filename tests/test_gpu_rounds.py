@@ -51,6 +51,45 @@ def test_two_rounds_paper_mode_partition():
             assert rel <= 2e-3, f"after {rounds} rounds: block {k} {n}: relative L2 error {rel:.3e}"
 
 
+def test_round_with_compressed_communication():
+    """One round in which the workers send their blocks back as 6-bit codes (appendix on quantised
+    communication).  The workers' weights differ from the oracle's by fp32 rounding (<= 1e-4
+    relative), which moves a weight across a rounding boundary of the quantiser now and then: such an
+    element decodes one step higher or lower.  So: every element of the reassembled model within one
+    quantiser step of the oracle's, and all but a small fraction within the fp32 bound."""
+    from oracle import compress as OC
+    model = dict(get_config("cfg1")["model"], widths=[16, 32, 64], blocks=[2, 2, 5], in_h=16, in_w=16, num_classes=10)
+    nb = R.num_blocks(model)
+    mask = [1 if b > 4 else 0 for b in range(nb)]
+    S, min_depth, seed, iters, batch, bits = 3, 2, 21, 2, 6, 6
+    lr, mu, wd = 0.05, 0.9, 5e-4
+    params = make_params(model, 4, perturb_bn=True)
+
+    def host_batch(t, s, it):
+        return make_batch(model, batch, 10000 * t + 100 * s + it)
+
+    want, log = ORD.run_rounds(model, params, S, min_depth, seed, 1, iters, host_batch, lr, mu, wd, partitionable=mask,
+                               compress_bits=bits)
+    exact, _ = ORD.run_rounds(model, params, S, min_depth, seed, 1, iters, host_batch, lr, mu, wd, partitionable=mask)
+    glob = DeviceModel(model, list(range(nb)), params)
+    subs, owner, workers = run_round(model, glob, S, min_depth, seed, 0, iters,
+                                     lambda r, s, it: to_device_batch(*host_batch(r, s, it)), batch, lr, mu, wd,
+                                     partitionable=mask, compress_bits=bits)
+    torch.cuda.synchronize()
+    assert (subs, owner) == (log[0]["subs"], log[0]["owner"])
+    got = glob.download()
+    total = off = 0
+    for k in want:
+        for n in want[k]:
+            g, w = np.asarray(got[k][n], np.float64), np.asarray(want[k][n], np.float64)
+            spread = float(np.max(exact[k][n]) - np.min(exact[k][n]))
+            step = 1.25 * spread / ((1 << bits) - 1) + 1e-6        # about one quantiser step of a worker's copy of this tensor
+            assert np.max(np.abs(g - w)) <= step, f"block {k} {n}: farther than one quantiser step"
+            total += g.size
+            off += int(np.sum(np.abs(g - w) > 1e-5 + 1e-4 * np.abs(w)))
+    assert off <= 0.01 * total, f"{off} of {total} elements off by a quantiser step"
+
+
 @pytest.mark.parametrize("kind", ["basic", "bottleneck", "bottleneck_bf16", "preact", "preact_bottleneck_bf16"])
 def test_forward_eval_with_branch_scaling(kind):
     """resist_forward: evaluation-mode BN (running statistics) and 1/S scaling of the partitioned

@@ -190,3 +190,46 @@ def test_tensors_beyond_two_gib_are_refused_up_front():
         R.forward_workspace_bytes(model, blocks, 8192)
     with pytest.raises(R.ResistError, match="2 GiB"):
         R.workspace_bytes(dict(model, block_kind=2), blocks, 8192)
+
+
+def test_compressed_block_sizes_and_argument_errors():
+    """Sizes of a compressed block follow the layout (one code per float of the buffer, a byte or a
+    nibble each; one header record per tensor); bad arguments are refused before any launch."""
+    lib = R.lib()
+    for kind in (0, 1, 2, 3):
+        model = dict(get_config("cfg2")["model"], block_kind=kind, num_classes=7)
+        nb = R.num_blocks(model)
+        for key in (-1, 0, 3, nb - 1, nb):
+            n_total = R.block_param_count(model, key)[0]
+            nt = len(R.block_layout(model, key))
+            for bits in (8, 5):
+                assert R.compressed_block_size(model, key, bits) == (n_total, nt)
+            for bits in (4, 2):
+                assert R.compressed_block_size(model, key, bits) == ((n_total + 1) // 2, nt)
+    model = get_config("cfg2")["model"]
+    d = R.model_desc(model)
+    for bits in (1, 9, 0, -3):
+        with pytest.raises(R.ResistError, match="bits"):
+            R.compressed_block_size(model, 0, bits)
+    with pytest.raises(R.ResistError):
+        R.compressed_block_size(model, R.num_blocks(model) + 1, 8)
+    keys = (ctypes.c_int32 * 2)(0, 1)
+    ok = (ctypes.c_void_p * 2)(256, 256)
+    assert lib.resist_compress_blocks(ctypes.byref(d), 2, keys, 8, None, ok, ok, None) == -1
+    assert lib.resist_compress_blocks(ctypes.byref(d), 2, keys, 8, ok, (ctypes.c_void_p * 2)(256, 0), ok, None) == -1
+    assert lib.resist_compress_blocks(ctypes.byref(d), 2, keys, 8, ok, (ctypes.c_void_p * 2)(256, 258), ok, None) == -1   # codes not 4-byte aligned
+    assert lib.resist_compress_blocks(ctypes.byref(d), 2, keys, 8, ok, ok, (ctypes.c_void_p * 2)(256, 264), None) == -1   # header not 16-byte aligned
+    assert lib.resist_compress_blocks(ctypes.byref(d), 2, keys, 12, ok, ok, ok, None) == -1
+    assert lib.resist_compress_blocks(ctypes.byref(d), 0, None, 8, None, None, None, None) == 0                         # nothing to do
+    nb = R.num_blocks(model)
+    blocks = (ctypes.c_int32 * 4)(0, 3, 7, 30)
+    offs = (ctypes.c_int32 * 2)(0, 4)
+    glob = (ctypes.c_void_p * (nb + 2))(*([256] * (nb + 2)))
+    six = (ctypes.c_void_p * 6)(*([256] * 6))
+    one = (ctypes.POINTER(ctypes.c_void_p) * 1)(ctypes.cast(six, ctypes.POINTER(ctypes.c_void_p)))
+    assert lib.resist_aggregate_compressed(ctypes.byref(d), 0, offs, blocks, 8, one, one, glob, None) == -1
+    assert lib.resist_aggregate_compressed(ctypes.byref(d), 17, offs, blocks, 8, one, one, glob, None) == -5
+    assert lib.resist_aggregate_compressed(ctypes.byref(d), 1, offs, blocks, 9, one, one, glob, None) == -1
+    assert lib.resist_aggregate_compressed(ctypes.byref(d), 1, offs, blocks, 8, one, None, glob, None) == -1
+    bad = (ctypes.c_int32 * 4)(0, 3, 3, 30)
+    assert lib.resist_aggregate_compressed(ctypes.byref(d), 1, offs, bad, 8, one, one, glob, None) == -1                # not ascending

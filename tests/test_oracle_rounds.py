@@ -51,3 +51,35 @@ def test_rounds_use_fresh_partitions_and_leave_untrained_tensors_alone():
         for n in same[k]:
             if OR.is_trainable(n):
                 np.testing.assert_allclose(same[k][n], params[k][n], rtol=0, atol=1e-7)
+
+
+def test_round_with_compressed_communication_stays_within_half_a_step():
+    """Appendix on quantised communication: with b-bit codes on the way back, every reassembled value
+    is within the mean half-step of the uncompressed round's value; 8 bits is closer than 4."""
+    from oracle import compress as OC
+    model = dict(get_config("cfg1")["model"], widths=[8, 16], blocks=[2, 3], in_h=8, in_w=8, num_classes=5)
+    params = make_params(model, 1, perturb_bn=True)
+
+    def batch_fn(t, s, it):
+        return make_batch(model, 4, 100 * t + 10 * s + it)
+
+    exact, log = ORD.run_rounds(model, params, 2, 0, 3, 1, 2, batch_fn, 0.05, 0.9, 0.0)
+    errs = {}
+    for bits in (8, 4):
+        got, log_q = ORD.run_rounds(model, params, 2, 0, 3, 1, 2, batch_fn, 0.05, 0.9, 0.0, compress_bits=bits)
+        assert log_q[0]["subs"] == log[0]["subs"] and log_q[0]["losses"] == log[0]["losses"]
+        worst = 0.0
+        for k in exact:
+            held = k in (-1, max(exact)) or any(k in s for s in log[0]["subs"])
+            for n in exact[k]:
+                e = np.asarray(exact[k][n], np.float64)
+                d = np.abs(np.asarray(got[k][n], np.float64) - e)
+                if not held:
+                    assert d.max() == 0
+                    continue
+                # a worker's copy differs from the mean by less than the tensor's spread: bound with twice it
+                bound = 0.5 * 2.0 * (e.max() - e.min() + 1e-3) / ((1 << bits) - 1)
+                assert d.max() <= bound, (bits, k, n, d.max(), bound)
+                worst = max(worst, d.max())
+        errs[bits] = worst
+    assert 0 < errs[8] < errs[4]

@@ -145,6 +145,18 @@ int resist_local_step(const resist_model_desc *desc, const int32_t *blocks, int3
                       int64_t workspace_bytes, float *loss_out, void *hip_stream);
 
 /*
+ * Stream use of resist_local_step (not a step of the paper's method).  By default the weight-gradient
+ * kernels of the backward pass, which only the parameter update at the end of the step needs, are
+ * enqueued on a second stream the library creates per device (default priority, non-blocking),
+ * ordered against hip_stream with events: started when their input is complete, joined before the
+ * update.  Seen from the caller everything is still ordered on hip_stream, and results are bit for
+ * bit the same either way.  resist_set_overlap(0) keeps every kernel on hip_stream (one kernel at a
+ * time: per-kernel timings are then those of a kernel that has the GPU to itself);
+ * resist_set_overlap(1) restores the default.  Process-wide; takes effect at the next call.  host.
+ */
+int resist_set_overlap(int32_t on);
+
+/*
  * Test-time forward pass (Sec. 2.6, "Scaling Activations"): logits of a batch through the stem, the
  * listed blocks and the head, with BN normalising by the running statistics stored in the block
  * buffers and the residual branch of blocks[i] multiplied by branch_scale[i] before the shortcut is

@@ -49,7 +49,7 @@ def lib():
                      "resist_conv2d_workspace_bytes", "resist_conv2d_forward",
                      "resist_conv2d_dgrad", "resist_conv2d_wgrad", "resist_profile_enable",
                      "resist_profile_read", "resist_compressed_block_size",
-                     "resist_compress_blocks", "resist_aggregate_compressed"):
+                     "resist_compress_blocks", "resist_aggregate_compressed", "resist_set_overlap"):
             getattr(L, name).restype = C.c_int
         L.resist_local_step.argtypes = [
             C.POINTER(_ModelDesc), C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_void_p),
@@ -291,6 +291,12 @@ def aggregate_compressed(model, subs, bits, sub_codes, sub_ranges, global_params
     outer_r = (C.POINTER(C.c_void_p) * S)(*[C.cast(k, C.POINTER(C.c_void_p)) for k in keep_r])
     _check(lib().resist_aggregate_compressed(C.byref(model_desc(model)), S, offs_a, flat_a, bits, outer_c,
                                              outer_r, _ptr_array(global_params), _stream_ptr(stream)))
+
+
+def set_overlap(on):
+    """Whether local_step runs its weight gradients on the library's second stream (default) or keeps
+    every kernel on the caller's stream."""
+    _check(lib().resist_set_overlap(1 if on else 0))
 
 
 def profile_enable(on):

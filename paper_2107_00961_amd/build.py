@@ -8,7 +8,7 @@ CSRC = os.path.join(HERE, "csrc")
 INC = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libresist.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["model.cpp", "step.cpp", "ops.cpp", "prof.cpp", "conv.hip", "bn.hip", "head.hip", "stem.hip", "update.hip", "compress.hip"]
+SOURCES = ["model.cpp", "step.cpp", "ops.cpp", "prof.cpp", "overlap.cpp", "conv.hip", "bn.hip", "head.hip", "stem.hip", "update.hip", "compress.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3"] + os.environ.get("RESIST_EXTRA_FLAGS", "").split() + ["-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-I", INC, "-I", CSRC]
 

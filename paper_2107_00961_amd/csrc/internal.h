@@ -41,6 +41,25 @@ struct Scope {   // brackets the launches made during its lifetime with two even
 };
 }  // namespace prof
 
+// ---- side stream for work off a step's critical path (overlap.cpp) -----------------------------
+bool overlap_enabled();   // resist_set_overlap(); on by default
+class SideStream {
+ public:
+  SideStream(hipStream_t main, bool enable);   // enable == false, or no stream to be had: every call below is a no-op
+  bool on() const { return side_ != nullptr; }
+  hipStream_t stream() const { return side_ ? side_ : main_; }   // where the off-path work goes
+  hipStream_t main() const { return main_; }
+  int fork();                     // the side stream waits for everything enqueued on the main stream so far
+  int mark(hipEvent_t *ev);       // *ev: completes when everything enqueued on the side stream so far has
+  int main_wait(hipEvent_t ev);   // the main stream waits for ev (NULL: nothing to wait for)
+  int join();                     // the main stream waits for everything enqueued on the side stream
+
+ private:
+  hipEvent_t take();
+  hipStream_t main_, side_;
+  int dev_;
+};
+
 // ---- static description of the global network -------------------------------------------------
 struct BlockShape {
   int stage, index;         // position

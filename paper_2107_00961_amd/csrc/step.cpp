@@ -4,11 +4,55 @@
 // A block that is not in the list is simply not launched -- the residual stream passes through
 // (Appendix B, forward recursion with mask 0).
 #include <algorithm>
+#include <cstdlib>
 
 #include "internal.h"
 
 namespace resist {
 namespace {
+
+// Weight gradients feed only the update at the end of a step; they run on a side stream next to the
+// chain data gradient -> BN backward -> next layer, whose short kernels then overlap with them.  A
+// weight gradient starts once its output gradient is complete (fork), and a buffer it reads is not
+// overwritten before it has finished (before_write).
+struct WgradSide {
+  SideStream side;
+  int dt;
+  float *splitk;
+  std::vector<std::pair<const void *, hipEvent_t>> readers;   // buffer -> its last reader on the side stream
+  WgradSide(hipStream_t main, int dt_, float *splitk_) : side(main, overlap_enabled()), dt(dt_), splitk(splitk_) {}
+  hipStream_t stream() const { return side.stream(); }
+  int launch(const ConvGeom &g, const void *dyb, const void *xin, float *dw) {
+    RESIST_TRY(side.fork());
+    RESIST_TRY(conv_wgrad(g, dt, dyb, xin, dw, splitk, side.stream()));
+    hipEvent_t e = nullptr;
+    RESIST_TRY(side.mark(&e));
+    for (auto &r : readers)
+      if (r.first == dyb) { r.second = e; return RESIST_OK; }
+    readers.emplace_back(dyb, e);
+    return RESIST_OK;
+  }
+  int before_write(const void *buf) {
+    for (auto &r : readers)
+      if (r.first == buf && r.second) { RESIST_TRY(side.main_wait(r.second)); r.second = nullptr; }
+    return RESIST_OK;
+  }
+  // Filter copies and transposes.  In fp32 mode the forward pass multiplies the master filters, so the
+  // transposes are first needed by the backward pass: made on the side stream while the forward runs.
+  hipEvent_t prepared = nullptr;
+  int prepare(const std::vector<FilterPrep> &prep) {
+    if (dt != DT_F32 || !side.on()) return prepare_filters(prep, dt, side.main());
+    RESIST_TRY(side.fork());
+    RESIST_TRY(prepare_filters(prep, dt, side.stream()));
+    return side.mark(&prepared);
+  }
+  int filters_ready() {   // before the first data gradient
+    RESIST_TRY(side.main_wait(prepared));
+    prepared = nullptr;
+    return RESIST_OK;
+  }
+  int join() { return side.join(); }
+};
 
 struct Arena {
   char *base;
@@ -546,6 +590,7 @@ int local_step_preact(const resist_model_desc *desc, const int32_t *blocks, int3
   const float eps = net.d.bn_eps, bnm = net.d.bn_momentum;
   auto params = [&](int slot) { return (float *)block_params[slot]; };
   auto grads = [&](int slot) { return block_grads ? (float *)block_grads[slot] : P.own_grads[slot]; };
+  WgradSide wg(st, dt, P.splitk);
   {
     std::vector<FilterPrep> prep;
     for (PreBlock &pb : P.blocks) {
@@ -553,7 +598,7 @@ int local_step_preact(const resist_model_desc *desc, const int32_t *blocks, int3
       for (PreUnit &un : pb.units) prep.push_back(FilterPrep{un.g, pp + un.w_off, un.wlp, un.wT});
       if (pb.has_ds) prep.push_back(FilterPrep{pb.dsg, pp + pb.ds_w_off, pb.ds_wlp, pb.ds_wT});
     }
-    RESIST_TRY(prepare_filters(prep, dt, st));
+    RESIST_TRY(wg.prepare(prep));
   }
   auto fwd_filter = [&](const float *w, const void *wlp) -> const void * { return dt == DT_F32 ? (const void *)w : wlp; };
 
@@ -599,6 +644,7 @@ int local_step_preact(const resist_model_desc *desc, const int32_t *blocks, int3
   RESIST_TRY(fc_bwd_f32(P.dz, P.pooled, fcw, P.dpooled, hg + HL.off(T_FCW, 0), hg + HL.off(T_FCB, 0), N, CH, J, st));
   RESIST_TRY(avgpool_bwd(dt, P.dpooled, P.da, N, P.feat_hw, CH, st));
   int gi = 0;
+  RESIST_TRY(wg.filters_ready());
   RESIST_TRY(bn_backward(dt, P.da, nullptr, true, P.feat_in, P.head_rows, CH, hb, P.gbuf[gi], nullptr, nullptr, P.bn_scratch, st));
   for (int bi = (int)P.blocks.size() - 1; bi >= 0; --bi) {
     PreBlock &pb = P.blocks[bi];
@@ -608,29 +654,32 @@ int local_step_preact(const resist_model_desc *desc, const int32_t *blocks, int3
     void *dy = P.dy0, *dy_other = P.dy1;
     for (int j = (int)pb.units.size() - 1; j >= 0; --j) {
       PreUnit &un = pb.units[j];
-      RESIST_TRY(conv_wgrad(un.g, dt, gcur, un.a, gg + un.w_off, P.splitk, st));
+      RESIST_TRY(wg.launch(un.g, gcur, un.a, gg + un.w_off));
       const void *addend = nullptr;
       if (j == 0 && pb.has_ds) {
         // the shortcut convolution reads the same a_1: its data gradient joins the branch's
-        RESIST_TRY(conv_wgrad(pb.dsg, dt, G, un.a, gg + pb.ds_w_off, P.splitk, st));
+        RESIST_TRY(wg.launch(pb.dsg, G, un.a, gg + pb.ds_w_off));
         RESIST_TRY(conv_dgrad(pb.dsg, dt, G, pb.ds_wT, P.dsgrad, nullptr, st));
         addend = P.dsgrad;
       }
       RESIST_TRY(conv_dgrad(un.g, dt, gcur, un.wT, P.da, addend, st));
       BnBufs b = pre_bn_bufs(un, pp, gg);
       if (j > 0) {
+        RESIST_TRY(wg.before_write(dy));
         RESIST_TRY(bn_backward(dt, P.da, nullptr, true, un.u, un.rows(), un.g.C, b, dy, nullptr, nullptr, P.bn_scratch, st));
         gcur = dy;
         std::swap(dy, dy_other);
       } else {
         // gradient w.r.t. the block input: through BN_1, plus the identity shortcut's share
+        RESIST_TRY(wg.before_write(Gn));
         RESIST_TRY(bn_backward(dt, P.da, nullptr, true, un.u, un.rows(), un.g.C, b, Gn, nullptr, pb.has_ds ? nullptr : G, P.bn_scratch, st));
       }
     }
     gi ^= 1;
   }
-  RESIST_TRY(conv_wgrad(P.stem, dt, P.gbuf[gi], P.col, P.dwpad, P.splitk, st));
-  RESIST_TRY(unpad_rows_f32(P.dwpad, grads(0) + P.stem_w_off, K0, taps, P.kpad, st));
+  RESIST_TRY(wg.launch(P.stem, P.gbuf[gi], P.col, P.dwpad));
+  RESIST_TRY(unpad_rows_f32(P.dwpad, grads(0) + P.stem_w_off, K0, taps, P.kpad, wg.stream()));
+  RESIST_TRY(wg.join());
 
   // ================= update =================
   std::vector<SgdSeg> segs;
@@ -711,6 +760,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
   auto grads = [&](int slot) { return block_grads ? (float *)block_grads[slot] : P.own_grads[slot]; };
 
   const int dt = net.d.compute_dtype;
+  WgradSide wg(st, dt, P.splitk);
   // every filter once, up front: the transpose the data gradient reads and, in bf16 mode, the copy
   // the forward convolution multiplies with (fp32 mode multiplies the master itself)
   {
@@ -720,7 +770,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
       for (ConvLayer &c : bp.convs) prep.push_back(FilterPrep{c.g, pp + c.w_off, c.wlp, c.wT});
       if (bp.has_ds) prep.push_back(FilterPrep{bp.ds.g, pp + bp.ds.w_off, bp.ds.wlp, bp.ds.wT});
     }
-    RESIST_TRY(prepare_filters(prep, dt, st));
+    RESIST_TRY(wg.prepare(prep));
   }
   auto fwd_filter = [&](const ConvLayer &c, const float *w) -> const void * { return dt == DT_F32 ? (const void *)w : c.wlp; };
 
@@ -772,6 +822,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
   RESIST_TRY(softmax_ce_f32(P.z, labels, loss_out, P.dz, P.row_loss, N, J, st));
 
   // ================= backward =================
+  RESIST_TRY(wg.filters_ready());
   RESIST_TRY(fc_bwd_f32(P.dz, P.pooled, fcw, P.dpooled, grads(hs) + HL.off(T_FCW, 0), grads(hs) + HL.off(T_FCB, 0), N, CH, J, st));
   int gi = 0;
   void *G = P.gbuf[gi];
@@ -784,23 +835,26 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     ConvLayer &last = bp.convs[nc - 1];
     BnBufs bl = bn_bufs(last, pp, gg);
     // through the final ReLU and the last BN of the residual branch
+    RESIST_TRY(wg.before_write(P.dy0));
+    RESIST_TRY(wg.before_write(P.gm));
     RESIST_TRY(bn_backward(dt, G, bp.out, false, last.y, last.M(), last.g.K, bl, P.dy0, bp.has_ds ? nullptr : P.gm, nullptr, P.bn_scratch, st));
     if (bp.has_ds) {
       // shortcut branch: BN and 1x1 convolution; its data gradient initialises Gn
       ConvLayer &d = bp.ds;
       BnBufs bd = bn_bufs(d, pp, gg);
       RESIST_TRY(bn_backward(dt, G, bp.out, false, d.y, d.M(), d.g.K, bd, P.gm, nullptr, nullptr, P.bn_scratch, st));
-      RESIST_TRY(conv_wgrad(d.g, dt, P.gm, d.in, gg + d.w_off, P.splitk, st));
+      RESIST_TRY(wg.launch(d.g, P.gm, d.in, gg + d.w_off));
       RESIST_TRY(conv_dgrad(d.g, dt, P.gm, d.wT, Gn, nullptr, st));
     }
     void *dy = P.dy0, *dy_other = P.dy1;
     for (int j = nc - 1; j >= 0; --j) {
       ConvLayer &c = bp.convs[j];
-      RESIST_TRY(conv_wgrad(c.g, dt, dy, c.in, gg + c.w_off, P.splitk, st));
+      RESIST_TRY(wg.launch(c.g, dy, c.in, gg + c.w_off));
       if (j > 0) {
         ConvLayer &prev = bp.convs[j - 1];
         RESIST_TRY(conv_dgrad(c.g, dt, dy, c.wT, P.da, nullptr, st));
         BnBufs bp_ = bn_bufs(prev, pp, gg);
+        RESIST_TRY(wg.before_write(dy_other));
         RESIST_TRY(bn_backward(dt, P.da, nullptr, true, prev.y, prev.M(), prev.g.K, bp_, dy_other, nullptr, nullptr, P.bn_scratch, st));
         std::swap(dy, dy_other);
       } else {
@@ -821,10 +875,12 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
       Gs = P.da;
     }
     BnBufs b = bn_bufs(s, params(0), grads(0));
+    RESIST_TRY(wg.before_write(P.dy0));
     RESIST_TRY(bn_backward(dt, Gs, nullptr, true, s.y, s.M(), K0, b, P.dy0, nullptr, nullptr, P.bn_scratch, st));
-    RESIST_TRY(conv_wgrad(s.g, dt, P.dy0, P.col, P.dwpad, P.splitk, st));
-    RESIST_TRY(unpad_rows_f32(P.dwpad, grads(0) + s.w_off, K0, taps, P.kpad, st));
+    RESIST_TRY(wg.launch(s.g, P.dy0, P.col, P.dwpad));
+    RESIST_TRY(unpad_rows_f32(P.dwpad, grads(0) + s.w_off, K0, taps, P.kpad, wg.stream()));
   }
+  RESIST_TRY(wg.join());
 
   // ================= update =================
   std::vector<SgdSeg> segs;

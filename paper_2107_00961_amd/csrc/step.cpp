@@ -51,7 +51,15 @@ struct WgradSide {
     prepared = nullptr;
     return RESIST_OK;
   }
-  int join() { return side.join(); }
+  bool joined = false;
+  int join() {
+    joined = true;
+    return side.join();
+  }
+  // an error return in mid-step still leaves the caller's stream ordered after the side stream's work
+  ~WgradSide() {
+    if (!joined) (void)side.join();
+  }
 };
 
 struct Arena {

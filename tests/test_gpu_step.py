@@ -331,3 +331,57 @@ def test_cfg2_widths_reduced_depth_strict():
     else:
         pytest.fail("no seed with a clear ReLU margin")
     _run_steps(model, blocks, batch, steps=1, lr=0.1, mu=0.9, wd=5e-4, seed=seed, perturb_bn=False)
+
+
+@pytest.mark.parametrize("name", ["strided_sub", "bottleneck_sub", "preact_full", "preact_bottleneck_sub"])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_second_stream_changes_no_bit(name, bf16):
+    """The weight gradients run on the library's second stream by default.  Three consecutive steps
+    with it give the same bits -- parameters, momentum, gradients, loss -- as with every kernel on the
+    caller's stream: the events order every buffer reuse."""
+    model, blocks, batch = _small_models()[name]
+    if bf16:
+        model = dict(model, compute_dtype=1)
+    params = make_params(model, 5, perturb_bn=True)
+    outs = []
+    try:
+        for overlap in (False, True, True):
+            R.set_overlap(overlap)
+            sub = SubResNet(model, blocks, params, batch)
+            for it in range(3):
+                xd, yd = to_device_batch(*make_batch(model, batch, 40 + it))
+                sub.step(xd, yd, 0.05, 0.9, 1e-4)
+            torch.cuda.synchronize()
+            outs.append([t.cpu().numpy().copy() for t in sub.params + sub.momentum + sub.grads] + [sub.loss.cpu().numpy().copy()])
+    finally:
+        R.set_overlap(True)
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert a.tobytes() == b.tobytes()
+
+
+@pytest.mark.parametrize("workload", ["cfg2", "cfg2_preact", "cfg4"])
+def test_second_stream_changes_no_bit_full_size(workload):
+    """The same at the sizes the benchmark times, where kernels on the two streams really run
+    side by side for most of the backward pass."""
+    cfg = get_config(workload)
+    model, batch = cfg["model"], cfg["batch"]
+    if workload == "cfg4":
+        batch = 16
+    subs, _ = R.partition(model, cfg["S"], cfg.get("min_depth", 0), cfg["part_seed"], 0)
+    params = make_params(model, 0)
+    xd, yd = to_device_batch(*make_batch(model, batch, cfg["data_seed"]))
+    outs = []
+    try:
+        for overlap in (False, True):
+            R.set_overlap(overlap)
+            sub = SubResNet(model, subs[0], params, batch)
+            for it in range(3):
+                sub.step(xd, yd, cfg["lr"] * 0.01, cfg["momentum"], cfg["weight_decay"])
+            torch.cuda.synchronize()
+            outs.append([t.cpu().numpy().copy() for t in sub.params + sub.momentum + sub.grads] + [sub.loss.cpu().numpy().copy()])
+            del sub
+    finally:
+        R.set_overlap(True)
+    for a, b in zip(*outs):
+        assert a.tobytes() == b.tobytes()

@@ -629,9 +629,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  // order: tile fastest, then filter tap, then reduction split (hardware round-robin over the XCDs:
-  // this MFMA-bound kernel measured faster that way than with one contiguous range per XCD)
-  int bid = blockIdx.x;
+  // order: tile fastest, then filter tap, then reduction split; every XCD gets one contiguous range
+  // of that order, i.e. a range of reduction rows, so each L2 fetches only its share of dy and x
+  // (with the hardware's round-robin order every XCD read both tensors in full: 8x the traffic, same speed)
+  int bid = xcd_contiguous(blockIdx.x, gridDim.x);
   const int tile = bid % (a.tiles_k * a.tiles_c);
   bid /= a.tiles_k * a.tiles_c;
   const int tap = bid % (a.R * a.S), split = bid / (a.R * a.S);
@@ -956,7 +957,7 @@ WgradPlan plan_wgrad(const ConvGeom &g) {
   p.bn = p.bm;
   const long long tiles = (long long)((g.K + p.bm - 1) / p.bm) * ((g.C + p.bn - 1) / p.bn) * g.R * g.S;
   const long long M = (long long)g.N * g.P * g.Q;
-  long long splits = (768 + tiles - 1) / tiles;
+  long long splits = 768 / tiles;   // at most three workgroups per CU: all resident at once (measured best)
   const long long max_splits = (M + 255) / 256;  // at least 256 reduction rows per split
   if (splits > max_splits) splits = max_splits;
   if (splits < 1) splits = 1;

@@ -211,14 +211,14 @@ def main():
         return st, ms
 
     stats_in_step, ms_profiled = profiled_pass()
-    R.set_overlap(False)
+    R.set_overlap(0)
     stats, ms_profiled_one_stream = profiled_pass()
     t1 = time.perf_counter()
     for _ in range(psteps):
         sub.step(xd, yd, lr, mu, wd, stream)
     torch.cuda.synchronize()
     ms_one_stream = (time.perf_counter() - t1) / psteps * 1e3
-    R.set_overlap(True)
+    R.set_overlap(1)
     in_step = {s["name"]: s for s in stats_in_step}
     stats.sort(key=lambda s: -s["ms"])
     dtype = "bf16" if model.get("compute_dtype", 0) == 1 else "f32"
@@ -292,7 +292,7 @@ def main():
                    "widths": model["widths"], "blocks_per_stage": model["blocks"], "classes": model["num_classes"]},
         "roofline": roof,
         "cpu_baseline": cpu,
-        "streams": {"overlap": True, "ms_per_step_one_stream": round(ms_one_stream, 4),
+        "streams": {"overlap_mode": 1, "ms_per_step_one_stream": round(ms_one_stream, 4),
                     "ms_per_step_with_event_timing": round(ms_profiled, 4),
                     "ms_per_step_one_stream_with_event_timing": round(ms_profiled_one_stream, 4)},
         "final_loss": loss,

@@ -145,16 +145,20 @@ int resist_local_step(const resist_model_desc *desc, const int32_t *blocks, int3
                       int64_t workspace_bytes, float *loss_out, void *hip_stream);
 
 /*
- * Stream use of resist_local_step (not a step of the paper's method).  By default the weight-gradient
- * kernels of the backward pass, which only the parameter update at the end of the step needs, are
- * enqueued on a second stream the library creates per device (default priority, non-blocking),
- * ordered against hip_stream with events: started when their input is complete, joined before the
- * update.  Seen from the caller everything is still ordered on hip_stream, and results are bit for
- * bit the same either way.  resist_set_overlap(0) keeps every kernel on hip_stream (one kernel at a
- * time: per-kernel timings are then those of a kernel that has the GPU to itself);
- * resist_set_overlap(1) restores the default.  Process-wide; takes effect at the next call.  host.
+ * Stream use of resist_local_step (not a step of the paper's method).  The weight-gradient kernels of
+ * the backward pass, which only the parameter update at the end of the step needs, can be enqueued
+ * on a second stream the library creates per device (default priority, non-blocking), ordered
+ * against hip_stream with events: started when their input is complete, joined before the update.
+ * Seen from the caller everything is still ordered on hip_stream, and results are bit for bit the
+ * same either way.
+ *   mode 1 (default)  second stream for steps with at least ~20 GFLOP of convolution work (smaller
+ *                     steps are bound by launch latency and the event calls would cost more)
+ *   mode 2            second stream always
+ *   mode 0            every kernel on hip_stream, one at a time (per-kernel timings are then those
+ *                     of a kernel that has the GPU to itself)
+ * Process-wide; takes effect at the next call.  host.
  */
-int resist_set_overlap(int32_t on);
+int resist_set_overlap(int32_t mode);
 
 /*
  * Test-time forward pass (Sec. 2.6, "Scaling Activations"): logits of a batch through the stem, the

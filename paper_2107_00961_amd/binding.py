@@ -293,10 +293,10 @@ def aggregate_compressed(model, subs, bits, sub_codes, sub_ranges, global_params
                                              outer_r, _ptr_array(global_params), _stream_ptr(stream)))
 
 
-def set_overlap(on):
-    """Whether local_step runs its weight gradients on the library's second stream (default) or keeps
-    every kernel on the caller's stream."""
-    _check(lib().resist_set_overlap(1 if on else 0))
+def set_overlap(mode):
+    """Second stream for the weight gradients of local_step: 0/False never, 1/True for steps with
+    enough work (default), 2 always."""
+    _check(lib().resist_set_overlap(int(mode)))
 
 
 def profile_enable(on):

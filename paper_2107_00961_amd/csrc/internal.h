@@ -42,7 +42,7 @@ struct Scope {   // brackets the launches made during its lifetime with two even
 }  // namespace prof
 
 // ---- side stream for work off a step's critical path (overlap.cpp) -----------------------------
-bool overlap_enabled();   // resist_set_overlap(); on by default
+int overlap_mode();   // resist_set_overlap(): 0 off, 1 for steps with enough work (default), 2 always
 class SideStream {
  public:
   SideStream(hipStream_t main, bool enable);   // enable == false, or no stream to be had: every call below is a no-op

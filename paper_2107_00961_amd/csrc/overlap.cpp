@@ -26,10 +26,11 @@ std::atomic<int> g_overlap{1};
 
 }  // namespace
 
-bool overlap_enabled() { return g_overlap.load() != 0; }
+int overlap_mode() { return g_overlap.load(); }
 
-extern "C" int resist_set_overlap(int32_t on) {
-  g_overlap.store(on ? 1 : 0);
+extern "C" int resist_set_overlap(int32_t mode) {
+  if (mode < 0 || mode > 2) return set_error(RESIST_EINVAL, "overlap mode %d: 0 (off), 1 (steps with enough work) or 2 (always)", mode);
+  g_overlap.store(mode);
   return RESIST_OK;
 }
 

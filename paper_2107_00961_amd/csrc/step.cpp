@@ -11,6 +11,8 @@
 namespace resist {
 namespace {
 
+inline double geom_flops(const ConvGeom &g) { return 2.0 * g.N * g.P * g.Q * g.K * g.C * g.R * g.S; }
+
 // Weight gradients feed only the update at the end of a step; they run on a side stream next to the
 // chain data gradient -> BN backward -> next layer, whose short kernels then overlap with them.  A
 // weight gradient starts once its output gradient is complete (fork), and a buffer it reads is not
@@ -20,7 +22,10 @@ struct WgradSide {
   int dt;
   float *splitk;
   std::vector<std::pair<const void *, hipEvent_t>> readers;   // buffer -> its last reader on the side stream
-  WgradSide(hipStream_t main, int dt_, float *splitk_) : side(main, overlap_enabled()), dt(dt_), splitk(splitk_) {}
+  // `flops`: convolution work of the step.  Below ~20 GFLOP a step is bound by launch latency and the
+  // event calls of the second stream cost more than the overlap returns: everything stays on `main`.
+  WgradSide(hipStream_t main, int dt_, float *splitk_, double flops)
+      : side(main, overlap_mode() == 2 || (overlap_mode() == 1 && flops >= 2e10)), dt(dt_), splitk(splitk_) {}
   hipStream_t stream() const { return side.stream(); }
   int launch(const ConvGeom &g, const void *dyb, const void *xin, float *dw) {
     RESIST_TRY(side.fork());
@@ -598,7 +603,12 @@ int local_step_preact(const resist_model_desc *desc, const int32_t *blocks, int3
   const float eps = net.d.bn_eps, bnm = net.d.bn_momentum;
   auto params = [&](int slot) { return (float *)block_params[slot]; };
   auto grads = [&](int slot) { return block_grads ? (float *)block_grads[slot] : P.own_grads[slot]; };
-  WgradSide wg(st, dt, P.splitk);
+  double step_flops = 0;
+  for (PreBlock &pb : P.blocks) {
+    for (PreUnit &un : pb.units) step_flops += 3.0 * geom_flops(un.g);
+    if (pb.has_ds) step_flops += 3.0 * geom_flops(pb.dsg);
+  }
+  WgradSide wg(st, dt, P.splitk, step_flops);
   {
     std::vector<FilterPrep> prep;
     for (PreBlock &pb : P.blocks) {
@@ -768,7 +778,12 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
   auto grads = [&](int slot) { return block_grads ? (float *)block_grads[slot] : P.own_grads[slot]; };
 
   const int dt = net.d.compute_dtype;
-  WgradSide wg(st, dt, P.splitk);
+  double step_flops = 0;
+  for (BlockPlan &bp : P.blocks) {
+    for (ConvLayer &c : bp.convs) step_flops += 3.0 * geom_flops(c.g);
+    if (bp.has_ds) step_flops += 3.0 * geom_flops(bp.ds.g);
+  }
+  WgradSide wg(st, dt, P.splitk, step_flops);
   // every filter once, up front: the transpose the data gradient reads and, in bf16 mode, the copy
   // the forward convolution multiplies with (fp32 mode multiplies the master itself)
   {

@@ -345,7 +345,7 @@ def test_second_stream_changes_no_bit(name, bf16):
     params = make_params(model, 5, perturb_bn=True)
     outs = []
     try:
-        for overlap in (False, True, True):
+        for overlap in (0, 2, 2):            # 2: also for steps this small
             R.set_overlap(overlap)
             sub = SubResNet(model, blocks, params, batch)
             for it in range(3):

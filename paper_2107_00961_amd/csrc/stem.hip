@@ -39,6 +39,59 @@ __global__ __launch_bounds__(256) void stem_im2col_kernel(const float *__restric
   Vec<T>::store(col + i * V, v);
 }
 
+// The same expansion, one workgroup per output row (n, p): the R input rows of the C channels that
+// this output row touches are staged in LDS with coalesced loads (rows outside the image as zeros),
+// a small table maps every im2col column to its LDS offset, and the Q*kpad outputs are then assembled
+// from LDS and written as 16-byte vectors.  The element-wise kernel above does one scattered global
+// load and a handful of integer divisions per element; at ImageNet size it ran at 1.2 TB/s.
+template <typename T>
+__global__ __launch_bounds__(256) void stem_im2col_rows_kernel(const float *__restrict__ x, T *__restrict__ col, int C, int H,
+                                                               int W, int R, int stride, int pad, int P, int Q, int kpad) {
+  extern __shared__ float lds[];          // [R][C][W] input rows, then kpad table entries
+  constexpr int V = Vec<T>::N;
+  const int n = blockIdx.x / P, p = blockIdx.x - n * P;
+  const int rows = R * C;
+  int *base_of = reinterpret_cast<int *>(lds + rows * W);   // LDS offset of column j at q = 0 without the -pad shift; -1: zero column
+  int *shift_of = base_of + kpad;                            // s - pad of column j
+  for (int i = threadIdx.x; i < rows * W; i += 256) {
+    const int rc = i / W, w = i - rc * W;
+    const int r = rc / C, c = rc - r * C;
+    const int ih = p * stride + r - pad;
+    lds[i] = (ih >= 0 && ih < H) ? x[((size_t)(n * C + c) * H + ih) * W + w] : 0.f;
+  }
+  for (int j = threadIdx.x; j < kpad; j += 256) {
+    int b = -1, sh = 0;
+    if (j < R * R * C) {
+      const int c = j % C, tap = j / C;
+      const int r = tap / R, s2 = tap - r * R;
+      b = (r * C + c) * W;
+      sh = s2 - pad;
+    }
+    base_of[j] = b;
+    shift_of[j] = sh;
+  }
+  __syncthreads();
+  // thread (ql, jv): vector jv of the row, output pixels ql, ql + nq, ...; its V table entries stay in registers
+  const int vpr = kpad / V;
+  const int nq = 256 / vpr;
+  const int ql = threadIdx.x / vpr, jv = threadIdx.x - ql * vpr;
+  if (ql >= nq) return;
+  int b[V], sh[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) { b[e] = base_of[jv * V + e]; sh[e] = shift_of[jv * V + e]; }
+  T *out = col + (size_t)blockIdx.x * Q * kpad + jv * V;
+  for (int q = ql; q < Q; q += nq) {
+    const int w0 = q * stride;
+    float v[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      const int iw = w0 + sh[e];
+      v[e] = (b[e] >= 0 && iw >= 0 && iw < W) ? lds[b[e] + iw] : 0.f;
+    }
+    Vec<T>::store(out + (size_t)q * kpad, v);
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void repitch_rows_kernel(const float *__restrict__ src, T *__restrict__ dst, int rows,
                                                            int n, int src_pitch, int dst_pitch) {
@@ -58,6 +111,17 @@ int stem_im2col(int dt, const float *x, void *col, int N, int C, int H, int W, i
   prof::Scope ps("stem_im2col", 0, 4.0 * N * C * H * W + (double)esize(dt) * total, st);
   const int V = dt == DT_BF16 ? 8 : 4;
   if (kpad % 32) return set_error(RESIST_ESHAPE, "im2col row length %d is not a multiple of 32", kpad);
+  const size_t lds_bytes = ((size_t)R * C * W + 2 * (size_t)kpad) * 4;
+  if (lds_bytes <= 48 * 1024 && (long long)N * P < 0x7fffffffLL && kpad / V <= 256) {
+    // one workgroup per output row, input rows staged in LDS
+    const dim3 rows_grid((unsigned)(N * P));
+    if (dt == DT_BF16)
+      hipLaunchKernelGGL(stem_im2col_rows_kernel<__bf16>, rows_grid, dim3(256), lds_bytes, st, x, (__bf16 *)col, C, H, W, R, stride, pad, P, Q, kpad);
+    else
+      hipLaunchKernelGGL(stem_im2col_rows_kernel<float>, rows_grid, dim3(256), lds_bytes, st, x, (float *)col, C, H, W, R, stride, pad, P, Q, kpad);
+    RESIST_CHECK_LAUNCH("stem_im2col");
+    return RESIST_OK;
+  }
   const dim3 grid((unsigned)((total / V + 255) / 256));
   if (dt == DT_BF16)
     hipLaunchKernelGGL(stem_im2col_kernel<__bf16>, grid, dim3(256), 0, st, x, (__bf16 *)col, N, C, H, W, R, stride, pad, P, Q, kpad);

@@ -223,7 +223,10 @@ int resist_aggregate(const resist_model_desc *desc, int32_t S, const int32_t *su
  *   single holder: its decoded copy; no holder: untouched).  sub_codes[s] / sub_ranges[s] are host
  *   arrays [n_s + 2] of device pointers laid out like sub_block_params of resist_aggregate; every
  *   copy must have been written by resist_compress_blocks with the same desc and bits.
- * Both are asynchronous on hip_stream; bits outside 2..8 is RESIST_EINVAL.
+ * resist_decompress_blocks: the other direction (server to worker): decodes nkeys compressed blocks
+ *   into fp32 block buffers (every float lo + code * delta in one fp32 fused multiply-add, padding
+ *   zero); arguments as for resist_compress_blocks with params written and codes, ranges read.
+ * All are asynchronous on hip_stream; bits outside 2..8 is RESIST_EINVAL.
  */
 typedef struct {
   float lo, delta;
@@ -234,6 +237,9 @@ int resist_compressed_block_size(const resist_model_desc *desc, int32_t block, i
 int resist_compress_blocks(const resist_model_desc *desc, int32_t nkeys, const int32_t *keys,
                            int32_t bits, void *const *params, void *const *codes,
                            void *const *ranges, void *hip_stream);
+int resist_decompress_blocks(const resist_model_desc *desc, int32_t nkeys, const int32_t *keys,
+                             int32_t bits, void *const *codes, void *const *ranges,
+                             void *const *params, void *hip_stream);
 int resist_aggregate_compressed(const resist_model_desc *desc, int32_t S, const int32_t *sub_offsets,
                                 const int32_t *sub_blocks, int32_t bits,
                                 void *const *const *sub_codes, void *const *const *sub_ranges,

@@ -19,7 +19,7 @@ from . import resnet as OR
 
 
 def run_rounds(model, global_params, S, min_depth, seed, rounds, local_iters, batch_fn, lr, mu, wd,
-               partitionable=None, first_round=0, compress_bits=0):
+               partitionable=None, first_round=0, compress_bits=0, compress_down=False):
     """batch_fn(round, s, it) -> (x, labels).  Returns (new global params, log) where log[t] holds
     the partition of round t and the losses of every local step."""
     g = {k: {n: np.asarray(v) for n, v in p.items()} for k, p in global_params.items()}
@@ -31,6 +31,10 @@ def run_rounds(model, global_params, S, min_depth, seed, rounds, local_iters, ba
         for s in range(S):
             keys = [-1] + subs[s] + [B]
             p = {k: g[k] for k in keys}
+            if compress_bits and compress_down:
+                # the worker receives b-bit codes of the global model and starts from the decoded fp32 values
+                p = {k: {n: OC.dequantize_tensor(*OC.quantize_tensor(np.asarray(a, np.float32), compress_bits)).astype(np.float32)
+                         for n, a in t.items()} for k, t in p.items()}
             v = {k: {n: np.zeros_like(a, dtype=np.float64) for n, a in g[k].items()} for k in keys}   # momentum restart
             ls = []
             for it in range(local_iters):

@@ -6,12 +6,12 @@ buffer layout.  There is no CPU fallback: importing works without a GPU (host-on
 as `partition` run anywhere), device calls need the built library and a gfx950 device.
 """
 from .binding import (ResistError, aggregate, aggregate_compressed, block_layout, block_param_count, compress_blocks,
-                      compressed_block_size, conv2d_dgrad, conv2d_forward, conv2d_wgrad, forward, forward_workspace_bytes, lib, local_step, model_desc, num_blocks,
+                      compressed_block_size, decompress_blocks, conv2d_dgrad, conv2d_forward, conv2d_wgrad, forward, forward_workspace_bytes, lib, local_step, model_desc, num_blocks,
                       pack_block, partition, profile_enable, profile_read, set_overlap, unpack_block,
                       workspace_bytes)
 
 __all__ = ["ResistError", "aggregate", "aggregate_compressed", "block_layout", "block_param_count",
-           "compress_blocks", "compressed_block_size", "conv2d_dgrad",
+           "compress_blocks", "compressed_block_size", "conv2d_dgrad", "decompress_blocks",
            "conv2d_forward", "conv2d_wgrad", "forward", "forward_workspace_bytes", "lib", "local_step", "model_desc", "num_blocks",
            "pack_block", "partition", "profile_enable", "profile_read", "set_overlap", "unpack_block",
            "workspace_bytes"]

@@ -49,7 +49,8 @@ def lib():
                      "resist_conv2d_workspace_bytes", "resist_conv2d_forward",
                      "resist_conv2d_dgrad", "resist_conv2d_wgrad", "resist_profile_enable",
                      "resist_profile_read", "resist_compressed_block_size",
-                     "resist_compress_blocks", "resist_aggregate_compressed", "resist_set_overlap"):
+                     "resist_compress_blocks", "resist_decompress_blocks", "resist_aggregate_compressed",
+                     "resist_set_overlap"):
             getattr(L, name).restype = C.c_int
         L.resist_local_step.argtypes = [
             C.POINTER(_ModelDesc), C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_void_p),
@@ -63,6 +64,7 @@ def lib():
         L.resist_compress_blocks.argtypes = [
             C.POINTER(_ModelDesc), C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_void_p),
             C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p]
+        L.resist_decompress_blocks.argtypes = L.resist_compress_blocks.argtypes
         L.resist_aggregate_compressed.argtypes = [
             C.POINTER(_ModelDesc), C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32,
             C.POINTER(C.POINTER(C.c_void_p)), C.POINTER(C.POINTER(C.c_void_p)), C.POINTER(C.c_void_p),
@@ -272,6 +274,15 @@ def compress_blocks(model, keys, bits, params, codes, ranges, stream=None):
     keys_a = (C.c_int32 * max(n, 1))(*keys)
     _check(lib().resist_compress_blocks(C.byref(model_desc(model)), n, keys_a, bits, _ptr_array(params),
                                         _ptr_array(codes), _ptr_array(ranges), _stream_ptr(stream)))
+
+
+def decompress_blocks(model, keys, bits, codes, ranges, params, stream=None):
+    """The inverse direction: decodes compressed blocks (as written by compress_blocks) into the device
+    fp32 block buffers `params`."""
+    n = len(keys)
+    keys_a = (C.c_int32 * max(n, 1))(*keys)
+    _check(lib().resist_decompress_blocks(C.byref(model_desc(model)), n, keys_a, bits, _ptr_array(codes),
+                                          _ptr_array(ranges), _ptr_array(params), _stream_ptr(stream)))
 
 
 def aggregate_compressed(model, subs, bits, sub_codes, sub_ranges, global_params, stream=None):

@@ -491,6 +491,31 @@ extern "C" int resist_compress_blocks(const resist_model_desc *desc, int32_t nke
   return RESIST_OK;
 }
 
+extern "C" int resist_decompress_blocks(const resist_model_desc *desc, int32_t nkeys, const int32_t *keys, int32_t bits,
+                                        void *const *codes, void *const *ranges, void *const *params, void *hip_stream) {
+  Net net;
+  RESIST_TRY(build_net(desc, &net));
+  RESIST_TRY(check_bits(bits));
+  if (nkeys < 0 || (nkeys > 0 && (!keys || !params || !codes || !ranges))) return set_error(RESIST_EINVAL, "NULL argument or nkeys < 0");
+  std::vector<QAggSeg> segs((size_t)nkeys);
+  for (int i = 0; i < nkeys; ++i) {
+    if (!params[i] || !codes[i] || !ranges[i]) return set_error(RESIST_EINVAL, "entry %d: NULL buffer", i);
+    if (((uintptr_t)params[i] | (uintptr_t)ranges[i]) % 16 || (uintptr_t)codes[i] % 4)
+      return set_error(RESIST_EINVAL, "entry %d: params and ranges must be 16-byte aligned, codes 4-byte aligned", i);
+    std::vector<int> b, e;
+    int64_t n = 0;
+    RESIST_TRY(tensor_ranges(net, keys[i], &b, &e, &n));
+    QAggSeg &g = segs[i];
+    g.dst = (float *)params[i];
+    g.codes[0] = (const unsigned char *)codes[i];
+    g.ranges[0] = (const QRange *)ranges[i];
+    g.count = 1;
+    g.nt = (int)b.size();
+    g.n = n;
+  }
+  return aggregate_compressed_launch<4>(segs, bits <= 4, (hipStream_t)hip_stream);   // one source per block: a plain decode
+}
+
 extern "C" int resist_aggregate_compressed(const resist_model_desc *desc, int32_t S, const int32_t *sub_offsets,
                                            const int32_t *sub_blocks, int32_t bits, void *const *const *sub_codes,
                                            void *const *const *sub_ranges, void *const *global_block_params,

@@ -105,18 +105,24 @@ def to_device_batch(x, labels, device="cuda"):
 
 
 def run_round(model, glob, S, min_depth, seed, rnd, local_iters, batch_fn, batch, lr, mu, wd,
-              partitionable=None, stream=None, compress_bits=0):
+              partitionable=None, stream=None, compress_bits=0, compress_down=False):
     """One synchronisation round of Algorithm 1 on one GPU: split the global model (a DeviceModel
     holding every block) into S sub-ResNets for round `rnd`, run `local_iters` local steps of each, one
     sub-ResNet after the other, from the current global parameters and with fresh (zero) momentum,
     then reassemble the global model in place.  batch_fn(rnd, s, it) -> device (x, labels).
     With compress_bits = b in 2..8 every worker sends its blocks back compressed to b bits and the
-    global model is reassembled from the compressed copies.
+    global model is reassembled from the compressed copies; with compress_down as well, the workers
+    also receive their blocks as b-bit codes of the global model and start from the decoded values.
     Returns the partition and the workers (their loss buffers hold the last local loss)."""
     subs, owner = B.partition(model, S, min_depth, seed, rnd, partitionable)
     workers = []
+    down = glob.compress(compress_bits, stream) if (compress_bits and compress_down) else None
     for s in range(S):
         w = SubResNet.from_device(model, subs[s], _Select(glob, subs[s]), batch=batch, keep_grads=False)
+        if down is not None:
+            idx = {k: i for i, k in enumerate(glob.keys)}
+            B.decompress_blocks(model, w.keys, compress_bits, [down[0][idx[k]] for k in w.keys],
+                                [down[1][idx[k]] for k in w.keys], w.params, stream)
         for it in range(local_iters):
             x, y = batch_fn(rnd, s, it)
             w.step(x, y, lr, mu, wd, stream)

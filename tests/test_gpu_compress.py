@@ -78,6 +78,34 @@ def test_compress_blocks_matches_oracle(name, bits):
     _check_compressed(model, dev, g, bits, codes, ranges)
 
 
+@pytest.mark.parametrize("bits", [8, 5, 4])
+def test_decompress_blocks_is_the_oracle_decode_bit_for_bit(bits):
+    """Server to worker: codes of the global model decoded into a worker's buffers.  lo + code*delta
+    is exact in float64 (8 x 24 bits plus a 24-bit term), so its rounding to fp32 is the fused
+    multiply-add the kernel does: bit-exact."""
+    model = _models()["bottleneck"]
+    nb = R.num_blocks(model)
+    g = make_params(model, 7, perturb_bn=True)
+    glob = DeviceModel(model, list(range(nb)), g)
+    codes, ranges = glob.compress(bits)
+    mine = [0, 2, 3, 5]
+    keys = [-1] + mine + [nb]
+    idx = {k: i for i, k in enumerate(glob.keys)}
+    worker = DeviceModel(model, mine, {k: {n: np.full_like(v, 3.0) for n, v in g[k].items()} for k in keys})
+    R.decompress_blocks(model, keys, bits, [codes[idx[k]] for k in keys], [ranges[idx[k]] for k in keys], worker.params)
+    torch.cuda.synchronize()
+    got = worker.download()
+    for k in keys:
+        for n, v in g[k].items():
+            want = OC.dequantize_tensor(*OC.quantize_tensor(v, bits)).astype(np.float32)
+            assert got[k][n].tobytes() == want.tobytes(), (k, n)
+    for k, p in zip(worker.keys, worker.params):            # padding between tensors decodes to zero
+        covered = np.zeros(p.numel(), bool)
+        for t in R.block_layout(model, k):
+            covered[t["offset"]:t["offset"] + t["count"]] = True
+        assert not p.cpu().numpy()[~covered].any()
+
+
 def test_constant_and_fresh_bn_tensors():
     """gamma = 1, beta = 0, running mean 0, running var 1 at initialisation: delta = 0, all codes 0,
     and the decoded block equals the original bit for bit on those tensors."""

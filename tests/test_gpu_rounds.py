@@ -51,7 +51,8 @@ def test_two_rounds_paper_mode_partition():
             assert rel <= 2e-3, f"after {rounds} rounds: block {k} {n}: relative L2 error {rel:.3e}"
 
 
-def test_round_with_compressed_communication():
+@pytest.mark.parametrize("down", [False, True])
+def test_round_with_compressed_communication(down):
     """One round in which the workers send their blocks back as 6-bit codes (appendix on quantised
     communication).  The workers' weights differ from the oracle's by fp32 rounding (<= 1e-4
     relative), which moves a weight across a rounding boundary of the quantiser now and then: such an
@@ -69,12 +70,12 @@ def test_round_with_compressed_communication():
         return make_batch(model, batch, 10000 * t + 100 * s + it)
 
     want, log = ORD.run_rounds(model, params, S, min_depth, seed, 1, iters, host_batch, lr, mu, wd, partitionable=mask,
-                               compress_bits=bits)
+                               compress_bits=bits, compress_down=down)
     exact, _ = ORD.run_rounds(model, params, S, min_depth, seed, 1, iters, host_batch, lr, mu, wd, partitionable=mask)
     glob = DeviceModel(model, list(range(nb)), params)
     subs, owner, workers = run_round(model, glob, S, min_depth, seed, 0, iters,
                                      lambda r, s, it: to_device_batch(*host_batch(r, s, it)), batch, lr, mu, wd,
-                                     partitionable=mask, compress_bits=bits)
+                                     partitionable=mask, compress_bits=bits, compress_down=down)
     torch.cuda.synchronize()
     assert (subs, owner) == (log[0]["subs"], log[0]["owner"])
     got = glob.download()
@@ -87,7 +88,10 @@ def test_round_with_compressed_communication():
             assert np.max(np.abs(g - w)) <= step, f"block {k} {n}: farther than one quantiser step"
             total += g.size
             off += int(np.sum(np.abs(g - w) > 1e-5 + 1e-4 * np.abs(w)))
-    assert off <= 0.01 * total, f"{off} of {total} elements off by a quantiser step"
+    # With compressed weights on the way down as well, the local steps start on the quantiser's grid and
+    # move every weight by a fraction of a step, which leaves more of them near a boundary of the upward
+    # quantiser (measured 2.3 % against 0.4 %).
+    assert off <= (0.05 if down else 0.01) * total, f"{off} of {total} elements off by a quantiser step"
 
 
 @pytest.mark.parametrize("kind", ["basic", "bottleneck", "bottleneck_bf16", "preact", "preact_bottleneck_bf16"])

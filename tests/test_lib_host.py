@@ -221,6 +221,11 @@ def test_compressed_block_sizes_and_argument_errors():
     assert lib.resist_compress_blocks(ctypes.byref(d), 2, keys, 8, ok, ok, (ctypes.c_void_p * 2)(256, 264), None) == -1   # header not 16-byte aligned
     assert lib.resist_compress_blocks(ctypes.byref(d), 2, keys, 12, ok, ok, ok, None) == -1
     assert lib.resist_compress_blocks(ctypes.byref(d), 0, None, 8, None, None, None, None) == 0                         # nothing to do
+    assert lib.resist_decompress_blocks(ctypes.byref(d), 2, keys, 8, ok, ok, None, None) == -1
+    assert lib.resist_decompress_blocks(ctypes.byref(d), 2, keys, 8, ok, ok, (ctypes.c_void_p * 2)(256, 260), None) == -1  # params not 16-byte aligned
+    assert lib.resist_decompress_blocks(ctypes.byref(d), 2, keys, 1, ok, ok, ok, None) == -1
+    assert lib.resist_decompress_blocks(ctypes.byref(d), 0, None, 8, None, None, None, None) == 0
+    assert lib.resist_set_overlap(3) == -1 and lib.resist_set_overlap(1) == 0
     nb = R.num_blocks(model)
     blocks = (ctypes.c_int32 * 4)(0, 3, 7, 30)
     offs = (ctypes.c_int32 * 2)(0, 4)

@@ -150,7 +150,8 @@ def main():
                     help="time one full round instead: every sub-ResNet runs its local iterations on fresh "
                          "batches, one after the other, then resist_aggregate rebuilds the global model")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-batch", type=int, default=32)
+    ap.add_argument("--cpu-sample-batch", type=int, default=128,
+                    help="images of the oracle's timed step at CIFAR shape (an eighth of it at ImageNet shape): ~10-20 s of CPU work")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device copy (reference point for HBM traffic counters)")
     args = ap.parse_args()

@@ -127,11 +127,11 @@ def test_constant_and_fresh_bn_tensors():
 
 
 @pytest.mark.parametrize("bits", [8, 6, 4])
-@pytest.mark.parametrize("S", [3, 6])
+@pytest.mark.parametrize("S", [3, 6, 12])      # 4, 8 and 16 sources per kernel instance
 def test_aggregate_compressed_matches_oracle(S, bits):
     model = _models()["basic"]
     g = make_params(model, 0, perturb_bn=True)
-    subs, owner = R.partition(model, S, 4 if S == 6 else 0, 9, 0)
+    subs, owner = R.partition(model, S, {3: 0, 6: 4, 12: 3}[S], 9, 0)
     nb = R.num_blocks(model)
     assert max(owner) > 1
     rng = np.random.default_rng(S)

@@ -95,13 +95,13 @@ def test_step_rejects_small_workspace():
         sub.step(x, y, 0.1, 0.9, 0.0)
 
 
-def test_aggregate_matches_oracle_and_invariants():
+@pytest.mark.parametrize("S", [3, 7, 13])      # 4, 8 and 16 sources per kernel instance
+def test_aggregate_matches_oracle_and_invariants(S):
     model = dict(get_config("cfg1")["model"], widths=[16, 32], blocks=[4, 5], in_h=8, in_w=8)
-    S = 3
     g = make_params(model, 0, perturb_bn=True)
     subs, owner = R.partition(model, S, 0, 9, 0)
     assert (subs, owner) == OP.partition(model["blocks"], S, 0, 9, 0)
-    assert 1 in owner and 2 in owner
+    assert S != 3 or (1 in owner and 2 in owner)
     nb = R.num_blocks(model)
     rng = np.random.default_rng(1)
     sub_logical = []
@@ -121,7 +121,7 @@ def test_aggregate_matches_oracle_and_invariants():
                 holder = [s for s in range(S) if k in subs[s]][0]
                 assert got[k][n].tobytes() == sub_logical[holder][k][n].tobytes()   # bitwise copy
             else:
-                assert_close(got[k][n], want[k][n], f"aggregate {k} {n}", rtol=2e-7, atol=1e-7)
+                assert_close(got[k][n], want[k][n], f"aggregate {k} {n}", rtol=max(2e-7, 6e-8 * S), atol=1e-7)
     # identical copies -> identity (exact for 1, 2, 4 holders; S = 3 within one rounding)
     same = [DeviceModel(model, subs[s], g) for s in range(S)]
     glob2 = DeviceModel(model, list(range(nb)), zeros_like_params(g))
@@ -130,10 +130,10 @@ def test_aggregate_matches_oracle_and_invariants():
     got2 = glob2.download()
     for k in g:
         for n in g[k]:
-            np.testing.assert_allclose(got2[k][n], g[k][n], rtol=2e-7, atol=0)
+            np.testing.assert_allclose(got2[k][n], g[k][n], rtol=max(2e-7, 6e-8 * S), atol=0)   # up to S fp32 roundings
     # a block held by nobody keeps its value: drop sub-ResNet 0 and aggregate the rest
     lonely = [b for b in range(nb) if owner[b] == 1 and b in subs[0]]
-    assert lonely
+    assert lonely or S != 3
     glob3 = DeviceModel(model, list(range(nb)), g)
     R.aggregate(model, subs[1:], [d.params for d in devs[1:]], glob3.params)
     torch.cuda.synchronize()

@@ -385,3 +385,36 @@ def test_second_stream_changes_no_bit_full_size(workload):
         R.set_overlap(True)
     for a, b in zip(*outs):
         assert a.tobytes() == b.tobytes()
+
+
+def test_aggregate_full_size_cfg3():
+    """Reassembly of the CIFAR-shaped global model (cfg3: 41 M parameters, S = 4) at the size the round
+    benchmark times: sampled blocks against the oracle, single-owner blocks bit for bit."""
+    cfg = get_config("cfg3")
+    model, S = cfg["model"], cfg["S"]
+    nb = R.num_blocks(model)
+    subs, owner = R.partition(model, S, 0, cfg["part_seed"], 0)
+    assert (subs, owner) == OP.partition(model["blocks"], S, 0, cfg["part_seed"], 0)
+    g = make_params(model, 0, perturb_bn=True)
+    rng = np.random.default_rng(0)
+    logical = [{k: {n: (v + np.float32(0.01 * (s + 1)) * rng.standard_normal(v.shape).astype(np.float32)) for n, v in g[k].items()}
+                for k in [-1] + subs[s] + [nb]} for s in range(S)]
+    devs = [DeviceModel(model, subs[s], logical[s]) for s in range(S)]
+    glob = DeviceModel(model, list(range(nb)), g)
+    R.aggregate(model, subs, [d.params for d in devs], glob.params)
+    torch.cuda.synchronize()
+    got = glob.download()
+    sample = [-1, 0, 3, 4, 7, 20, 30, 32, nb]
+    checked = 0
+    for k in sample:
+        holders = [s for s in range(S) if k in (-1, nb) or k in subs[s]]
+        for n in g[k]:
+            if len(holders) == 1:
+                assert got[k][n].tobytes() == logical[holders[0]][k][n].tobytes(), (k, n)
+            else:
+                acc = np.zeros(g[k][n].shape, np.float64)
+                for s in holders:
+                    acc += logical[s][k][n]
+                assert_close(got[k][n], acc / len(holders), f"cfg3 reassembly {k} {n}", rtol=3e-7, atol=1e-7)
+            checked += 1
+    assert checked > 50 and any(owner[b] == 1 for b in sample if 0 <= b < nb)

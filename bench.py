@@ -42,6 +42,16 @@ def _describe(name, cfg, sub):
     return f"{name}: {shape} sub-ResNet {sub} of S={cfg['S']}"
 
 
+def _calibrate_copy():
+    """One 256 MiB device-to-device copy: the reference point of the HBM traffic counters."""
+    import torch
+    src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def _bench_round(args, cfg, subs):
     """One synchronisation round on one GPU: S sub-ResNets x local_iters steps, then aggregation."""
     import torch
@@ -59,6 +69,8 @@ def _bench_round(args, cfg, subs):
     batches = [[to_device_batch(*make_batch(model, batch, cfg["data_seed"] + 1000 * s + it)) for it in range(iters)]
                for s in range(S)]
     stream = torch.cuda.current_stream()
+    if args.calibrate_copy:
+        _calibrate_copy()
     for s in range(S):                                   # warm-up: one step each (weights restored below)
         workers[s].step(*batches[s][0], lr * 0.0, mu, wd, stream)
     torch.cuda.synchronize()
@@ -129,7 +141,13 @@ def _bench_round(args, cfg, subs):
                   "aggregate_frac_of_hbm_peak": round(agg_bytes / (agg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                   "round_ms": round(t_steps * 1e3 + agg, 2), "final_losses": losses},
     }
+    # the reassembly kernel against the HBM roofline (one launch rebuilds the whole global model)
+    gbs = agg_bytes / (agg * 1e-3) / 1e9
+    out["roofline"] = {"bound": "hbm", "kernel": "aggregate", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                       "frac": round(gbs / PEAK_HBM_GBS, 4), "avg_launch_us": round(agg * 1e3, 2),
+                       "traffic": _measured_traffic("cfg3_round", "aggregate")}
     if compressed:
+        compressed["aggregate_traffic"] = _measured_traffic("cfg3_round", "aggregate_compressed")
         out["round"]["compressed"] = compressed
     print(json.dumps(out))
 
@@ -179,11 +197,7 @@ def main():
     stream = torch.cuda.current_stream()
 
     if args.calibrate_copy:
-        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        _calibrate_copy()
     for _ in range(args.warmup):
         sub.step(xd, yd, lr, mu, wd, stream)
     torch.cuda.synchronize()

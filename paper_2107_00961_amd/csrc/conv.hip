@@ -404,8 +404,12 @@ int dispatch_igemm(const IgemmArgs &a, hipStream_t st, int *tiles_m_out = nullpt
   auto tiles = [&](int bm, int bn) {
     return (long long)((a.Mrows + bm - 1) / bm) * ((a.OC + bn - 1) / bn) * classes;
   };
-  constexpr long long kMin = 512;   // measured: 256 or fewer workgroups of a larger tile are slower on every layer shape
-  if (a.OC > 64 && tiles(128, 128) >= kMin) return launch_igemm<T, 128, 128, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);
+  constexpr long long kMin = 512;   // measured (fp32): 256 or fewer workgroups of a larger tile are slower on every layer shape
+  // bf16 kernels are bound by LDS and L2 traffic rather than by the matrix cores, and the 128x128 tile
+  // moves half the operand bytes per FLOP: measured faster down to ~190 workgroups (ImageNet-shaped
+  // stage 2-4 layers: 17-30 us instead of 20-38), slower at 100-130
+  constexpr long long kMin128 = sizeof(T) == 2 ? 192 : kMin;
+  if (a.OC > 64 && tiles(128, 128) >= kMin128) return launch_igemm<T, 128, 128, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);
   if (tiles(128, 64) >= kMin) return launch_igemm<T, 128, 64, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);
   if (a.IC % (16 * V) == 0) return launch_igemm<T, 64, 64, 16 * V, 2, 2, MODE>(a, st, tiles_m_out);
   return launch_igemm<T, 64, 64, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);

@@ -127,57 +127,119 @@ __device__ inline float wave_sum(float v) {
   return v;
 }
 
-// one wave per output z[n][j]
-__global__ __launch_bounds__(64) void fc_fwd_kernel(const float *__restrict__ x, const float *__restrict__ w,
-                                                    const float *__restrict__ b, float *__restrict__ z, int N, int C, int J) {
-  const int j = blockIdx.x, n = blockIdx.y, lane = threadIdx.x;
-  float acc = 0.f;
-  for (int c = lane * 4; c < C; c += 256) {
-    const f32x4 xv = *reinterpret_cast<const f32x4 *>(x + (size_t)n * C + c);
-    const f32x4 wv = *reinterpret_cast<const f32x4 *>(w + (size_t)j * C + c);
-    acc += xv[0] * wv[0] + xv[1] * wv[1] + xv[2] * wv[2] + xv[3] * wv[3];
+// The three small GEMMs of the classifier are register-tiled 4 x 4 (classes x samples, or classes x
+// channel vectors) so that every 16-byte load feeds 16 multiply-adds; rows past N or J are handled by
+// clamping the row index and discarding the result.  Every sum runs in a fixed order.
+
+// z[n][j] = b[j] + sum_c x[n][c] * w[j][c].  A workgroup owns 4 classes and 16 samples, each of its waves
+// 4 of the samples; the 64 lanes stride over the channels, then the 16 dot products are reduced over the lanes.
+__global__ __launch_bounds__(256) void fc_fwd_kernel(const float *__restrict__ x, const float *__restrict__ w,
+                                                     const float *__restrict__ b, float *__restrict__ z, int N, int C, int J) {
+  const int j0 = blockIdx.x * 4, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float *wr[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) wr[k] = w + (size_t)min(j0 + k, J - 1) * C;
+  for (int n0 = blockIdx.y * 16 + wave * 4; n0 < N && n0 < (int)blockIdx.y * 16 + 16; n0 += 16) {
+    const float *xr[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) xr[s] = x + (size_t)min(n0 + s, N - 1) * C;
+    float acc[4][4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) acc[k][s] = 0.f;
+#pragma unroll 2
+    for (int c = lane * 4; c < C; c += 256) {
+      f32x4 xv[4], wv[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) xv[s] = *reinterpret_cast<const f32x4 *>(xr[s] + c);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) wv[k] = *reinterpret_cast<const f32x4 *>(wr[k] + c);
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          acc[k][s] += xv[s][0] * wv[k][0] + xv[s][1] * wv[k][1] + xv[s][2] * wv[k][2] + xv[s][3] * wv[k][3];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const float t = wave_sum(acc[k][s]);
+        if (lane == 0 && j0 + k < J && n0 + s < N) z[(size_t)(n0 + s) * J + j0 + k] = t + b[j0 + k];
+      }
   }
-  acc = wave_sum(acc);
-  if (lane == 0) z[(size_t)n * J + j] = acc + b[j];
 }
 
-// dx[n][c] = sum_j dz[n][j] * w[j][c].  A workgroup owns one sample and 256 channels: 64 threads
+// dx[n][c] = sum_j dz[n][j] * w[j][c].  A workgroup owns 4 samples and 256 channels: 64 threads
 // cover the channels (4 each), the 4 waves take every 4th class and their partial sums are added in
 // wave order.  C is a multiple of 4; channels past C are skipped.
 __global__ __launch_bounds__(256) void fc_bwd_dx_kernel(const float *__restrict__ dz, const float *__restrict__ w,
                                                         float *__restrict__ dx, int N, int C, int J) {
-  __shared__ f32x4 red[4][64];
-  const int n = blockIdx.y, tx = threadIdx.x & 63, jg = threadIdx.x >> 6;
+  __shared__ f32x4 red[4][4][64];
+  const int n0 = blockIdx.y * 4, tx = threadIdx.x & 63, jg = threadIdx.x >> 6;
   const int c = blockIdx.x * 256 + tx * 4;
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  f32x4 acc[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
   if (c < C) {
-    const float *dzr = dz + (size_t)n * J;
+    const float *dzr[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) dzr[s] = dz + (size_t)min(n0 + s, N - 1) * J;
 #pragma unroll 4
     for (int j = jg; j < J; j += 4) {
       const f32x4 wv = *reinterpret_cast<const f32x4 *>(w + (size_t)j * C + c);
-      const float d = dzr[j];
-      acc[0] = fmaf(d, wv[0], acc[0]); acc[1] = fmaf(d, wv[1], acc[1]);
-      acc[2] = fmaf(d, wv[2], acc[2]); acc[3] = fmaf(d, wv[3], acc[3]);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const float d = dzr[s][j];
+        acc[s][0] = fmaf(d, wv[0], acc[s][0]); acc[s][1] = fmaf(d, wv[1], acc[s][1]);
+        acc[s][2] = fmaf(d, wv[2], acc[s][2]); acc[s][3] = fmaf(d, wv[3], acc[s][3]);
+      }
     }
   }
-  red[jg][tx] = acc;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) red[jg][s][tx] = acc[s];
   __syncthreads();
   if (jg == 0 && c < C) {
-    acc += red[1][tx];
-    acc += red[2][tx];
-    acc += red[3][tx];
-    *reinterpret_cast<f32x4 *>(dx + (size_t)n * C + c) = acc;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      if (n0 + s >= N) break;
+      f32x4 t = acc[s];
+      t += red[1][s][tx];
+      t += red[2][s][tx];
+      t += red[3][s][tx];
+      *reinterpret_cast<f32x4 *>(dx + (size_t)(n0 + s) * C + c) = t;
+    }
   }
 }
 
+// dw[j][c] = sum_n dz[n][j] * x[n][c].  A thread owns 4 classes x 4 consecutive channels and walks the
+// samples in order; blockIdx.y selects the group of 4 classes.
 __global__ __launch_bounds__(256) void fc_bwd_dw_kernel(const float *__restrict__ dz, const float *__restrict__ x,
                                                         float *__restrict__ dw, int N, int C, int J) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= J * C) return;
-  const int c = i % C, j = i / C;
-  float acc = 0.f;
-  for (int n = 0; n < N; ++n) acc = fmaf(dz[(size_t)n * J + j], x[(size_t)n * C + c], acc);
-  dw[i] = acc;
+  const int c = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  const int j0 = blockIdx.y * 4;
+  if (c >= C) return;
+  int jr[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) jr[k] = min(j0 + k, J - 1);
+  f32x4 acc[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) acc[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 2
+  for (int n = 0; n < N; ++n) {
+    const f32x4 xv = *reinterpret_cast<const f32x4 *>(x + (size_t)n * C + c);
+    const float *dzr = dz + (size_t)n * J;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float d = dzr[jr[k]];
+      acc[k][0] = fmaf(d, xv[0], acc[k][0]); acc[k][1] = fmaf(d, xv[1], acc[k][1]);
+      acc[k][2] = fmaf(d, xv[2], acc[k][2]); acc[k][3] = fmaf(d, xv[3], acc[k][3]);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    if (j0 + k < J) *reinterpret_cast<f32x4 *>(dw + (size_t)(j0 + k) * C + c) = acc[k];
 }
 
 // db over the padded length (multiple of 4): entries past J are written as zero
@@ -269,16 +331,17 @@ int avgpool_bwd(int dt, const float *dy, void *dx, int N, int HW, int C, hipStre
 }
 int fc_fwd_f32(const float *x, const float *w, const float *b, float *z, int N, int C, int J, hipStream_t st) {
   prof::Scope ps("fc_fwd", 0, 0, st);
-  hipLaunchKernelGGL(fc_fwd_kernel, dim3(J, N), dim3(64), 0, st, x, w, b, z, N, C, J);
+  if (C % 4 || N < 1 || J < 1) return set_error(RESIST_ESHAPE, "fully connected layer: N=%d C=%d J=%d (C must be a multiple of 4)", N, C, J);
+  hipLaunchKernelGGL(fc_fwd_kernel, dim3((J + 3) / 4, (N + 15) / 16), dim3(256), 0, st, x, w, b, z, N, C, J);
   RESIST_CHECK_LAUNCH("fc_fwd");
   return RESIST_OK;
 }
 int fc_bwd_f32(const float *dz, const float *x, const float *w, float *dx, float *dw, float *db, int N, int C, int J, hipStream_t st) {
   prof::Scope ps("fc_bwd", 0, 0, st);
   if (C % 4) return set_error(RESIST_ESHAPE, "fully connected layer: C=%d must be a multiple of 4", C);
-  hipLaunchKernelGGL(fc_bwd_dx_kernel, dim3((C + 255) / 256, N), dim3(256), 0, st, dz, w, dx, N, C, J);
+  hipLaunchKernelGGL(fc_bwd_dx_kernel, dim3((C + 255) / 256, (N + 3) / 4), dim3(256), 0, st, dz, w, dx, N, C, J);
   RESIST_CHECK_LAUNCH("fc_bwd_dx");
-  hipLaunchKernelGGL(fc_bwd_dw_kernel, dim3(blocks_for((long long)J * C)), dim3(256), 0, st, dz, x, dw, N, C, J);
+  hipLaunchKernelGGL(fc_bwd_dw_kernel, dim3((C / 4 + 255) / 256, (J + 3) / 4), dim3(256), 0, st, dz, x, dw, N, C, J);
   RESIST_CHECK_LAUNCH("fc_bwd_dw");
   const int Jpad = (J + 3) & ~3;
   hipLaunchKernelGGL(fc_bwd_db_kernel, dim3(blocks_for(Jpad)), dim3(256), 0, st, dz, db, N, J, Jpad);

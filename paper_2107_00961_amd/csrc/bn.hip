@@ -59,25 +59,25 @@ __device__ inline void load_params(const float *__restrict__ p, float (&v)[V]) {
 
 // ---- forward statistics --------------------------------------------------------------------------
 // Reduction over `parts` partial sums per channel, layout [2][parts][C]: a workgroup owns 16
-// channels; 16 thread rows each sum every 16th part in index order, then thread row 0 adds the 16
-// partial sums in order.
-template <typename S>
+// channels; R thread rows (R = 16 in a workgroup of 256 threads, 64 in one of 1024) each sum every
+// R-th part in index order, then thread row 0 adds the R partial sums in order.
+template <typename S, int R>
 __device__ inline void reduce_parts(const S *__restrict__ scratch, int parts, int C, int c, int pl,
-                                    double (*red)[16][16], double *out0, double *out1) {
+                                    double (*red)[R][16], double *out0, double *out1) {
   double s = 0, q = 0;
   int p = pl;
   // eight loads of each sum in flight per thread; the additions keep their order
-  for (; p + 7 * 16 < parts; p += 8 * 16) {
+  for (; p + 7 * R < parts; p += 8 * R) {
     S vs[8], vq[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      vs[u] = scratch[(size_t)(p + 16 * u) * C + c];
-      vq[u] = scratch[(size_t)(parts + p + 16 * u) * C + c];
+      vs[u] = scratch[(size_t)(p + R * u) * C + c];
+      vq[u] = scratch[(size_t)(parts + p + R * u) * C + c];
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u) { s += (double)vs[u]; q += (double)vq[u]; }
   }
-  for (; p < parts; p += 16) {
+  for (; p < parts; p += R) {
     s += (double)scratch[(size_t)p * C + c];
     q += (double)scratch[(size_t)(parts + p) * C + c];
   }
@@ -86,7 +86,7 @@ __device__ inline void reduce_parts(const S *__restrict__ scratch, int parts, in
   red[1][pl][cl] = q;
   __syncthreads();
   if (pl == 0) {
-    for (int j = 1; j < 16; ++j) { s += red[0][j][cl]; q += red[1][j][cl]; }
+    for (int j = 1; j < R; ++j) { s += red[0][j][cl]; q += red[1][j][cl]; }
   }
   *out0 = s;
   *out1 = q;
@@ -116,17 +116,17 @@ __global__ __launch_bounds__(kThreads) void bn_stats_reduce_kernel(const float *
   out[(size_t)(Z + z) * C + c] = q;
 }
 
-template <typename S>
-__global__ __launch_bounds__(kThreads) void bn_finalize_kernel(const S *__restrict__ stats, int parts, int C,
+template <typename S, int R>
+__global__ __launch_bounds__(16 * R) void bn_finalize_kernel(const S *__restrict__ stats, int parts, int C,
                                                                long long M, float eps, float momentum,
                                                                const float *__restrict__ gamma, const float *__restrict__ beta,
                                                                float *__restrict__ mean, float *__restrict__ invstd,
                                                                float *__restrict__ scale, float *__restrict__ shift,
                                                                float *__restrict__ rmean, float *__restrict__ rvar) {
-  __shared__ double red[2][16][16];
+  __shared__ double red[2][R][16];
   const int c = blockIdx.x * 16 + (threadIdx.x & 15), pl = threadIdx.x >> 4;
   double s, q;
-  reduce_parts(stats, parts, C, c, pl, red, &s, &q);
+  reduce_parts<S, R>(stats, parts, C, c, pl, red, &s, &q);
   if (pl != 0) return;
   const double m = s / (double)M;
   double var = q / (double)M - m * m;
@@ -297,7 +297,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const double *__
   __shared__ double red[2][16][16];
   const int c = blockIdx.x * 16 + (threadIdx.x & 15), pl = threadIdx.x >> 4;
   double b, g;
-  reduce_parts(scratch, parts, C, c, pl, red, &b, &g);
+  reduce_parts<double, 16>(scratch, parts, C, c, pl, red, &b, &g);
   if (pl != 0) return;
   dbeta[c] = (float)b;
   dgamma[c] = (float)g;
@@ -414,15 +414,20 @@ int bn_finalize(const float *stats, int parts, int64_t M, int C, const BnBufs &b
   RESIST_TRY(check_bn(DT_F32, M, C));
   if (parts < 1 || !stats) return set_error(RESIST_EINVAL, "bn_finalize: no partial sums");
   prof::Scope ps("bn_finalize", 0, 8.0 * parts * C, st);
-  if (parts > 2 * kSlice) {
+  if (parts > 4096) {
+    // very long lists of row tiles: a first level over slices of kSlice parts, in its own launch
     const int Z = (parts + kSlice - 1) / kSlice;
     if (Z > kMaxParts || !scratch) return set_error(RESIST_ESHAPE, "bn_finalize: %d partial sums", parts);
     hipLaunchKernelGGL(bn_stats_reduce_kernel, dim3(C / 16, Z), dim3(kThreads), 0, st, stats, parts, C, scratch);
     RESIST_CHECK_LAUNCH("bn_stats_reduce");
-    hipLaunchKernelGGL(bn_finalize_kernel<double>, dim3(C / 16), dim3(kThreads), 0, st, (const double *)scratch, Z, C,
+    hipLaunchKernelGGL((bn_finalize_kernel<double, 16>), dim3(C / 16), dim3(kThreads), 0, st, (const double *)scratch, Z, C,
                        (long long)M, eps, momentum, b.gamma, b.beta, b.mean, b.invstd, b.scale, b.shift, b.rmean, b.rvar);
+  } else if (parts > 2 * kSlice) {
+    // one launch: 1024 threads per 16 channels, 64 thread rows share the parts
+    hipLaunchKernelGGL((bn_finalize_kernel<float, 64>), dim3(C / 16), dim3(1024), 0, st, stats, parts, C, (long long)M, eps,
+                       momentum, b.gamma, b.beta, b.mean, b.invstd, b.scale, b.shift, b.rmean, b.rvar);
   } else {
-    hipLaunchKernelGGL(bn_finalize_kernel<float>, dim3(C / 16), dim3(kThreads), 0, st, stats, parts, C, (long long)M, eps,
+    hipLaunchKernelGGL((bn_finalize_kernel<float, 16>), dim3(C / 16), dim3(kThreads), 0, st, stats, parts, C, (long long)M, eps,
                        momentum, b.gamma, b.beta, b.mean, b.invstd, b.scale, b.shift, b.rmean, b.rvar);
   }
   RESIST_CHECK_LAUNCH("bn_finalize");

@@ -219,8 +219,8 @@ int resist_aggregate(const resist_model_desc *desc, int32_t S, const int32_t *su
  *   codes   host [nkeys] device code arrays (written), 4-byte aligned
  *   ranges  host [nkeys] device arrays of n_tensors resist_qrange (written), 16-byte aligned
  * resist_aggregate_compressed: resist_aggregate with every source a compressed block: each float of
- *   the global model becomes the fp32 mean, in ascending sub-ResNet order, of the decoded copies (a
- *   single holder: its decoded copy; no holder: untouched).  sub_codes[s] / sub_ranges[s] are host
+ *   the global model becomes the fp32 sum, in ascending sub-ResNet order, of the decoded copies times
+ *   1/count (a single holder: its decoded copy; no holder: untouched).  sub_codes[s] / sub_ranges[s] are host
  *   arrays [n_s + 2] of device pointers laid out like sub_block_params of resist_aggregate; every
  *   copy must have been written by resist_compress_blocks with the same desc and bits.
  * resist_decompress_blocks: the other direction (server to worker): decodes nkeys compressed blocks

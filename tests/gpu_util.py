@@ -27,3 +27,217 @@ def compare_trees(got, want, what, names=None, **kw):
                 continue
             assert name in got[key], f"{what}: block {key} lacks {name}"
             assert_close(got[key][name], w, f"{what} block {key} {name}", **kw)
+
+
+def rel_l2(a, b):
+    return float(np.linalg.norm(np.asarray(a, np.float64) - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def _check_full_size_step(sub, before, loss, grads, new_p, what):
+    """One full-size fp32 step of `sub` (device) against the oracle's step from the state `before`."""
+    import paper_2107_00961_amd as R
+    model, blocks = sub.model, sub.blocks
+    nb = R.num_blocks(model)
+    last = blocks[-1]
+    tail = "conv3" if model["block_kind"] == 1 else "conv2"
+    tail_bn = "bn3" if model["block_kind"] == 1 else "bn2"
+    assert_close(sub.loss.cpu().numpy()[0], loss, f"{what} loss")
+    got_g, got_p = sub.download_grads(), sub.download()
+    worst = {"head": 0.0, "tail": 0.0, "other": 0.0, "update": 0.0}
+    for k in sub.keys:
+        for name, g in grads[k].items():
+            a = got_g[k][name].astype(np.float64)
+            if k == nb:
+                assert_close(a, g, f"{what} grad block {k} {name}")
+            rel = np.linalg.norm(a - g) / np.linalg.norm(g)
+            is_tail = k == last and name.startswith((tail, tail_bn))
+            cls = "head" if k == nb else ("tail" if is_tail else "other")
+            worst[cls] = max(worst[cls], rel)
+            assert rel <= (5e-3 if is_tail else 2e-2), f"{what} grad block {k} {name}: relative L2 error {rel:.3e}"
+            upd = np.linalg.norm(np.asarray(before[k][name], np.float64) - new_p[k][name])
+            err = np.linalg.norm(got_p[k][name].astype(np.float64) - new_p[k][name])
+            worst["update"] = max(worst["update"], err / max(upd, 1e-30))
+            assert err <= 2e-2 * upd + 1e-7 * np.linalg.norm(new_p[k][name]), f"{what} update block {k} {name}"
+        for name in new_p[k]:
+            if name.endswith(("_rm", "_rv")):      # running statistics: forward quantities, well conditioned
+                assert_close(got_p[k][name], new_p[k][name], f"{what} running stat block {k} {name}")
+    print(f"{what}: worst relative L2 -- head gradients {worst['head']:.2e}, last block's tail {worst['tail']:.2e}, "
+          f"other gradients {worst['other']:.2e}; parameter error / applied update {worst['update']:.2e}", flush=True)
+
+
+def full_size_check(cfg_name, what, which=0, second_step=False):
+    """Full-size fp32 check in the launch configuration the benchmark times: the first local step of
+    sub-ResNet `which` of the configuration's partition against the oracle.
+
+    At this depth and batch the training step is ill-conditioned with respect to fp32 rounding:
+    a pre-activation within rounding distance of zero flips its ReLU decision, which moves the
+    weight gradients of that layer and of every earlier layer by a few 1e-3 of their norm
+    (tests/test_oracle_sensitivity.py measures the same response in the float64 oracle itself).
+    The element-wise fp32 bound is therefore applied to the loss, the running statistics and the
+    tensors no ReLU decision stands behind (the head: a flipped decision belongs to an activation
+    that is zero to rounding either way, so forward quantities are continuous in it).  The tail of
+    the last block has exactly one ReLU layer behind it (the block's output, 1 M decisions, each
+    within fp32 accumulation error of zero with probability ~4e-6, so a handful flip, each moving the
+    gradient by ~1e-3 of its norm): bound 5e-3 in relative L2 norm.  Every other gradient tensor is
+    bounded in relative L2 norm by 2e-2, every parameter tensor by 2e-2 of the update applied to it.
+
+    second_step: the step after it as well.  After one step at the configuration's learning rate the
+    two chains' parameters differ by up to 2e-2 of an update that is itself a large fraction of the
+    weights, and the second step amplifies that difference (the gradient of the stem moves by more than
+    a tenth): a chained comparison says nothing about the kernels.  So the second step is checked from
+    the ORACLE's state after its first step, loaded into a second device sub-ResNet (parameters,
+    running statistics and momentum rounded to fp32): same bounds as the first step, now with non-zero
+    momentum.  The HIP path's own chain takes its second step too (its loss is compared, relative
+    2e-2) and is what this function returns: the weights two local steps on the GPU leave behind."""
+    import torch
+    import paper_2107_00961_amd as R
+    from oracle import resnet as OR
+    from paper_2107_00961_amd.harness import SubResNet, to_device_batch
+    from resist_inputs import get_config, make_batch, make_params, zeros_like_params
+
+    cfg = get_config(cfg_name)
+    model = cfg["model"]
+    lr, mu, wd = cfg["lr"], cfg["momentum"], cfg["weight_decay"]
+    subs, _ = R.partition(model, cfg["S"], cfg["min_depth"], cfg["part_seed"], 0)
+    blocks = subs[which]
+    params = make_params(model, 0)
+    sub = SubResNet(model, blocks, params, cfg["batch"])
+    x, y = make_batch(model, cfg["batch"], cfg["data_seed"] + 1000 * which)
+    xd, yd = to_device_batch(x, y)
+    print(f"{what}: gpu step", flush=True)
+    sub.step(xd, yd, lr, mu, wd)
+    torch.cuda.synchronize()
+    print(f"{what}: oracle step", flush=True)
+    loss, grads, p1, v1 = OR.local_step(model, blocks, params, zeros_like_params(params), x, y, lr, mu, wd)
+    _check_full_size_step(sub, params, loss, grads, p1, what)
+    if not second_step:
+        # bit-identical when repeated from the same state
+        sub2 = SubResNet(model, blocks, params, cfg["batch"])
+        sub2.step(xd, yd, lr, mu, wd)
+        torch.cuda.synchronize()
+        for a, b in zip(sub.params, sub2.params):
+            assert torch.equal(a, b)
+        return sub
+    x2, y2 = make_batch(model, cfg["batch"], cfg["data_seed"] + 1000 * which + 1)
+    xd2, yd2 = to_device_batch(x2, y2)
+    from_oracle = SubResNet(model, blocks, p1, cfg["batch"])
+    for k, v in zip(from_oracle.keys, from_oracle.momentum):
+        v.copy_(torch.from_numpy(R.pack_block(model, k, v1[k], trainable_only=True)))
+    print(f"{what}: gpu second step (from the oracle's state, and the device's own chain)", flush=True)
+    from_oracle.step(xd2, yd2, lr, mu, wd)
+    sub.step(xd2, yd2, lr, mu, wd)
+    torch.cuda.synchronize()
+    print(f"{what}: oracle second step", flush=True)
+    loss2, grads2, p2, _ = OR.local_step(model, blocks, p1, v1, x2, y2, lr, mu, wd)
+    _check_full_size_step(from_oracle, p1, loss2, grads2, p2, f"{what} second step")
+    own = float(sub.loss.cpu().numpy()[0])
+    print(f"{what}: second-step loss of the device's own chain {own:.6f}, oracle chain {loss2:.6f}", flush=True)
+    assert abs(own - loss2) <= 2e-2 * abs(loss2)
+    return sub
+
+
+# What can be asked of a bf16 step (compute_dtype = 1).  Each stored activation carries a relative
+# rounding error of up to 2^-9.  A pre-activation within that distance of zero flips its ReLU decision,
+# and a fraction f of flipped decisions moves a gradient tensor by about sqrt(f) of its norm: the
+# unrounded float64 oracle and its own bf16-emulating variant (same arithmetic, values rounded at the
+# storage points; pinned by an independent autograd graph in tests/test_oracle_quant.py) already differ
+# by 5-60 % in the gradients of a deep network, while the loss differs by ~1e-3.  Nor can two bf16
+# computations be expected to agree with each other closely: a discrepancy d much smaller than a bf16
+# ulp moves a fraction ~d/2^-8 of the values across a rounding boundary, each by a whole ulp, so after a
+# few layers any two evaluation orders (fp32 MFMA sums here, float64 sums in the oracle) differ by a
+# good part of the bf16 noise itself.  The checks:
+#  (1) loss against the emulating oracle, relative 2e-3;
+#  (2) the stated bar for bf16 variants, against the UNROUNDED oracle: every updated weight tensor
+#      within relative 2e-2 (L2 norm) -- asserted for every tensor except those that
+#      tests/golden/bf16_storage_reach.json lists for the case: tensors that bf16 storage by itself
+#      (the emulating oracle, no GPU involved) moves by more than 1e-2, written by
+#      tests/golden/make_bf16_storage_reach.py; those are held to 1.5 x the recorded distance, a
+#      constant.  Tensors that start at zero (BN beta) have no relative distance: covered by (3);
+#  (3) every gradient tensor: the HIP path's distance from the unrounded oracle is at most
+#      max(2e-2, 1.5 x the emulating oracle's distance), i.e. the kernels add no error beyond what
+#      bf16 storage itself causes (no bar is stated for bf16 gradients);
+#  (4) on shallow networks, where no cascade has built up, every gradient tensor of the HIP path is
+#      within `emu_bar` of the emulating oracle's while the unrounded oracle is 1e-1 away: the kernels
+#      round where the emulation rounds;
+#  (5) running statistics (forward quantities) against the emulating oracle, relative L2 1e-2.
+# The convolution kernels on their own are checked tightly in tests/test_gpu_conv.py.
+_REACH = None
+
+
+def _storage_reach(what):
+    global _REACH
+    if _REACH is None:
+        import json
+        import os
+        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "bf16_storage_reach.json")
+        with open(path) as f:
+            _REACH = json.load(f)
+    return _REACH[what]
+
+
+def bf16_step_check(what):
+    """One bf16 step of the case `what` of tests/bf16_cases.py: HIP path against both oracles."""
+    import torch
+    from oracle import resnet as OR
+    from paper_2107_00961_amd.harness import SubResNet, to_device_batch
+    from resist_inputs import make_batch, make_params, zeros_like_params
+    from tests.bf16_cases import bf16_cases
+
+    case = bf16_cases()[what]
+    model = dict(case["model"], compute_dtype=1)
+    blocks, batch, lr, mu, wd, emu_bar = case["blocks"], case["batch"], case["lr"], case["mu"], case["wd"], case["emu_bar"]
+    reach = _storage_reach(what)
+    params = make_params(model, case["seed"], perturb_bn=case["perturb_bn"])
+    x, y = make_batch(model, batch, case["data_seed"])
+    sub = SubResNet(model, blocks, params, batch)
+    xd, yd = to_device_batch(x, y)
+    print(f"{what}: bf16 gpu step", flush=True)
+    sub.step(xd, yd, lr, mu, wd)
+    torch.cuda.synchronize()
+    print(f"{what}: oracle steps", flush=True)
+    zero = zeros_like_params(params)
+    loss_e, grads_e, p_e, _ = OR.local_step(model, blocks, params, zero, x, y, lr, mu, wd, emulate_bf16=True)
+    loss_f, grads_f, p_f, _ = OR.local_step(model, blocks, params, zero, x, y, lr, mu, wd)
+    got_g, got_p = sub.download_grads(), sub.download()
+    assert_close(sub.loss.cpu().numpy()[0], loss_e, f"{what} loss vs emulating oracle", rtol=2e-3, atol=1e-5)
+    worst = worst_emu = worst_w = 0.0
+    n_stated = 0
+    failures = []
+    for k in sub.keys:
+        for name, g in grads_f[k].items():
+            r_gpu, r_emu = rel_l2(got_g[k][name], g), rel_l2(grads_e[k][name], g)
+            worst = max(worst, r_gpu)
+            if r_gpu > max(2e-2, 1.5 * r_emu):
+                failures.append(f"grad block {k} {name}: {r_gpu:.3e} from the unrounded oracle, emulating oracle {r_emu:.3e}")
+            if emu_bar is not None:
+                r = rel_l2(got_g[k][name], grads_e[k][name])
+                worst_emu = max(worst_emu, r)
+                if r > emu_bar:
+                    failures.append(f"grad block {k} {name}: {r:.3e} from the emulating oracle ({r_emu:.3e} unrounded)")
+        for name, w in p_f[k].items():
+            if name.endswith(("_rm", "_rv")):
+                r = rel_l2(got_p[k][name], p_e[k][name])
+                if r > 1e-2:
+                    failures.append(f"running stat block {k} {name}: relative L2 error {r:.3e}")
+            elif np.linalg.norm(params[k][name]) > 0:
+                r, r_emu = rel_l2(got_p[k][name], w), rel_l2(p_e[k][name], w)
+                recorded = reach.get(f"{k}/{name}")
+                if recorded is None:
+                    n_stated += 1
+                    worst_w = max(worst_w, r)
+                    if r > 2e-2:
+                        failures.append(f"weights block {k} {name}: {r:.3e} from the unrounded oracle (stated bar 2e-2; "
+                                        f"emulating oracle {r_emu:.3e})")
+                else:
+                    print(f"BF16W | {what} | block {k} {name} | storage alone {recorded:.3e} | gpu {r:.3e}", flush=True)
+                    if abs(r_emu - recorded) > 0.02 * recorded:
+                        failures.append(f"weights block {k} {name}: the recorded storage distance {recorded:.3e} is stale "
+                                        f"(now {r_emu:.3e}): rerun tests/golden/make_bf16_storage_reach.py")
+                    if r > 1.5 * recorded:
+                        failures.append(f"weights block {k} {name}: {r:.3e} from the unrounded oracle, bf16 storage alone "
+                                        f"accounts for {recorded:.3e}")
+    print(f"{what}: worst rel L2 -- gradients vs unrounded oracle {worst:.3e}, vs emulating oracle {worst_emu:.3e}; "
+          f"updated weights vs unrounded oracle {worst_w:.3e} over the {n_stated} tensors held to the stated 2e-2 "
+          f"({len(reach)} beyond the reach of bf16 storage)", flush=True)
+    assert not failures, f"{what}: " + "; ".join(failures)
+    return sub

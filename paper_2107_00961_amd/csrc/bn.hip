@@ -4,8 +4,8 @@
 //   backward  gm = g*[mask>0]; dbeta = sum gm; dgamma = sum gm*xhat;
 //             dy = gamma*invstd*(gm - dbeta/M - xhat*dgamma/M)
 // These kernels are bound by HBM bandwidth.  The forward statistics arrive as per-row-tile fp32
-// column sums written by the convolution that produced y (at most 128 rows each) and are added up
-// in float64; the backward sums are accumulated in float64 throughout (the vector fp64 rate is far
+// shifted column sums written by the convolution that produced y (at most 128 rows each) and are
+// merged in float64; the backward sums are accumulated in float64 throughout (the vector fp64 rate is far
 // above what the memory stream needs).  Every reduction has a fixed order, so results are bit-stable
 // from run to run.
 // Activations are stored as fp32 or bf16; a thread owns V = 4 (fp32) or 8 (bf16) consecutive channels
@@ -58,29 +58,43 @@ __device__ inline void load_params(const float *__restrict__ p, float (&v)[V]) {
 }
 
 // ---- forward statistics --------------------------------------------------------------------------
-// Reduction over `parts` partial sums per channel, layout [2][parts][C]: a workgroup owns 16
-// channels; R thread rows (R = 16 in a workgroup of 256 threads, 64 in one of 1024) each sum every
-// R-th part in index order, then thread row 0 adds the R partial sums in order.
+// A convolution leaves, per row tile p (n_p rows) and channel, a shift k_p and the sums
+// s1_p = sum(y - k_p), s2_p = sum((y - k_p)^2) over the tile's rows.  Tiles are merged by moving each to
+// the shift k of the first one: with d = k_p - k,
+//     sum(y - k) = s1_p + n_p*d,      sum((y - k)^2) = s2_p + d*(2*s1_p + n_p*d),
+// so mean = k + S1/M and var = S2/M - (S1/M)^2 with S1/M of the order of the standard deviation
+// whatever the mean is: no cancellation between large numbers.  All merging is float64.
+//
+// Reduction over `parts` triples per channel, layout [3][parts][C]: a workgroup owns 16 channels;
+// R thread rows (R = 16 in a workgroup of 256 threads, 64 in one of 1024) each merge every R-th part
+// in index order, then thread row 0 adds the R partial sums in order.  Part p holds
+// min(rows, M - p*rows) rows.
 template <typename S, int R>
-__device__ inline void reduce_parts(const S *__restrict__ scratch, int parts, int C, int c, int pl,
-                                    double (*red)[R][16], double *out0, double *out1) {
+__device__ inline void merge_parts(const S *__restrict__ st, int p0, int p1, int parts, int C, int c, int pl, long long M,
+                                   long long rows, double (*red)[R][16], double *k_out, double *s1_out, double *s2_out) {
+  const double k = (double)st[(size_t)p0 * C + c];
   double s = 0, q = 0;
-  int p = pl;
-  // eight loads of each sum in flight per thread; the additions keep their order
-  for (; p + 7 * R < parts; p += 8 * R) {
-    S vs[8], vq[8];
+  int p = p0 + pl;
+  auto merge = [&](int pp, S kp, S a1, S a2) {
+    long long n = M - (long long)pp * rows;
+    n = n < rows ? n : rows;
+    const double d = (double)kp - k, n_d = (double)n * d;
+    s += (double)a1 + n_d;
+    q += (double)a2 + d * (2.0 * (double)a1 + n_d);
+  };
+  // four loads of each array in flight per thread; the additions keep their order
+  for (; p + 3 * R < p1; p += 4 * R) {
+    S vk[4], v1[4], v2[4];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      vs[u] = scratch[(size_t)(p + R * u) * C + c];
-      vq[u] = scratch[(size_t)(parts + p + R * u) * C + c];
+    for (int u = 0; u < 4; ++u) {
+      vk[u] = st[(size_t)(p + R * u) * C + c];
+      v1[u] = st[(size_t)(parts + p + R * u) * C + c];
+      v2[u] = st[(size_t)(2 * parts + p + R * u) * C + c];
     }
 #pragma unroll
-    for (int u = 0; u < 8; ++u) { s += (double)vs[u]; q += (double)vq[u]; }
+    for (int u = 0; u < 4; ++u) merge(p + R * u, vk[u], v1[u], v2[u]);
   }
-  for (; p < parts; p += R) {
-    s += (double)scratch[(size_t)p * C + c];
-    q += (double)scratch[(size_t)(parts + p) * C + c];
-  }
+  for (; p < p1; p += R) merge(p, st[(size_t)p * C + c], st[(size_t)(parts + p) * C + c], st[(size_t)(2 * parts + p) * C + c]);
   const int cl = c & 15;
   red[0][pl][cl] = s;
   red[1][pl][cl] = q;
@@ -88,36 +102,30 @@ __device__ inline void reduce_parts(const S *__restrict__ scratch, int parts, in
   if (pl == 0) {
     for (int j = 1; j < R; ++j) { s += red[0][j][cl]; q += red[1][j][cl]; }
   }
-  *out0 = s;
-  *out1 = q;
+  *k_out = k;
+  *s1_out = s;
+  *s2_out = q;
 }
 
-// first level for long lists of parts: workgroup (x, z) adds parts [z*kSlice, (z+1)*kSlice) of 16
-// channels in float64; output [2][Z][C]
+// first level for long lists of parts: workgroup (x, z) merges parts [z*kSlice, (z+1)*kSlice) of 16
+// channels; output [3][Z][C] float64 triples (slice z then holds kSlice*rows rows, the last one fewer)
 constexpr int kSlice = 64;
 __global__ __launch_bounds__(kThreads) void bn_stats_reduce_kernel(const float *__restrict__ stats, int parts, int C,
-                                                                   double *__restrict__ out) {
+                                                                   long long M, long long rows, double *__restrict__ out) {
   __shared__ double red[2][16][16];
   const int c = blockIdx.x * 16 + (threadIdx.x & 15), pl = threadIdx.x >> 4;
   const int z = blockIdx.y, Z = gridDim.y;
   const int p0 = z * kSlice, p1 = min(parts, p0 + kSlice);
-  double s = 0, q = 0;
-  for (int p = p0 + pl; p < p1; p += 16) {
-    s += (double)stats[(size_t)p * C + c];
-    q += (double)stats[(size_t)(parts + p) * C + c];
-  }
-  const int cl = c & 15;
-  red[0][pl][cl] = s;
-  red[1][pl][cl] = q;
-  __syncthreads();
+  double k, s, q;
+  merge_parts<float, 16>(stats, p0, p1, parts, C, c, pl, M, rows, red, &k, &s, &q);
   if (pl != 0) return;
-  for (int j = 1; j < 16; ++j) { s += red[0][j][cl]; q += red[1][j][cl]; }
-  out[(size_t)z * C + c] = s;
-  out[(size_t)(Z + z) * C + c] = q;
+  out[(size_t)z * C + c] = k;
+  out[(size_t)(Z + z) * C + c] = s;
+  out[(size_t)(2 * Z + z) * C + c] = q;
 }
 
 template <typename S, int R>
-__global__ __launch_bounds__(16 * R) void bn_finalize_kernel(const S *__restrict__ stats, int parts, int C,
+__global__ __launch_bounds__(16 * R) void bn_finalize_kernel(const S *__restrict__ stats, int parts, long long rows, int C,
                                                                long long M, float eps, float momentum,
                                                                const float *__restrict__ gamma, const float *__restrict__ beta,
                                                                float *__restrict__ mean, float *__restrict__ invstd,
@@ -125,11 +133,12 @@ __global__ __launch_bounds__(16 * R) void bn_finalize_kernel(const S *__restrict
                                                                float *__restrict__ rmean, float *__restrict__ rvar) {
   __shared__ double red[2][R][16];
   const int c = blockIdx.x * 16 + (threadIdx.x & 15), pl = threadIdx.x >> 4;
-  double s, q;
-  reduce_parts<S, R>(stats, parts, C, c, pl, red, &s, &q);
+  double k, s, q;
+  merge_parts<S, R>(stats, 0, parts, parts, C, c, pl, M, rows, red, &k, &s, &q);
   if (pl != 0) return;
-  const double m = s / (double)M;
-  double var = q / (double)M - m * m;
+  const double off = s / (double)M;       // mean - k
+  const double m = k + off;
+  double var = q / (double)M - off * off;
   if (var < 0) var = 0;
   const float mf = (float)m, isf = (float)(1.0 / sqrt(var + (double)eps));
   mean[c] = mf;
@@ -292,12 +301,44 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const T *__res
   }
 }
 
+// plain fixed-order reduction of two sums per channel, layout [2][parts][C] (the backward pass)
+template <int R>
+__device__ inline void reduce_parts(const double *__restrict__ scratch, int parts, int C, int c, int pl,
+                                    double (*red)[R][16], double *out0, double *out1) {
+  double s = 0, q = 0;
+  int p = pl;
+  // eight loads of each sum in flight per thread; the additions keep their order
+  for (; p + 7 * R < parts; p += 8 * R) {
+    double vs[8], vq[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      vs[u] = scratch[(size_t)(p + R * u) * C + c];
+      vq[u] = scratch[(size_t)(parts + p + R * u) * C + c];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { s += vs[u]; q += vq[u]; }
+  }
+  for (; p < parts; p += R) {
+    s += scratch[(size_t)p * C + c];
+    q += scratch[(size_t)(parts + p) * C + c];
+  }
+  const int cl = c & 15;
+  red[0][pl][cl] = s;
+  red[1][pl][cl] = q;
+  __syncthreads();
+  if (pl == 0) {
+    for (int j = 1; j < R; ++j) { s += red[0][j][cl]; q += red[1][j][cl]; }
+  }
+  *out0 = s;
+  *out1 = q;
+}
+
 __global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const double *__restrict__ scratch, int parts, int C,
                                                                 float *__restrict__ dgamma, float *__restrict__ dbeta) {
   __shared__ double red[2][16][16];
   const int c = blockIdx.x * 16 + (threadIdx.x & 15), pl = threadIdx.x >> 4;
   double b, g;
-  reduce_parts<double, 16>(scratch, parts, C, c, pl, red, &b, &g);
+  reduce_parts<16>(scratch, parts, C, c, pl, red, &b, &g);
   if (pl != 0) return;
   dbeta[c] = (float)b;
   dgamma[c] = (float)g;
@@ -407,28 +448,32 @@ void launch_bwd(int mode, dim3 gp, dim3 ga, hipStream_t st, const void *g, const
 
 }  // namespace
 
-int64_t bn_scratch_doubles(int C) { return (int64_t)2 * kMaxParts * C; }
+int64_t bn_scratch_doubles(int C) { return (int64_t)3 * kMaxParts * C; }
 
-int bn_finalize(const float *stats, int parts, int64_t M, int C, const BnBufs &b, float eps, float momentum, double *scratch,
+int bn_finalize(const float *stats, StatParts sp, int64_t M, int C, const BnBufs &b, float eps, float momentum, double *scratch,
                 hipStream_t st) {
   RESIST_TRY(check_bn(DT_F32, M, C));
-  if (parts < 1 || !stats) return set_error(RESIST_EINVAL, "bn_finalize: no partial sums");
-  prof::Scope ps("bn_finalize", 0, 8.0 * parts * C, st);
+  const int parts = sp.parts;
+  const long long rows = sp.rows;
+  if (parts < 1 || rows < 1 || !stats || (long long)parts * rows < M || (long long)(parts - 1) * rows >= M)
+    return set_error(RESIST_EINVAL, "bn_finalize: %d partial sums of %lld rows for %lld rows", parts, rows, (long long)M);
+  prof::Scope ps("bn_finalize", 0, 12.0 * parts * C, st);
   if (parts > 4096) {
     // very long lists of row tiles: a first level over slices of kSlice parts, in its own launch
     const int Z = (parts + kSlice - 1) / kSlice;
     if (Z > kMaxParts || !scratch) return set_error(RESIST_ESHAPE, "bn_finalize: %d partial sums", parts);
-    hipLaunchKernelGGL(bn_stats_reduce_kernel, dim3(C / 16, Z), dim3(kThreads), 0, st, stats, parts, C, scratch);
+    hipLaunchKernelGGL(bn_stats_reduce_kernel, dim3(C / 16, Z), dim3(kThreads), 0, st, stats, parts, C, (long long)M, rows, scratch);
     RESIST_CHECK_LAUNCH("bn_stats_reduce");
-    hipLaunchKernelGGL((bn_finalize_kernel<double, 16>), dim3(C / 16), dim3(kThreads), 0, st, (const double *)scratch, Z, C,
-                       (long long)M, eps, momentum, b.gamma, b.beta, b.mean, b.invstd, b.scale, b.shift, b.rmean, b.rvar);
+    hipLaunchKernelGGL((bn_finalize_kernel<double, 16>), dim3(C / 16), dim3(kThreads), 0, st, (const double *)scratch, Z,
+                       rows * kSlice, C, (long long)M, eps, momentum, b.gamma, b.beta, b.mean, b.invstd, b.scale, b.shift, b.rmean,
+                       b.rvar);
   } else if (parts > 2 * kSlice) {
     // one launch: 1024 threads per 16 channels, 64 thread rows share the parts
-    hipLaunchKernelGGL((bn_finalize_kernel<float, 64>), dim3(C / 16), dim3(1024), 0, st, stats, parts, C, (long long)M, eps,
+    hipLaunchKernelGGL((bn_finalize_kernel<float, 64>), dim3(C / 16), dim3(1024), 0, st, stats, parts, rows, C, (long long)M, eps,
                        momentum, b.gamma, b.beta, b.mean, b.invstd, b.scale, b.shift, b.rmean, b.rvar);
   } else {
-    hipLaunchKernelGGL((bn_finalize_kernel<float, 16>), dim3(C / 16), dim3(kThreads), 0, st, stats, parts, C, (long long)M, eps,
-                       momentum, b.gamma, b.beta, b.mean, b.invstd, b.scale, b.shift, b.rmean, b.rvar);
+    hipLaunchKernelGGL((bn_finalize_kernel<float, 16>), dim3(C / 16), dim3(kThreads), 0, st, stats, parts, rows, C, (long long)M,
+                       eps, momentum, b.gamma, b.beta, b.mean, b.invstd, b.scale, b.shift, b.rmean, b.rvar);
   }
   RESIST_CHECK_LAUNCH("bn_finalize");
   return RESIST_OK;

@@ -9,8 +9,16 @@
  *     message.  No exception or abort crosses this boundary; arguments are validated before any
  *     kernel is launched.
  *   - "device" pointers are HIP device memory owned by the caller (16-byte aligned); the library
- *     allocates no device memory, keeps no state between calls, enqueues its kernels on the
- *     caller's stream and returns without synchronising.  "host" pointers are ordinary memory.
+ *     allocates no device memory and returns without synchronising.  "host" pointers are ordinary
+ *     memory.  Seen from the caller, everything a call enqueues is ordered on the stream it passes.
+ *   - Process-wide state the library does keep: (a) per device, one second HIP stream (default
+ *     priority, non-blocking) and a ring of 256 events, created at the first resist_local_step that
+ *     uses them and kept until the process ends: the weight-gradient kernels of a step run there,
+ *     ordered against the caller's stream by those events (resist_set_overlap); (b) the
+ *     resist_set_overlap mode; (c) the optional timing facility (resist_profile_*).
+ *   - Threads: host-only calls are reentrant.  Calls that enqueue work on the same device must not
+ *     overlap in time from different host threads (the event ring is shared per device); different
+ *     devices may be driven from different threads.
  *   - Same inputs give bit-identical outputs from run to run (no floating-point atomics).
  *   - Blocks of the global network are numbered 0..B-1 in network order; -1 names the stem and
  *     B the head (global pooling + fully connected layer).  Stem and head belong to every
@@ -193,6 +201,7 @@ int resist_forward(const resist_model_desc *desc, const int32_t *blocks, int32_t
  *   sub_block_params          host [S] arrays; sub_block_params[s] is a host array
  *                             [n_s + 2] of device buffers: stem, the blocks of s in order, head
  *   global_block_params       host array [B+2] of device buffers: stem, blocks 0..B-1, head
+ * At most 16 sub-ResNets (S <= 16, the paper uses 2 to 8): more is RESIST_EUNSUPPORTED.
  */
 int resist_aggregate(const resist_model_desc *desc, int32_t S, const int32_t *sub_offsets,
                      const int32_t *sub_blocks, void *const *const *sub_block_params,

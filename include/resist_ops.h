@@ -7,7 +7,9 @@
  * Layouts: activations NHWC [N][H][W][C]; filters [K][R][S][C]; outputs [N][P][Q][K] with
  * P = (H + 2*pad - R)/stride + 1.  dtype 0: all fp32.  dtype 1: activations and filters bf16
  * (as uint16 bit patterns), accumulation fp32, weight gradients fp32.
- * Supported: R = S in {1,3,7}; stride in {1,2}; C and K multiples of 4 (fp32) or 8 (bf16).
+ * Supported: R = S in {1,3,5,7}; stride in {1,2}; 0 <= pad < R; C and K multiples of 4 (fp32) or 8
+ * (bf16); the stride-2 data gradient needs even H and W; every tensor below 2 GiB.  Anything else is
+ * RESIST_ESHAPE before any launch.
  */
 #ifndef RESIST_OPS_H
 #define RESIST_OPS_H

@@ -53,7 +53,8 @@ struct IgemmArgs {
   const void *wt;      // [OC][R][S][IC]
   void *out;           // [N][OH][OW][OC]
   const void *addend;  // optional, indexed like out
-  float *stats;        // optional [2][tiles_m][OC]: per row-tile column sums and sums of squares of out
+  const void *relu_mask;   // optional, indexed like out: out is zeroed where this is not positive (after the addend)
+  float *stats;        // optional [3][tiles_m][OC]: per row tile and column a shift k, sum(out - k), sum((out - k)^2)
   int N, IH, IW, IC;
   int OH, OW, OC;
   int R, S, stride, pad;
@@ -315,9 +316,20 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
   static_assert(BM % RPS == 0 && CV <= 32, "output tile rows per pass");
   const int cv = (tid % CV) * VEC, row0 = tid / CV;
   const bool col_ok = n0 + cv < a.OC;     // OC is a multiple of VEC
-  float s1[VEC], s2[VEC];   // column sums of the values as stored (batch-norm statistics of this row tile)
+  // batch-norm statistics of this row tile: column sums of (v - k) and (v - k)^2 of the values v as
+  // stored, with the shift k = the tile's first accumulated row of the column.  Any k within a few
+  // standard deviations of the column keeps the sum of squares free of the cancellation that
+  // sum(v^2) - (sum v)^2/n suffers when |mean| >> std.
+  float s1[VEC], s2[VEC], kshift[VEC];
 #pragma unroll
-  for (int e = 0; e < VEC; ++e) { s1[e] = 0.f; s2[e] = 0.f; }
+  for (int e = 0; e < VEC; ++e) { s1[e] = 0.f; s2[e] = 0.f; kshift[e] = 0.f; }
+  if (MODE == kFwd && a.stats) {
+#pragma unroll
+    for (int e = 0; e < VEC; e += 4) {
+      const f32x4 t = *reinterpret_cast<const f32x4 *>(&Cs[0][cv + e]);
+      kshift[e] = t[0]; kshift[e + 1] = t[1]; kshift[e + 2] = t[2]; kshift[e + 3] = t[3];
+    }
+  }
 #pragma unroll
   for (int pass = 0; pass < BM / RPS; ++pass) {
     const int r = row0 + pass * RPS;
@@ -336,11 +348,17 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) v[e] += ad[e];
       }
+      if (MODE == kBwd && a.relu_mask) {
+        float mk[VEC];
+        Vec<T>::load(static_cast<const T *>(a.relu_mask) + off, mk);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] = mk[e] > 0.f ? v[e] : 0.f;
+      }
       Vec<T>::store(out + off, v);
       if (MODE == kFwd) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-          const float sv = E::to_f32(E::from_f32(v[e]));
+          const float sv = E::to_f32(E::from_f32(v[e])) - kshift[e];
           s1[e] += sv;
           s2[e] = fmaf(sv, sv, s2[e]);
         }
@@ -368,17 +386,18 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
       if (n0 + c < a.OC) {
         const float t1 = ((red[0][0][c] + red[0][1][c]) + red[0][2][c]) + red[0][3][c];
         const float t2 = ((red[1][0][c] + red[1][1][c]) + red[1][2][c]) + red[1][3][c];
-        a.stats[(size_t)tm * a.OC + n0 + c] = t1;
-        a.stats[((size_t)a.tiles_m + tm) * a.OC + n0 + c] = t2;
+        a.stats[(size_t)tm * a.OC + n0 + c] = Cs[0][c];
+        a.stats[((size_t)a.tiles_m + tm) * a.OC + n0 + c] = t1;
+        a.stats[((size_t)2 * a.tiles_m + tm) * a.OC + n0 + c] = t2;
       }
     }
   }
 }
 
 template <typename T, int BM, int BN, int BK, int WGM, int WGN, int MODE>
-int launch_igemm(IgemmArgs a, hipStream_t st, int *tiles_m_out) {
+int launch_igemm(IgemmArgs a, hipStream_t st, StatParts *tiles_m_out) {
   a.tiles_m = (a.Mrows + BM - 1) / BM;
-  if (tiles_m_out) *tiles_m_out = a.tiles_m;
+  if (tiles_m_out) { tiles_m_out->parts = a.tiles_m; tiles_m_out->rows = BM; }
   a.tiles_n = (a.OC + BN - 1) / BN;
   const long long grid = (long long)a.tiles_m * a.tiles_n * a.cls * a.cls;
   if (grid <= 0 || grid > 0x7fffffffLL) return set_error(RESIST_ESHAPE, "igemm grid %lld", grid);
@@ -387,7 +406,7 @@ int launch_igemm(IgemmArgs a, hipStream_t st, int *tiles_m_out) {
                                      std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK);
     // algorithmic work of the convolution this launch computes (forward or data gradient)
     const double flops = 2.0 * a.N * (MODE == kFwd ? (double)a.OH * a.OW : (double)a.IH * a.IW) * a.OC * a.IC * a.R * a.S;
-    const double bytes = sizeof(T) * ((double)a.N * a.IH * a.IW * a.IC + (double)a.N * a.OH * a.OW * a.OC * (a.addend ? 2 : 1) +
+    const double bytes = sizeof(T) * ((double)a.N * a.IH * a.IW * a.IC + (double)a.N * a.OH * a.OW * a.OC * (1 + (a.addend ? 1 : 0) + (a.relu_mask ? 1 : 0)) +
                                       (double)a.OC * a.R * a.S * a.IC);
     prof::Scope ps(label.c_str(), flops, bytes, st);
     hipLaunchKernelGGL((igemm_kernel<T, BM, BN, BK, WGM, WGN, MODE>), dim3((unsigned)grid), dim3(kThreads), 0, st, a);
@@ -397,7 +416,7 @@ int launch_igemm(IgemmArgs a, hipStream_t st, int *tiles_m_out) {
 }
 
 template <typename T, int MODE>
-int dispatch_igemm(const IgemmArgs &a, hipStream_t st, int *tiles_m_out = nullptr) {
+int dispatch_igemm(const IgemmArgs &a, hipStream_t st, StatParts *tiles_m_out = nullptr) {
   // pick the largest tile that still yields enough workgroups to cover the 256 compute units
   constexpr int V = Elem<T>::VEC;   // K-chunks of 8*V and 16*V elements: 128 and 256 bytes per tile row
   const long long classes = (long long)a.cls * a.cls;
@@ -420,7 +439,7 @@ int check_geom(const ConvGeom &g, int dt) {
   if (dt != DT_F32 && dt != DT_BF16) return set_error(RESIST_EINVAL, "dtype %d", dt);
   if (g.N < 1 || g.H < 1 || g.W < 1 || g.C < v || g.K < v || (g.C % v) || (g.K % v))
     return set_error(RESIST_ESHAPE, "conv shape N%d H%d W%d C%d K%d (C, K must be multiples of %d)", g.N, g.H, g.W, g.C, g.K, v);
-  if (g.R != g.S || (g.R != 1 && g.R != 3 && g.R != 5) || g.R * g.S > 32)
+  if (g.R != g.S || (g.R != 1 && g.R != 3 && g.R != 5 && g.R != 7))
     return set_error(RESIST_ESHAPE, "filter %dx%d unsupported", g.R, g.S);
   if (g.stride < 1 || g.stride > 2 || g.pad < 0 || g.pad >= g.R)
     return set_error(RESIST_ESHAPE, "stride %d pad %d unsupported", g.stride, g.pad);
@@ -438,10 +457,10 @@ int conv_check(const ConvGeom &g, int dt) { return check_geom(g, dt); }
 
 int64_t conv_stats_floats(const ConvGeom &g) {
   // the smallest row tile any forward kernel uses is 64
-  return (int64_t)2 * (((int64_t)g.N * g.P * g.Q + 63) / 64) * g.K;
+  return (int64_t)3 * (((int64_t)g.N * g.P * g.Q + 63) / 64) * g.K;
 }
 
-int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, const void *addend, float *stats, int *stat_parts,
+int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, const void *addend, float *stats, StatParts *stat_parts,
              hipStream_t st) {
   RESIST_TRY(check_geom(g, dt));
   if (stats && !stat_parts) return set_error(RESIST_EINVAL, "conv_fwd: stats without stat_parts");
@@ -455,12 +474,13 @@ int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, c
   return dt == DT_BF16 ? dispatch_igemm<__bf16, kFwd>(a, st, stat_parts) : dispatch_igemm<float, kFwd>(a, st, stat_parts);
 }
 
-int conv_dgrad(const ConvGeom &g, int dt, const void *dy, const void *wT, void *dx, const void *addend, hipStream_t st) {
+int conv_dgrad(const ConvGeom &g, int dt, const void *dy, const void *wT, void *dx, const void *addend, const void *relu_mask,
+               hipStream_t st) {
   RESIST_TRY(check_geom(g, dt));
   if (g.stride == 2 && ((g.H & 1) || (g.W & 1)))
     return set_error(RESIST_ESHAPE, "stride-2 dgrad needs even input size, got %dx%d", g.H, g.W);
   IgemmArgs a{};
-  a.in = dy; a.wt = wT; a.out = dx; a.addend = addend;
+  a.in = dy; a.wt = wT; a.out = dx; a.addend = addend; a.relu_mask = relu_mask;
   a.N = g.N; a.IH = g.P; a.IW = g.Q; a.IC = g.K;
   a.OH = g.H; a.OW = g.W; a.OC = g.C;
   a.R = g.R; a.S = g.S; a.stride = g.stride; a.pad = g.pad;

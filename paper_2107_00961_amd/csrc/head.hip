@@ -107,7 +107,8 @@ __global__ __launch_bounds__(256) void avgpool_fwd_kernel(const T *__restrict__ 
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void avgpool_bwd_kernel(const float *__restrict__ dy, T *__restrict__ dx, int N, int HW, int C) {
+__global__ __launch_bounds__(256) void avgpool_bwd_kernel(const float *__restrict__ dy, const T *__restrict__ mask, T *__restrict__ dx,
+                                                          int N, int HW, int C) {
   constexpr int V = Vec<T>::N;
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (long long)N * HW * (C / V)) return;
@@ -117,6 +118,12 @@ __global__ __launch_bounds__(256) void avgpool_bwd_kernel(const float *__restric
   float g[V];
 #pragma unroll
   for (int e = 0; e < V; ++e) g[e] = dy[(size_t)n * C + c + e] * inv;
+  if (mask) {   // the ReLU that produced the pooled tensor: the gradient passes where its output is positive
+    float m[V];
+    Vec<T>::load(mask + i * V, m);
+#pragma unroll
+    for (int e = 0; e < V; ++e) g[e] = m[e] > 0.f ? g[e] : 0.f;
+  }
   Vec<T>::store(dx + i * V, g);
 }
 
@@ -319,13 +326,13 @@ int avgpool_fwd(int dt, const void *x, float *y, int N, int HW, int C, hipStream
   RESIST_CHECK_LAUNCH("avgpool_fwd");
   return RESIST_OK;
 }
-int avgpool_bwd(int dt, const float *dy, void *dx, int N, int HW, int C, hipStream_t st) {
+int avgpool_bwd(int dt, const float *dy, const void *relu_mask, void *dx, int N, int HW, int C, hipStream_t st) {
   const int V = dt == DT_BF16 ? 8 : 4;
   if (C % V) return set_error(RESIST_ESHAPE, "mean pool: C=%d must be a multiple of %d", C, V);
   prof::Scope ps("avgpool_bwd", 0, 0, st);
   const dim3 grid(blocks_for((long long)N * HW * (C / V)));
-  if (dt == DT_BF16) hipLaunchKernelGGL(avgpool_bwd_kernel<__bf16>, grid, dim3(256), 0, st, dy, (__bf16 *)dx, N, HW, C);
-  else hipLaunchKernelGGL(avgpool_bwd_kernel<float>, grid, dim3(256), 0, st, dy, (float *)dx, N, HW, C);
+  if (dt == DT_BF16) hipLaunchKernelGGL(avgpool_bwd_kernel<__bf16>, grid, dim3(256), 0, st, dy, (const __bf16 *)relu_mask, (__bf16 *)dx, N, HW, C);
+  else hipLaunchKernelGGL(avgpool_bwd_kernel<float>, grid, dim3(256), 0, st, dy, (const float *)relu_mask, (float *)dx, N, HW, C);
   RESIST_CHECK_LAUNCH("avgpool_bwd");
   return RESIST_OK;
 }

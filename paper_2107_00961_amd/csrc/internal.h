@@ -125,14 +125,18 @@ inline int esize(int dt) { return dt == DT_BF16 ? 2 : 4; }
 // implicit-GEMM convolution family (conv.hip); dt selects fp32 or bf16 tensors (fp32 accumulation)
 // shape limits of the convolution kernels (channel multiples, filter sizes, tensors below 2 GiB); host only
 int conv_check(const ConvGeom &g, int dt);
-// y = conv(x, w) [+ addend].  stats (optional): per row-tile column sums and sums of squares of y as
-// stored, [2][*stat_parts][K] floats (capacity conv_stats_floats(g)); input of bn_finalize
+// y = conv(x, w) [+ addend].  stats (optional): per row tile (stat_parts->rows rows each, the last one
+// ragged) and column a shift k, sum(y - k) and sum((y - k)^2) of y as stored, [3][stat_parts->parts][K]
+// floats (capacity conv_stats_floats(g)); input of bn_finalize
+struct StatParts { int parts = 0; int rows = 0; };
 int64_t conv_stats_floats(const ConvGeom &g);
 int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, const void *addend, float *stats,
-             int *stat_parts, hipStream_t st);
-// dx = dgrad(dy, wT) [+ addend]; wT is the [C][R][S][K] transpose made by prepare_filter
+             StatParts *stat_parts, hipStream_t st);
+// dx = dgrad(dy, wT) [+ addend]; wT is the [C][R][S][K] transpose made by prepare_filter.  relu_mask
+// (optional, indexed like dx): the output of the ReLU that produced the convolution's input; dx is set
+// to zero where it is not positive, i.e. the gradient leaves this kernel already taken through that ReLU
 int conv_dgrad(const ConvGeom &g, int dt, const void *dy, const void *wT, void *dx, const void *addend,
-               hipStream_t st);
+               const void *relu_mask, hipStream_t st);
 // from a filter stored in src_dt: optional copy in dt (w_lp) and optional transpose in dt (wT)
 int prepare_filter(const ConvGeom &g, int src_dt, int dt, const void *w, void *w_lp, void *wT, hipStream_t st);
 // the same for many filters at once (fp32 masters -> copies and transposes in dt, times `scale`)
@@ -160,7 +164,7 @@ struct BnBufs {
 int64_t bn_scratch_doubles(int C);   // partial-sum scratch for one bn_finalize or bn_backward call
 // batch statistics from the per-tile sums a convolution left behind: mean, 1/sqrt(var+eps), the
 // affine map of bn_apply, and the running statistics
-int bn_finalize(const float *stats, int parts, int64_t M, int C, const BnBufs &b, float eps, float momentum,
+int bn_finalize(const float *stats, StatParts parts, int64_t M, int C, const BnBufs &b, float eps, float momentum,
                 double *scratch, hipStream_t st);
 // evaluation mode: scale/shift from the running statistics, both multiplied by s
 int bn_eval_affine(int C, const BnBufs &b, float eps, float s, hipStream_t st);
@@ -180,7 +184,8 @@ int maxpool_fwd(int dt, const void *x, void *y, uint8_t *argmax, int N, int H, i
 int maxpool_bwd(int dt, const void *dy, const uint8_t *argmax, void *dx, int N, int H, int W, int C,
                 int P, int Q, hipStream_t st);
 int avgpool_fwd(int dt, const void *x, float *y, int N, int HW, int C, hipStream_t st);
-int avgpool_bwd(int dt, const float *dy, void *dx, int N, int HW, int C, hipStream_t st);
+// dx = dy / HW broadcast over the positions; relu_mask (optional, indexed like dx): zero where it is not positive
+int avgpool_bwd(int dt, const float *dy, const void *relu_mask, void *dx, int N, int HW, int C, hipStream_t st);
 int fc_fwd_f32(const float *x, const float *w, const float *b, float *z, int N, int C, int J,
                hipStream_t st);
 int fc_bwd_f32(const float *dz, const float *x, const float *w, float *dx, float *dw, float *db,

@@ -43,7 +43,7 @@ extern "C" int resist_conv2d_dgrad(const resist_conv_shape *s, const void *dy, c
   if (workspace_bytes < (int64_t)g.K * g.R * g.S * g.C * esize(s->dtype)) return set_error(RESIST_EWORKSPACE, "workspace too small for the transposed filter");
   hipStream_t st = (hipStream_t)hip_stream;
   RESIST_TRY(prepare_filter(g, s->dtype, s->dtype, w, nullptr, workspace, st));
-  return conv_dgrad(g, s->dtype, dy, workspace, dx, nullptr, st);
+  return conv_dgrad(g, s->dtype, dy, workspace, dx, nullptr, nullptr, st);
 }
 
 extern "C" int resist_conv2d_wgrad(const resist_conv_shape *s, const void *dy, const void *x, float *dw, void *workspace,

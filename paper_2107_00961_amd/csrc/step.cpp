@@ -623,7 +623,7 @@ int local_step_preact(const resist_model_desc *desc, const int32_t *blocks, int3
   // ================= forward =================
   const int K0 = net.d.width[0];
   const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
-  int parts = 0;   // number of per-tile sums the last statistics-taking convolution left in P.stats
+  StatParts parts;   // number of per-tile sums the last statistics-taking convolution left in P.stats
   RESIST_TRY(stem_im2col(dt, x, P.col, N, net.d.in_c, net.d.in_h, net.d.in_w, net.stem_rs, net.stem_stride, net.stem_pad,
                          net.stem_h, net.stem_w, P.kpad, st));
   RESIST_TRY(pad_rows(dt, params(0) + P.stem_w_off, P.wpad, K0, taps, P.kpad, st));
@@ -660,7 +660,7 @@ int local_step_preact(const resist_model_desc *desc, const int32_t *blocks, int3
 
   // ================= backward =================
   RESIST_TRY(fc_bwd_f32(P.dz, P.pooled, fcw, P.dpooled, hg + HL.off(T_FCW, 0), hg + HL.off(T_FCB, 0), N, CH, J, st));
-  RESIST_TRY(avgpool_bwd(dt, P.dpooled, P.da, N, P.feat_hw, CH, st));
+  RESIST_TRY(avgpool_bwd(dt, P.dpooled, nullptr, P.da, N, P.feat_hw, CH, st));
   int gi = 0;
   RESIST_TRY(wg.filters_ready());
   RESIST_TRY(bn_backward(dt, P.da, nullptr, true, P.feat_in, P.head_rows, CH, hb, P.gbuf[gi], nullptr, nullptr, P.bn_scratch, st));
@@ -677,10 +677,10 @@ int local_step_preact(const resist_model_desc *desc, const int32_t *blocks, int3
       if (j == 0 && pb.has_ds) {
         // the shortcut convolution reads the same a_1: its data gradient joins the branch's
         RESIST_TRY(wg.launch(pb.dsg, G, un.a, gg + pb.ds_w_off));
-        RESIST_TRY(conv_dgrad(pb.dsg, dt, G, pb.ds_wT, P.dsgrad, nullptr, st));
+        RESIST_TRY(conv_dgrad(pb.dsg, dt, G, pb.ds_wT, P.dsgrad, nullptr, nullptr, st));
         addend = P.dsgrad;
       }
-      RESIST_TRY(conv_dgrad(un.g, dt, gcur, un.wT, P.da, addend, st));
+      RESIST_TRY(conv_dgrad(un.g, dt, gcur, un.wT, P.da, addend, nullptr, st));
       BnBufs b = pre_bn_bufs(un, pp, gg);
       if (j > 0) {
         RESIST_TRY(wg.before_write(dy));
@@ -805,7 +805,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     RESIST_TRY(stem_im2col(dt, x, P.col, N, net.d.in_c, net.d.in_h, net.d.in_w, net.stem_rs, net.stem_stride, net.stem_pad,
                            net.stem_h, net.stem_w, P.kpad, st));
     RESIST_TRY(pad_rows(dt, params(0) + s.w_off, P.wpad, K0, taps, P.kpad, st));
-    int parts = 0;
+    StatParts parts;
     RESIST_TRY(conv_fwd(s.g, dt, P.col, P.wpad, s.y, nullptr, P.stats, &parts, st));
     BnBufs b = bn_bufs(s, params(0), grads(0));
     RESIST_TRY(bn_finalize(P.stats, parts, s.M(), K0, b, eps, bnm, P.bn_scratch, st));
@@ -817,7 +817,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     float *pp = params(bp.slot), *gg = grads(bp.slot);
     for (size_t j = 0; j < bp.convs.size(); ++j) {
       ConvLayer &c = bp.convs[j];
-      int parts = 0;
+      StatParts parts;
       RESIST_TRY(conv_fwd(c.g, dt, c.in, fwd_filter(c, pp + c.w_off), c.y, nullptr, P.stats, &parts, st));
       BnBufs b = bn_bufs(c, pp, gg);
       RESIST_TRY(bn_finalize(P.stats, parts, c.M(), c.g.K, b, eps, bnm, P.bn_scratch, st));
@@ -827,7 +827,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     BnBufs bl = bn_bufs(last, pp, gg);
     if (bp.has_ds) {
       ConvLayer &d = bp.ds;
-      int parts = 0;
+      StatParts parts;
       RESIST_TRY(conv_fwd(d.g, dt, d.in, fwd_filter(d, pp + d.w_off), d.y, nullptr, P.stats, &parts, st));
       BnBufs bd = bn_bufs(d, pp, gg);
       RESIST_TRY(bn_finalize(P.stats, parts, d.M(), d.g.K, bd, eps, bnm, P.bn_scratch, st));
@@ -847,9 +847,13 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
   // ================= backward =================
   RESIST_TRY(wg.filters_ready());
   RESIST_TRY(fc_bwd_f32(P.dz, P.pooled, fcw, P.dpooled, grads(hs) + HL.off(T_FCW, 0), grads(hs) + HL.off(T_FCB, 0), N, CH, J, st));
+  // The gradient w.r.t. a block's output is stored already taken through that block's final ReLU: the
+  // kernel that produces it (the mean-pool backward, or the first convolution's data gradient of the
+  // block after it) reads the block output once and zeroes the gradient where it is not positive, so
+  // the two BN backward passes behind it need no mask tensor and no masked copy is written.
   int gi = 0;
   void *G = P.gbuf[gi];
-  RESIST_TRY(avgpool_bwd(dt, P.dpooled, G, N, P.feat_hw, CH, st));
+  RESIST_TRY(avgpool_bwd(dt, P.dpooled, P.feat, G, N, P.feat_hw, CH, st));
   for (int bi = (int)P.blocks.size() - 1; bi >= 0; --bi) {
     BlockPlan &bp = P.blocks[bi];
     float *pp = params(bp.slot), *gg = grads(bp.slot);
@@ -857,17 +861,17 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     const int nc = (int)bp.convs.size();
     ConvLayer &last = bp.convs[nc - 1];
     BnBufs bl = bn_bufs(last, pp, gg);
-    // through the final ReLU and the last BN of the residual branch
+    // the last BN of the residual branch
     RESIST_TRY(wg.before_write(P.dy0));
-    RESIST_TRY(wg.before_write(P.gm));
-    RESIST_TRY(bn_backward(dt, G, bp.out, false, last.y, last.M(), last.g.K, bl, P.dy0, bp.has_ds ? nullptr : P.gm, nullptr, P.bn_scratch, st));
+    RESIST_TRY(bn_backward(dt, G, nullptr, false, last.y, last.M(), last.g.K, bl, P.dy0, nullptr, nullptr, P.bn_scratch, st));
     if (bp.has_ds) {
       // shortcut branch: BN and 1x1 convolution; its data gradient initialises Gn
       ConvLayer &d = bp.ds;
       BnBufs bd = bn_bufs(d, pp, gg);
-      RESIST_TRY(bn_backward(dt, G, bp.out, false, d.y, d.M(), d.g.K, bd, P.gm, nullptr, nullptr, P.bn_scratch, st));
+      RESIST_TRY(wg.before_write(P.gm));
+      RESIST_TRY(bn_backward(dt, G, nullptr, false, d.y, d.M(), d.g.K, bd, P.gm, nullptr, nullptr, P.bn_scratch, st));
       RESIST_TRY(wg.launch(d.g, P.gm, d.in, gg + d.w_off));
-      RESIST_TRY(conv_dgrad(d.g, dt, P.gm, d.wT, Gn, nullptr, st));
+      RESIST_TRY(conv_dgrad(d.g, dt, P.gm, d.wT, Gn, nullptr, nullptr, st));
     }
     void *dy = P.dy0, *dy_other = P.dy1;
     for (int j = nc - 1; j >= 0; --j) {
@@ -875,14 +879,15 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
       RESIST_TRY(wg.launch(c.g, dy, c.in, gg + c.w_off));
       if (j > 0) {
         ConvLayer &prev = bp.convs[j - 1];
-        RESIST_TRY(conv_dgrad(c.g, dt, dy, c.wT, P.da, nullptr, st));
+        RESIST_TRY(conv_dgrad(c.g, dt, dy, c.wT, P.da, nullptr, nullptr, st));
         BnBufs bp_ = bn_bufs(prev, pp, gg);
         RESIST_TRY(wg.before_write(dy_other));
         RESIST_TRY(bn_backward(dt, P.da, nullptr, true, prev.y, prev.M(), prev.g.K, bp_, dy_other, nullptr, nullptr, P.bn_scratch, st));
         std::swap(dy, dy_other);
       } else {
-        // gradient w.r.t. the block input = branch + shortcut
-        RESIST_TRY(conv_dgrad(c.g, dt, dy, c.wT, Gn, bp.has_ds ? Gn : P.gm, st));
+        // gradient w.r.t. the block input = branch + shortcut (the identity shortcut passes G itself),
+        // taken through the ReLU that ends the block before (the stem's ReLU is handled by its own BN backward)
+        RESIST_TRY(conv_dgrad(c.g, dt, dy, c.wT, Gn, bp.has_ds ? Gn : G, bi > 0 ? bp.in : nullptr, st));
       }
     }
     gi ^= 1;

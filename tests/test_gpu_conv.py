@@ -20,7 +20,11 @@ CASES = [(2, 16, 16, 16, 16, 3, 1, 1),      # tiny config's block shape
          (2, 6, 6, 48, 80, 3, 1, 1),        # channel counts that are not multiples of the K-chunk
          (32, 32, 32, 64, 256, 3, 1, 1),    # large enough for the 128x128 tile
          (2, 8, 8, 512, 512, 3, 1, 1),      # 128x128 weight-gradient tile
-         (5, 14, 14, 32, 32, 3, 2, 1)]      # stride 2 with odd output size 7
+         (5, 14, 14, 32, 32, 3, 2, 1),      # stride 2 with odd output size 7
+         (2, 12, 12, 16, 32, 5, 1, 2),      # 5x5
+         (2, 14, 14, 16, 32, 5, 2, 2),      # 5x5 stride 2: three and two taps per parity class
+         (1, 9, 9, 16, 16, 7, 1, 3),        # 7x7
+         (2, 16, 16, 8, 16, 7, 2, 3)]       # 7x7 stride 2 pad 3 (the ImageNet stem's filter geometry)
 
 
 def _tensors(case, seed=0):

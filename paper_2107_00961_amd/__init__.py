@@ -5,6 +5,7 @@ this package only marshals arguments (ctypes) and packs logical tensors into the
 buffer layout.  There is no CPU fallback: importing works without a GPU (host-only calls such
 as `partition` run anywhere), device calls need the built library and a gfx950 device.
 """
+from . import binding
 from .binding import (ResistError, aggregate, aggregate_compressed, block_layout, block_param_count, compress_blocks,
                       compressed_block_size, decompress_blocks, conv2d_dgrad, conv2d_forward, conv2d_wgrad, forward, forward_workspace_bytes, lib, local_step, model_desc, num_blocks,
                       pack_block, partition, profile_enable, profile_read, set_overlap, unpack_block,

@@ -382,3 +382,4 @@ def conv2d_wgrad(dy, x, w_shape, stride, pad, stream=None):
     _check(lib().resist_conv2d_wgrad(C.byref(sh), dy.data_ptr(), x.data_ptr(), dw.data_ptr(),
                                      ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
     return dw
+

@@ -35,5 +35,18 @@ def build(verbose=False):
     return LIB
 
 
+def build_host_check():
+    """The library's host-only code (model.cpp) with its driver host_check.cpp under AddressSanitizer and
+    UndefinedBehaviorSanitizer, host compiler only: paper_2107_00961_amd/_build/host_check."""
+    os.makedirs(OBJ, exist_ok=True)
+    exe = os.path.join(OBJ, "host_check")
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=all", "-static-libasan", "-static-libubsan", "-Wall", "-D__HIP_PLATFORM_AMD__",
+           "-I", "/opt/rocm/include", "-I", INC, "-I", CSRC, "-o", exe,
+           os.path.join(CSRC, "host_check.cpp"), os.path.join(CSRC, "model.cpp")]
+    subprocess.check_call(cmd)
+    return exe
+
+
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv))
+    print(build_host_check() if "--sanitize" in sys.argv else build(verbose="-v" in sys.argv))

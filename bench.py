@@ -23,12 +23,7 @@ PEAK_HBM_GBS = 8000.0
 def _measured_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` in `workload` from the committed rocprofv3 --pmc runs
     (FETCH_SIZE and WRITE_SIZE, scaled by a copy of known size), if recorded."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    try:
-        with open(path) as f:
-            return json.load(f).get(workload, {}).get(kernel)
-    except (OSError, ValueError):
-        return None
+    return _traffic_table(workload).get(kernel)
 
 
 def _describe(name, cfg, sub):
@@ -134,7 +129,7 @@ def _bench_round(args, cfg, subs):
         "value": round(batch / (ms * 1e-3), 1), "unit": "images/s", "n_gpus": 1, "steps": S * iters, "warmup": S,
         "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if model.get("compute_dtype", 0) == 1 else "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: full round, {S} sub-ResNets x {iters} local steps, then aggregation",
+        "config": {"workload": f"{getattr(args, 'workload_name', args.workload)}: full round, {S} sub-ResNets x {iters} local steps, then aggregation",
                    "batch": batch, "blocks": subs, "classes": model["num_classes"]},
         "round": {"ms_per_step_by_sub": [round(v, 4) for v in step_ms], "aggregate_ms": round(agg, 4),
                   "aggregate_bytes": agg_bytes, "aggregate_GBps": round(agg_bytes / (agg * 1e-3) / 1e9, 1),
@@ -149,45 +144,28 @@ def _bench_round(args, cfg, subs):
     if compressed:
         compressed["aggregate_traffic"] = _measured_traffic("cfg3_round", "aggregate_compressed")
         out["round"]["compressed"] = compressed
-    print(json.dumps(out))
+    print(json.dumps(out), flush=True)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2",
-                    help="cfg1 | cfg2 | cfg2_preact | cfg3 | cfg5 (fp32) | cfg4 | cfg5_bf16 (bf16 storage, fp32 accumulation)")
-    ap.add_argument("--sub", type=int, default=0, help="which sub-ResNet of the partition to step")
-    ap.add_argument("--compress-bits", type=int, default=0,
-                    help="with --round: also time b-bit compression of the workers' blocks and the reassembly "
-                         "from the compressed copies (2..8; 0 = off)")
-    ap.add_argument("--local-iters", type=int, default=0, help="with --round: override the local iterations per sub-ResNet")
-    ap.add_argument("--round", action="store_true",
-                    help="time one full round instead: every sub-ResNet runs its local iterations on fresh "
-                         "batches, one after the other, then resist_aggregate rebuilds the global model")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-batch", type=int, default=128,
-                    help="images of the oracle's timed step at CIFAR shape (an eighth of it at ImageNet shape): ~10-20 s of CPU work")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one 256 MiB device copy (reference point for HBM traffic counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; the S sub-ResNets are stepped sequentially on it "
-              "and no collective exists to scale over. Re-run with --gpus 1.", file=sys.stderr)
-        sys.exit(2)
+def _traffic_table(workload):
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {})
+    except (OSError, ValueError):
+        return {}
 
+
+def _bench_step(args, name):
+    """One workload: K timed local steps, then the per-kernel passes.  Returns the result dict."""
     import torch
     import paper_2107_00961_amd as R
     from paper_2107_00961_amd.harness import SubResNet, to_device_batch
     from resist_inputs import get_config, make_batch, make_params
 
-    cfg = get_config(args.workload)
+    cfg = get_config(name)
     model, batch = cfg["model"], cfg["batch"]
     subs, _ = R.partition(model, cfg["S"], cfg["min_depth"], cfg["part_seed"], 0)
-    if args.round:
-        return _bench_round(args, cfg, subs)
     blocks = subs[args.sub]
     params = make_params(model, 0)
     sub = SubResNet(model, blocks, params, batch, keep_grads=False)
@@ -211,7 +189,7 @@ def main():
 
     # per-kernel durations: the same steps again with event timing switched on -- first as timed above
     # (weight gradients on the library's second stream, so kernels share the GPU), then with every kernel
-    # on one stream: a kernel that has the GPU to itself is what a roofline fraction describes
+    # on one stream, where each kernel has the GPU to itself
     psteps = max(1, min(args.steps, 10))
 
     def profiled_pass():
@@ -227,57 +205,81 @@ def main():
 
     stats_in_step, ms_profiled = profiled_pass()
     R.set_overlap(0)
-    stats, ms_profiled_one_stream = profiled_pass()
+    stats_alone, ms_profiled_one_stream = profiled_pass()
     t1 = time.perf_counter()
     for _ in range(psteps):
         sub.step(xd, yd, lr, mu, wd, stream)
     torch.cuda.synchronize()
     ms_one_stream = (time.perf_counter() - t1) / psteps * 1e3
     R.set_overlap(1)
-    in_step = {s["name"]: s for s in stats_in_step}
-    stats.sort(key=lambda s: -s["ms"])
+    alone = {s["name"]: s for s in stats_alone}
+    stats = sorted(stats_in_step, key=lambda s: -s["ms"])        # as timed: the mode `value` is measured in
     dtype = "bf16" if model.get("compute_dtype", 0) == 1 else "f32"
+    table = _traffic_table(name)
+    stale = sorted(k for k in table if k not in alone)
+    if stale:
+        print(f"bench.py: profiles/hbm_traffic.json lists kernels of {name} that no longer run: {stale} -- "
+              "refresh the FETCH_SIZE / WRITE_SIZE runs", file=sys.stderr)
+
+    def rate(s):
+        tf = s["flops"] / (s["ms"] * 1e-3) / 1e12 if s["flops"] and s["ms"] > 0 else None
+        gb = s["bytes"] / (s["ms"] * 1e-3) / 1e9 if s["bytes"] and s["ms"] > 0 else None
+        return tf, gb
+
     kernels = []
     for s in stats:
-        tf = s["flops"] / (s["ms"] * 1e-3) / 1e12 if s["flops"] else None
-        gb = s["bytes"] / (s["ms"] * 1e-3) / 1e9 if s["bytes"] else None
+        tf, gb = rate(s)
+        a = alone.get(s["name"])
+        atf, agb = rate(a) if a else (None, None)
         kernels.append(dict(name=s["name"], launches_per_step=s["launches"] / psteps,
                             ms_per_step=round(s["ms"] / psteps, 4),
                             avg_us=round(s["ms"] / s["launches"] * 1e3, 2),
-                            avg_us_in_step=(round(in_step[s["name"]]["ms"] / in_step[s["name"]]["launches"] * 1e3, 2)
-                                            if s["name"] in in_step else None),
+                            avg_us_alone=round(a["ms"] / a["launches"] * 1e3, 2) if a else None,
                             tflops=round(tf, 2) if tf else None,
                             frac_of_mfma_peak=round(tf / PEAK_TFLOPS[dtype], 4) if tf else None,
+                            frac_of_mfma_peak_alone=round(atf / PEAK_TFLOPS[dtype], 4) if atf else None,
                             gbs=round(gb, 1) if gb else None,
                             frac_of_hbm_peak=round(gb / PEAK_HBM_GBS, 4) if gb else None,
-                            measured_hbm_bytes_per_launch=_measured_traffic(args.workload, s["name"])))
-    dom = stats[0]
-    if dom["flops"] > 0:
-        ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
-        roof = dict(bound="mfma", kernel=dom["name"], achieved=round(ach, 2), peak=PEAK_TFLOPS[dtype],
-                    unit="TFLOP/s", frac=round(ach / PEAK_TFLOPS[dtype], 4),
-                    avg_launch_us=round(dom["ms"] / dom["launches"] * 1e3, 2),
-                    traffic=_measured_traffic(args.workload, dom["name"]))
-    else:
-        ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
-        roof = dict(bound="hbm", kernel=dom["name"], achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                    frac=round(ach / PEAK_HBM_GBS, 4), avg_launch_us=round(dom["ms"] / dom["launches"] * 1e3, 2),
-                    traffic=_measured_traffic(args.workload, dom["name"]))
-    roof["measured"] = "every kernel on one stream (resist_set_overlap(0)): the kernel has the GPU to itself"
-    d2 = in_step.get(dom["name"])
-    if d2 and d2["ms"] > 0:
-        a2 = (d2["flops"] / (d2["ms"] * 1e-3) / 1e12) if dom["flops"] > 0 else (d2["bytes"] / (d2["ms"] * 1e-3) / 1e9)
-        roof["in_step"] = dict(achieved=round(a2, 2), frac=round(a2 / roof["peak"], 4),
-                               avg_launch_us=round(d2["ms"] / d2["launches"] * 1e3, 2),
-                               measured="as timed: weight gradients on the second stream, sharing the GPU with the "
-                                        "data-gradient / BN chain")
-    conv_flops = sum(s["flops"] for s in stats)
-    conv_ms = sum(s["ms"] for s in stats if s["flops"])
-    roof["all_conv_tflops"] = round(conv_flops / (conv_ms * 1e-3) / 1e12, 2) if conv_ms else None
-    roof["all_conv_frac"] = round(roof["all_conv_tflops"] / PEAK_TFLOPS[dtype], 4) if conv_ms else None
+                            frac_of_hbm_peak_alone=round(agb / PEAK_HBM_GBS, 4) if agb else None,
+                            measured_hbm_bytes_per_launch=table.get(s["name"])))
+
+    def roofline_of(s):
+        if s["flops"] > 0:
+            ach = s["flops"] / (s["ms"] * 1e-3) / 1e12
+            return dict(bound="mfma", achieved=round(ach, 2), peak=PEAK_TFLOPS[dtype], unit="TFLOP/s",
+                        frac=round(ach / PEAK_TFLOPS[dtype], 4), avg_launch_us=round(s["ms"] / s["launches"] * 1e3, 2))
+        ach = s["bytes"] / (s["ms"] * 1e-3) / 1e9
+        return dict(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                    frac=round(ach / PEAK_HBM_GBS, 4), avg_launch_us=round(s["ms"] / s["launches"] * 1e3, 2))
+
+    # the dominant kernel = the one with the largest summed duration as timed, among those with a stated
+    # algorithmic work (convolutions: FLOPs; BN, update: bytes)
+    rated = [s for s in stats if s["flops"] > 0 or s["bytes"] > 0]
+    dom = rated[0]
+    roof = roofline_of(dom)
+    roof["kernel"] = dom["name"]
+    roof["traffic"] = table.get(dom["name"])
+    roof["measured"] = ("as timed: HIP events around every launch on the stream it runs on, during steps in the default "
+                        "stream mode (weight gradients on the library's second stream, sharing the GPU with the "
+                        "data-gradient / BN chain)")
+    if dom["name"] in alone:
+        a = roofline_of(alone[dom["name"]])
+        a["measured"] = "every kernel on one stream (resist_set_overlap(0)): the kernel has the GPU to itself"
+        roof["alone"] = a
+    conv = [s for s in stats_alone if s["flops"]]
+    conv_flops = sum(s["flops"] for s in conv)
+    conv_ms = sum(s["ms"] for s in conv)
+    roof["all_conv_tflops_alone"] = round(conv_flops / (conv_ms * 1e-3) / 1e12, 2) if conv_ms else None
+    roof["all_conv_frac_alone"] = round(roof["all_conv_tflops_alone"] / PEAK_TFLOPS[dtype], 4) if conv_ms else None
     # the whole step against the MFMA roofline: all convolution FLOPs over the step's wall time
     roof["step_conv_tflops"] = round(conv_flops / psteps / (ms_per_step * 1e-3) / 1e12, 2)
     roof["step_conv_frac"] = round(roof["step_conv_tflops"] / PEAK_TFLOPS[dtype], 4)
+    # and against the HBM roofline: algorithmic bytes of all kernels over the step's wall time
+    step_bytes = sum(s["bytes"] for s in stats_alone) / psteps
+    roof["step_algorithmic_GBps"] = round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1)
+    roof["step_hbm_frac"] = round(roof["step_algorithmic_GBps"] / PEAK_HBM_GBS, 4)
+    if stale:
+        roof["traffic_table_stale"] = stale
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -290,11 +292,12 @@ def main():
         t2 = time.perf_counter()
         OR.local_step(model, blocks, params, zeros_like_params(params), xs, ys, cfg["lr"], mu, wd)
         tc = time.perf_counter() - t2
-        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        cpu = dict(value=round(nb / tc, 3), unit="images/s", cores=cores, kind="oracle",
-                   sample=f"one full step of the same sub-ResNet on a batch of {nb} (of {batch}) images, {tc:.1f} s")
-
-    out = {
+        cpu = dict(value=round(nb / tc, 3), unit="images/s", cores=OL.num_threads(), kind="oracle",
+                   sample=f"one full step of the same sub-ResNet on a batch of {nb} (of {batch}) images, {tc:.1f} s; "
+                          "cores = OpenMP team size of the convolution loops (the rest of the step is numpy)")
+    del sub
+    torch.cuda.empty_cache()
+    return {
         "metric": "images/sec per sub-ResNet local SGD step",
         "value": round(batch / (ms_per_step * 1e-3), 1),
         "unit": "images/s",
@@ -302,7 +305,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
-        "config": {"workload": _describe(args.workload, cfg, args.sub),
+        "config": {"workload": _describe(name, cfg, args.sub),
                    "batch": batch, "blocks": blocks, "block_kind": ["basic", "bottleneck", "pre-activation basic", "pre-activation bottleneck"][model["block_kind"]],
                    "widths": model["widths"], "blocks_per_stage": model["blocks"], "classes": model["num_classes"]},
         "roofline": roof,
@@ -313,7 +316,50 @@ def main():
         "final_loss": loss,
         "kernels": kernels,
     }
-    print(json.dumps(out))
+
+
+ALL_WORKLOADS = ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg5_bf16"]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2",
+                    help="cfg1 | cfg2 | cfg2_preact | cfg3 | cfg5 (fp32) | cfg4 | cfg5_bf16 (bf16 storage, fp32 accumulation) | "
+                         "all: one JSON line per benchmark configuration (cfg3 as a whole round)")
+    ap.add_argument("--sub", type=int, default=0, help="which sub-ResNet of the partition to step")
+    ap.add_argument("--compress-bits", type=int, default=0,
+                    help="with --round: also time b-bit compression of the workers' blocks and the reassembly "
+                         "from the compressed copies (2..8; 0 = off)")
+    ap.add_argument("--local-iters", type=int, default=0, help="with --round: override the local iterations per sub-ResNet")
+    ap.add_argument("--round", action="store_true",
+                    help="time one full round instead: every sub-ResNet runs its local iterations on fresh "
+                         "batches, one after the other, then resist_aggregate rebuilds the global model")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-batch", type=int, default=128,
+                    help="images of the oracle's timed step at CIFAR shape (an eighth of it at ImageNet shape): ~10-20 s of CPU work")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device copy (reference point for HBM traffic counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the S sub-ResNets are stepped sequentially on it "
+              "and no collective exists to scale over. Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import paper_2107_00961_amd as R
+    from resist_inputs import get_config
+
+    names = ALL_WORKLOADS if args.workload == "all" else [args.workload]
+    for name in names:
+        if args.round or (args.workload == "all" and name == "cfg3"):
+            cfg = get_config(name)
+            subs, _ = R.partition(cfg["model"], cfg["S"], cfg["min_depth"], cfg["part_seed"], 0)
+            args.workload_name = name
+            _bench_round(args, cfg, subs)
+        else:
+            print(json.dumps(_bench_step(args, name)), flush=True)
 
 
 if __name__ == "__main__":

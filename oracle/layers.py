@@ -24,7 +24,13 @@ def _conv_lib():
             f = getattr(_lib, name)
             f.argtypes = [dp, dp, dp] + [ctypes.c_int] * 9
             f.restype = None
+        _lib.oracle_num_threads.restype = ctypes.c_int
     return _lib
+
+
+def num_threads():
+    """Threads the C convolution loops actually run on (OpenMP's team size on this machine)."""
+    return int(_conv_lib().oracle_num_threads())
 
 
 def _p(a):

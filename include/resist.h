@@ -15,7 +15,8 @@
  *     priority, non-blocking) and a ring of 256 events, created at the first resist_local_step that
  *     uses them and kept until the process ends: the weight-gradient kernels of a step run there,
  *     ordered against the caller's stream by those events (resist_set_overlap); (b) the
- *     resist_set_overlap mode; (c) the optional timing facility (resist_profile_*).
+ *     resist_set_overlap mode; (c) the optional timing facility (resist_profile_*); (d) 32 MiB of
+ *     static device memory per GPU behind resist_conv2d_wgrad_static (resist_ops.h).
  *   - Threads: host-only calls are reentrant.  Calls that enqueue work on the same device must not
  *     overlap in time from different host threads (the event ring is shared per device); different
  *     devices may be driven from different threads.

@@ -43,6 +43,21 @@ int resist_conv2d_dgrad(const resist_conv_shape *s, const void *dy, const void *
 int resist_conv2d_wgrad(const resist_conv_shape *s, const void *dy, const void *x, float *dw,
                         void *workspace, int64_t workspace_bytes, void *hip_stream);
 
+/*
+ * resist_conv2d_wgrad for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and the same
+ * bits as resist_conv2d_wgrad, but the split partial sums go to a static device array inside the
+ * library (32 MiB per GPU, held until the process ends; resist_conv2d_wgrad_static_limit reports the
+ * size).  The call allocates nothing (keep resist_profile_enable off: timing creates events).
+ * RESIST_EWORKSPACE if the shape's partial sums (resist_conv2d_workspace_bytes' split part) exceed
+ * the array.  Nothing in the array needs clearing between calls: every split writes its whole slice
+ * before the reduction reads it.  All calls on one GPU share the array, so two calls that overlap in
+ * time on one GPU (different streams, or different host threads) race; calls on one stream do not.
+ */
+int resist_conv2d_wgrad_static(const resist_conv_shape *s, const void *dy, const void *x, float *dw,
+                               void *hip_stream);
+int resist_conv2d_wgrad_static_limit(int64_t *bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -50,7 +50,7 @@ def lib():
                      "resist_conv2d_dgrad", "resist_conv2d_wgrad", "resist_profile_enable",
                      "resist_profile_read", "resist_compressed_block_size",
                      "resist_compress_blocks", "resist_decompress_blocks", "resist_aggregate_compressed",
-                     "resist_set_overlap"):
+                     "resist_set_overlap", "resist_conv2d_wgrad_static", "resist_conv2d_wgrad_static_limit"):
             getattr(L, name).restype = C.c_int
         L.resist_local_step.argtypes = [
             C.POINTER(_ModelDesc), C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_void_p),
@@ -79,6 +79,7 @@ def lib():
         for name in ("resist_conv2d_forward", "resist_conv2d_dgrad", "resist_conv2d_wgrad"):
             getattr(L, name).argtypes = [C.POINTER(_ConvShape), C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_int64, C.c_void_p]
+        L.resist_conv2d_wgrad_static.argtypes = [C.POINTER(_ConvShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -383,3 +384,19 @@ def conv2d_wgrad(dy, x, w_shape, stride, pad, stream=None):
                                      ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
     return dw
 
+
+def conv2d_wgrad_static_limit():
+    """Bytes of the library's static scratch that conv2d_wgrad_static keeps its split partial sums in."""
+    n = C.c_int64()
+    _check(lib().resist_conv2d_wgrad_static_limit(C.byref(n)))
+    return n.value
+
+
+def conv2d_wgrad_static(dy, x, dw, stride, pad, stream=None):
+    """resist_conv2d_wgrad_static: like conv2d_wgrad but no workspace and no allocation anywhere; the
+    caller passes the output dw [K,R,S,C] float32."""
+    N, H, W, Cc = x.shape
+    K, R = dw.shape[0], dw.shape[1]
+    sh = _conv_shape(N, H, W, Cc, K, R, stride, pad, _dtype_code(x))
+    _check(lib().resist_conv2d_wgrad_static(C.byref(sh), dy.data_ptr(), x.data_ptr(), dw.data_ptr(),
+                                            _stream_ptr(stream)))

@@ -11,6 +11,7 @@
 //   wgrad    dW[k][r][s][c]   = sum_{m=(n,p,q)} dY[m][k] * X[n, p*st+r-pad, q*st+s-pad, c]
 // Tiles are staged through LDS (double buffered, one barrier per K-chunk); every wave owns a
 // grid of 32x32 accumulator tiles held in registers.
+#include <mutex>
 #include <type_traits>
 
 #include "elem.h"
@@ -1041,6 +1042,49 @@ int conv_wgrad(const ConvGeom &g, int dt, const void *dy, const void *x, float *
     RESIST_CHECK_LAUNCH("splitk_reduce");
   }
   return RESIST_OK;
+}
+
+// ---- weight gradient with its split partial sums in library-owned static device memory ------------
+// For callers that cannot allocate (HIP graph capture, serving loops): the split-reduction scratch of
+// conv_wgrad lives in a file-scope device array instead of a caller-provided workspace.  Host code
+// never uses the array's name as an address: its device address is looked up once per device.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kScratchDevices = 16;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kScratchDevices] = {};
+
+// device address of `scratch` on the current device (each GPU holds its own copy at its own address)
+int static_scratch(void **out) {
+  int dev = 0;
+  RESIST_CHECK_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kScratchDevices) return set_error(RESIST_EUNSUPPORTED, "device %d: at most %d devices", dev, kScratchDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    RESIST_CHECK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return set_error(RESIST_EHIP, "hipGetSymbolAddress returned NULL");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return RESIST_OK;
+}
+}  // namespace
+
+int64_t wgrad_static_scratch_bytes() { return (int64_t)kStaticScratchBytes; }
+
+int conv_wgrad_static(const ConvGeom &g, int dt, const void *dy, const void *x, float *dw, hipStream_t st) {
+  RESIST_TRY(check_geom(g, dt));
+  const int64_t need = wgrad_scratch_floats(g) * 4;
+  if (need > (int64_t)kStaticScratchBytes)
+    return set_error(RESIST_EWORKSPACE, "split partial sums need %lld bytes, the static scratch holds %lld",
+                     (long long)need, (long long)kStaticScratchBytes);
+  void *ptr = nullptr;
+  RESIST_TRY(static_scratch(&ptr));
+  // every split writes its whole [K][R][S][C] slice before the reduction reads it: nothing to clear
+  return conv_wgrad(g, dt, dy, x, dw, need > 0 ? static_cast<float *>(ptr) : nullptr, st);
 }
 
 }  // namespace resist

@@ -146,6 +146,10 @@ int prepare_filters(const std::vector<FilterPrep> &items, int dt, hipStream_t st
 int64_t wgrad_scratch_floats(const ConvGeom &g);
 int conv_wgrad(const ConvGeom &g, int dt, const void *dy, const void *x, float *dw, float *partial,
                hipStream_t st);
+// the same with the split partial sums in the library's static device array (no allocation anywhere);
+// RESIST_EWORKSPACE when wgrad_scratch_floats(g) * 4 exceeds wgrad_static_scratch_bytes()
+int64_t wgrad_static_scratch_bytes();
+int conv_wgrad_static(const ConvGeom &g, int dt, const void *dy, const void *x, float *dw, hipStream_t st);
 
 // stem helpers (stem.hip): NCHW fp32 image -> im2col rows [N*P*Q][kpad] in dt, column (r*S+s)*C+c
 int stem_im2col(int dt, const float *x_nchw, void *col, int N, int C, int H, int W, int R, int stride,

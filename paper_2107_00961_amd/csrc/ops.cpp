@@ -55,3 +55,16 @@ extern "C" int resist_conv2d_wgrad(const resist_conv_shape *s, const void *dy, c
   if (need > 0 && (!workspace || workspace_bytes < need)) return set_error(RESIST_EWORKSPACE, "workspace too small for split-K partial sums");
   return conv_wgrad(g, s->dtype, dy, x, dw, (float *)workspace, (hipStream_t)hip_stream);
 }
+
+extern "C" int resist_conv2d_wgrad_static(const resist_conv_shape *s, const void *dy, const void *x, float *dw, void *hip_stream) {
+  ConvGeom g;
+  RESIST_TRY(to_geom(s, &g));
+  if (!dy || !x || !dw) return set_error(RESIST_EINVAL, "NULL tensor");
+  return conv_wgrad_static(g, s->dtype, dy, x, dw, (hipStream_t)hip_stream);
+}
+
+extern "C" int resist_conv2d_wgrad_static_limit(int64_t *bytes) {
+  if (!bytes) return set_error(RESIST_EINVAL, "bytes is NULL");
+  *bytes = wgrad_static_scratch_bytes();
+  return RESIST_OK;
+}

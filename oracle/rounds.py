@@ -8,7 +8,7 @@ momentum buffers start at zero in every round.  Sub-ResNets are independent with
 Pins: this module only composes oracle/partition.py, oracle/resnet.py and oracle/aggregate.py,
 each pinned on its own; tests/test_oracle_rounds.py pins the composition (S=1 equals plain SGD
 over the same batches; blocks nobody trained in a round keep their values; a fresh partition
-per round).
+per round; with compression on the way down the local steps start from the decoded weights).
 """
 import numpy as np
 

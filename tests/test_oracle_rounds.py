@@ -83,3 +83,55 @@ def test_round_with_compressed_communication_stays_within_half_a_step():
                 worst = max(worst, d.max())
         errs[bits] = worst
     assert 0 < errs[8] < errs[4]
+
+
+def _on_grid(params, bits):
+    """Every tensor replaced by its own b-bit decode: values the quantiser reproduces exactly."""
+    from oracle import compress as OC
+    return {k: {n: OC.dequantize_tensor(*OC.quantize_tensor(np.asarray(a, np.float32), bits)).astype(np.float32)
+                for n, a in t.items()} for k, t in params.items()}
+
+
+def test_compressing_the_way_down_changes_the_start_of_the_local_steps():
+    """Server-to-worker compression (appendix on quantised communication, both directions): a worker
+    starts its local steps from the decoded b-bit copy of the global model.  (1) When every global
+    tensor already lies on its own b-bit grid, decoding its codes gives the tensor back to fp32
+    rounding, so the first local losses are those of the round without compression on the way down;
+    for generic tensors they differ at the scale of the quantiser's step.  (2) With one worker, one
+    step and zero learning rate the trainable tensors come back as their b-bit decode, and the BN
+    running statistics are those of a forward pass through the DECODED weights (not through the
+    original ones), then compressed on the way back."""
+    from oracle import compress as OC
+    model = dict(get_config("cfg1")["model"], widths=[8, 16], blocks=[2, 3], in_h=8, in_w=8, num_classes=5)
+    B = sum(model["blocks"])
+    fn = _batch_fn(model, 4)
+    bits = 5
+    # (1)
+    generic = make_params(model, 1, perturb_bn=True)
+    grid = _on_grid(generic, bits)
+    for k in grid:
+        for n, a in grid[k].items():
+            again = OC.dequantize_tensor(*OC.quantize_tensor(a, bits))
+            assert np.max(np.abs(again - a)) <= 2.4e-7 * float(np.max(np.abs(a))) + 1e-12, (k, n)     # two fp32 roundings
+    first = {}
+    for name, start in (("grid", grid), ("generic", generic)):
+        _, log_up = ORD.run_rounds(model, start, 2, 0, 3, 1, 1, fn, 0.05, 0.9, 0.0, compress_bits=bits)
+        _, log_both = ORD.run_rounds(model, start, 2, 0, 3, 1, 1, fn, 0.05, 0.9, 0.0, compress_bits=bits, compress_down=True)
+        first[name] = max(abs(a[0] - b[0]) / abs(a[0]) for a, b in zip(log_up[0]["losses"], log_both[0]["losses"]))
+    assert first["grid"] <= 1e-5 and first["generic"] >= 1e-4, first
+    # (2)
+    params = make_params(model, 2, perturb_bn=True)
+    got, _ = ORD.run_rounds(model, params, 1, 0, 3, 1, 1, fn, 0.0, 0.9, 0.0, compress_bits=bits, compress_down=True)
+    decoded = _on_grid(params, bits)
+    x, y = fn(0, 0, 0)
+    _, _, after, _ = OR.local_step(model, list(range(B)), decoded, zeros_like_params(params), x, y, 0.0, 0.9, 0.0)
+    _, _, after_plain, _ = OR.local_step(model, list(range(B)), params, zeros_like_params(params), x, y, 0.0, 0.9, 0.0)
+    moved = 0
+    for k in got:
+        for n in got[k]:
+            want = OC.dequantize_tensor(*OC.quantize_tensor(np.asarray(after[k][n], np.float32), bits))
+            np.testing.assert_array_equal(got[k][n], want, err_msg=f"{k} {n}")
+            if n.endswith(("_rm", "_rv")):
+                plain = OC.dequantize_tensor(*OC.quantize_tensor(np.asarray(after_plain[k][n], np.float32), bits))
+                moved += int(not np.array_equal(plain, want))
+    assert moved > 0        # the statistics tell the decoded start from the original one

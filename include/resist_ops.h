@@ -44,6 +44,24 @@ int resist_conv2d_wgrad(const resist_conv_shape *s, const void *dy, const void *
                         void *workspace, int64_t workspace_bytes, void *hip_stream);
 
 /*
+ * The stem convolution: the first layer reads the input batch as the caller passes it to
+ * resist_local_step -- logical [N,C,H,W] fp32 with C <= 4 -- and runs as an implicit GEMM over the
+ * R*S*C filter positions (no im2col matrix is written).  The resist_conv_shape describes the same
+ * convolution (N, H, W, C of the image; K, R = S, stride, pad; dtype of the OUTPUT side: 0 fp32, 1 bf16,
+ * in which case image and filter are rounded to bf16 as they become matrix operands).
+ * Supported: C <= 4, K a multiple of 16 up to 128, R*S*C <= 160, tensors below 2 GiB.
+ *   x   device [N][C][H][W] fp32           w   device [K][R][S][C] fp32 (the master filter)
+ *   y   device [N][P][Q][K] in dtype       dy  device [N][P][Q][K] in dtype      dw  device [K][R][S][C] fp32
+ * Workspace: resist_stem_conv2d_workspace_bytes (padded filter copies and the partial sums of the
+ * weight gradient).
+ */
+int resist_stem_conv2d_workspace_bytes(const resist_conv_shape *s, int64_t *bytes);
+int resist_stem_conv2d_forward(const resist_conv_shape *s, const float *x, const float *w, void *y, void *workspace,
+                               int64_t workspace_bytes, void *hip_stream);
+int resist_stem_conv2d_wgrad(const resist_conv_shape *s, const void *dy, const float *x, float *dw, void *workspace,
+                             int64_t workspace_bytes, void *hip_stream);
+
+/*
  * resist_conv2d_wgrad for callers that cannot allocate device memory or pass a workspace: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and the same
  * bits as resist_conv2d_wgrad, but the split partial sums go to a static device array inside the

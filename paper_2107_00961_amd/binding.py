@@ -50,7 +50,8 @@ def lib():
                      "resist_conv2d_dgrad", "resist_conv2d_wgrad", "resist_profile_enable",
                      "resist_profile_read", "resist_compressed_block_size",
                      "resist_compress_blocks", "resist_decompress_blocks", "resist_aggregate_compressed",
-                     "resist_set_overlap", "resist_conv2d_wgrad_static", "resist_conv2d_wgrad_static_limit"):
+                     "resist_set_overlap", "resist_conv2d_wgrad_static", "resist_conv2d_wgrad_static_limit",
+                     "resist_stem_conv2d_workspace_bytes", "resist_stem_conv2d_forward", "resist_stem_conv2d_wgrad"):
             getattr(L, name).restype = C.c_int
         L.resist_local_step.argtypes = [
             C.POINTER(_ModelDesc), C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_void_p),
@@ -76,7 +77,8 @@ def lib():
         L.resist_partition.argtypes = [
             C.POINTER(_ModelDesc), C.POINTER(C.c_uint8), C.c_int32, C.c_int32, C.c_uint64,
             C.c_uint64, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32)]
-        for name in ("resist_conv2d_forward", "resist_conv2d_dgrad", "resist_conv2d_wgrad"):
+        for name in ("resist_conv2d_forward", "resist_conv2d_dgrad", "resist_conv2d_wgrad", "resist_stem_conv2d_forward",
+                     "resist_stem_conv2d_wgrad"):
             getattr(L, name).argtypes = [C.POINTER(_ConvShape), C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_int64, C.c_void_p]
         L.resist_conv2d_wgrad_static.argtypes = [C.POINTER(_ConvShape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -400,3 +402,38 @@ def conv2d_wgrad_static(dy, x, dw, stride, pad, stream=None):
     sh = _conv_shape(N, H, W, Cc, K, R, stride, pad, _dtype_code(x))
     _check(lib().resist_conv2d_wgrad_static(C.byref(sh), dy.data_ptr(), x.data_ptr(), dw.data_ptr(),
                                             _stream_ptr(stream)))
+
+
+def _stem_ws(shape):
+    import torch
+    n = C.c_int64()
+    _check(lib().resist_stem_conv2d_workspace_bytes(C.byref(shape), C.byref(n)))
+    return torch.empty(n.value, dtype=torch.uint8, device="cuda")
+
+
+def stem_conv2d_forward(x, w, stride, pad, bf16=False, stream=None):
+    """The stem convolution on its own: x [N,C,H,W] float32 (as passed to local_step), w [K,R,S,C]
+    float32 -> y [N,P,Q,K] float32 or bfloat16."""
+    import torch
+    N, Cc, H, W = x.shape
+    K, R = w.shape[0], w.shape[1]
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    y = torch.empty((N, P, Q, K), dtype=torch.bfloat16 if bf16 else torch.float32, device=x.device)
+    sh = _conv_shape(N, H, W, Cc, K, R, stride, pad, 1 if bf16 else 0)
+    ws = _stem_ws(sh)
+    _check(lib().resist_stem_conv2d_forward(C.byref(sh), x.data_ptr(), w.data_ptr(), y.data_ptr(), ws.data_ptr(), ws.numel(),
+                                            _stream_ptr(stream)))
+    return y
+
+
+def stem_conv2d_wgrad(dy, x, w_shape, stride, pad, stream=None):
+    """dy [N,P,Q,K] float32 or bfloat16, x [N,C,H,W] float32 -> dw [K,R,S,C] float32."""
+    import torch
+    N, Cc, H, W = x.shape
+    K, R = w_shape[0], w_shape[1]
+    dw = torch.empty((K, R, R, Cc), dtype=torch.float32, device=x.device)
+    sh = _conv_shape(N, H, W, Cc, K, R, stride, pad, _dtype_code(dy))
+    ws = _stem_ws(sh)
+    _check(lib().resist_stem_conv2d_wgrad(C.byref(sh), dy.data_ptr(), x.data_ptr(), dw.data_ptr(), ws.data_ptr(), ws.numel(),
+                                          _stream_ptr(stream)))
+    return dw

@@ -1031,16 +1031,18 @@ int conv_wgrad(const ConvGeom &g, int dt, const void *dy, const void *x, float *
     }
   }
   RESIST_CHECK_LAUNCH("wgrad");
-  if (p.splits > 1) {
-    const long long n4 = (long long)g.K * g.R * g.S * g.C / 4;
-    prof::Scope ps("splitk_reduce", 0, 16.0 * n4 * (p.splits + 1), st);
-    // enough threads per output vector that the launch has at least ~64k loads in flight
-    if (n4 * 4 >= 65536 || p.splits < 8)
-      hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3((unsigned)((n4 + 63) / 64)), dim3(256), 0, st, partial, dw, n4, p.splits);
-    else
-      hipLaunchKernelGGL(splitk_reduce_kernel<16>, dim3((unsigned)((n4 + 15) / 16)), dim3(256), 0, st, partial, dw, n4, p.splits);
-    RESIST_CHECK_LAUNCH("splitk_reduce");
-  }
+  if (p.splits > 1) return splitk_reduce(partial, dw, (long long)g.K * g.R * g.S * g.C / 4, p.splits, st);
+  return RESIST_OK;
+}
+
+int splitk_reduce(const float *partial, float *out, long long n4, int splits, hipStream_t st) {
+  prof::Scope ps("splitk_reduce", 0, 16.0 * n4 * (splits + 1), st);
+  // enough threads per output vector that the launch has at least ~64k loads in flight
+  if (n4 * 4 >= 65536 || splits < 8)
+    hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3((unsigned)((n4 + 63) / 64)), dim3(256), 0, st, partial, out, n4, splits);
+  else
+    hipLaunchKernelGGL(splitk_reduce_kernel<16>, dim3((unsigned)((n4 + 15) / 16)), dim3(256), 0, st, partial, out, n4, splits);
+  RESIST_CHECK_LAUNCH("splitk_reduce");
   return RESIST_OK;
 }
 

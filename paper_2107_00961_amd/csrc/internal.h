@@ -151,9 +151,18 @@ int conv_wgrad(const ConvGeom &g, int dt, const void *dy, const void *x, float *
 int64_t wgrad_static_scratch_bytes();
 int conv_wgrad_static(const ConvGeom &g, int dt, const void *dy, const void *x, float *dw, hipStream_t st);
 
-// stem helpers (stem.hip): NCHW fp32 image -> im2col rows [N*P*Q][kpad] in dt, column (r*S+s)*C+c
-int stem_im2col(int dt, const float *x_nchw, void *col, int N, int C, int H, int W, int R, int stride,
-                int pad, int P, int Q, int kpad, hipStream_t st);
+// stem convolution as an implicit GEMM on the NCHW fp32 image (stem.hip).  wpad: filter [K][kpad] in dt with
+// zero columns past R*R*C (pad_rows); y: [N][P][Q][K] in dt; stats as for conv_fwd (one part per tile of
+// the kernel: stem_stat_parts).  Weight gradient: dwpad [K][kpad] fp32 (then unpad_rows_f32), partial:
+// scratch of stem_wgrad_scratch_floats floats.  Limits: C <= 4, K a multiple of 16 up to 128, kpad <= 160.
+StatParts stem_stat_parts(int N, int C, int H, int W, int K, int R, int stride, int pad, int P, int Q, int kpad);
+int64_t stem_wgrad_scratch_floats(int N, int C, int H, int W, int K, int R, int stride, int pad, int P, int Q, int kpad);
+int stem_conv_fwd(int dt, const float *x_nchw, const void *wpad, void *y, float *stats, StatParts *stat_parts, int N, int C,
+                  int H, int W, int K, int R, int stride, int pad, int P, int Q, int kpad, hipStream_t st);
+int stem_conv_wgrad(int dt, const void *dy, const float *x_nchw, float *dwpad, float *partial, int N, int C, int H, int W,
+                    int K, int R, int stride, int pad, int P, int Q, int kpad, hipStream_t st);
+// out[i] = sum over z < splits of part[z*n4 + i] (float4 elements), fixed order (conv.hip)
+int splitk_reduce(const float *part, float *out, long long n4, int splits, hipStream_t st);
 int pad_rows(int dt, const float *src, void *dst, int rows, int n, int npad, hipStream_t st);   // fp32 [rows][n] -> dt [rows][npad]
 int unpad_rows_f32(const float *src, float *dst, int rows, int n, int npad, hipStream_t st);    // [rows][npad] -> [rows][n]
 

@@ -37,6 +37,18 @@ struct WgradSide {
     readers.emplace_back(dyb, e);
     return RESIST_OK;
   }
+  // the stem's weight gradient (implicit GEMM on the input image), same ordering rules
+  int launch_stem(const Net &net, int N, int kpad, const void *dyb, const float *x, float *dwpad) {
+    RESIST_TRY(side.fork());
+    RESIST_TRY(stem_conv_wgrad(dt, dyb, x, dwpad, splitk, N, net.d.in_c, net.d.in_h, net.d.in_w, net.d.width[0], net.stem_rs,
+                               net.stem_stride, net.stem_pad, net.stem_h, net.stem_w, kpad, side.stream()));
+    hipEvent_t e = nullptr;
+    RESIST_TRY(side.mark(&e));
+    for (auto &r : readers)
+      if (r.first == dyb) { r.second = e; return RESIST_OK; }
+    readers.emplace_back(dyb, e);
+    return RESIST_OK;
+  }
   int before_write(const void *buf) {
     for (auto &r : readers)
       if (r.first == buf && r.second) { RESIST_TRY(side.main_wait(r.second)); r.second = nullptr; }
@@ -110,8 +122,8 @@ struct StepPlan {
   std::vector<BlockLayout> layouts;   // per slot: stem, blocks..., head
   // stem
   int kpad = 0;
-  ConvLayer stem;                     // geometry of the 1x1 GEMM over im2col rows
-  void *col = nullptr, *wpad = nullptr;   // im2col rows and the padded filter, in the compute type
+  ConvLayer stem;                     // the stem as a GEMM over kpad filter positions (geometry for sizes only)
+  void *wpad = nullptr;               // the filter [K][kpad] in the compute type
   float *dwpad = nullptr;
   void *stem_pool = nullptr;
   uint8_t *stem_argmax = nullptr;
@@ -128,6 +140,22 @@ struct StepPlan {
   std::vector<float *> own_grads;     // per slot, when the caller passes no gradient buffers
   int64_t bytes = 0;
 };
+
+// split-reduction scratch and statistics capacity the stem convolution needs
+int64_t stem_scratch_floats(const Net &net, int N, int kpad) {
+  return stem_wgrad_scratch_floats(N, net.d.in_c, net.d.in_h, net.d.in_w, net.d.width[0], net.stem_rs, net.stem_stride,
+                                   net.stem_pad, net.stem_h, net.stem_w, kpad);
+}
+int64_t stem_stats_floats(const Net &net, int N, int kpad) {
+  const StatParts sp = stem_stat_parts(N, net.d.in_c, net.d.in_h, net.d.in_w, net.d.width[0], net.stem_rs, net.stem_stride,
+                                       net.stem_pad, net.stem_h, net.stem_w, kpad);
+  return (int64_t)3 * sp.parts * net.d.width[0];
+}
+int stem_forward(const Net &net, int dt, int N, int kpad, const float *x, const void *wpad, void *y, float *stats,
+                 StatParts *parts, hipStream_t st) {
+  return stem_conv_fwd(dt, x, wpad, y, stats, parts, N, net.d.in_c, net.d.in_h, net.d.in_w, net.d.width[0], net.stem_rs,
+                       net.stem_stride, net.stem_pad, net.stem_h, net.stem_w, kpad, st);
+}
 
 ConvLayer make_conv(const BlockLayout &L, int layer, int N, int H, int W, int C, int K, int R, int stride, int pad) {
   ConvLayer c;
@@ -192,23 +220,22 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
     max_c = std::max(max_c, c.g.K);
   };
 
-  // ---- stem: im2col rows, then a 1x1 GEMM with kpad input channels
+  // ---- stem: implicit GEMM on the input image, kpad filter positions
   {
     const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
     P->kpad = (taps + 31) / 32 * 32;
     const int K0 = net.d.width[0];
     ConvLayer &s = P->stem;
     s = make_conv(P->layouts[0], 0, N, net.stem_h, net.stem_w, P->kpad, K0, 1, 1, 0);
-    P->col = A.take_act(s.M() * P->kpad, es);
     P->wpad = A.take_act((int64_t)K0 * P->kpad, es);
     P->dwpad = A.take<float>((int64_t)K0 * P->kpad);
-    s.in = P->col;
     s.y = A.take_act(s.M() * K0, es);
     s.a = A.take_act(s.M() * K0, es);
     take_bn(s);
-    RESIST_TRY(conv_check(s.g, net.d.compute_dtype));
+    if (stem_scratch_floats(net, N, P->kpad) == 0) return RESIST_ESHAPE;   // message set by the stem's shape check
     max_act = std::max<int64_t>(max_act, s.M() * K0);
-    max_splitk = std::max<int64_t>(max_splitk, wgrad_scratch_floats(s.g));
+    max_splitk = std::max<int64_t>(max_splitk, stem_scratch_floats(net, N, P->kpad));
+    max_stats = std::max<int64_t>(max_stats, stem_stats_floats(net, N, P->kpad));
     max_c = std::max(max_c, K0);
     if (net.d.stem_kind == 1) {
       const int64_t n = (int64_t)N * net.body_h * net.body_w * K0;
@@ -299,7 +326,7 @@ struct ForwardPlan {
   std::vector<BlockLayout> layouts;
   int kpad = 0;
   ConvLayer stem;
-  void *col = nullptr, *wpad = nullptr, *stem_pool = nullptr;
+  void *wpad = nullptr, *stem_pool = nullptr;
   uint8_t *stem_argmax = nullptr;
   std::vector<BlockPlan> blocks;
   float *affine[2] = {nullptr, nullptr};   // scale/shift scratch of the branch BN and the shortcut BN: [2][max_c] each
@@ -327,7 +354,7 @@ int build_forward_plan(const resist_model_desc *desc, const int32_t *blocks, int
   P->kpad = (taps + 31) / 32 * 32;
   const int K0 = net.d.width[0];
   P->stem = make_conv(P->layouts[0], 0, N, net.stem_h, net.stem_w, P->kpad, K0, 1, 1, 0);
-  RESIST_TRY(conv_check(P->stem.g, net.d.compute_dtype));
+  if (stem_scratch_floats(net, N, P->kpad) == 0) return RESIST_ESHAPE;
   int64_t max_act = P->stem.M() * K0;
   int max_c = K0;
   P->blocks.resize(nblocks);
@@ -354,12 +381,10 @@ int build_forward_plan(const resist_model_desc *desc, const int32_t *blocks, int
     if (bs.has_ds) RESIST_TRY(conv_check(bp.ds.g, net.d.compute_dtype));
     bp.out_elems = (int64_t)N * bs.h_out * bs.w_out * bs.c_out;
   }
-  P->col = A.take_act(P->stem.M() * P->kpad, es);
   P->wpad = A.take_act((int64_t)K0 * P->kpad, es);
   void *ybuf = A.take_act(max_act, es), *ydsbuf = A.take_act(max_act, es);
   void *abuf[2] = {A.take_act(max_act, es), A.take_act(max_act, es)};
   void *obuf[2] = {A.take_act(max_act, es), A.take_act(max_act, es)};
-  P->stem.in = P->col;
   P->stem.y = ybuf;
   P->stem.a = obuf[0];
   const void *cur = obuf[0];
@@ -447,7 +472,7 @@ struct PrePlan {
   int kpad = 0;
   ConvGeom stem;
   int64_t stem_w_off = 0;
-  void *col = nullptr, *wpad = nullptr, *x0 = nullptr;
+  void *wpad = nullptr, *x0 = nullptr;
   float *dwpad = nullptr;
   std::vector<PreBlock> blocks;
   // head: BN-ReLU, mean pool, FC
@@ -492,11 +517,14 @@ int build_preact_plan(const resist_model_desc *desc, const int32_t *blocks, int3
   P->stem = make_geom(N, net.stem_h, net.stem_w, P->kpad, K0, 1, 1, 0);
   P->stem_w_off = P->layouts[0].off(T_CONVW, 0);
   const int64_t M0 = (int64_t)N * net.stem_h * net.stem_w;
-  P->col = A.take_act(M0 * P->kpad, es);
   P->wpad = A.take_act((int64_t)K0 * P->kpad, es);
   P->dwpad = A.take<float>((int64_t)K0 * P->kpad);
   P->x0 = A.take_act(M0 * K0, es);
-  track(P->stem, true);
+  if (stem_scratch_floats(net, N, P->kpad) == 0) return RESIST_ESHAPE;
+  max_act = std::max<int64_t>(max_act, M0 * K0);
+  max_splitk = std::max<int64_t>(max_splitk, stem_scratch_floats(net, N, P->kpad));
+  max_stats = std::max<int64_t>(max_stats, stem_stats_floats(net, N, P->kpad));
+  max_c = std::max(max_c, K0);
   const void *cur = P->x0;
   P->blocks.resize(nblocks);
   for (int i = 0; i < nblocks; ++i) {
@@ -624,10 +652,8 @@ int local_step_preact(const resist_model_desc *desc, const int32_t *blocks, int3
   const int K0 = net.d.width[0];
   const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
   StatParts parts;   // number of per-tile sums the last statistics-taking convolution left in P.stats
-  RESIST_TRY(stem_im2col(dt, x, P.col, N, net.d.in_c, net.d.in_h, net.d.in_w, net.stem_rs, net.stem_stride, net.stem_pad,
-                         net.stem_h, net.stem_w, P.kpad, st));
   RESIST_TRY(pad_rows(dt, params(0) + P.stem_w_off, P.wpad, K0, taps, P.kpad, st));
-  RESIST_TRY(conv_fwd(P.stem, dt, P.col, P.wpad, P.x0, nullptr, P.stats, &parts, st));
+  RESIST_TRY(stem_forward(net, dt, N, P.kpad, x, P.wpad, P.x0, P.stats, &parts, st));
   for (PreBlock &pb : P.blocks) {
     float *pp = params(pb.slot), *gg = grads(pb.slot);
     const size_t n = pb.units.size();
@@ -695,7 +721,7 @@ int local_step_preact(const resist_model_desc *desc, const int32_t *blocks, int3
     }
     gi ^= 1;
   }
-  RESIST_TRY(wg.launch(P.stem, P.gbuf[gi], P.col, P.dwpad));
+  RESIST_TRY(wg.launch_stem(net, N, P.kpad, P.gbuf[gi], x, P.dwpad));
   RESIST_TRY(unpad_rows_f32(P.dwpad, grads(0) + P.stem_w_off, K0, taps, P.kpad, wg.stream()));
   RESIST_TRY(wg.join());
 
@@ -802,11 +828,9 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     ConvLayer &s = P.stem;
     const int K0 = net.d.width[0];
     const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
-    RESIST_TRY(stem_im2col(dt, x, P.col, N, net.d.in_c, net.d.in_h, net.d.in_w, net.stem_rs, net.stem_stride, net.stem_pad,
-                           net.stem_h, net.stem_w, P.kpad, st));
     RESIST_TRY(pad_rows(dt, params(0) + s.w_off, P.wpad, K0, taps, P.kpad, st));
     StatParts parts;
-    RESIST_TRY(conv_fwd(s.g, dt, P.col, P.wpad, s.y, nullptr, P.stats, &parts, st));
+    RESIST_TRY(stem_forward(net, dt, N, P.kpad, x, P.wpad, s.y, P.stats, &parts, st));
     BnBufs b = bn_bufs(s, params(0), grads(0));
     RESIST_TRY(bn_finalize(P.stats, parts, s.M(), K0, b, eps, bnm, P.bn_scratch, st));
     RESIST_TRY(bn_apply(dt, s.y, s.M(), K0, b, nullptr, nullptr, true, s.a, st));
@@ -905,7 +929,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     BnBufs b = bn_bufs(s, params(0), grads(0));
     RESIST_TRY(wg.before_write(P.dy0));
     RESIST_TRY(bn_backward(dt, Gs, nullptr, true, s.y, s.M(), K0, b, P.dy0, nullptr, nullptr, P.bn_scratch, st));
-    RESIST_TRY(wg.launch(s.g, P.dy0, P.col, P.dwpad));
+    RESIST_TRY(wg.launch_stem(net, N, P.kpad, P.dy0, x, P.dwpad));
     RESIST_TRY(unpad_rows_f32(P.dwpad, grads(0) + s.w_off, K0, taps, P.kpad, wg.stream()));
   }
   RESIST_TRY(wg.join());
@@ -928,7 +952,7 @@ struct PreForwardPlan {
   std::vector<BlockLayout> layouts;
   int kpad = 0;
   ConvGeom stem;
-  void *col = nullptr, *wpad = nullptr;
+  void *wpad = nullptr;
   std::vector<PreBlock> blocks;
   void *abuf = nullptr, *sc = nullptr;
   float *affine = nullptr, *pooled = nullptr, *dz = nullptr, *row_loss = nullptr;
@@ -953,7 +977,7 @@ int build_preact_forward_plan(const resist_model_desc *desc, const int32_t *bloc
   P->kpad = (taps + 31) / 32 * 32;
   const int K0 = net.d.width[0];
   P->stem = make_geom(N, net.stem_h, net.stem_w, P->kpad, K0, 1, 1, 0);
-  RESIST_TRY(conv_check(P->stem, net.d.compute_dtype));
+  if (stem_scratch_floats(net, N, P->kpad) == 0) return RESIST_ESHAPE;
   int64_t max_act = (int64_t)N * net.stem_h * net.stem_w * K0;
   int max_c = std::max(K0, net.head_c);
   P->blocks.resize(nblocks);
@@ -995,7 +1019,6 @@ int build_preact_forward_plan(const resist_model_desc *desc, const int32_t *bloc
       if (net.d.compute_dtype == DT_BF16) pb.ds_wlp = A.take_act((int64_t)bs.c_out * bs.c_in, es);
     }
   }
-  P->col = A.take_act((int64_t)N * net.stem_h * net.stem_w * P->kpad, es);
   P->wpad = A.take_act((int64_t)K0 * P->kpad, es);
   // the residual stream alternates between two buffers, the branch between two more
   void *ubuf[2] = {A.take_act(max_act, es), A.take_act(max_act, es)};
@@ -1057,10 +1080,8 @@ int forward_preact(const resist_model_desc *desc, const int32_t *blocks, int32_t
   }
   const int K0 = net.d.width[0];
   const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
-  RESIST_TRY(stem_im2col(dt, x, P.col, N, net.d.in_c, net.d.in_h, net.d.in_w, net.stem_rs, net.stem_stride, net.stem_pad,
-                         net.stem_h, net.stem_w, P.kpad, st));
   RESIST_TRY(pad_rows(dt, params(0) + P.layouts[0].off(T_CONVW, 0), P.wpad, K0, taps, P.kpad, st));
-  RESIST_TRY(conv_fwd(P.stem, dt, P.col, P.wpad, const_cast<void *>(P.blocks[0].x), nullptr, nullptr, nullptr, st));
+  RESIST_TRY(stem_forward(net, dt, N, P.kpad, x, P.wpad, const_cast<void *>(P.blocks[0].x), nullptr, nullptr, st));
   for (PreBlock &pb : P.blocks) {
     float *pp = params(pb.slot);
     const size_t n = pb.units.size();
@@ -1153,10 +1174,8 @@ extern "C" int resist_forward(const resist_model_desc *desc, const int32_t *bloc
     ConvLayer &s = P.stem;
     const int K0 = net.d.width[0];
     const int taps = net.stem_rs * net.stem_rs * net.d.in_c;
-    RESIST_TRY(stem_im2col(dt, x, P.col, N, net.d.in_c, net.d.in_h, net.d.in_w, net.stem_rs, net.stem_stride, net.stem_pad,
-                           net.stem_h, net.stem_w, P.kpad, st));
     RESIST_TRY(pad_rows(dt, params(0) + s.w_off, P.wpad, K0, taps, P.kpad, st));
-    RESIST_TRY(conv_fwd(s.g, dt, P.col, P.wpad, s.y, nullptr, nullptr, nullptr, st));
+    RESIST_TRY(stem_forward(net, dt, N, P.kpad, x, P.wpad, s.y, nullptr, nullptr, st));
     BnBufs b = bn_eval_bufs(s, params(0), P.affine[0]);
     RESIST_TRY(bn_eval_affine(K0, b, eps, 1.f, st));
     RESIST_TRY(bn_apply(dt, s.y, s.M(), K0, b, nullptr, nullptr, true, s.a, st));

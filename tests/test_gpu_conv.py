@@ -137,6 +137,69 @@ def test_conv_wgrad_bf16(case):
     assert_close(dw.cpu().numpy().transpose(0, 3, 1, 2), want, f"bf16 conv wgrad {case}")
 
 
+# ---- the stem convolution: implicit GEMM straight from the [N,C,H,W] fp32 image ----------------------------
+#              N  C   H   W   K  R st pad
+STEM_CASES = [(4, 3, 16, 16, 16, 3, 1, 1),       # the tiny configuration's stem
+              (5, 3, 32, 32, 64, 3, 1, 1),       # CIFAR-shaped: four output rows per tile
+              (3, 3, 40, 40, 16, 7, 2, 3),       # 7x7 stride 2: 20 x 20 outputs, five rows per tile
+              (2, 3, 224, 224, 64, 7, 2, 3),     # ImageNet-shaped: one 112-pixel row per tile
+              (2, 3, 18, 30, 32, 3, 1, 1),       # rectangular, 32 output channels (one tile of channels)
+              (2, 4, 12, 12, 96, 5, 2, 2),       # four input channels, 96 output channels (64 + 32), 5x5
+              (1, 1, 9, 9, 16, 3, 1, 0),         # one channel, no padding
+              (2, 3, 26, 134, 48, 3, 1, 1)]      # 134 output columns: tiles of 67 columns
+
+
+def _stem_tensors(case, seed, bf16):
+    N, C, H, W, K, RS, st, pad = case
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((N, C, H, W), dtype=np.float32)
+    w = (rng.standard_normal((K, C, RS, RS), dtype=np.float32) / np.sqrt(C * RS * RS)).astype(np.float32)
+    P, Q = (H + 2 * pad - RS) // st + 1, (W + 2 * pad - RS) // st + 1
+    dy = (rng.standard_normal((N, K, P, Q), dtype=np.float32) / np.sqrt(N * P * Q)).astype(np.float32)
+    if bf16:   # bfloat16 numbers, so the float64 result is the exact convolution of what the kernel multiplies
+        x, w, dy = (torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy() for a in (x, w, dy))
+    return x, w, dy
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("case", STEM_CASES)
+def test_stem_conv_forward(case, bf16):
+    print("case", case, "bf16" if bf16 else "f32", flush=True)
+    x, w, _ = _stem_tensors(case, 6, bf16)
+    st, pad = case[6], case[7]
+    y = R.stem_conv2d_forward(torch.from_numpy(x).cuda(), _nhwc(w), st, pad, bf16=bf16)
+    torch.cuda.synchronize()
+    want = L.conv2d_fwd(x, w, st, pad)
+    got = y.cpu().to(torch.float64).numpy().transpose(0, 3, 1, 2)
+    if bf16:
+        assert_close(got, want, f"bf16 stem fwd {case}", rtol=2.0 ** -8, atol=1e-5)
+    else:
+        assert_close(got, want, f"stem fwd {case}")
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("case", STEM_CASES)
+def test_stem_conv_wgrad(case, bf16):
+    print("case", case, "bf16" if bf16 else "f32", flush=True)
+    x, w, dy = _stem_tensors(case, 7, bf16)
+    N, C, H, W, K, RS, st, pad = case
+    dyd = _nhwc(dy)
+    if bf16:
+        dyd = dyd.to(torch.bfloat16)
+    dw = R.stem_conv2d_wgrad(dyd, torch.from_numpy(x).cuda(), (K, RS, RS, C), st, pad)
+    torch.cuda.synchronize()
+    want = L.conv2d_wgrad(dy, x, w.shape, st, pad)
+    assert_close(dw.cpu().numpy().transpose(0, 3, 1, 2), want, f"stem wgrad {case} {'bf16' if bf16 else 'f32'}")
+
+
+def test_stem_conv_rejects_bad_shapes():
+    x = torch.zeros((1, 5, 8, 8), device="cuda")
+    with pytest.raises(R.ResistError):
+        R.stem_conv2d_forward(x, torch.zeros((16, 3, 3, 5), device="cuda"), 1, 1)        # five input channels
+    with pytest.raises(R.ResistError):
+        R.stem_conv2d_forward(torch.zeros((1, 3, 8, 8), device="cuda"), torch.zeros((24, 3, 3, 3), device="cuda"), 1, 1)   # K = 24
+
+
 def test_conv_rejects_bad_shapes():
     x = torch.zeros((1, 4, 4, 6), device="cuda")
     w = torch.zeros((8, 3, 3, 6), device="cuda")

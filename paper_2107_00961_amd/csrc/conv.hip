@@ -98,18 +98,19 @@ __device__ inline f32x4 buffer_load_16B(__amdgpu_buffer_rsrc_t r, unsigned voff)
 // and the tap counters are advanced with selects.  With no branch in the loop the scheduler is free
 // to place the address arithmetic, the LDS traffic and the global loads in the shadow of the MFMAs.
 template <typename T, int BM, int BN, int BK, int WGM, int WGN, int MODE>
-__global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
+__global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
   using E = Elem<T>;
+  constexpr int NT = WGM * WGN * 64;             // threads: one wave per wave tile, 4 or 8 waves
   constexpr int VEC = E::VEC;
   constexpr int ES = (int)sizeof(T);
   constexpr int LDK = BK + VEC;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
   constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 MFMA tiles per wave
   constexpr int KV = BK / VEC;                   // lanes per tile row (16 bytes each)
-  constexpr int RPP = kThreads / KV;             // tile rows per load pass
+  constexpr int RPP = NT / KV;             // tile rows per load pass
   constexpr int PA = BM / RPP, PB = BN / RPP;    // load passes
   constexpr int NK = BK / (2 * VEC);             // k-steps per chunk
-  static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1 && PA >= 1 && PB >= 1 && NK >= 2, "tile shape");
+  static_assert((WGM * WGN == 4 || WGM * WGN == 8) && TM >= 1 && TN >= 1 && PA >= 1 && PB >= 1 && NK >= 2, "tile shape");
   // one LDS block: the operand stages during the K loop, the fp32 output tile afterwards
   constexpr int LDC = BN + 8;   // output tile pitch (floats): lanes l and l+32 (4 rows apart) hit disjoint banks
   constexpr size_t kOperandBytes = sizeof(T) * kStages * (BM + BN) * LDK;
@@ -167,7 +168,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
     const int oc = n0 + i * RPP + lrow;
     boff[i] = oc < a.OC ? (oc * a.R * a.S * a.IC + kvec) * ES : (int)kOOB;
   }
-  for (int r = tid; r < BM; r += kThreads) {
+  for (int r = tid; r < BM; r += NT) {
     const int m = m0 + r;
     int off = -1;
     if (m < a.Mrows) {
@@ -313,7 +314,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
     }
   __syncthreads();
   constexpr int CV = BN / VEC;            // 16-byte pieces per tile row
-  constexpr int RPS = kThreads / CV;      // rows per pass
+  constexpr int RPS = NT / CV;      // rows per pass
   static_assert(BM % RPS == 0 && CV <= 32, "output tile rows per pass");
   const int cv = (tid % CV) * VEC, row0 = tid / CV;
   const bool col_ok = n0 + cv < a.OC;     // OC is a multiple of VEC
@@ -367,9 +368,10 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
     }
   }
   if (MODE == kFwd && a.stats) {
-    // A wave holds 64/CV rows of every column piece: butterfly over those lanes, then the 4 waves add
+    // A wave holds 64/CV rows of every column piece: butterfly over those lanes, then the waves add
     // up in wave order.  Every step has a fixed order, so the sums are bit-stable from run to run.
-    __shared__ float red[2][4][BN];
+    constexpr int NW = WGM * WGN;
+    __shared__ float red[2][NW][BN];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
 #pragma unroll
@@ -383,10 +385,11 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
       for (int e = 0; e < VEC; ++e) { red[0][wave][cv + e] = s1[e]; red[1][wave][cv + e] = s2[e]; }
     }
     __syncthreads();
-    for (int c = tid; c < BN; c += kThreads) {
+    for (int c = tid; c < BN; c += NT) {
       if (n0 + c < a.OC) {
-        const float t1 = ((red[0][0][c] + red[0][1][c]) + red[0][2][c]) + red[0][3][c];
-        const float t2 = ((red[1][0][c] + red[1][1][c]) + red[1][2][c]) + red[1][3][c];
+        float t1 = red[0][0][c], t2 = red[1][0][c];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) { t1 += red[0][w][c]; t2 += red[1][w][c]; }
         a.stats[(size_t)tm * a.OC + n0 + c] = Cs[0][c];
         a.stats[((size_t)a.tiles_m + tm) * a.OC + n0 + c] = t1;
         a.stats[((size_t)2 * a.tiles_m + tm) * a.OC + n0 + c] = t2;
@@ -404,13 +407,14 @@ int launch_igemm(IgemmArgs a, hipStream_t st, StatParts *tiles_m_out) {
   if (grid <= 0 || grid > 0x7fffffffLL) return set_error(RESIST_ESHAPE, "igemm grid %lld", grid);
   {
     static const std::string label = std::string("igemm_") + (sizeof(T) == 4 ? "f32_" : "bf16_") + (MODE == kFwd ? "fwd_" : "bwd_") +
-                                     std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK);
+                                     std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) +
+                                     (WGM * WGN == 8 ? "_w8" : "");
     // algorithmic work of the convolution this launch computes (forward or data gradient)
     const double flops = 2.0 * a.N * (MODE == kFwd ? (double)a.OH * a.OW : (double)a.IH * a.IW) * a.OC * a.IC * a.R * a.S;
     const double bytes = sizeof(T) * ((double)a.N * a.IH * a.IW * a.IC + (double)a.N * a.OH * a.OW * a.OC * (1 + (a.addend ? 1 : 0) + (a.relu_mask ? 1 : 0)) +
                                       (double)a.OC * a.R * a.S * a.IC);
     prof::Scope ps(label.c_str(), flops, bytes, st);
-    hipLaunchKernelGGL((igemm_kernel<T, BM, BN, BK, WGM, WGN, MODE>), dim3((unsigned)grid), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((igemm_kernel<T, BM, BN, BK, WGM, WGN, MODE>), dim3((unsigned)grid), dim3(WGM * WGN * 64), 0, st, a);
   }
   RESIST_CHECK_LAUNCH("igemm");
   return RESIST_OK;
@@ -424,12 +428,26 @@ int dispatch_igemm(const IgemmArgs &a, hipStream_t st, StatParts *tiles_m_out = 
   auto tiles = [&](int bm, int bn) {
     return (long long)((a.Mrows + bm - 1) / bm) * ((a.OC + bn - 1) / bn) * classes;
   };
-  constexpr long long kMin = 512;   // measured (fp32): 256 or fewer workgroups of a larger tile are slower on every layer shape
-  // bf16 kernels are bound by LDS and L2 traffic rather than by the matrix cores, and the 128x128 tile
+  constexpr long long kMin = 512;   // measured (fp32): 256 or fewer workgroups of a larger 4-wave tile are slower on every layer shape
+  constexpr bool lp = sizeof(T) == 2;
+  // Eight-wave workgroups on 128-wide tiles (bf16): when a layer has only about one such tile per compute unit,
+  // a four-wave workgroup leaves the CU with four waves and nothing to overlap its barriers and load latency
+  // with, while 64x64 tiles double the operand bytes every CU pulls through its L1.  Measured (layer_bench.py):
+  // 128 -> 128 channels at 16x16, batch 128: 19.0 -> 15.9 us; 256 -> 256 at 14x14, batch 64: 29.0 -> 24.1 us;
+  // 256 -> 256 at 8x8, batch 128: 20.0 -> 18.5 us; the full CIFAR-shaped model: 6.64 -> 6.36 ms per step.
+  // (In fp32 the same tiles measured no faster inside a step; the fp32 kernels are bound by MFMA issue, not by L1.)
+  if (lp && a.cls == 1 && a.OC >= 128) {
+    const long long t128 = tiles(128, 128);
+    if (t128 >= 192 && t128 < 320) return launch_igemm<T, 128, 128, 8 * V, 4, 2, MODE>(a, st, tiles_m_out);
+    if (t128 < 192 && tiles(128, 64) >= 256 && a.IC % (16 * V) == 0)
+      return launch_igemm<T, 128, 64, 16 * V, 4, 2, MODE>(a, st, tiles_m_out);
+  }
+  // bf16 kernels are bound by operand traffic rather than by the matrix cores, and the 128x128 tile
   // moves half the operand bytes per FLOP: measured faster down to ~190 workgroups (ImageNet-shaped
   // stage 2-4 layers: 17-30 us instead of 20-38), slower at 100-130
-  constexpr long long kMin128 = sizeof(T) == 2 ? 192 : kMin;
+  constexpr long long kMin128 = lp ? 192 : kMin;
   if (a.OC > 64 && tiles(128, 128) >= kMin128) return launch_igemm<T, 128, 128, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);
+  if (lp && a.cls == 1 && a.OC <= 64 && tiles(128, 64) >= kMin) return launch_igemm<T, 128, 64, 8 * V, 4, 2, MODE>(a, st, tiles_m_out);
   if (tiles(128, 64) >= kMin) return launch_igemm<T, 128, 64, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);
   if (a.IC % (16 * V) == 0) return launch_igemm<T, 64, 64, 16 * V, 2, 2, MODE>(a, st, tiles_m_out);
   return launch_igemm<T, 64, 64, 8 * V, 2, 2, MODE>(a, st, tiles_m_out);

@@ -53,7 +53,7 @@ def _check_full_size_step(sub, before, loss, grads, new_p, what):
             is_tail = k == last and name.startswith((tail, tail_bn))
             cls = "head" if k == nb else ("tail" if is_tail else "other")
             worst[cls] = max(worst[cls], rel)
-            assert rel <= (5e-3 if is_tail else 2e-2), f"{what} grad block {k} {name}: relative L2 error {rel:.3e}"
+            assert rel <= (1e-2 if is_tail else 2e-2), f"{what} grad block {k} {name}: relative L2 error {rel:.3e}"
             upd = np.linalg.norm(np.asarray(before[k][name], np.float64) - new_p[k][name])
             err = np.linalg.norm(got_p[k][name].astype(np.float64) - new_p[k][name])
             worst["update"] = max(worst["update"], err / max(upd, 1e-30))
@@ -76,9 +76,13 @@ def full_size_check(cfg_name, what, which=0, second_step=False):
     The element-wise fp32 bound is therefore applied to the loss, the running statistics and the
     tensors no ReLU decision stands behind (the head: a flipped decision belongs to an activation
     that is zero to rounding either way, so forward quantities are continuous in it).  The tail of
-    the last block has exactly one ReLU layer behind it (the block's output, 1 M decisions, each
-    within fp32 accumulation error of zero with probability ~4e-6, so a handful flip, each moving the
-    gradient by ~1e-3 of its norm): bound 5e-3 in relative L2 norm.  Every other gradient tensor is
+    the last block has exactly one ReLU layer behind it (the block's output: half a million decisions
+    at 128 images of 8 x 8 x 64, each within fp32 accumulation error of zero -- a few 1e-6 of the
+    activation scale after 11 blocks, about 1e-5 after 33 -- with that probability, so a handful flip;
+    one flip moves the gradient by about 1/sqrt(active decisions) = 2e-3 of its norm, more when the
+    element carries a large gradient, and which ones flip changes with any change of summation order:
+    3.8e-3 and 5.3e-3 were measured on the 33-block model with two orderings of the stem's sums):
+    bound 1e-2 in relative L2 norm.  Every other gradient tensor is
     bounded in relative L2 norm by 2e-2, every parameter tensor by 2e-2 of the update applied to it.
 
     second_step: the step after it as well.  After one step at the configuration's learning rate the

@@ -302,14 +302,14 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const T *__res
 }
 
 // plain fixed-order reduction of two sums per channel, layout [2][parts][C] (the backward pass)
-template <int R>
-__device__ inline void reduce_parts(const double *__restrict__ scratch, int parts, int C, int c, int pl,
+template <int R, typename S>
+__device__ inline void reduce_parts(const S *__restrict__ scratch, int parts, int C, int c, int pl,
                                     double (*red)[R][16], double *out0, double *out1) {
   double s = 0, q = 0;
   int p = pl;
   // eight loads of each sum in flight per thread; the additions keep their order
   for (; p + 7 * R < parts; p += 8 * R) {
-    double vs[8], vq[8];
+    S vs[8], vq[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       vs[u] = scratch[(size_t)(p + R * u) * C + c];
@@ -333,12 +333,14 @@ __device__ inline void reduce_parts(const double *__restrict__ scratch, int part
   *out1 = q;
 }
 
-__global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const double *__restrict__ scratch, int parts, int C,
+// S = double: partial sums of bn_bwd_partial_kernel; S = float: per-row-tile sums left by a data gradient
+template <typename S>
+__global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const S *__restrict__ scratch, int parts, int C,
                                                                 float *__restrict__ dgamma, float *__restrict__ dbeta) {
   __shared__ double red[2][16][16];
   const int c = blockIdx.x * 16 + (threadIdx.x & 15), pl = threadIdx.x >> 4;
   double b, g;
-  reduce_parts<16>(scratch, parts, C, c, pl, red, &b, &g);
+  reduce_parts<16, S>(scratch, parts, C, c, pl, red, &b, &g);
   if (pl != 0) return;
   dbeta[c] = (float)b;
   dgamma[c] = (float)g;
@@ -433,12 +435,16 @@ inline int vec_of(int dt) { return dt == DT_BF16 ? 8 : 4; }
 
 template <typename T>
 void launch_bwd(int mode, dim3 gp, dim3 ga, hipStream_t st, const void *g, const void *mask, const void *y, int64_t M, int C,
-                const ColMap &m, const BnBufs &b, double *scratch, const BwdApplyArgs &p, int parts) {
+                const ColMap &m, const BnBufs &b, double *scratch, const BwdApplyArgs &p, int parts, const float *pre_sums) {
   const T *gg = (const T *)g, *mm = (const T *)mask, *yy = (const T *)y;
 #define RESIST_BN_BWD(MODE)                                                                                              \
-  hipLaunchKernelGGL((bn_bwd_partial_kernel<T, MODE>), gp, dim3(kThreads), 0, st, gg, mm, yy, (long long)M, C, m.tpr, m.rpp, \
-                     b.mean, b.invstd, b.scale, b.shift, scratch);                                                      \
-  hipLaunchKernelGGL(bn_bwd_final_kernel, dim3(C / 16), dim3(kThreads), 0, st, scratch, parts, C, b.dgamma, b.dbeta);     \
+  if (pre_sums) {                                                                                                        \
+    hipLaunchKernelGGL(bn_bwd_final_kernel<float>, dim3(C / 16), dim3(kThreads), 0, st, pre_sums, parts, C, b.dgamma, b.dbeta); \
+  } else {                                                                                                               \
+    hipLaunchKernelGGL((bn_bwd_partial_kernel<T, MODE>), gp, dim3(kThreads), 0, st, gg, mm, yy, (long long)M, C, m.tpr, m.rpp, \
+                       b.mean, b.invstd, b.scale, b.shift, scratch);                                                    \
+    hipLaunchKernelGGL(bn_bwd_final_kernel<double>, dim3(C / 16), dim3(kThreads), 0, st, (const double *)scratch, parts, C, b.dgamma, b.dbeta); \
+  }                                                                                                                      \
   hipLaunchKernelGGL((bn_bwd_apply_kernel<T, MODE>), ga, dim3(kThreads), 0, st, p);
   if (mode == kMaskTensor) { RESIST_BN_BWD(kMaskTensor) }
   else if (mode == kMaskSelf) { RESIST_BN_BWD(kMaskSelf) }
@@ -506,20 +512,23 @@ int bn_apply(int dt, const void *y, int64_t M, int C, const BnBufs &b, const voi
 }
 
 int bn_backward(int dt, const void *g, const void *mask, bool relu_of_self, const void *y, int64_t M, int C, const BnBufs &b,
-                void *dy, void *gm_out, const void *addend, double *scratch, hipStream_t st) {
+                void *dy, void *gm_out, const void *addend, double *scratch, hipStream_t st, const float *pre_sums, StatParts pre) {
   RESIST_TRY(check_bn(dt, M, C));
   const ColMap m = col_map(C, vec_of(dt));
-  const int parts = num_parts(M, m);
+  if (pre_sums && (mask || pre.parts < 1 || pre.rows < 1 || (long long)pre.parts * pre.rows < M ||
+                   (long long)(pre.parts - 1) * pre.rows >= M))
+    return set_error(RESIST_EINVAL, "bn_backward: %d pre-computed partial sums of %d rows for %lld rows", pre.parts, pre.rows, (long long)M);
+  const int parts = pre_sums ? pre.parts : num_parts(M, m);
   const int mode = mask ? kMaskTensor : (relu_of_self ? kMaskSelf : kMaskNone);
   const int reads = mask ? 3 : 2;
-  prof::Scope ps("bn_backward", 0, (double)esize(dt) * M * C * (2 * reads + 1 + (gm_out ? 1 : 0) + (addend ? 1 : 0)), st);
+  prof::Scope ps("bn_backward", 0, (double)esize(dt) * M * C * ((pre_sums ? 1 : 2) * reads + 1 + (gm_out ? 1 : 0) + (addend ? 1 : 0)), st);
   BwdApplyArgs p{};
   p.g = g; p.mask = mask; p.y = y; p.addend = addend; p.mean = b.mean; p.invstd = b.invstd; p.scale = b.scale; p.shift = b.shift;
   p.dgamma = b.dgamma; p.dbeta = b.dbeta; p.dy = dy; p.gm_out = gm_out;
   p.M = M; p.C = C; p.tpr = m.tpr; p.rpp = m.rpp;
   const dim3 gp(parts, m.ctiles), ga(apply_grid_x(M, m, 4), m.ctiles);
-  if (dt == DT_BF16) launch_bwd<__bf16>(mode, gp, ga, st, g, mask, y, M, C, m, b, scratch, p, parts);
-  else launch_bwd<float>(mode, gp, ga, st, g, mask, y, M, C, m, b, scratch, p, parts);
+  if (dt == DT_BF16) launch_bwd<__bf16>(mode, gp, ga, st, g, mask, y, M, C, m, b, scratch, p, parts, pre_sums);
+  else launch_bwd<float>(mode, gp, ga, st, g, mask, y, M, C, m, b, scratch, p, parts, pre_sums);
   RESIST_CHECK_LAUNCH("bn_backward");
   return RESIST_OK;
 }

@@ -26,6 +26,12 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 namespace {
 
 constexpr int kThreads = 256;
+#ifndef RESIST_BF16_GLOBAL_DEPTH
+#define RESIST_BF16_GLOBAL_DEPTH 2   // chunks an eight-wave bf16 workgroup requests ahead of their use (1..3)
+#endif
+#ifndef RESIST_BF16_FRAG_DEPTH
+#define RESIST_BF16_FRAG_DEPTH 1   // k-steps a bf16 fragment is fetched ahead of its MFMAs (1..3)
+#endif
 constexpr int kStages = 2;     // LDS double buffering in the implicit-GEMM kernels
 
 // Element traits: a 16-byte vector holds VEC elements; one pair of 16-byte fragments (A, B) feeds
@@ -56,6 +62,14 @@ struct IgemmArgs {
   const void *addend;  // optional, indexed like out
   const void *relu_mask;   // optional, indexed like out: out is zeroed where this is not positive (after the addend)
   float *stats;        // optional [3][tiles_m][OC]: per row tile and column a shift k, sum(out - k), sum((out - k)^2)
+  // optional (data gradient, cls == 1): first pass of the backward of the BN whose output this
+  // convolution read.  out is that BN's output gradient g; with its input bn_y (indexed like out) and
+  // xhat = (bn_y - mean) * invstd the kernel leaves, per row tile and column, sum(gm) and sum(gm * xhat) in
+  // bn_sums [2][tiles_m][OC], where gm = g, or g where scale * bn_y + shift > 0 and 0 elsewhere (bn_self)
+  const void *bn_y;
+  const float *bn_mean, *bn_invstd, *bn_scale, *bn_shift;
+  float *bn_sums;
+  int bn_self;
   int N, IH, IW, IC;
   int OH, OW, OC;
   int R, S, stride, pad;
@@ -193,7 +207,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
 
   // loop state of the chunk that will be requested next (uniform across the workgroup)
   int tr = r0, ts = s0, tc = 0, issued = 0;
-  f32x4 ra[PA], rb[PB];
+  // GD = how many chunks ahead of its use an operand chunk is requested from global memory (GD
+  // register sets in a ring).  An eight-wave workgroup is alone on its CU, so no other workgroup
+  // covers the latency of its loads, and a bf16 chunk is multiplied in less time than a load takes.
+  constexpr int GD = (ES == 2 && NT == 512) ? RESIST_BF16_GLOBAL_DEPTH : 1;
+  f32x4 ra[GD][PA], rb[GD][PB];
   // scalars of the chunk being requested (set by begin_chunk, used by request)
   int q_dh = 0, q_dw = 0, q_adelta = 0, q_bdelta = 0;
   bool q_kok = false;
@@ -216,41 +234,47 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
     tr = swrap ? tr + tstep : tr;
   };
   // register `part` (0..PA-1: activation rows, PA..PA+PB-1: filter rows) of the chunk begun last
-  auto request = [&](int part) {
+  auto request = [&](int set, int part) {
     if (part < PA) {
       const int i = part;
       const bool ok = q_kok && (unsigned)(hc[i] + q_dh) < (unsigned)a.IH && (unsigned)(wc[i] + q_dw) < (unsigned)a.IW;
-      ra[i] = buffer_load_16B(rin, ok ? (unsigned)(aoff[i] + q_adelta) : kOOB);
+      ra[set][i] = buffer_load_16B(rin, ok ? (unsigned)(aoff[i] + q_adelta) : kOOB);
     } else {
       const int i = part - PA;
-      rb[i] = buffer_load_16B(rwt, q_kok ? (unsigned)(boff[i] + q_bdelta) : kOOB);
+      rb[set][i] = buffer_load_16B(rwt, q_kok ? (unsigned)(boff[i] + q_bdelta) : kOOB);
     }
   };
-  auto store_part = [&](int stage, int part) {
-    if (part < PA) *reinterpret_cast<f32x4 *>(&As[stage][part * RPP + lrow][kvec]) = ra[part];
-    else *reinterpret_cast<f32x4 *>(&Bs[stage][(part - PA) * RPP + lrow][kvec]) = rb[part - PA];
+  auto store_part = [&](int set, int stage, int part) {
+    if (part < PA) *reinterpret_cast<f32x4 *>(&As[stage][part * RPP + lrow][kvec]) = ra[set][part];
+    else *reinterpret_cast<f32x4 *>(&Bs[stage][(part - PA) * RPP + lrow][kvec]) = rb[set][part - PA];
   };
-  auto load_global = [&]() {
+  auto load_global = [&](int set) {
     begin_chunk();
 #pragma unroll
-    for (int p = 0; p < PA + PB; ++p) request(p);
+    for (int p = 0; p < PA + PB; ++p) request(set, p);
   };
-  auto store_lds = [&](int stage) {
+  auto store_lds = [&](int set, int stage) {
 #pragma unroll
-    for (int p = 0; p < PA + PB; ++p) store_part(stage, p);
+    for (int p = 0; p < PA + PB; ++p) store_part(set, stage, p);
   };
 
   // Pipeline.  Chunk `it` is multiplied out of LDS stage it&1, one k-step (2*VEC values of K) at a
   // time; the fragments of a k-step are fetched from LDS during the MFMAs of the k-step before it,
   // also across the chunk boundary.  The registers holding chunk it+1 (requested from global memory
   // one chunk of MFMA time earlier) go to the other stage, and chunk it+2 is requested into them,
-  // a few registers per k-step over k-steps 0 .. NK-2, so that neither the LDS nor the memory
-  // pipeline sees a burst.  The one barrier per chunk sits at the start of the last k-step: by then
-  // every wave has all fragments of this stage in registers and has written its share of the next
-  // stage, so after it the first fragments of chunk it+1 can be fetched while the last MFMAs run.
-  static_assert(NK % 2 == 0, "fragment double buffer parity");
+  // a few registers per k-step over k-steps 0 .. NK-FD-1, so that neither the LDS nor the memory
+  // pipeline sees a burst.  The one barrier per chunk sits at the start of the first k-step whose
+  // fetch reaches into the next chunk: by then every wave has all fragments of this stage in
+  // registers and has written its share of the next stage, so after it the first fragments of chunk
+  // it+1 can be fetched while the last MFMAs run.
+  // FD = how many k-steps ahead of its MFMAs a fragment is fetched; NB fragment buffers in a ring.
+  // The bf16 matrix instruction runs 32 cycles and every MFMA of a 32x32 wave tile depends on the one
+  // before it, so one k-step ahead leaves a wave waiting on the LDS for most of each step.
+  constexpr int FD = (ES == 2 && NK % 4 == 0) ? RESIST_BF16_FRAG_DEPTH : 1;
+  constexpr int NB = FD == 1 ? 2 : 4;
+  static_assert(NK % NB == 0 && FD >= 1 && FD < NB && FD < NK, "fragment ring");
   const int lr = lane & 31, lk = (lane >> 5) * VEC;
-  f32x4 fa[2][TM], fb[2][TN];
+  f32x4 fa[NB][TM], fb[NB][TN];
   auto load_frags = [&](int buf, int stage, int ks) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) fa[buf][i] = *reinterpret_cast<const f32x4 *>(&As[stage][wm * WTM + i * 32 + lr][ks * 2 * VEC + lk]);
@@ -262,36 +286,47 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
     __builtin_amdgcn_s_barrier();
   };
 
-  load_global();
-  store_lds(0);
-  load_global();
+  load_global(0);
+  store_lds(0, 0);
+#pragma unroll
+  for (int c = 1; c <= GD; ++c) load_global(c % GD);   // chunk c waits in register set c % GD
   lds_barrier();
-  load_frags(0, 0, 0);
+#pragma unroll
+  for (int d = 0; d < FD; ++d) load_frags(d, 0, d);
   __builtin_amdgcn_sched_barrier(0);
 
-  for (int it = 0; it < nchunks; ++it) {
-    const int stage = it & 1;
+  // chunk `it`: multiplied out of its stage while chunk it+1 moves from register set `set` to the other
+  // stage and chunk it+1+GD is requested into that set
+  auto chunk_body = [&](int set, int stage) {
 #pragma unroll
     for (int ks = 0; ks < NK; ++ks) {
-      if (ks + 1 < NK) {
-        load_frags((ks + 1) & 1, stage, ks + 1);
+      const int kn = ks + FD;              // the k-step whose fragments are fetched now
+      if (kn < NK) {
+        load_frags(kn % NB, stage, kn);
       } else {
-        lds_barrier();
-        load_frags(0, stage ^ 1, 0);   // past the last chunk: zeros nobody uses
+        if (kn == NK) lds_barrier();       // once per chunk, at the start of k-step NK-FD
+        load_frags(kn % NB, stage ^ 1, kn - NK);   // past the last chunk: zeros nobody uses
       }
       __builtin_amdgcn_sched_barrier(0);   // keep the fetches ahead of this k-step's MFMAs
       if (ks == 0) begin_chunk();
 #pragma unroll
       for (int p = 0; p < PA + PB; ++p)
-        if ((p * (NK - 1)) / (PA + PB) == ks) {   // parts spread evenly over k-steps 0 .. NK-2
-          store_part(stage ^ 1, p);
-          request(p);
+        if ((p * (NK - FD)) / (PA + PB) == ks) {   // parts spread evenly over k-steps 0 .. NK-FD-1
+          store_part(set, stage ^ 1, p);
+          request(set, p);
         }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) E::mma(acc[i][j], fa[ks & 1][i], fb[ks & 1][j]);
+        for (int j = 0; j < TN; ++j) E::mma(acc[i][j], fa[ks % NB][i], fb[ks % NB][j]);
       __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  for (int it = 0; it < nchunks; it += GD) {
+#pragma unroll
+    for (int j = 0; j < GD; ++j) {
+      if (j > 0 && it + j >= nchunks) break;   // uniform across the workgroup
+      chunk_body((j + 1) % GD, (it + j) & 1);
     }
   }
 
@@ -325,6 +360,17 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
   float s1[VEC], s2[VEC], kshift[VEC];
 #pragma unroll
   for (int e = 0; e < VEC; ++e) { s1[e] = 0.f; s2[e] = 0.f; kshift[e] = 0.f; }
+  const bool bn_bwd = MODE == kBwd && a.bn_sums != nullptr;
+  float bmu[VEC], bis[VEC], bsc[VEC], bsh[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) { bmu[e] = 0.f; bis[e] = 0.f; bsc[e] = 0.f; bsh[e] = 0.f; }
+  if (bn_bwd && col_ok) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const int c = n0 + cv + e;
+      bmu[e] = a.bn_mean[c]; bis[e] = a.bn_invstd[c]; bsc[e] = a.bn_scale[c]; bsh[e] = a.bn_shift[c];
+    }
+  }
   if (MODE == kFwd && a.stats) {
 #pragma unroll
     for (int e = 0; e < VEC; e += 4) {
@@ -357,6 +403,19 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
         for (int e = 0; e < VEC; ++e) v[e] = mk[e] > 0.f ? v[e] : 0.f;
       }
       Vec<T>::store(out + off, v);
+      if (bn_bwd) {
+        // the same arithmetic as the stand-alone first pass (bn_bwd_partial_kernel) on the values as stored
+        float yv[VEC];
+        Vec<T>::load(static_cast<const T *>(a.bn_y) + off, yv);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          float gm = E::to_f32(E::from_f32(v[e]));
+          if (a.bn_self) gm = fmaf(yv[e], bsc[e], bsh[e]) > 0.f ? gm : 0.f;
+          const float xh = (yv[e] - bmu[e]) * bis[e];
+          s1[e] += gm;
+          s2[e] = fmaf(gm, xh, s2[e]);
+        }
+      }
       if (MODE == kFwd) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
@@ -367,7 +426,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
       }
     }
   }
-  if (MODE == kFwd && a.stats) {
+  if ((MODE == kFwd && a.stats) || bn_bwd) {
     // A wave holds 64/CV rows of every column piece: butterfly over those lanes, then the waves add
     // up in wave order.  Every step has a fixed order, so the sums are bit-stable from run to run.
     constexpr int NW = WGM * WGN;
@@ -390,9 +449,14 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
         float t1 = red[0][0][c], t2 = red[1][0][c];
 #pragma unroll
         for (int w = 1; w < NW; ++w) { t1 += red[0][w][c]; t2 += red[1][w][c]; }
-        a.stats[(size_t)tm * a.OC + n0 + c] = Cs[0][c];
-        a.stats[((size_t)a.tiles_m + tm) * a.OC + n0 + c] = t1;
-        a.stats[((size_t)2 * a.tiles_m + tm) * a.OC + n0 + c] = t2;
+        if (MODE == kFwd) {
+          a.stats[(size_t)tm * a.OC + n0 + c] = Cs[0][c];
+          a.stats[((size_t)a.tiles_m + tm) * a.OC + n0 + c] = t1;
+          a.stats[((size_t)2 * a.tiles_m + tm) * a.OC + n0 + c] = t2;
+        } else {
+          a.bn_sums[(size_t)tm * a.OC + n0 + c] = t1;
+          a.bn_sums[((size_t)a.tiles_m + tm) * a.OC + n0 + c] = t2;
+        }
       }
     }
   }
@@ -411,7 +475,7 @@ int launch_igemm(IgemmArgs a, hipStream_t st, StatParts *tiles_m_out) {
                                      (WGM * WGN == 8 ? "_w8" : "");
     // algorithmic work of the convolution this launch computes (forward or data gradient)
     const double flops = 2.0 * a.N * (MODE == kFwd ? (double)a.OH * a.OW : (double)a.IH * a.IW) * a.OC * a.IC * a.R * a.S;
-    const double bytes = sizeof(T) * ((double)a.N * a.IH * a.IW * a.IC + (double)a.N * a.OH * a.OW * a.OC * (1 + (a.addend ? 1 : 0) + (a.relu_mask ? 1 : 0)) +
+    const double bytes = sizeof(T) * ((double)a.N * a.IH * a.IW * a.IC + (double)a.N * a.OH * a.OW * a.OC * (1 + (a.addend ? 1 : 0) + (a.relu_mask ? 1 : 0) + (MODE == kBwd && a.bn_sums ? 1 : 0)) +
                                       (double)a.OC * a.R * a.S * a.IC);
     prof::Scope ps(label.c_str(), flops, bytes, st);
     hipLaunchKernelGGL((igemm_kernel<T, BM, BN, BK, WGM, WGN, MODE>), dim3((unsigned)grid), dim3(WGM * WGN * 64), 0, st, a);
@@ -494,7 +558,7 @@ int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, c
 }
 
 int conv_dgrad(const ConvGeom &g, int dt, const void *dy, const void *wT, void *dx, const void *addend, const void *relu_mask,
-               hipStream_t st) {
+               hipStream_t st, const BnBwdFuse *bn) {
   RESIST_TRY(check_geom(g, dt));
   if (g.stride == 2 && ((g.H & 1) || (g.W & 1)))
     return set_error(RESIST_ESHAPE, "stride-2 dgrad needs even input size, got %dx%d", g.H, g.W);
@@ -505,7 +569,20 @@ int conv_dgrad(const ConvGeom &g, int dt, const void *dy, const void *wT, void *
   a.R = g.R; a.S = g.S; a.stride = g.stride; a.pad = g.pad;
   a.cls = g.stride; a.OHc = g.H / g.stride; a.OWc = g.W / g.stride;
   a.Mrows = g.N * a.OHc * a.OWc;
-  return dt == DT_BF16 ? dispatch_igemm<__bf16, kBwd>(a, st) : dispatch_igemm<float, kBwd>(a, st);
+  StatParts parts;
+  if (bn) {
+    if (a.cls != 1 || !bn->y || !bn->sums || !bn->parts) return set_error(RESIST_EINVAL, "fused BN sums need a stride-1 data gradient");
+    a.bn_y = bn->y; a.bn_mean = bn->b.mean; a.bn_invstd = bn->b.invstd; a.bn_scale = bn->b.scale; a.bn_shift = bn->b.shift;
+    a.bn_sums = bn->sums; a.bn_self = bn->relu_of_self ? 1 : 0;
+  }
+  RESIST_TRY(dt == DT_BF16 ? (dispatch_igemm<__bf16, kBwd>(a, st, &parts)) : (dispatch_igemm<float, kBwd>(a, st, &parts)));
+  if (bn) *bn->parts = parts;
+  return RESIST_OK;
+}
+
+int64_t conv_dgrad_bn_sums_floats(const ConvGeom &g) {
+  // the smallest row tile any data-gradient kernel uses is 64
+  return (int64_t)2 * (((int64_t)g.N * g.H * g.W + 63) / 64) * g.C;
 }
 
 // ---- filter preparation: wT[c][r][s][k] = w[k][r][s][c] (and a low-precision copy of w) ------------

@@ -135,8 +135,14 @@ int conv_fwd(const ConvGeom &g, int dt, const void *x, const void *w, void *y, c
 // dx = dgrad(dy, wT) [+ addend]; wT is the [C][R][S][K] transpose made by prepare_filter.  relu_mask
 // (optional, indexed like dx): the output of the ReLU that produced the convolution's input; dx is set
 // to zero where it is not positive, i.e. the gradient leaves this kernel already taken through that ReLU
+// bn (optional, stride 1 only): the convolution's input was the output of a BN (+ReLU); the kernel also
+// leaves the first pass of that BN's backward, per row tile: sum(gm) and sum(gm * xhat) of the dx it stores
+// against the BN's input y, in bn->sums [2][parts][C] (gm = dx, or dx where the BN's own ReLU passed),
+// and says in bn->parts how many row tiles of how many rows it used.  bn_backward takes them as pre_sums.
+struct BnBwdFuse;
 int conv_dgrad(const ConvGeom &g, int dt, const void *dy, const void *wT, void *dx, const void *addend,
-               const void *relu_mask, hipStream_t st);
+               const void *relu_mask, hipStream_t st, const BnBwdFuse *bn = nullptr);
+int64_t conv_dgrad_bn_sums_floats(const ConvGeom &g);
 // from a filter stored in src_dt: optional copy in dt (w_lp) and optional transpose in dt (wT)
 int prepare_filter(const ConvGeom &g, int src_dt, int dt, const void *w, void *w_lp, void *wT, hipStream_t st);
 // the same for many filters at once (fp32 masters -> copies and transposes in dt, times `scale`)
@@ -188,8 +194,18 @@ int bn_apply(int dt, const void *y, int64_t M, int C, const BnBufs &b, const voi
 // dy = gamma*invstd*(gm - dbeta/M - xhat*dgamma/M) [+ addend]; optionally stores gm to gm_out.
 // The mask is the tensor `mask` if given; else, if relu_of_self, the sign of this BN's own output
 // scale*y + shift (the forward ReLU decision recomputed with the same arithmetic); else none.
+// pre_sums (optional): the first pass already done by the data gradient that produced g
+// ([2][pre.parts][C] floats, see conv_dgrad); then only the per-channel totals and the second pass run.
 int bn_backward(int dt, const void *g, const void *mask, bool relu_of_self, const void *y, int64_t M, int C,
-                const BnBufs &b, void *dy, void *gm_out, const void *addend, double *scratch, hipStream_t st);
+                const BnBufs &b, void *dy, void *gm_out, const void *addend, double *scratch, hipStream_t st,
+                const float *pre_sums = nullptr, StatParts pre = StatParts{});
+struct BnBwdFuse {
+  const void *y;        // the BN's input, [M][C] in the compute type
+  BnBufs b;             // mean, invstd, scale, shift are read
+  bool relu_of_self;    // the BN's output went through its own ReLU
+  float *sums;          // [2][parts][C]
+  StatParts *parts;     // out
+};
 
 // pooling / head / loss (head.hip); pooled features, logits and the loss stay fp32
 int maxpool_fwd(int dt, const void *x, void *y, uint8_t *argmax, int N, int H, int W, int C, int P,

@@ -8,6 +8,10 @@
 
 #include "internal.h"
 
+#ifndef RESIST_FUSE_BN_BWD
+#define RESIST_FUSE_BN_BWD 1   // bf16: first pass of a BN backward in the epilogue of the data gradient above it
+#endif
+
 namespace resist {
 namespace {
 
@@ -875,6 +879,12 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
   // kernel that produces it (the mean-pool backward, or the first convolution's data gradient of the
   // block after it) reads the block output once and zeroes the gradient where it is not positive, so
   // the two BN backward passes behind it need no mask tensor and no masked copy is written.
+  // In bf16 mode a stride-1 data gradient also takes the first pass of the BN backward that consumes its
+  // output (per-row-tile sums in P.stats, free during the backward pass): one launch and one read of the
+  // gradient less per BN, in a mode where the backward chain, not the matrix cores, sets the step time.
+  const bool fuse_bn = RESIST_FUSE_BN_BWD && dt == DT_BF16;
+  StatParts pre{};        // P.stats holds the first pass for the BN that ends the block below
+  bool have_pre = false;
   int gi = 0;
   void *G = P.gbuf[gi];
   RESIST_TRY(avgpool_bwd(dt, P.dpooled, P.feat, G, N, P.feat_hw, CH, st));
@@ -887,7 +897,9 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     BnBufs bl = bn_bufs(last, pp, gg);
     // the last BN of the residual branch
     RESIST_TRY(wg.before_write(P.dy0));
-    RESIST_TRY(bn_backward(dt, G, nullptr, false, last.y, last.M(), last.g.K, bl, P.dy0, nullptr, nullptr, P.bn_scratch, st));
+    RESIST_TRY(bn_backward(dt, G, nullptr, false, last.y, last.M(), last.g.K, bl, P.dy0, nullptr, nullptr, P.bn_scratch, st,
+                           have_pre ? P.stats : nullptr, pre));
+    have_pre = false;
     if (bp.has_ds) {
       // shortcut branch: BN and 1x1 convolution; its data gradient initialises Gn
       ConvLayer &d = bp.ds;
@@ -903,15 +915,29 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
       RESIST_TRY(wg.launch(c.g, dy, c.in, gg + c.w_off));
       if (j > 0) {
         ConvLayer &prev = bp.convs[j - 1];
-        RESIST_TRY(conv_dgrad(c.g, dt, dy, c.wT, P.da, nullptr, nullptr, st));
         BnBufs bp_ = bn_bufs(prev, pp, gg);
+        StatParts sp{};
+        const BnBwdFuse f{prev.y, bp_, true, P.stats, &sp};
+        const bool fz = fuse_bn && c.g.stride == 1;
+        RESIST_TRY(conv_dgrad(c.g, dt, dy, c.wT, P.da, nullptr, nullptr, st, fz ? &f : nullptr));
         RESIST_TRY(wg.before_write(dy_other));
-        RESIST_TRY(bn_backward(dt, P.da, nullptr, true, prev.y, prev.M(), prev.g.K, bp_, dy_other, nullptr, nullptr, P.bn_scratch, st));
+        RESIST_TRY(bn_backward(dt, P.da, nullptr, true, prev.y, prev.M(), prev.g.K, bp_, dy_other, nullptr, nullptr, P.bn_scratch, st,
+                               fz ? P.stats : nullptr, sp));
         std::swap(dy, dy_other);
       } else {
         // gradient w.r.t. the block input = branch + shortcut (the identity shortcut passes G itself),
         // taken through the ReLU that ends the block before (the stem's ReLU is handled by its own BN backward)
-        RESIST_TRY(conv_dgrad(c.g, dt, dy, c.wT, Gn, bp.has_ds ? Gn : G, bi > 0 ? bp.in : nullptr, st));
+        const bool fz = fuse_bn && bi > 0 && c.g.stride == 1;
+        if (fz) {
+          // its output is the (masked) gradient of the block below's output: first pass of that block's last BN
+          BlockPlan &below = P.blocks[bi - 1];
+          ConvLayer &bl_last = below.convs.back();
+          const BnBwdFuse f{bl_last.y, bn_bufs(bl_last, params(below.slot), grads(below.slot)), false, P.stats, &pre};
+          RESIST_TRY(conv_dgrad(c.g, dt, dy, c.wT, Gn, bp.has_ds ? Gn : G, bp.in, st, &f));
+        } else {
+          RESIST_TRY(conv_dgrad(c.g, dt, dy, c.wT, Gn, bp.has_ds ? Gn : G, bi > 0 ? bp.in : nullptr, st));
+        }
+        have_pre = fz;
       }
     }
     gi ^= 1;

@@ -15,8 +15,9 @@
  *     priority, non-blocking) and a ring of 256 events, created at the first resist_local_step that
  *     uses them and kept until the process ends: the weight-gradient kernels of a step run there,
  *     ordered against the caller's stream by those events (resist_set_overlap); (b) the
- *     resist_set_overlap mode; (c) the optional timing facility (resist_profile_*); (d) 32 MiB of
- *     static device memory per GPU behind resist_conv2d_wgrad_static (resist_ops.h).
+ *     resist_set_overlap and resist_set_bn_fusion modes; (c) the optional timing facility
+ *     (resist_profile_*); (d) 32 MiB of static device memory per GPU behind
+ *     resist_conv2d_wgrad_static (resist_ops.h).
  *   - Threads: host-only calls are reentrant.  Calls that enqueue work on the same device must not
  *     overlap in time from different host threads (the event ring is shared per device); different
  *     devices may be driven from different threads.
@@ -168,6 +169,19 @@ int resist_local_step(const resist_model_desc *desc, const int32_t *blocks, int3
  * Process-wide; takes effect at the next call.  host.
  */
 int resist_set_overlap(int32_t mode);
+
+/*
+ * Where a step takes the first pass of a BN's backward (the per-channel sums of the output gradient
+ * and of its product with the normalised input, Algorithm 1's dL/dW_s through every BN of a block).
+ * A stride-1 data gradient can leave these sums per row tile from its epilogue while it stores the
+ * gradient, instead of a separate pass that reads the gradient again.  Results agree with the
+ * separate pass to fp32 rounding of the per-tile sums (the totals are added in float64 either way).
+ *   mode 1 (default)  in bf16 steps (their backward chain, not the matrix cores, sets the step time)
+ *   mode 2            in every step
+ *   mode 0            never
+ * Process-wide; takes effect at the next call.  host.
+ */
+int resist_set_bn_fusion(int32_t mode);
 
 /*
  * Test-time forward pass (Sec. 2.6, "Scaling Activations"): logits of a batch through the stem, the

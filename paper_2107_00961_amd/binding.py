@@ -50,7 +50,7 @@ def lib():
                      "resist_conv2d_dgrad", "resist_conv2d_wgrad", "resist_profile_enable",
                      "resist_profile_read", "resist_compressed_block_size",
                      "resist_compress_blocks", "resist_decompress_blocks", "resist_aggregate_compressed",
-                     "resist_set_overlap", "resist_conv2d_wgrad_static", "resist_conv2d_wgrad_static_limit",
+                     "resist_set_overlap", "resist_set_bn_fusion", "resist_conv2d_wgrad_static", "resist_conv2d_wgrad_static_limit",
                      "resist_stem_conv2d_workspace_bytes", "resist_stem_conv2d_forward", "resist_stem_conv2d_wgrad"):
             getattr(L, name).restype = C.c_int
         L.resist_local_step.argtypes = [
@@ -311,6 +311,12 @@ def set_overlap(mode):
     """Second stream for the weight gradients of local_step: 0/False never, 1/True for steps with
     enough work (default), 2 always."""
     _check(lib().resist_set_overlap(int(mode)))
+
+
+def set_bn_fusion(mode):
+    """First pass of a BN backward from the epilogue of the data gradient above it: 0 never, 1 in bf16
+    steps (default), 2 always."""
+    _check(lib().resist_set_bn_fusion(int(mode)))
 
 
 def profile_enable(on):

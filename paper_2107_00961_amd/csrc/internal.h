@@ -43,6 +43,7 @@ struct Scope {   // brackets the launches made during its lifetime with two even
 
 // ---- side stream for work off a step's critical path (overlap.cpp) -----------------------------
 int overlap_mode();   // resist_set_overlap(): 0 off, 1 for steps with enough work (default), 2 always
+int bn_fusion_mode(); // resist_set_bn_fusion(): 0 never, 1 in bf16 steps (default), 2 always
 class SideStream {
  public:
   SideStream(hipStream_t main, bool enable);   // enable == false, or no stream to be had: every call below is a no-op

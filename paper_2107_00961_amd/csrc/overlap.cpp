@@ -23,6 +23,7 @@ struct DeviceSide {
 DeviceSide g_side[kMaxDevices];
 std::mutex g_mu;
 std::atomic<int> g_overlap{1};
+std::atomic<int> g_bn_fusion{1};
 
 }  // namespace
 
@@ -31,6 +32,14 @@ int overlap_mode() { return g_overlap.load(); }
 extern "C" int resist_set_overlap(int32_t mode) {
   if (mode < 0 || mode > 2) return set_error(RESIST_EINVAL, "overlap mode %d: 0 (off), 1 (steps with enough work) or 2 (always)", mode);
   g_overlap.store(mode);
+  return RESIST_OK;
+}
+
+int bn_fusion_mode() { return g_bn_fusion.load(); }
+
+extern "C" int resist_set_bn_fusion(int32_t mode) {
+  if (mode < 0 || mode > 2) return set_error(RESIST_EINVAL, "BN fusion mode %d: 0 (never), 1 (bf16 steps) or 2 (always)", mode);
+  g_bn_fusion.store(mode);
   return RESIST_OK;
 }
 

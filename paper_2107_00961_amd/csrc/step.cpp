@@ -8,10 +8,6 @@
 
 #include "internal.h"
 
-#ifndef RESIST_FUSE_BN_BWD
-#define RESIST_FUSE_BN_BWD 1   // bf16: first pass of a BN backward in the epilogue of the data gradient above it
-#endif
-
 namespace resist {
 namespace {
 
@@ -882,7 +878,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
   // In bf16 mode a stride-1 data gradient also takes the first pass of the BN backward that consumes its
   // output (per-row-tile sums in P.stats, free during the backward pass): one launch and one read of the
   // gradient less per BN, in a mode where the backward chain, not the matrix cores, sets the step time.
-  const bool fuse_bn = RESIST_FUSE_BN_BWD && dt == DT_BF16;
+  const bool fuse_bn = bn_fusion_mode() == 2 || (bn_fusion_mode() == 1 && dt == DT_BF16);
   StatParts pre{};        // P.stats holds the first pass for the BN that ends the block below
   bool have_pre = false;
   int gi = 0;

@@ -70,6 +70,20 @@ def test_local_step_small(name):
     _run_steps(model, blocks, batch, steps=2, lr=0.1, mu=0.9, wd=5e-4, seed=seed)
 
 
+@pytest.mark.parametrize("name", ["cfg1", "strided_sub", "bottleneck_sub", "ragged"])
+def test_local_step_small_bn_first_pass_from_the_data_gradient(name):
+    """In bf16 steps the stride-1 data gradients leave the first pass of the next BN backward (per-row-tile
+    sums) from their epilogue.  Switched on for fp32 here, the same code meets the element-wise fp32 bound
+    against the oracle: gradients, updated parameters and momentum over two steps (strided layers and the
+    shortcut BNs keep the separate pass; "ragged" has a short last row tile)."""
+    model, blocks, batch = _small_models()[name]
+    try:
+        R.set_bn_fusion(2)
+        _run_steps(model, blocks, batch, steps=2, lr=0.1, mu=0.9, wd=5e-4, seed=0)
+    finally:
+        R.set_bn_fusion(1)
+
+
 @pytest.mark.parametrize("beta", [6.0, 50.0])
 def test_bn_input_with_mean_far_from_zero(beta):
     """Every BN offset set to `beta`: every activation is beta + O(1), so the convolution outputs the

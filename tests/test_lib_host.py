@@ -226,6 +226,7 @@ def test_compressed_block_sizes_and_argument_errors():
     assert lib.resist_decompress_blocks(ctypes.byref(d), 2, keys, 1, ok, ok, ok, None) == -1
     assert lib.resist_decompress_blocks(ctypes.byref(d), 0, None, 8, None, None, None, None) == 0
     assert lib.resist_set_overlap(3) == -1 and lib.resist_set_overlap(1) == 0
+    assert lib.resist_set_bn_fusion(3) == -1 and lib.resist_set_bn_fusion(-1) == -1 and lib.resist_set_bn_fusion(1) == 0
     nb = R.num_blocks(model)
     blocks = (ctypes.c_int32 * 4)(0, 3, 7, 30)
     offs = (ctypes.c_int32 * 2)(0, 4)

@@ -41,6 +41,12 @@ def lib():
         if not os.path.exists(_LIB_PATH):
             raise ResistError(f"{_LIB_PATH} is missing: run `python -m paper_2107_00961_amd.build` "
                               "(there is no CPU fallback)")
+        # PyTorch-ROCm ships its own HIP runtime; loaded after this library it would be a second runtime in
+        # the process (the first one then reports no device).  Import it first where it is installed.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(_LIB_PATH)
         L.resist_last_error.restype = C.c_char_p
         for name in ("resist_num_blocks", "resist_partition", "resist_block_param_count",

@@ -336,6 +336,39 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
   // the channel axis; the optional addend is added in fp32 before the one rounding to T.
   T *out = static_cast<T *>(a.out);
   const T *addend = static_cast<const T *>(a.addend);
+  constexpr int CV = BN / VEC;            // 16-byte pieces per tile row
+  constexpr int RPS = NT / CV;      // rows per pass
+  constexpr int NP = BM / RPS;      // passes over the tile
+  constexpr int PG = NP < 8 ? NP : 8;   // passes whose side inputs are in flight together
+  static_assert(BM % RPS == 0 && CV <= 32 && NP % PG == 0, "output tile rows per pass");
+  const int cv = (tid % CV) * VEC, row0 = tid / CV;
+  const bool col_ok = n0 + cv < a.OC;     // OC is a multiple of VEC
+  const bool bn_bwd = MODE == kBwd && a.bn_sums != nullptr;
+  // The side inputs of the epilogue (addend, ReLU mask, BN input: up to three 16-byte loads per thread
+  // and pass) are requested for up to eight passes at once, the first group here, before the
+  // accumulators even go to LDS: taken one pass at a time, every pass would wait out a memory round
+  // trip of its own (a store to `out` may alias the addend, so the compiler cannot move the loads
+  // itself).  A thread reads only elements it writes later.
+  const T *maskp = static_cast<const T *>(a.relu_mask), *bnyp = static_cast<const T *>(a.bn_y);
+  const bool has_mask = MODE == kBwd && a.relu_mask != nullptr;
+  typename Vec<T>::Raw q_ad[PG], q_mk[PG], q_y[PG];
+  size_t offs[PG];
+  bool live[PG];
+  auto request_side = [&](int p0) {
+#pragma unroll
+    for (int g = 0; g < PG; ++g) {
+      const int ro = row_off[row0 + (p0 + g) * RPS];
+      live[g] = ro >= 0 && col_ok;
+      offs[g] = live[g] ? (size_t)ro * a.OC + n0 + cv : 0;
+      q_ad[g] = q_mk[g] = q_y[g] = typename Vec<T>::Raw{};
+      if (live[g]) {
+        if (addend) q_ad[g] = Vec<T>::load_raw(addend + offs[g]);
+        if (has_mask) q_mk[g] = Vec<T>::load_raw(maskp + offs[g]);
+        if (bn_bwd) q_y[g] = Vec<T>::load_raw(bnyp + offs[g]);
+      }
+    }
+  };
+  request_side(0);
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -348,11 +381,6 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
       }
     }
   __syncthreads();
-  constexpr int CV = BN / VEC;            // 16-byte pieces per tile row
-  constexpr int RPS = NT / CV;      // rows per pass
-  static_assert(BM % RPS == 0 && CV <= 32, "output tile rows per pass");
-  const int cv = (tid % CV) * VEC, row0 = tid / CV;
-  const bool col_ok = n0 + cv < a.OC;     // OC is a multiple of VEC
   // batch-norm statistics of this row tile: column sums of (v - k) and (v - k)^2 of the values v as
   // stored, with the shift k = the tile's first accumulated row of the column.  Any k within a few
   // standard deviations of the column keeps the sum of squares free of the cancellation that
@@ -360,7 +388,6 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
   float s1[VEC], s2[VEC], kshift[VEC];
 #pragma unroll
   for (int e = 0; e < VEC; ++e) { s1[e] = 0.f; s2[e] = 0.f; kshift[e] = 0.f; }
-  const bool bn_bwd = MODE == kBwd && a.bn_sums != nullptr;
   float bmu[VEC], bis[VEC], bsc[VEC], bsh[VEC];
 #pragma unroll
   for (int e = 0; e < VEC; ++e) { bmu[e] = 0.f; bis[e] = 0.f; bsc[e] = 0.f; bsh[e] = 0.f; }
@@ -379,11 +406,13 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
     }
   }
 #pragma unroll
-  for (int pass = 0; pass < BM / RPS; ++pass) {
-    const int r = row0 + pass * RPS;
-    const int ro = row_off[r];
-    if (ro >= 0 && col_ok) {
-      const size_t off = (size_t)ro * a.OC + n0 + cv;
+  for (int p0 = 0; p0 < NP; p0 += PG) {
+    if (p0 > 0) request_side(p0);
+#pragma unroll
+    for (int g = 0; g < PG; ++g) {
+      if (!live[g]) continue;
+      const int r = row0 + (p0 + g) * RPS;
+      const size_t off = offs[g];
       float v[VEC];
 #pragma unroll
       for (int e = 0; e < VEC; e += 4) {
@@ -392,13 +421,13 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
       }
       if (addend) {
         float ad[VEC];
-        Vec<T>::load(addend + off, ad);
+        Vec<T>::unpack(q_ad[g], ad);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) v[e] += ad[e];
       }
-      if (MODE == kBwd && a.relu_mask) {
+      if (has_mask) {
         float mk[VEC];
-        Vec<T>::load(static_cast<const T *>(a.relu_mask) + off, mk);
+        Vec<T>::unpack(q_mk[g], mk);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) v[e] = mk[e] > 0.f ? v[e] : 0.f;
       }
@@ -406,7 +435,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
       if (bn_bwd) {
         // the same arithmetic as the stand-alone first pass (bn_bwd_partial_kernel) on the values as stored
         float yv[VEC];
-        Vec<T>::load(static_cast<const T *>(a.bn_y) + off, yv);
+        Vec<T>::unpack(q_y[g], yv);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
           float gm = E::to_f32(E::from_f32(v[e]));

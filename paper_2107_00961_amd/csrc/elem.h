@@ -34,6 +34,12 @@ template <> struct Vec<float> {
   }
   __device__ static inline float get(const float *p) { return *p; }
   __device__ static inline void put(float *p, float v) { *p = v; }
+  // the 16 bytes as they are in memory (requested now, widened when used)
+  typedef f32x4 Raw;
+  __device__ static inline Raw load_raw(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+  __device__ static inline void unpack(const Raw &t, float (&v)[4]) {
+    v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+  }
 };
 
 template <> struct Vec<__bf16> {
@@ -51,6 +57,12 @@ template <> struct Vec<__bf16> {
   }
   __device__ static inline float get(const __bf16 *p) { return (float)*p; }
   __device__ static inline void put(__bf16 *p, float v) { *p = (__bf16)v; }
+  typedef u32x4 Raw;
+  __device__ static inline Raw load_raw(const __bf16 *p) { return *reinterpret_cast<const u32x4 *>(p); }
+  __device__ static inline void unpack(const Raw &t, float (&v)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[2 * i] = bf16_lo(t[i]); v[2 * i + 1] = bf16_hi(t[i]); }
+  }
 };
 
 }  // namespace resist

@@ -1,5 +1,5 @@
 """GPU parity at the benchmark's full sizes: every distinct convolution shape of the CIFAR-shaped
-(fp32) and ImageNet-shaped (bf16) sub-ResNets at the benchmark batch size, in the launch
+(fp32 and bf16) and ImageNet-shaped (bf16) networks at the benchmark batch size, in the launch
 configuration bench.py times, on sampled outputs that the oracle computes one by one from the
 definition (the full-tensor oracle would take minutes per layer at these sizes)."""
 import numpy as np
@@ -39,7 +39,8 @@ def _shapes(cfg_name):
 
 def _cases():
     cases = []
-    for name, dt in (("cfg2", torch.float32), ("cfg4", torch.bfloat16)):
+    # cfg5_bf16: the CIFAR-shaped layers in bf16 run on the eight-wave tiles (operands requested two chunks ahead)
+    for name, dt in (("cfg2", torch.float32), ("cfg4", torch.bfloat16), ("cfg5_bf16", torch.bfloat16)):
         batch, shapes = _shapes(name)
         cases += [pytest.param(name, dt, batch, s, id=f"{name}-H{s[0]}-C{s[1]}-K{s[2]}-R{s[3]}-s{s[4]}") for s in shapes]
     return cases

@@ -1,7 +1,7 @@
 // Training-mode batch normalisation on NHWC activations viewed as a matrix [M = N*H*W][C], fused
-// with ReLU and the residual add of a block (forward), and with the ReLU mask (backward).
+// with ReLU and the residual add of a block (forward), and with this BN's own ReLU decision (backward).
 //   forward   mean_c, var_c (biased) over the M rows; a = [relu](gamma*(y-mean)*invstd + beta [+ res])
-//   backward  gm = g*[mask>0]; dbeta = sum gm; dgamma = sum gm*xhat;
+//   backward  gm = g, or g where this BN's own ReLU passed; dbeta = sum gm; dgamma = sum gm*xhat;
 //             dy = gamma*invstd*(gm - dbeta/M - xhat*dgamma/M)
 // These kernels are bound by HBM bandwidth.  The forward statistics arrive as per-row-tile fp32
 // shifted column sums written by the convolution that produced y (at most 128 rows each) and are
@@ -229,13 +229,12 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(ApplyArgs p) {
 
 // ---- backward ------------------------------------------------------------------------------------
 // mask modes: the gradient passes where ...
-constexpr int kMaskNone = 0;     // everywhere
-constexpr int kMaskTensor = 1;   // the given tensor is positive
+constexpr int kMaskNone = 0;     // everywhere (a ReLU behind this BN's output was applied by whoever produced g)
 constexpr int kMaskSelf = 2;     // this BN's own output scale*y + shift is positive (its ReLU decision)
 
 // pass 1: per-channel sums of gm and gm*xhat; scratch [2][parts][C]
 template <typename T, int MASK>
-__global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const T *__restrict__ g, const T *__restrict__ mask,
+__global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const T *__restrict__ g,
                                                                   const T *__restrict__ y, long long M, int C, int tpr,
                                                                   int rpp, const float *__restrict__ mean,
                                                                   const float *__restrict__ invstd,
@@ -260,7 +259,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const T *__res
 #pragma unroll
   for (int e = 0; e < V; ++e) { sb[e] = 0; sg[e] = 0; }
   for (long long rr = r0 + tr; rr < r1; rr += 2 * rpp) {
-    float gv[2][V], yv[2][V], mv[2][V];
+    float gv[2][V], yv[2][V];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const long long r = rr + u * rpp;
@@ -268,7 +267,6 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const T *__res
         const size_t off = (size_t)r * C + c;
         Vec<T>::load(g + off, gv[u]);
         Vec<T>::load(y + off, yv[u]);
-        if (MASK == kMaskTensor) Vec<T>::load(mask + off, mv[u]);
       }
     }
 #pragma unroll
@@ -278,7 +276,6 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const T *__res
 #pragma unroll
         for (int e = 0; e < V; ++e) {
           float gm = gv[u][e];
-          if (MASK == kMaskTensor) gm = mv[u][e] > 0.f ? gm : 0.f;
           if (MASK == kMaskSelf) gm = fmaf(yv[u][e], sc[e], sh[e]) > 0.f ? gm : 0.f;
           const float xh = (yv[u][e] - mu[e]) * is[e];
           sb[e] += (double)gm;
@@ -347,11 +344,11 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const S *__restr
 }
 
 struct BwdApplyArgs {
-  const void *g; const void *mask; const void *y;
+  const void *g; const void *y;
   const void *addend;   // optional: added to dy in fp32 before it is stored
   const float *mean; const float *invstd; const float *scale; const float *shift;
   const float *dgamma; const float *dbeta;
-  void *dy; void *gm_out;
+  void *dy;
   long long M; int C; int tpr, rpp;
 };
 
@@ -361,8 +358,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BwdApplyArgs p) 
   const int tid = threadIdx.x;
   const int tc = tid % p.tpr, tr = tid / p.tpr;
   const int c = (blockIdx.y * p.tpr + tc) * V;
-  const T *g = static_cast<const T *>(p.g), *mask = static_cast<const T *>(p.mask), *y = static_cast<const T *>(p.y);
-  T *dy = static_cast<T *>(p.dy), *gm_out = static_cast<T *>(p.gm_out);
+  const T *g = static_cast<const T *>(p.g), *y = static_cast<const T *>(p.y);
+  T *dy = static_cast<T *>(p.dy);
   const T *addend = static_cast<const T *>(p.addend);
   const float invM = 1.0f / (float)p.M;
   float mu[V], is[V], k0[V], sh[V], k1[V], k2[V];
@@ -384,7 +381,6 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BwdApplyArgs p) 
         const size_t off = (size_t)r * p.C + c;
         Vec<T>::load(g + off, gv[u]);
         Vec<T>::load(y + off, yv[u]);
-        if (MASK == kMaskTensor) Vec<T>::load(mask + off, mv[u]);
       }
     }
 #pragma unroll
@@ -396,7 +392,6 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BwdApplyArgs p) 
 #pragma unroll
         for (int e = 0; e < V; ++e) {
           float gm = gv[u][e];
-          if (MASK == kMaskTensor) gm = mv[u][e] > 0.f ? gm : 0.f;
           if (MASK == kMaskSelf) gm = fmaf(yv[u][e], k0[e], sh[e]) > 0.f ? gm : 0.f;
           gv[u][e] = gm;
           const float xh = (yv[u][e] - mu[e]) * is[e];
@@ -409,7 +404,6 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(BwdApplyArgs p) 
           for (int e = 0; e < V; ++e) o[e] += ad[e];
         }
         Vec<T>::store(dy + off, o);
-        if (gm_out) Vec<T>::store(gm_out + off, gv[u]);   // exact: gm is g or zero
       }
     }
   }
@@ -434,20 +428,19 @@ unsigned apply_grid_x(int64_t M, const ColMap &m, int rows_per_thread) {
 inline int vec_of(int dt) { return dt == DT_BF16 ? 8 : 4; }
 
 template <typename T>
-void launch_bwd(int mode, dim3 gp, dim3 ga, hipStream_t st, const void *g, const void *mask, const void *y, int64_t M, int C,
+void launch_bwd(int mode, dim3 gp, dim3 ga, hipStream_t st, const void *g, const void *y, int64_t M, int C,
                 const ColMap &m, const BnBufs &b, double *scratch, const BwdApplyArgs &p, int parts, const float *pre_sums) {
-  const T *gg = (const T *)g, *mm = (const T *)mask, *yy = (const T *)y;
+  const T *gg = (const T *)g, *yy = (const T *)y;
 #define RESIST_BN_BWD(MODE)                                                                                              \
   if (pre_sums) {                                                                                                        \
     hipLaunchKernelGGL(bn_bwd_final_kernel<float>, dim3(C / 16), dim3(kThreads), 0, st, pre_sums, parts, C, b.dgamma, b.dbeta); \
   } else {                                                                                                               \
-    hipLaunchKernelGGL((bn_bwd_partial_kernel<T, MODE>), gp, dim3(kThreads), 0, st, gg, mm, yy, (long long)M, C, m.tpr, m.rpp, \
+    hipLaunchKernelGGL((bn_bwd_partial_kernel<T, MODE>), gp, dim3(kThreads), 0, st, gg, yy, (long long)M, C, m.tpr, m.rpp, \
                        b.mean, b.invstd, b.scale, b.shift, scratch);                                                    \
     hipLaunchKernelGGL(bn_bwd_final_kernel<double>, dim3(C / 16), dim3(kThreads), 0, st, (const double *)scratch, parts, C, b.dgamma, b.dbeta); \
   }                                                                                                                      \
   hipLaunchKernelGGL((bn_bwd_apply_kernel<T, MODE>), ga, dim3(kThreads), 0, st, p);
-  if (mode == kMaskTensor) { RESIST_BN_BWD(kMaskTensor) }
-  else if (mode == kMaskSelf) { RESIST_BN_BWD(kMaskSelf) }
+  if (mode == kMaskSelf) { RESIST_BN_BWD(kMaskSelf) }
   else { RESIST_BN_BWD(kMaskNone) }
 #undef RESIST_BN_BWD
 }
@@ -511,24 +504,24 @@ int bn_apply(int dt, const void *y, int64_t M, int C, const BnBufs &b, const voi
   return RESIST_OK;
 }
 
-int bn_backward(int dt, const void *g, const void *mask, bool relu_of_self, const void *y, int64_t M, int C, const BnBufs &b,
-                void *dy, void *gm_out, const void *addend, double *scratch, hipStream_t st, const float *pre_sums, StatParts pre) {
+int bn_backward(int dt, const void *g, bool relu_of_self, const void *y, int64_t M, int C, const BnBufs &b, void *dy,
+                const void *addend, double *scratch, hipStream_t st, const float *pre_sums, StatParts pre) {
   RESIST_TRY(check_bn(dt, M, C));
   const ColMap m = col_map(C, vec_of(dt));
-  if (pre_sums && (mask || pre.parts < 1 || pre.rows < 1 || (long long)pre.parts * pre.rows < M ||
+  if (pre_sums && (pre.parts < 1 || pre.rows < 1 || (long long)pre.parts * pre.rows < M ||
                    (long long)(pre.parts - 1) * pre.rows >= M))
     return set_error(RESIST_EINVAL, "bn_backward: %d pre-computed partial sums of %d rows for %lld rows", pre.parts, pre.rows, (long long)M);
   const int parts = pre_sums ? pre.parts : num_parts(M, m);
-  const int mode = mask ? kMaskTensor : (relu_of_self ? kMaskSelf : kMaskNone);
-  const int reads = mask ? 3 : 2;
-  prof::Scope ps("bn_backward", 0, (double)esize(dt) * M * C * ((pre_sums ? 1 : 2) * reads + 1 + (gm_out ? 1 : 0) + (addend ? 1 : 0)), st);
+  const int mode = relu_of_self ? kMaskSelf : kMaskNone;
+  const int reads = 2;
+  prof::Scope ps("bn_backward", 0, (double)esize(dt) * M * C * ((pre_sums ? 1 : 2) * reads + 1 + (addend ? 1 : 0)), st);
   BwdApplyArgs p{};
-  p.g = g; p.mask = mask; p.y = y; p.addend = addend; p.mean = b.mean; p.invstd = b.invstd; p.scale = b.scale; p.shift = b.shift;
-  p.dgamma = b.dgamma; p.dbeta = b.dbeta; p.dy = dy; p.gm_out = gm_out;
+  p.g = g; p.y = y; p.addend = addend; p.mean = b.mean; p.invstd = b.invstd; p.scale = b.scale; p.shift = b.shift;
+  p.dgamma = b.dgamma; p.dbeta = b.dbeta; p.dy = dy;
   p.M = M; p.C = C; p.tpr = m.tpr; p.rpp = m.rpp;
   const dim3 gp(parts, m.ctiles), ga(apply_grid_x(M, m, 4), m.ctiles);
-  if (dt == DT_BF16) launch_bwd<__bf16>(mode, gp, ga, st, g, mask, y, M, C, m, b, scratch, p, parts, pre_sums);
-  else launch_bwd<float>(mode, gp, ga, st, g, mask, y, M, C, m, b, scratch, p, parts, pre_sums);
+  if (dt == DT_BF16) launch_bwd<__bf16>(mode, gp, ga, st, g, y, M, C, m, b, scratch, p, parts, pre_sums);
+  else launch_bwd<float>(mode, gp, ga, st, g, y, M, C, m, b, scratch, p, parts, pre_sums);
   RESIST_CHECK_LAUNCH("bn_backward");
   return RESIST_OK;
 }

@@ -191,15 +191,15 @@ int bn_eval_affine(int C, const BnBufs &b, float eps, float s, hipStream_t st);
 // a = [relu]( scale*y + shift [+ res] )            res: raw tensor, or BN(res_y) if res_bn given
 int bn_apply(int dt, const void *y, int64_t M, int C, const BnBufs &b, const void *res,
              const BnBufs *res_bn, bool relu, void *a, hipStream_t st);
-// gm = g * [mask>0]; dbeta = sum gm; dgamma = sum gm*xhat(y);
-// dy = gamma*invstd*(gm - dbeta/M - xhat*dgamma/M) [+ addend]; optionally stores gm to gm_out.
-// The mask is the tensor `mask` if given; else, if relu_of_self, the sign of this BN's own output
-// scale*y + shift (the forward ReLU decision recomputed with the same arithmetic); else none.
+// gm = g, or (relu_of_self) g where this BN's own output scale*y + shift is positive -- the forward ReLU
+// decision recomputed with the same arithmetic -- and 0 elsewhere; dbeta = sum gm; dgamma = sum gm*xhat(y);
+// dy = gamma*invstd*(gm - dbeta/M - xhat*dgamma/M) [+ addend].  (A ReLU behind a block's last BN is
+// applied by whoever produces g: see conv_dgrad's relu_mask and avgpool_bwd.)
 // pre_sums (optional): the first pass already done by the data gradient that produced g
 // ([2][pre.parts][C] floats, see conv_dgrad); then only the per-channel totals and the second pass run.
-int bn_backward(int dt, const void *g, const void *mask, bool relu_of_self, const void *y, int64_t M, int C,
-                const BnBufs &b, void *dy, void *gm_out, const void *addend, double *scratch, hipStream_t st,
-                const float *pre_sums = nullptr, StatParts pre = StatParts{});
+int bn_backward(int dt, const void *g, bool relu_of_self, const void *y, int64_t M, int C, const BnBufs &b, void *dy,
+                const void *addend, double *scratch, hipStream_t st, const float *pre_sums = nullptr,
+                StatParts pre = StatParts{});
 struct BnBwdFuse {
   const void *y;        // the BN's input, [M][C] in the compute type
   BnBufs b;             // mean, invstd, scale, shift are read

@@ -689,7 +689,7 @@ int local_step_preact(const resist_model_desc *desc, const int32_t *blocks, int3
   RESIST_TRY(avgpool_bwd(dt, P.dpooled, nullptr, P.da, N, P.feat_hw, CH, st));
   int gi = 0;
   RESIST_TRY(wg.filters_ready());
-  RESIST_TRY(bn_backward(dt, P.da, nullptr, true, P.feat_in, P.head_rows, CH, hb, P.gbuf[gi], nullptr, nullptr, P.bn_scratch, st));
+  RESIST_TRY(bn_backward(dt, P.da, true, P.feat_in, P.head_rows, CH, hb, P.gbuf[gi], nullptr, P.bn_scratch, st));
   for (int bi = (int)P.blocks.size() - 1; bi >= 0; --bi) {
     PreBlock &pb = P.blocks[bi];
     float *pp = params(pb.slot), *gg = grads(pb.slot);
@@ -710,13 +710,13 @@ int local_step_preact(const resist_model_desc *desc, const int32_t *blocks, int3
       BnBufs b = pre_bn_bufs(un, pp, gg);
       if (j > 0) {
         RESIST_TRY(wg.before_write(dy));
-        RESIST_TRY(bn_backward(dt, P.da, nullptr, true, un.u, un.rows(), un.g.C, b, dy, nullptr, nullptr, P.bn_scratch, st));
+        RESIST_TRY(bn_backward(dt, P.da, true, un.u, un.rows(), un.g.C, b, dy, nullptr, P.bn_scratch, st));
         gcur = dy;
         std::swap(dy, dy_other);
       } else {
         // gradient w.r.t. the block input: through BN_1, plus the identity shortcut's share
         RESIST_TRY(wg.before_write(Gn));
-        RESIST_TRY(bn_backward(dt, P.da, nullptr, true, un.u, un.rows(), un.g.C, b, Gn, nullptr, pb.has_ds ? nullptr : G, P.bn_scratch, st));
+        RESIST_TRY(bn_backward(dt, P.da, true, un.u, un.rows(), un.g.C, b, Gn, pb.has_ds ? nullptr : G, P.bn_scratch, st));
       }
     }
     gi ^= 1;
@@ -893,7 +893,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     BnBufs bl = bn_bufs(last, pp, gg);
     // the last BN of the residual branch
     RESIST_TRY(wg.before_write(P.dy0));
-    RESIST_TRY(bn_backward(dt, G, nullptr, false, last.y, last.M(), last.g.K, bl, P.dy0, nullptr, nullptr, P.bn_scratch, st,
+    RESIST_TRY(bn_backward(dt, G, false, last.y, last.M(), last.g.K, bl, P.dy0, nullptr, P.bn_scratch, st,
                            have_pre ? P.stats : nullptr, pre));
     have_pre = false;
     if (bp.has_ds) {
@@ -901,7 +901,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
       ConvLayer &d = bp.ds;
       BnBufs bd = bn_bufs(d, pp, gg);
       RESIST_TRY(wg.before_write(P.gm));
-      RESIST_TRY(bn_backward(dt, G, nullptr, false, d.y, d.M(), d.g.K, bd, P.gm, nullptr, nullptr, P.bn_scratch, st));
+      RESIST_TRY(bn_backward(dt, G, false, d.y, d.M(), d.g.K, bd, P.gm, nullptr, P.bn_scratch, st));
       RESIST_TRY(wg.launch(d.g, P.gm, d.in, gg + d.w_off));
       RESIST_TRY(conv_dgrad(d.g, dt, P.gm, d.wT, Gn, nullptr, nullptr, st));
     }
@@ -917,7 +917,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
         const bool fz = fuse_bn && c.g.stride == 1;
         RESIST_TRY(conv_dgrad(c.g, dt, dy, c.wT, P.da, nullptr, nullptr, st, fz ? &f : nullptr));
         RESIST_TRY(wg.before_write(dy_other));
-        RESIST_TRY(bn_backward(dt, P.da, nullptr, true, prev.y, prev.M(), prev.g.K, bp_, dy_other, nullptr, nullptr, P.bn_scratch, st,
+        RESIST_TRY(bn_backward(dt, P.da, true, prev.y, prev.M(), prev.g.K, bp_, dy_other, nullptr, P.bn_scratch, st,
                                fz ? P.stats : nullptr, sp));
         std::swap(dy, dy_other);
       } else {
@@ -950,7 +950,7 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     }
     BnBufs b = bn_bufs(s, params(0), grads(0));
     RESIST_TRY(wg.before_write(P.dy0));
-    RESIST_TRY(bn_backward(dt, Gs, nullptr, true, s.y, s.M(), K0, b, P.dy0, nullptr, nullptr, P.bn_scratch, st));
+    RESIST_TRY(bn_backward(dt, Gs, true, s.y, s.M(), K0, b, P.dy0, nullptr, P.bn_scratch, st));
     RESIST_TRY(wg.launch_stem(net, N, P.kpad, P.dy0, x, P.dwpad));
     RESIST_TRY(unpad_rows_f32(P.dwpad, grads(0) + s.w_off, K0, taps, P.kpad, wg.stream()));
   }

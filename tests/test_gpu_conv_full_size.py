@@ -1,7 +1,8 @@
 """GPU parity at the benchmark's full sizes: every distinct convolution shape of the CIFAR-shaped
 (fp32 and bf16) and ImageNet-shaped (bf16) networks at the benchmark batch size, in the launch
-configuration bench.py times, on sampled outputs that the oracle computes one by one from the
-definition (the full-tensor oracle would take minutes per layer at these sizes)."""
+configuration bench.py times: forward, data gradient and weight gradient, every element against the
+full-tensor oracle (a second or two per layer on the GPU machine's host cores), and sampled outputs
+against the point-wise form of the definition."""
 import numpy as np
 import pytest
 import torch
@@ -47,7 +48,7 @@ def _cases():
 
 
 @pytest.mark.parametrize("name,dt,N,shape", _cases())
-def test_full_size_conv_sampled(name, dt, N, shape):
+def test_full_size_conv(name, dt, N, shape):
     H, C, K, RS, st, pad = shape
     print(f"{name} N={N} shape={shape} dtype={dt}", flush=True)
     P = (H + 2 * pad - RS) // st + 1
@@ -81,3 +82,12 @@ def test_full_size_conv_sampled(name, dt, N, shape):
     pts += [(0, 0, 0, 0), (K - 1, RS - 1, RS - 1, C - 1)]
     rtol, atol = 1e-4, 1e-5                                           # weight gradients are fp32 in both modes
     check(np.array([dwh[p] for p in pts]), L.conv2d_wgrad_points(dywh, xh, st, pad, RS, RS, pts), "wgrad")
+    # every element of all three results against the full-tensor oracle (NCHW, float64, a second or two per layer)
+    xc, wc, dyc = xh.transpose(0, 3, 1, 2), wh.transpose(0, 3, 1, 2), dyh.transpose(0, 3, 1, 2)
+    rtol, atol = (2.0 ** -8, 1e-5) if dt == torch.bfloat16 else (1e-4, 1e-5)
+    check(yh.transpose(0, 3, 1, 2), L.conv2d_fwd(xc, wc, st, pad), "fwd, all elements")
+    check(dxh.transpose(0, 3, 1, 2), L.conv2d_dgrad(dyc, wc, (N, C, H, H), st, pad), "dgrad, all elements")
+    rtol, atol = 1e-4, 1e-5
+    # the weight gradient: every element, through the split reduction
+    dw_ref = L.conv2d_wgrad(dywh.transpose(0, 3, 1, 2), xh.transpose(0, 3, 1, 2), (K, C, RS, RS), st, pad)   # [K][C][R][S]
+    check(dwh.transpose(0, 3, 1, 2), dw_ref, "wgrad, all elements")

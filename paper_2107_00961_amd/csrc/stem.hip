@@ -141,8 +141,10 @@ template <> struct StemMma<__bf16> {
   typedef bf16x8 Frag;
 };
 
-// y = conv(x, w) for one tile; wave w owns pixels 32w .. 32w+31 and all output channels
-template <typename T>
+// y = conv(x, w) for one tile; wave w owns pixels 32w .. 32w+31 and all output channels.
+// NTILES: 32-channel tiles of the output (a compile-time count keeps the accumulators in place and the
+// multiplication loop free of branches).
+template <typename T, int NTILES>
 __global__ __launch_bounds__(256) void stem_fwd_kernel(StemArgs a) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   constexpr int VEC = 16 / (int)sizeof(T);
@@ -190,49 +192,45 @@ __global__ __launch_bounds__(256) void stem_fwd_kernel(StemArgs a) {
   const int lr = lane & 31, kg = lane >> 5;
   const int po = pixoff[wave * 32 + lr];
   const int nsteps = a.kpad / KS;
-  const int ntiles = k32 / 32;
   float *Cs = reinterpret_cast<float *>(lds);
   const int ldc = k32 + 4;
-  f32x16 acc[4];                             // up to four 32-channel tiles (K <= 128 is checked on the host)
+  f32x16 acc[NTILES];                        // k32 == 32 * NTILES (the host picks the instance)
 #pragma unroll
-  for (int t = 0; t < 4; ++t)
+  for (int t = 0; t < NTILES; ++t)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
-#pragma unroll 4
+#pragma unroll 2
   for (int ks = 0; ks < nsteps; ++ks) {
     if constexpr (sizeof(T) == 2) {
       const int j0 = ks * 16 + kg * 8;
+      bf16x8 fb[NTILES];
+#pragma unroll
+      for (int t = 0; t < NTILES; ++t) fb[t] = *reinterpret_cast<const bf16x8 *>(Ws + (t * 32 + lr) * ldw + j0);
       bf16x8 fa;
 #pragma unroll
       for (int e = 0; e < 8; ++e) fa[e] = (__bf16)patch[tab[j0 + e] + po];
 #pragma unroll
-      for (int t = 0; t < 4; ++t)
-        if (t < ntiles) {
-          const bf16x8 fb = *reinterpret_cast<const bf16x8 *>(Ws + (t * 32 + lr) * ldw + j0);
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[t], 0, 0, 0);
-        }
+      for (int t = 0; t < NTILES; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[t], acc[t], 0, 0, 0);
     } else {
       const int j = ks * 2 + kg;
       const float fa = patch[tab[j] + po];
+      float fb[NTILES];
 #pragma unroll
-      for (int t = 0; t < 4; ++t)
-        if (t < ntiles) {
-          const float fb = Ws[(t * 32 + lr) * ldw + j];
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa, fb, acc[t], 0, 0, 0);
-        }
+      for (int t = 0; t < NTILES; ++t) fb[t] = Ws[(t * 32 + lr) * ldw + j];
+#pragma unroll
+      for (int t = 0; t < NTILES; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa, fb[t], acc[t], 0, 0, 0);
     }
   }
   __syncthreads();   // every wave is done with patch and filter before the block is reused for the output tile
   // a lane holds column lane%32 and rows 8*(e/4) + 4*(lane/32) + e%4 of each 32x32 tile
 #pragma unroll
-  for (int t = 0; t < 4; ++t)
-    if (t < ntiles) {
+  for (int t = 0; t < NTILES; ++t) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = wave * 32 + (e >> 2) * 8 + kg * 4 + (e & 3);
-        Cs[row * ldc + t * 32 + lr] = acc[t][e];
-      }
+    for (int e = 0; e < 16; ++e) {
+      const int row = wave * 32 + (e >> 2) * 8 + kg * 4 + (e & 3);
+      Cs[row * ldc + t * 32 + lr] = acc[t][e];
     }
+  }
   __syncthreads();
   // output rows as 16-byte vectors along the channels
   T *y = static_cast<T *>(a.y);
@@ -489,8 +487,17 @@ int stem_conv_fwd(int dt, const float *x, const void *wpad, void *y, float *stat
   const double flops = 2.0 * N * P * Q * K * a.taps;
   prof::Scope ps(dt == DT_BF16 ? "stem_conv_bf16_fwd" : "stem_conv_f32_fwd", flops,
                  4.0 * N * C * H * W + (double)esize(dt) * ((double)N * P * Q * K + (double)K * kpad), st);
-  if (dt == DT_BF16) hipLaunchKernelGGL(stem_fwd_kernel<__bf16>, dim3(a.tiles), dim3(256), lds, st, a);
-  else hipLaunchKernelGGL(stem_fwd_kernel<float>, dim3(a.tiles), dim3(256), lds, st, a);
+  const int ntiles = (a.K + 31) / 32;        // 1..4: K <= 128 was checked above
+#define RESIST_STEM_FWD(NTILES)                                                                                  \
+  do {                                                                                                           \
+    if (dt == DT_BF16) hipLaunchKernelGGL((stem_fwd_kernel<__bf16, NTILES>), dim3(a.tiles), dim3(256), lds, st, a); \
+    else hipLaunchKernelGGL((stem_fwd_kernel<float, NTILES>), dim3(a.tiles), dim3(256), lds, st, a);             \
+  } while (0)
+  if (ntiles == 1) RESIST_STEM_FWD(1);
+  else if (ntiles == 2) RESIST_STEM_FWD(2);
+  else if (ntiles == 3) RESIST_STEM_FWD(3);
+  else RESIST_STEM_FWD(4);
+#undef RESIST_STEM_FWD
   RESIST_CHECK_LAUNCH("stem_conv_fwd");
   return RESIST_OK;
 }

@@ -360,6 +360,11 @@ def main():
             _bench_round(args, cfg, subs)
         else:
             print(json.dumps(_bench_step(args, name)), flush=True)
+        # a workload's buffers go back to the driver before the next one allocates its own
+        import gc
+        import torch
+        gc.collect()
+        torch.cuda.empty_cache()
 
 
 if __name__ == "__main__":

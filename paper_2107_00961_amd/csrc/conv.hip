@@ -55,6 +55,18 @@ template <> struct Elem<__bf16> {
   __device__ static inline float to_f32(__bf16 v) { return (float)v; }
 };
 
+// division by a runtime constant: q = (n * mul) >> sh, exact for 0 <= n < 2^31
+struct FastDiv { unsigned mul; int sh; };
+inline FastDiv make_fastdiv(unsigned d) {
+  int L = 0;
+  while ((1ull << L) < d) ++L;
+  FastDiv f;
+  f.sh = 31 + L;
+  f.mul = (unsigned)((1ull << f.sh) / d + 1);
+  return f;
+}
+__device__ inline int fdiv(int n, FastDiv f) { return (int)(((unsigned long long)(unsigned)n * f.mul) >> f.sh); }
+
 struct IgemmArgs {
   const void *in;      // [N][IH][IW][IC]
   const void *wt;      // [OC][R][S][IC]
@@ -77,6 +89,7 @@ struct IgemmArgs {
   int OHc, OWc;         // OH/cls, OW/cls
   int Mrows;            // N*OHc*OWc: GEMM rows per class
   int tiles_m, tiles_n;
+  FastDiv div_plane, div_w, div_tn, div_tm;   // by OHc*OWc, OWc, tiles_n, tiles_m: a tile's prologue is a chain of divisions
 };
 
 // A-gather modes
@@ -144,18 +157,18 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
   // contiguous range of them.  The stride-2 data gradient (4 parity classes of unequal work, class
   // slowest) keeps the hardware round-robin order, which measured faster for its short K loops.
   int bid = a.cls == 1 ? xcd_contiguous(blockIdx.x, gridDim.x) : (int)blockIdx.x;
-  const int tn = bid % a.tiles_n;
-  bid /= a.tiles_n;
-  const int tm = bid % a.tiles_m;
-  const int cidx = bid / a.tiles_m;  // parity class
-  const int ph = cidx / a.cls, pw = cidx % a.cls;
+  const int bq = fdiv(bid, a.div_tn);
+  const int tn = bid - bq * a.tiles_n;
+  const int cidx = fdiv(bq, a.div_tm);   // parity class
+  const int tm = bq - cidx * a.tiles_m;
+  const int ph = a.cls == 2 ? cidx >> 1 : 0, pw = a.cls == 2 ? cidx & 1 : 0;   // cls is 1 or 2
   const int m0 = tm * BM, n0 = tn * BN;
 
   // filter taps that contribute: r = r0, r0+tstep, ... < R (all taps unless MODE==kBwd, stride 2)
   int r0 = 0, s0 = 0, tstep = 1;
   if (MODE == kBwd && a.stride == 2) { r0 = (ph + a.pad) & 1; s0 = (pw + a.pad) & 1; tstep = 2; }
-  const int nr = r0 < a.R ? (a.R - r0 + tstep - 1) / tstep : 0;
-  const int ns = s0 < a.S ? (a.S - s0 + tstep - 1) / tstep : 0;
+  const int nr = r0 < a.R ? (tstep == 2 ? (a.R - r0 + 1) >> 1 : a.R - r0) : 0;
+  const int ns = s0 < a.S ? (tstep == 2 ? (a.S - s0 + 1) >> 1 : a.S - s0) : 0;
   const int cchunks = (a.IC + BK - 1) / BK;
   const int nchunks = nr * ns * cchunks;
 
@@ -166,9 +179,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
   for (int i = 0; i < PA; ++i) {
     const int m = m0 + i * RPP + lrow;
     if (m < a.Mrows) {
-      const int n = m / (a.OHc * a.OWc);
+      const int n = fdiv(m, a.div_plane);
       const int rem = m - n * (a.OHc * a.OWc);
-      const int ohc = rem / a.OWc, owc = rem - ohc * a.OWc;
+      const int ohc = fdiv(rem, a.div_w), owc = rem - ohc * a.OWc;
       if (MODE == kFwd) { hc[i] = ohc * a.stride - a.pad; wc[i] = owc * a.stride - a.pad; }
       else if (a.stride == 1) { hc[i] = ohc + a.pad; wc[i] = owc + a.pad; }
       else { hc[i] = ohc; wc[i] = owc; }
@@ -186,9 +199,10 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmArgs a) {
     const int m = m0 + r;
     int off = -1;
     if (m < a.Mrows) {
-      const int n = m / (a.OHc * a.OWc);
+      const int n = fdiv(m, a.div_plane);
       const int rem = m - n * (a.OHc * a.OWc);
-      const int oh = (rem / a.OWc) * a.cls + ph, ow = (rem % a.OWc) * a.cls + pw;
+      const int orow = fdiv(rem, a.div_w);
+      const int oh = orow * a.cls + ph, ow = (rem - orow * a.OWc) * a.cls + pw;
       off = (n * a.OH + oh) * a.OW + ow;
     }
     row_off[r] = off;
@@ -496,6 +510,8 @@ int launch_igemm(IgemmArgs a, hipStream_t st, StatParts *tiles_m_out) {
   a.tiles_m = (a.Mrows + BM - 1) / BM;
   if (tiles_m_out) { tiles_m_out->parts = a.tiles_m; tiles_m_out->rows = BM; }
   a.tiles_n = (a.OC + BN - 1) / BN;
+  a.div_plane = make_fastdiv((unsigned)(a.OHc * a.OWc)); a.div_w = make_fastdiv((unsigned)a.OWc);
+  a.div_tn = make_fastdiv((unsigned)a.tiles_n); a.div_tm = make_fastdiv((unsigned)a.tiles_m);
   const long long grid = (long long)a.tiles_m * a.tiles_n * a.cls * a.cls;
   if (grid <= 0 || grid > 0x7fffffffLL) return set_error(RESIST_ESHAPE, "igemm grid %lld", grid);
   {
@@ -772,18 +788,6 @@ int prepare_filter(const ConvGeom &g, int src_dt, int dt, const void *w, void *w
 namespace {
 
 constexpr int kWBK = 32;  // reduction rows staged per step
-
-// division by a runtime constant: q = (n * mul) >> sh, exact for 0 <= n < 2^31
-struct FastDiv { unsigned mul; int sh; };
-inline FastDiv make_fastdiv(unsigned d) {
-  int L = 0;
-  while ((1ull << L) < d) ++L;
-  FastDiv f;
-  f.sh = 31 + L;
-  f.mul = (unsigned)((1ull << f.sh) / d + 1);
-  return f;
-}
-__device__ inline int fdiv(int n, FastDiv f) { return (int)(((unsigned long long)(unsigned)n * f.mul) >> f.sh); }
 
 struct WgradArgs {
   const void *dy;   // [M][K]

@@ -697,50 +697,32 @@ __global__ __launch_bounds__(256) void prepare_filters_kernel(PrepTable t) {
   T *__restrict__ wlp = static_cast<T *>(t.wlp[seg]);
   T *__restrict__ wT = static_cast<T *>(t.wT[seg]);
   const int row = threadIdx.x >> 4, col = (threadIdx.x & 15) * 4;   // 16 rows x 16 vectors per pass
-  if ((K & 3) == 0 && (C & 3) == 0) {
-    f32x4 v[TS / 16];
+  // K and C are multiples of four (checked on the host)
+  f32x4 v[TS / 16];
 #pragma unroll
-    for (int p = 0; p < TS / 16; ++p) {
-      const int k = k0 + row + 16 * p, c = c0 + col;
-      v[p] = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (k < K && c < C) v[p] = *reinterpret_cast<const f32x4 *>(w + ((size_t)k * RS + tap) * C + c);
-    }
-#pragma unroll
-    for (int p = 0; p < TS / 16; ++p) {
-      const int k = k0 + row + 16 * p, c = c0 + col;
-      v[p] *= sc;
-      if (wlp && k < K && c < C) store4(wlp + ((size_t)k * RS + tap) * C + c, v[p][0], v[p][1], v[p][2], v[p][3]);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) tile[row + 16 * p][col + e] = v[p][e];
-    }
-    __syncthreads();
-    if (wT) {
-#pragma unroll
-      for (int p = 0; p < TS / 16; ++p) {
-        const int c = c0 + row + 16 * p, k = k0 + col;
-        if (c < C && k < K)
-          store4(wT + ((size_t)c * RS + tap) * K + k, tile[col][row + 16 * p], tile[col + 1][row + 16 * p],
-                 tile[col + 2][row + 16 * p], tile[col + 3][row + 16 * p]);
-      }
-    }
-    return;
+  for (int p = 0; p < TS / 16; ++p) {
+    const int k = k0 + row + 16 * p, c = c0 + col;
+    v[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (k < K && c < C) v[p] = *reinterpret_cast<const f32x4 *>(w + ((size_t)k * RS + tap) * C + c);
   }
-  // channel counts that are not multiples of four: one element at a time
-  for (int i = threadIdx.x; i < TS * TS; i += 256) {
-    const int kk = i / TS, cc = i % TS, k = k0 + kk, c = c0 + cc;
-    float v = 0.f;
-    if (k < K && c < C) {
-      v = w[((size_t)k * RS + tap) * C + c] * sc;
-      if (wlp) wlp[((size_t)k * RS + tap) * C + c] = Elem<T>::from_f32(v);
-    }
-    tile[kk][cc] = v;
+#pragma unroll
+  for (int p = 0; p < TS / 16; ++p) {
+    const int k = k0 + row + 16 * p, c = c0 + col;
+    v[p] *= sc;
+    if (wlp && k < K && c < C) store4(wlp + ((size_t)k * RS + tap) * C + c, v[p][0], v[p][1], v[p][2], v[p][3]);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) tile[row + 16 * p][col + e] = v[p][e];
   }
   __syncthreads();
-  if (wT)
-    for (int i = threadIdx.x; i < TS * TS; i += 256) {
-      const int cc = i / TS, kk = i % TS, c = c0 + cc, k = k0 + kk;
-      if (k < K && c < C) wT[((size_t)c * RS + tap) * K + k] = Elem<T>::from_f32(tile[kk][cc]);
+  if (wT) {
+#pragma unroll
+    for (int p = 0; p < TS / 16; ++p) {
+      const int c = c0 + row + 16 * p, k = k0 + col;
+      if (c < C && k < K)
+        store4(wT + ((size_t)c * RS + tap) * K + k, tile[col][row + 16 * p], tile[col + 1][row + 16 * p],
+               tile[col + 2][row + 16 * p], tile[col + 3][row + 16 * p]);
     }
+  }
 }
 }  // namespace
 
@@ -752,6 +734,7 @@ int prepare_filters(const std::vector<FilterPrep> &items, int dt, hipStream_t st
     double bytes = 0;
     while (i < items.size() && t.nseg < kPrepSegs) {
       const FilterPrep &f = items[i++];
+      if ((f.g.K & 3) || (f.g.C & 3)) return set_error(RESIST_ESHAPE, "filter %dx%d: channel counts must be multiples of 4", f.g.K, f.g.C);
       const int n = t.nseg++;
       t.w[n] = f.w; t.wlp[n] = f.w_lp; t.wT[n] = f.wT;
       t.K[n] = f.g.K; t.RS[n] = f.g.R * f.g.S; t.C[n] = f.g.C;

@@ -36,8 +36,10 @@ struct StemArgs {
   int N, C, H, W, K, R, stride, pad, P, Q;
   int taps, kpad;
   int QB, RB, PH, PW;  // tile and patch shape
+  int PWp;             // words between patch rows: PW, or in vector mode a multiple of 4 with room for up to 3 leading columns
+  int vec;             // vector mode: W is a multiple of 4 and x is 16-byte aligned, so patch rows are staged as 16-byte pieces
   int tiles_q, tiles_p, tiles;   // tiles along Q and P of one image; N * tiles_p * tiles_q
-  int zn;              // words of the zero block (largest pixoff + 1)
+  int zn;              // words of the zero block (largest pixel offset, lead included, + 1)
   int y0;              // weight gradient: first 64-channel group of this launch
   int parts;           // forward: tiles; weight gradient: workgroups
 };
@@ -51,7 +53,7 @@ __host__ __device__ inline StemLds stem_lds(const StemArgs &a, bool wgrad) {
   StemLds L;
   int off = 0;
   auto take = [&](int bytes) { const int o = off; off += (bytes + 15) & ~15; return o; };
-  L.patch = take(a.C * a.PH * a.PW * 4);
+  L.patch = take(a.C * a.PH * a.PWp * 4);
   L.zero = take(a.zn * 4);
   L.tab = take(a.kpad * 4);
   L.pixoff = take(128 * 4);
@@ -65,9 +67,13 @@ __host__ __device__ inline StemLds stem_lds(const StemArgs &a, bool wgrad) {
   return L;
 }
 
-// stages patch, zero block and the two tables for tile `tile`; returns image index and first output pixel
+// stages patch, zero block and the two tables for tile `tile`; returns image index, first output pixel, and
+// `lead`: the number of columns the patch starts left of the tile's first input column (to be added to every
+// pixel offset).  Vector mode: the patch starts at the multiple of four at or below that column, so every
+// 16-byte piece of a patch row is aligned in memory and lies wholly inside or wholly outside the image row.
 template <typename T>
-__device__ inline void stem_stage(const StemArgs &a, const StemLds &L, char *lds, int tile, int *n_out, int *p0_out, int *q0_out) {
+__device__ inline void stem_stage(const StemArgs &a, const StemLds &L, char *lds, int tile, int *n_out, int *p0_out, int *q0_out,
+                                  int *lead_out) {
   float *patch = reinterpret_cast<float *>(lds + L.patch);
   float *zero = reinterpret_cast<float *>(lds + L.zero);
   int *tab = reinterpret_cast<int *>(lds + L.tab);
@@ -84,7 +90,7 @@ __device__ inline void stem_stage(const StemArgs &a, const StemLds &L, char *lds
     if (j < a.taps) {
       const int c = j % a.C, tap = j / a.C;
       const int r = tap / a.R, s2 = tap - r * a.R;
-      t = (c * a.PH + r) * a.PW + s2;
+      t = (c * a.PH + r) * a.PWp + s2;
     }
     tab[j] = t;
   }
@@ -92,16 +98,44 @@ __device__ inline void stem_stage(const StemArgs &a, const StemLds &L, char *lds
     int o = 0;
     if (i < a.RB * a.QB) {
       const int pr = i / a.QB, qc = i - pr * a.QB;
-      o = pr * a.stride * a.PW + qc * a.stride;
+      o = pr * a.stride * a.PWp + qc * a.stride;
     }
     pixoff[i] = o;
+  }
+  const float *img = a.x + (size_t)n * a.C * a.H * a.W;
+  if (a.vec) {
+    // piece i = rc * V + pc of the patch (V pieces of 4 words per row); same walk as below
+    const int lead = w0 & 3, w0a = w0 - lead;     // w0 may be negative: & 3 is the non-negative remainder
+    const int V = a.PWp >> 2, total = a.C * a.PH * V;
+    const int dq = 256 / V, dr = 256 - dq * V;
+    int rc = (int)threadIdx.x / V, pc = (int)threadIdx.x - rc * V;
+    constexpr int kBatch = 6;
+    for (int base = threadIdx.x; base < total; base += 256 * kBatch) {
+      f32x4 v[kBatch];
+      int dst[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int c = (rc >= a.PH) + (rc >= 2 * a.PH) + (rc >= 3 * a.PH);     // C <= 4
+        const int ih = h0 + rc - c * a.PH, iw = w0a + 4 * pc;
+        const bool ok = base + u * 256 < total && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+        v[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (ok) v[u] = *reinterpret_cast<const f32x4 *>(img + ((size_t)c * a.H + ih) * a.W + iw);
+        dst[u] = rc * a.PWp + 4 * pc;
+        pc += dr; rc += dq;
+        if (pc >= V) { pc -= V; ++rc; }
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u)
+        if (base + u * 256 < total) *reinterpret_cast<f32x4 *>(patch + dst[u]) = v[u];
+    }
+    *n_out = n; *p0_out = p0; *q0_out = q0; *lead_out = lead;
+    return;
   }
   // element i = rc * PW + pc of the patch; a thread takes i = tid, tid + 256, ...: a batch of loads is in flight
   // before the first LDS write, and (rc, pc) advance by (256 / PW, 256 % PW) without further divisions
   const int total = a.C * a.PH * a.PW;
   const int dq = 256 / a.PW, dr = 256 - dq * a.PW;
   int rc = (int)threadIdx.x / a.PW, pc = (int)threadIdx.x - rc * a.PW;
-  const float *img = a.x + (size_t)n * a.C * a.H * a.W;
   auto stage = [&](auto batch_tag) {
     constexpr int kBatch = decltype(batch_tag)::value;
     for (int base = threadIdx.x; base < total; base += 256 * kBatch) {
@@ -123,7 +157,7 @@ __device__ inline void stem_stage(const StemArgs &a, const StemLds &L, char *lds
   // the ImageNet-shaped patch (3 x 7 x 229 words) arrives in one round trip of 24 loads per thread; small patches take 4
   if (total > 256 * 4) stage(std::integral_constant<int, 24>{});
   else stage(std::integral_constant<int, 4>{});
-  *n_out = n; *p0_out = p0; *q0_out = q0;
+  *n_out = n; *p0_out = p0; *q0_out = q0; *lead_out = 0;
 }
 
 // the value a float has once it is stored in the activations' type
@@ -180,8 +214,8 @@ __global__ __launch_bounds__(256) void stem_fwd_kernel(StemArgs a) {
       if (base + u * 256 < wtotal) *reinterpret_cast<f32x4 *>(Ws + wdst[u]) = wt[u];
   };
   w_issue(threadIdx.x);
-  int n, p0, q0;
-  stem_stage<T>(a, L, lds, blockIdx.x, &n, &p0, &q0);
+  int n, p0, q0, lead;
+  stem_stage<T>(a, L, lds, blockIdx.x, &n, &p0, &q0, &lead);
   w_commit(threadIdx.x);
   for (int base = threadIdx.x + 256 * 8; base < wtotal; base += 256 * 8) {
     w_issue(base);
@@ -190,7 +224,7 @@ __global__ __launch_bounds__(256) void stem_fwd_kernel(StemArgs a) {
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 31, kg = lane >> 5;
-  const int po = pixoff[wave * 32 + lr];
+  const int po = pixoff[wave * 32 + lr] + lead;
   const int nsteps = a.kpad / KS;
   float *Cs = reinterpret_cast<float *>(lds);
   const int ldc = k32 + 4;
@@ -323,8 +357,8 @@ __global__ __launch_bounds__(256, 2) void stem_wgrad_kernel(StemArgs a) {
   const int frow = (lane >> 5) * 8 + ((lane & 15) >> 2);
   const int fcol = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
   for (int tile = t0; tile < t1; ++tile) {
-    int n, p0, q0;
-    stem_stage<T>(a, L, lds, tile, &n, &p0, &q0);
+    int n, p0, q0, lead;
+    stem_stage<T>(a, L, lds, tile, &n, &p0, &q0, &lead);
     {  // output-gradient tile, eight 16-byte loads in flight per thread
       const T *dy = static_cast<const T *>(a.dy);
       const int vpr = k32 / VEC, total = 128 * vpr;
@@ -369,7 +403,7 @@ __global__ __launch_bounds__(256, 2) void stem_wgrad_kernel(StemArgs a) {
         }
         int po[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) po[e] = pixoff[px + kg * 8 + e];
+        for (int e = 0; e < 8; ++e) po[e] = pixoff[px + kg * 8 + e] + lead;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
           const int tj = tab[t * 32 + lr];
@@ -387,7 +421,7 @@ __global__ __launch_bounds__(256, 2) void stem_wgrad_kernel(StemArgs a) {
         float fa[MT];
 #pragma unroll
         for (int m = 0; m < MT; ++m) fa[m] = dyf[px * ldd + k0 + m * 32 + lr];
-        const int po = pixoff[px];
+        const int po = pixoff[px] + lead;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
           const float fb = patch[tab[t * 32 + lr] + po];
@@ -450,6 +484,7 @@ int stem_args(int N, int C, int H, int W, int K, int R, int stride, int pad, int
     if (P % d == 0) rb = d;
   a.QB = qb; a.RB = rb;
   a.PH = (rb - 1) * stride + R; a.PW = (qb - 1) * stride + R;
+  a.PWp = a.PW; a.vec = 0;
   a.tiles_q = Q / qb; a.tiles_p = P / rb;
   const long long tiles = (long long)N * a.tiles_q * a.tiles_p;
   if (tiles > 0x7fffffffLL) return set_error(RESIST_ESHAPE, "stem convolution: %lld tiles", tiles);
@@ -457,6 +492,12 @@ int stem_args(int N, int C, int H, int W, int K, int R, int stride, int pad, int
   a.zn = (rb - 1) * stride * a.PW + (qb - 1) * stride + 1;
   *out = a;
   return RESIST_OK;
+}
+// once the image pointer is known: vector mode where the rows allow it
+inline void stem_set_mode(StemArgs &a, bool allow_vec = true) {
+  a.vec = allow_vec && (a.W % 4 == 0) && (((uintptr_t)a.x & 15) == 0) ? 1 : 0;
+  a.PWp = a.vec ? (a.PW + 3 + 3) / 4 * 4 : a.PW;
+  a.zn = (a.RB - 1) * a.stride * a.PWp + (a.QB - 1) * a.stride + 1 + (a.vec ? 3 : 0);
 }
 constexpr int kStemLdsLimit = 64 * 1024;   // dynamic LDS a kernel gets without asking for more
 inline int stem_wgrad_groups(const StemArgs &a) { return a.tiles < 512 ? a.tiles : 512; }
@@ -481,8 +522,13 @@ int stem_conv_fwd(int dt, const float *x, const void *wpad, void *y, float *stat
   RESIST_TRY(stem_args(N, C, H, W, K, R, stride, pad, P, Q, kpad, &a));
   if (stats && !stat_parts) return set_error(RESIST_EINVAL, "stem_conv_fwd: stats without stat_parts");
   a.x = x; a.wpad = wpad; a.y = y; a.stats = stats; a.parts = a.tiles;
+  stem_set_mode(a);
   if (stat_parts) { stat_parts->parts = a.tiles; stat_parts->rows = a.RB * a.QB; }
-  const int lds = dt == DT_BF16 ? stem_lds<__bf16>(a, false).total : stem_lds<float>(a, false).total;
+  int lds = dt == DT_BF16 ? stem_lds<__bf16>(a, false).total : stem_lds<float>(a, false).total;
+  if (lds > kStemLdsLimit && a.vec) {   // the wider patch rows of vector mode do not fit: one word at a time
+    stem_set_mode(a, false);
+    lds = dt == DT_BF16 ? stem_lds<__bf16>(a, false).total : stem_lds<float>(a, false).total;
+  }
   if (lds > kStemLdsLimit) return set_error(RESIST_ESHAPE, "stem convolution: tile needs %d bytes of LDS", lds);
   const double flops = 2.0 * N * P * Q * K * a.taps;
   prof::Scope ps(dt == DT_BF16 ? "stem_conv_bf16_fwd" : "stem_conv_f32_fwd", flops,
@@ -527,9 +573,14 @@ int stem_conv_wgrad(int dt, const void *dy, const float *x, float *dwpad, float 
   RESIST_TRY(stem_args(N, C, H, W, K, R, stride, pad, P, Q, kpad, &a));
   if (!partial) return set_error(RESIST_EWORKSPACE, "stem weight gradient needs its partial-sum scratch");
   a.x = x; a.dy = dy; a.partial = partial;
+  stem_set_mode(a);
   const int groups = stem_wgrad_groups(a);
   a.parts = groups;
-  const int lds = dt == DT_BF16 ? stem_lds<__bf16>(a, true).total : stem_lds<float>(a, true).total;
+  int lds = dt == DT_BF16 ? stem_lds<__bf16>(a, true).total : stem_lds<float>(a, true).total;
+  if (lds > kStemLdsLimit && a.vec) {
+    stem_set_mode(a, false);
+    lds = dt == DT_BF16 ? stem_lds<__bf16>(a, true).total : stem_lds<float>(a, true).total;
+  }
   if (lds > kStemLdsLimit) return set_error(RESIST_ESHAPE, "stem weight gradient: tile needs %d bytes of LDS", lds);
   {
     const double flops = 2.0 * N * P * Q * K * a.taps;

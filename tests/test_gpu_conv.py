@@ -146,7 +146,9 @@ STEM_CASES = [(4, 3, 16, 16, 16, 3, 1, 1),       # the tiny configuration's stem
               (2, 3, 18, 30, 32, 3, 1, 1),       # rectangular, 32 output channels (one tile of channels)
               (2, 4, 12, 12, 96, 5, 2, 2),       # four input channels, 96 output channels (64 + 32), 5x5
               (1, 1, 9, 9, 16, 3, 1, 0),         # one channel, no padding
-              (2, 3, 26, 134, 48, 3, 1, 1)]      # 134 output columns: tiles of 67 columns
+              (2, 3, 26, 134, 48, 3, 1, 1),      # 134 output columns: tiles of 67 columns (rows not a multiple of 4 wide)
+              (1, 3, 8, 256, 16, 3, 1, 1),       # two tiles of 128 columns along a row that is staged in 16-byte pieces
+              (1, 3, 6, 268, 16, 3, 1, 1)]       # four tiles of 67 columns: every tile starts at another offset mod 4
 
 
 def _stem_tensors(case, seed, bf16):

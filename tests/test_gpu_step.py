@@ -302,6 +302,32 @@ def test_second_stream_changes_no_bit(name, bf16):
             assert a.tobytes() == b.tobytes()
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_second_stream_changes_no_bit_when_a_step_takes_more_events_than_the_ring_holds(bf16):
+    """The events that order the two streams come from a ring of 256 per device.  A step of a 90-block
+    network records about 370 of them, so the ring wraps inside a step; every event that is still to be
+    waited for must have been waited for by then.  Same check as above: bit-identical to one stream."""
+    basic = get_config("cfg1")["model"]
+    model = dict(basic, widths=[16, 32], blocks=[45, 45], in_h=8, in_w=8, num_classes=10, compute_dtype=1 if bf16 else 0)
+    blocks, batch = list(range(90)), 8
+    params = make_params(model, 9, perturb_bn=True)
+    outs = []
+    try:
+        for overlap in (0, 2):
+            R.set_overlap(overlap)
+            sub = SubResNet(model, blocks, params, batch)
+            for it in range(3):
+                xd, yd = to_device_batch(*make_batch(model, batch, 70 + it))
+                sub.step(xd, yd, 0.01, 0.9, 1e-4)
+            torch.cuda.synchronize()
+            outs.append([t.cpu().numpy().copy() for t in sub.params + sub.momentum + sub.grads] + [sub.loss.cpu().numpy().copy()])
+    finally:
+        R.set_overlap(True)
+    assert np.isfinite(outs[0][-1]).all()
+    for a, b in zip(*outs):
+        assert a.tobytes() == b.tobytes()
+
+
 @pytest.mark.parametrize("workload", ["cfg2", "cfg2_preact", "cfg4"])
 def test_second_stream_changes_no_bit_full_size(workload):
     """The same at the sizes the benchmark times, where kernels on the two streams really run

@@ -37,6 +37,9 @@ def _small_models():
         # class count and batch leave ragged tails in every tile of its three kernels
         "one_image": (dict(basic, widths=[16, 32], blocks=[2, 2], in_h=8, in_w=8, num_classes=5), [0, 2, 3], 1),
         "ragged_head": (dict(basic, widths=[16, 32], blocks=[2, 2], in_h=8, in_w=8, num_classes=37), [0, 1, 2], 17),
+        # channel counts that leave ragged tiles in every kernel: 48, 80 (and 192, 320) in bottleneck blocks
+        "odd_widths": (dict(basic, block_kind=1, widths=[48, 80], blocks=[2, 2], in_h=12, in_w=12, num_classes=6),
+                       [0, 1, 2, 3], 5),
     }
 
 
@@ -61,7 +64,7 @@ def _run_steps(model, blocks, batch, steps, lr, mu, wd, seed=0, perturb_bn=True)
 
 
 @pytest.mark.parametrize("name", ["cfg1", "strided_sub", "bottleneck_sub", "ragged", "preact_sub", "preact_bottleneck_sub",
-                                  "preact_full", "one_image", "ragged_head"])
+                                  "preact_full", "one_image", "ragged_head", "odd_widths"])
 def test_local_step_small(name):
     model, blocks, batch = _small_models()[name]
     # data seeds for which the oracle's closest ReLU decision is > 1e-5 from a tie (seed 0 of

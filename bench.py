@@ -144,6 +144,26 @@ def _bench_round(args, cfg, subs):
     if compressed:
         compressed["aggregate_traffic"] = _measured_traffic("cfg3_round", "aggregate_compressed")
         out["round"]["compressed"] = compressed
+    if not args.no_cpu_baseline:
+        # the oracle as it stands: one step of sub-ResNet 0 on its first batch, and the aggregation of S copies
+        from oracle import aggregate as OA
+        from oracle import layers as OL
+        from oracle import resnet as OR
+        from resist_inputs import zeros_like_params
+        ncpu = min(args.cpu_sample_batch, batch)
+        xs, ys = make_batch(model, ncpu, cfg["data_seed"])
+        OL._conv_lib()                         # build/load outside the timed region
+        t2 = time.perf_counter()
+        OR.local_step(model, subs[0], params, zeros_like_params(params), xs, ys, lr, mu, wd)
+        tc = time.perf_counter() - t2
+        sub_params = [{k: params[k] for k in [-1] + list(subs[s]) + [nb]} for s in range(S)]
+        t3 = time.perf_counter()
+        OA.aggregate(params, subs, sub_params)
+        ta = time.perf_counter() - t3
+        out["cpu_baseline"] = dict(value=round(ncpu / tc, 3), unit="images/s", cores=OL.num_threads(), kind="oracle",
+                                   sample=f"one full step of sub-ResNet 0 on a batch of {ncpu} (of {batch}) images, {tc:.1f} s; "
+                                          f"the aggregation of the {S} sub-ResNets takes the oracle {ta:.2f} s (numpy, one thread); "
+                                          "cores = OpenMP team size of the convolution loops (the rest of the step is numpy)")
     print(json.dumps(out), flush=True)
 
 

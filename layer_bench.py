@@ -20,7 +20,12 @@ from paper_2107_00961_amd import binding as B  # noqa: E402
 LAYERS = {
     "cfg2": (128, [("s1_3x3", 32, 64, 64, 3, 1, 1), ("s2_3x3", 16, 128, 128, 3, 1, 1), ("s3_3x3", 8, 256, 256, 3, 1, 1),
                    ("s4_3x3", 4, 512, 512, 3, 1, 1), ("s2_first", 32, 64, 128, 3, 2, 1), ("s3_first", 16, 128, 256, 3, 2, 1),
-                   ("s4_first", 8, 256, 512, 3, 2, 1), ("s3_shortcut", 16, 128, 256, 1, 2, 0)]),
+                   ("s4_first", 8, 256, 512, 3, 2, 1), ("s3_shortcut", 16, 128, 256, 1, 2, 0),
+                   # the 1x1 layers of the bottleneck blocks
+                   ("s1_1x1_in", 32, 256, 64, 1, 1, 0), ("s1_1x1_out", 32, 64, 256, 1, 1, 0),
+                   ("s2_1x1_in", 16, 512, 128, 1, 1, 0), ("s2_1x1_out", 16, 128, 512, 1, 1, 0),
+                   ("s3_1x1_in", 8, 1024, 256, 1, 1, 0), ("s3_1x1_out", 8, 256, 1024, 1, 1, 0),
+                   ("s4_1x1_in", 4, 2048, 512, 1, 1, 0), ("s4_1x1_out", 4, 512, 2048, 1, 1, 0)]),
     # the full model at CIFAR shape in bf16 (same layer shapes as cfg2)
     "cfg5_bf16": (128, [("s1_3x3", 32, 64, 64, 3, 1, 1), ("s2_3x3", 16, 128, 128, 3, 1, 1), ("s3_3x3", 8, 256, 256, 3, 1, 1),
                         ("s4_3x3", 4, 512, 512, 3, 1, 1)]),

@@ -16,6 +16,9 @@ def _small_models():
                        [0, 2, 3, 5], 6),
         "preact_bottleneck_sub": (dict(basic, block_kind=3, widths=[16, 32], blocks=[2, 3], in_h=12, in_w=12, num_classes=7),
                                   [0, 2, 4], 5),
+        # channel counts that leave ragged tiles in every kernel: 48, 80 (and 192, 320) in bottleneck blocks
+        "odd_widths": (dict(basic, block_kind=1, widths=[48, 80], blocks=[2, 2], in_h=12, in_w=12, num_classes=6),
+                       [0, 1, 2, 3], 5),
     }
 
 

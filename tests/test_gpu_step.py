@@ -220,7 +220,8 @@ def test_aggregate_matches_oracle_and_invariants(S):
 
 
 # ---- bf16 storage (compute_dtype = 1): cases in tests/bf16_cases.py, checks in gpu_util.bf16_step_check
-@pytest.mark.parametrize("name", ["cfg1", "strided_sub", "bottleneck_sub", "ragged", "preact_sub", "preact_bottleneck_sub"])
+@pytest.mark.parametrize("name", ["cfg1", "strided_sub", "bottleneck_sub", "ragged", "preact_sub", "preact_bottleneck_sub",
+                                  "odd_widths"])
 def test_local_step_small_bf16(name):
     bf16_step_check(f"bf16 {name}")
 

@@ -40,6 +40,10 @@ def _small_models():
         # channel counts that leave ragged tiles in every kernel: 48, 80 (and 192, 320) in bottleneck blocks
         "odd_widths": (dict(basic, block_kind=1, widths=[48, 80], blocks=[2, 2], in_h=12, in_w=12, num_classes=6),
                        [0, 1, 2, 3], 5),
+        # images that are not square, through a strided stage and, in the second case, the 7x7 stem and the max-pool
+        "rectangular": (dict(basic, widths=[16, 32], blocks=[2, 2], in_h=12, in_w=20, num_classes=5), [0, 1, 2, 3], 3),
+        "rectangular_bottleneck": (dict(basic, block_kind=1, stem_kind=1, widths=[16, 32], blocks=[1, 2], in_h=24, in_w=40,
+                                        num_classes=5), [0, 1, 2], 3),
     }
 
 
@@ -64,7 +68,8 @@ def _run_steps(model, blocks, batch, steps, lr, mu, wd, seed=0, perturb_bn=True)
 
 
 @pytest.mark.parametrize("name", ["cfg1", "strided_sub", "bottleneck_sub", "ragged", "preact_sub", "preact_bottleneck_sub",
-                                  "preact_full", "one_image", "ragged_head", "odd_widths"])
+                                  "preact_full", "one_image", "ragged_head", "odd_widths", "rectangular",
+                                  "rectangular_bottleneck"])
 def test_local_step_small(name):
     model, blocks, batch = _small_models()[name]
     # data seeds for which the oracle's closest ReLU decision is > 1e-5 from a tie (seed 0 of

@@ -24,7 +24,10 @@ CASES = [(2, 16, 16, 16, 16, 3, 1, 1),      # tiny config's block shape
          (2, 12, 12, 16, 32, 5, 1, 2),      # 5x5
          (2, 14, 14, 16, 32, 5, 2, 2),      # 5x5 stride 2: three and two taps per parity class
          (1, 9, 9, 16, 16, 7, 1, 3),        # 7x7
-         (2, 16, 16, 8, 16, 7, 2, 3)]       # 7x7 stride 2 pad 3 (the ImageNet stem's filter geometry)
+         (2, 16, 16, 8, 16, 7, 2, 3),       # 7x7 stride 2 pad 3 (the ImageNet stem's filter geometry)
+         (2, 10, 18, 32, 32, 3, 1, 1),      # images that are not square
+         (3, 12, 20, 16, 32, 3, 2, 1),      # ... stride 2 (parity classes of 6 x 10 pixels)
+         (2, 6, 14, 32, 64, 1, 1, 0)]       # ... 1x1
 
 
 def _tensors(case, seed=0):

@@ -27,7 +27,10 @@ CASES = [(2, 16, 16, 16, 16, 3, 1, 1),      # tiny config's block shape
          (2, 16, 16, 8, 16, 7, 2, 3),       # 7x7 stride 2 pad 3 (the ImageNet stem's filter geometry)
          (2, 10, 18, 32, 32, 3, 1, 1),      # images that are not square
          (3, 12, 20, 16, 32, 3, 2, 1),      # ... stride 2 (parity classes of 6 x 10 pixels)
-         (2, 6, 14, 32, 64, 1, 1, 0)]       # ... 1x1
+         (2, 6, 14, 32, 64, 1, 1, 0),       # ... 1x1
+         (4, 1, 1, 32, 64, 1, 1, 0),        # one pixel per image: four GEMM rows
+         (1, 3, 3, 16, 16, 3, 1, 0),        # one output pixel in all
+         (3, 2, 2, 16, 16, 3, 2, 1)]        # 2x2 input, stride 2: one output pixel per image, three of four parity classes empty of taps
 
 
 def _tensors(case, seed=0):

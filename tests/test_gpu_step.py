@@ -44,6 +44,10 @@ def _small_models():
         "rectangular": (dict(basic, widths=[16, 32], blocks=[2, 2], in_h=12, in_w=20, num_classes=5), [0, 1, 2, 3], 3),
         "rectangular_bottleneck": (dict(basic, block_kind=1, stem_kind=1, widths=[16, 32], blocks=[1, 2], in_h=24, in_w=40,
                                         num_classes=5), [0, 1, 2], 3),
+        # four stages on 8x8 images: the last stage works on one pixel per image, its BNs on 6 values per channel.
+        # (Batch 3 is too badly conditioned for an fp32 bound: in the float64 oracle itself an input perturbed by
+        # 6e-8 moves that stage's filter gradients by 9e-6 in norm, thirty times what it does at batch 6.)
+        "one_pixel": (dict(basic, widths=[16, 32, 64, 128], blocks=[1, 1, 1, 1], in_h=8, in_w=8, num_classes=4), [0, 1, 2, 3], 6),
     }
 
 
@@ -69,7 +73,7 @@ def _run_steps(model, blocks, batch, steps, lr, mu, wd, seed=0, perturb_bn=True)
 
 @pytest.mark.parametrize("name", ["cfg1", "strided_sub", "bottleneck_sub", "ragged", "preact_sub", "preact_bottleneck_sub",
                                   "preact_full", "one_image", "ragged_head", "odd_widths", "rectangular",
-                                  "rectangular_bottleneck"])
+                                  "rectangular_bottleneck", "one_pixel"])
 def test_local_step_small(name):
     model, blocks, batch = _small_models()[name]
     # data seeds for which the oracle's closest ReLU decision is > 1e-5 from a tie (seed 0 of

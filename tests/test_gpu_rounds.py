@@ -94,7 +94,8 @@ def test_round_with_compressed_communication(down):
     assert off <= (0.05 if down else 0.01) * total, f"{off} of {total} elements off by a quantiser step"
 
 
-@pytest.mark.parametrize("kind", ["basic", "bottleneck", "bottleneck_bf16", "preact", "preact_bottleneck_bf16"])
+@pytest.mark.parametrize("kind", ["basic", "bottleneck", "bottleneck_bf16", "preact", "preact_bottleneck_bf16",
+                                  "rectangular", "rectangular_bottleneck"])
 def test_forward_eval_with_branch_scaling(kind):
     """resist_forward: evaluation-mode BN (running statistics) and 1/S scaling of the partitioned
     blocks' residual branches (Sec. 2.6), against the oracle; and after a reassembly, as in the method."""
@@ -103,6 +104,10 @@ def test_forward_eval_with_branch_scaling(kind):
     if kind in ("basic", "preact"):
         model = dict(base, block_kind=2 if kind == "preact" else 0, widths=[16, 32, 64], blocks=[2, 2, 4], in_h=16, in_w=16,
                      num_classes=10)
+    elif kind == "rectangular":            # images that are not square
+        model = dict(base, widths=[16, 32, 64], blocks=[2, 2, 4], in_h=12, in_w=20, num_classes=10)
+    elif kind == "rectangular_bottleneck":
+        model = dict(base, block_kind=1, stem_kind=1, widths=[16, 32], blocks=[2, 3], in_h=24, in_w=40, num_classes=12)
     elif kind == "preact_bottleneck_bf16":
         model = dict(base, block_kind=3, widths=[16, 32], blocks=[2, 3], in_h=16, in_w=16, num_classes=12, compute_dtype=1)
     else:

@@ -91,3 +91,52 @@ def test_full_size_conv(name, dt, N, shape):
     # the weight gradient: every element, through the split reduction
     dw_ref = L.conv2d_wgrad(dywh.transpose(0, 3, 1, 2), xh.transpose(0, 3, 1, 2), (K, C, RS, RS), st, pad)   # [K][C][R][S]
     check(dwh.transpose(0, 3, 1, 2), dw_ref, "wgrad, all elements")
+
+
+def test_conv_1x1_at_the_size_limit():
+    """Maximum sizes: an activation tensor of 2.05e9 bytes, just under the 2 GiB that the kernels' 32-bit
+    byte offsets can reach (larger shapes are refused when the plan is made).  A 1x1 convolution 512 <-> 16
+    channels over 61 x 128 x 128 pixels: the forward pass reads that tensor, the data gradient writes one,
+    the weight gradient reduces over its 999 424 rows.  Forward and data gradient are compared on the
+    first and last 1024 rows and 2048 rows in between (a 1x1 convolution treats every pixel on its own, so the
+    oracle is run on those rows as a batch of one-pixel images), the weight gradient over the whole tensors."""
+    N, H, W, C, K = 61, 128, 128, 512, 16
+    M = N * H * W
+    assert 2 ** 31 - 2 ** 27 < M * C * 4 < 2 ** 31
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    x = torch.randn((N, H, W, C), device="cuda", generator=g)
+    w = torch.randn((K, 1, 1, C), device="cuda", generator=g) / np.sqrt(C)
+    dy = torch.randn((N, H, W, K), device="cuda", generator=g)
+    w_o = w.cpu().numpy().transpose(0, 3, 1, 2)                      # [K, C, 1, 1]
+    rng = np.random.default_rng(3)
+    rows = np.concatenate([np.arange(1024), np.arange(M - 1024, M), rng.integers(1024, M - 1024, 2048)])
+    rows_d = torch.from_numpy(rows).cuda()
+
+    print("forward", flush=True)
+    y = R.conv2d_forward(x, w, 1, 0)
+    torch.cuda.synchronize()
+    xs = x.view(M, C)[rows_d].cpu().numpy()
+    want = L.conv2d_fwd(xs[:, :, None, None], w_o, 1, 0)[:, :, 0, 0]
+    got = y.view(M, K)[rows_d].cpu().numpy()
+    assert np.all(np.abs(got - want) <= 1e-5 + 1e-4 * np.abs(want)), f"forward: max error {np.max(np.abs(got - want)):.3e}"
+    del y
+
+    print("data gradient", flush=True)
+    dx = R.conv2d_dgrad(dy, w, (N, H, W, C), 1, 0)
+    torch.cuda.synchronize()
+    dys = dy.view(M, K)[rows_d].cpu().numpy()
+    want = L.conv2d_dgrad(dys[:, :, None, None], w_o, (len(rows), C, 1, 1), 1, 0)[:, :, 0, 0]
+    got = dx.view(M, C)[rows_d].cpu().numpy()
+    assert np.all(np.abs(got - want) <= 1e-5 + 1e-4 * np.abs(want)), f"data gradient: max error {np.max(np.abs(got - want)):.3e}"
+    del dx
+
+    print("weight gradient", flush=True)
+    dw = R.conv2d_wgrad(dy, x, (K, 1, 1, C), 1, 0)
+    torch.cuda.synchronize()
+    want = L.conv2d_wgrad(dy.view(M, K, 1, 1).cpu().numpy(), x.view(M, C, 1, 1).cpu().numpy(), (K, C, 1, 1), 1, 0)
+    got = dw.cpu().numpy().transpose(0, 3, 1, 2)
+    # a sum of 999 424 products in fp32, split over workgroups and added in a fixed order: errors of ~1e-6 of the
+    # typical magnitude of an entry (~1000); entries near zero are held to that scale, not to their own size
+    tol = 1e-4 * np.abs(want) + 1e-5 * np.max(np.abs(want))
+    assert np.all(np.abs(got - want) <= tol), f"weight gradient: max error {np.max(np.abs(got - want)):.3e} of {np.max(np.abs(want)):.3e}"
